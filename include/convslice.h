@@ -1,0 +1,126 @@
+/*
+ * convslice.h -- C ABI of libconvslice.so (AMD Instinct MI355X, gfx950 only).
+ *
+ * One device's share of a convolutional layer as defined by arXiv 1712.02546,
+ * Section 4.1.2 and Algorithms 1-2: every device receives the same input maps
+ * and a contiguous block [k0,k1) of the layer's kernels, convolves all inputs
+ * with its own kernels and returns its own output maps, which the master puts
+ * side by side.  The abstract counts the backward convolutions in the same
+ * distributed work, so the library has three entry points: forward, input
+ * gradient, weight gradient.
+ *
+ * Conventions (the paper prints no formula; these are the textbook ones):
+ *   cross-correlation, zero padding, no bias, no activation,
+ *   P = floor((H + 2*pad_h - R) / stride_h) + 1, Q likewise,
+ *   row-major tensors, innermost index last:
+ *     x, dx : [N][C][H][W]        w, dw : [K][C][R][S]        y, dy : [N][K][P][Q]
+ *
+ * Slice addressing.  w, dw, y and dy always point at FULL-layer tensors with K
+ * channels; a call reads and writes only channels k0 <= k < k1 and never
+ * touches the others, so calls on disjoint slices that share y (or dw)
+ * assemble the whole layer in place.  dx receives the partial sum over the
+ * slice's kernels; with accumulate = 1 it is added to what dx holds, so the
+ * slices of a partition can be summed by consecutive calls on one stream.  A
+ * device that holds only its own kernels and maps in memory uses K = k1-k0,
+ * k0 = 0 on its packed buffers.
+ *
+ * Pointers.  x, w, y, dy, dx, dw and ws are DEVICE pointers (hipMalloc'ed or
+ * equivalent, e.g. a PyTorch-ROCm tensor's data_ptr()), owned by the caller,
+ * 16-byte aligned.  desc is a HOST pointer, read before the call returns.
+ * Inputs are never written.  ws is scratch the caller provides: at least
+ * conv_workspace_bytes(desc, pass) bytes, 256-byte aligned, contents
+ * undefined before and after.  Calls that overlap in time must not share ws.
+ *
+ * Execution.  Work is enqueued on hip_stream (a hipStream_t passed as void*,
+ * NULL = default stream) and the call returns without synchronising.  The
+ * library allocates no device memory and keeps no state between calls apart
+ * from one-time kernel attribute set-up.
+ *
+ * Errors.  Every entry point returns CONV_OK (0) or a negative conv_status_t.
+ * All argument checks happen before the first launch; on an argument error
+ * nothing is enqueued.  k0 == k1 is valid: forward and weight gradient do
+ * nothing, input gradient zero-fills dx unless accumulate = 1.
+ *
+ * Precision.  CONV_F32: fp32 tensors, fp32 matrix-core (MFMA) products and
+ * accumulation.  CONV_BF16: x, w, y, dy, dx are bfloat16 (upper 16 bits of an
+ * fp32, round-to-nearest-even on output), accumulation is fp32, dw is fp32.
+ *
+ * Limits.  Each tensor (and each internal transposed copy, whose batch extent
+ * is rounded up to a multiple of 32) must have fewer than 2^31 elements;
+ * R*S <= 1024.  Otherwise CONV_ERR_SHAPE.
+ */
+#ifndef CONVSLICE_H
+#define CONVSLICE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CONV_OK = 0,
+  CONV_ERR_NULL = -1,      /* a required pointer is NULL                         */
+  CONV_ERR_SHAPE = -2,     /* non-positive extent, P < 1 or Q < 1, limit exceeded */
+  CONV_ERR_SLICE = -3,     /* not 0 <= k0 <= k1 <= K                             */
+  CONV_ERR_DTYPE = -4,     /* dtype is not a conv_dtype_t                        */
+  CONV_ERR_WORKSPACE = -5, /* ws_bytes too small, or ws missing / misaligned     */
+  CONV_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch                   */
+  CONV_ERR_ALIGN = -7,     /* a tensor pointer is not 16-byte aligned            */
+  CONV_ERR_PASS = -8       /* pass is not a conv_pass_t                          */
+} conv_status_t;
+
+typedef enum { CONV_F32 = 0, CONV_BF16 = 1 } conv_dtype_t;
+
+typedef enum { CONV_PASS_FWD = 0, CONV_PASS_BWD_DATA = 1, CONV_PASS_BWD_WEIGHT = 2 } conv_pass_t;
+
+typedef struct {
+  int32_t N, C, H, W;      /* input extents                                  */
+  int32_t K, R, S;         /* FULL layer: K kernels of C x R x S             */
+  int32_t stride_h, stride_w;
+  int32_t pad_h, pad_w;
+  int32_t k0, k1;          /* this device's kernels, 0 <= k0 <= k1 <= K      */
+  int32_t dtype;           /* conv_dtype_t of x, w, y, dy, dx (dw is fp32)   */
+  int32_t accumulate;      /* conv_bwd_data only: 0 -> dx = ..., 1 -> dx += ... */
+} conv_desc_t;
+
+/* Output extents P and Q of the layer.  Returns CONV_OK or CONV_ERR_*. */
+int conv_output_dims(const conv_desc_t *desc, int32_t *P, int32_t *Q);
+
+/* Scratch bytes the given pass needs for this descriptor (0 on invalid input). */
+size_t conv_workspace_bytes(const conv_desc_t *desc, int pass);
+
+/*
+ * Forward pass of the slice (Algorithm 2's loop over the device's own maps):
+ *   y[n,k,p,q] = sum_{c,r,s} x[n,c,p*stride_h-pad_h+r,q*stride_w-pad_w+s] * w[k,c,r,s]
+ * for k0 <= k < k1.  Reads x (all C channels) and w[k0:k1]; writes y[:,k0:k1].
+ */
+int conv_fwd(const conv_desc_t *desc, const void *x, const void *w, void *y,
+             void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Input gradient of the slice (backward convolution, abstract):
+ *   dx[n,c,h,v] (+)= sum_{k0<=k<k1} sum_{r,s} dy[n,k,p,q] * w[k,c,r,s]
+ * over the (p,q) with p*stride_h-pad_h+r = h and q*stride_w-pad_w+s = v.
+ * Reads dy[:,k0:k1] and w[k0:k1]; writes (accumulate=0) or adds to
+ * (accumulate=1) the whole of dx.  Pixels no window covers receive 0.
+ */
+int conv_bwd_data(const conv_desc_t *desc, const void *dy, const void *w, void *dx,
+                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Weight gradient of the slice (backward convolution, abstract):
+ *   dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*stride_h-pad_h+r,q*stride_w-pad_w+s]
+ * for k0 <= k < k1.  Reads x and dy[:,k0:k1]; writes dw[k0:k1] (always fp32).
+ */
+int conv_bwd_weight(const conv_desc_t *desc, const void *x, const void *dy, void *dw,
+                    void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Static, never-NULL description of a status code. */
+const char *conv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVSLICE_H */

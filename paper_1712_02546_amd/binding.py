@@ -1,0 +1,142 @@
+"""ctypes binding of libconvslice.so: same names as the C ABI, argument marshalling only.
+
+Tensors are PyTorch-ROCm tensors used as plain device buffers (``data_ptr()``);
+the stream is torch's current HIP stream unless one is given.  There is no
+fallback: if the library has not been built, importing the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconvslice.so")
+
+CONV_F32, CONV_BF16 = 0, 1
+PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
+
+EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_bwd_data",
+           "conv_bwd_weight", "conv_status_string")
+
+
+class conv_desc_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
+        "k0", "k1", "dtype", "accumulate")]
+
+
+@dataclass(frozen=True)
+class ConvDesc:
+    """Host-side mirror of conv_desc_t (k1 = -1 means the whole layer)."""
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    R: int
+    S: int
+    stride_h: int = 1
+    stride_w: int = 1
+    pad_h: int = 0
+    pad_w: int = 0
+    k0: int = 0
+    k1: int = -1
+    dtype: int = CONV_F32
+    accumulate: int = 0
+
+    def c_struct(self) -> conv_desc_t:
+        k1 = self.K if self.k1 < 0 else self.k1
+        return conv_desc_t(self.N, self.C, self.H, self.W, self.K, self.R, self.S,
+                           self.stride_h, self.stride_w, self.pad_h, self.pad_w,
+                           self.k0, k1, self.dtype, self.accumulate)
+
+
+class ConvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libconvslice.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1712_02546_amd.build` "
+                "(hipcc, gfx950). There is no CPU or PyTorch fallback.")
+        lib = ctypes.CDLL(LIB_PATH)
+        dp = ctypes.POINTER(conv_desc_t)
+        vp = ctypes.c_void_p
+        lib.conv_output_dims.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        lib.conv_output_dims.restype = ctypes.c_int
+        lib.conv_workspace_bytes.argtypes = [dp, ctypes.c_int]
+        lib.conv_workspace_bytes.restype = ctypes.c_size_t
+        for name in ("conv_fwd", "conv_bwd_data", "conv_bwd_weight"):
+            f = getattr(lib, name)
+            f.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+            f.restype = ctypes.c_int
+        lib.conv_status_string.argtypes = [ctypes.c_int]
+        lib.conv_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().conv_status_string(int(status)).decode()
+
+
+def conv_output_dims(desc: ConvDesc) -> tuple[int, int]:
+    p, q = ctypes.c_int32(), ctypes.c_int32()
+    cd = desc.c_struct()
+    rc = load().conv_output_dims(ctypes.byref(cd), ctypes.byref(p), ctypes.byref(q))
+    if rc != 0:
+        raise ConvError(rc, "conv_output_dims")
+    return int(p.value), int(q.value)
+
+
+def conv_workspace_bytes(desc: ConvDesc, which: int) -> int:
+    cd = desc.c_struct()
+    return int(load().conv_workspace_bytes(ctypes.byref(cd), int(which)))
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> int:
+    if stream is not None:
+        return int(stream)
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _call(name: str, desc: ConvDesc, a, b, out, ws, stream, raw_status: bool):
+    cd = desc.c_struct()
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = getattr(load(), name)(ctypes.byref(cd), _ptr(a), _ptr(b), _ptr(out), _ptr(ws), ws_bytes,
+                               _stream(stream))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, name)
+    return out
+
+
+def conv_fwd(desc: ConvDesc, x, w, y, ws=None, stream=None, raw_status=False):
+    """y[:, k0:k1] = conv(x, w[k0:k1]) enqueued on the stream; returns y."""
+    return _call("conv_fwd", desc, x, w, y, ws, stream, raw_status)
+
+
+def conv_bwd_data(desc: ConvDesc, dy, w, dx, ws=None, stream=None, raw_status=False):
+    """dx (+)= input gradient from dy[:, k0:k1] and w[k0:k1]; returns dx."""
+    return _call("conv_bwd_data", desc, dy, w, dx, ws, stream, raw_status)
+
+
+def conv_bwd_weight(desc: ConvDesc, x, dy, dw, ws=None, stream=None, raw_status=False):
+    """dw[k0:k1] = weight gradient from x and dy[:, k0:k1]; returns dw (fp32)."""
+    return _call("conv_bwd_weight", desc, x, dy, dw, ws, stream, raw_status)

@@ -1,0 +1,138 @@
+// Shared device-side definitions for the gfx950 convolution kernels.
+//
+// Internal data layout ("batch-innermost"): every tensor the matrix-core kernels
+// touch is first re-laid with the image index n as the fastest dimension, padded
+// with zeros to Np = 32*ceil(N/32):
+//     x_t [C][H][W][Np]     y_t / dy_t [Ks][P][Q][Np]     dx_t [C][H][W][Np]
+// A 32-lane MFMA column block is then "32 images at one pixel": every operand
+// row is a dense, 128-byte-aligned run, padding and stride decide per block (not
+// per element) whether a filter tap contributes, and the input-gradient pass
+// visits only the taps that really reach a pixel (no work on padded zeros).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cs {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int NT = 256;             // threads per workgroup: 4 wavefronts in a 2x2 grid
+constexpr int BM = 128;             // tile rows  (GEMM M)
+constexpr int BN = 128;             // tile cols  (GEMM N) = 4 column blocks of 32
+constexpr int BK = 32;              // reduction elements per staged chunk
+constexpr int LDT = 129;            // LDS row pitch for operands stored transposed (scalar stores)
+constexpr int LDV = 132;            // LDS row pitch for operands stored as float4 rows
+constexpr int STAGE = BK * LDV;     // floats per operand per buffer
+constexpr int SMEM_BYTES = 4 * STAGE * 4;  // A and B, double buffered
+
+struct Geo {
+  int N, Np, NB;                    // batch, padded batch, Np/32
+  int C, H, W, K, R, S, P, Q;
+  int sh, sw, ph, pw;
+  int k0, Ks;
+  int HW, PQ, RS, CRS;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// Round-to-nearest-even fp32 -> bfloat16; NaN stays NaN (quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_as_f32(const T* p);
+template <> __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_as_f32<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void store_from_f32(T* p, float v);
+template <> __device__ __forceinline__ void store_from_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// Workgroup id -> (row tile mb, column tile ct).  Workgroups are dealt round-robin
+// to the 8 XCDs, each with its own L2.  Column tiles are taken in groups of 8; a
+// group and all MB row tiles against it stay on one XCD and are consecutive in
+// that XCD's dispatch order, so the tiles resident together share both operand
+// panels.  Returns false for the padding ids of a ragged last group.
+__device__ __forceinline__ bool tile_of_block(int g, int MB, int CT, int& mb, int& ct) {
+  const int xcd = g & 7;
+  const int s = g >> 3;
+  const int per_group = 8 * MB;
+  const int gl = s / per_group;
+  const int rem = s - gl * per_group;
+  mb = rem >> 3;
+  ct = ((gl * 8 + xcd) << 3) + (rem & 7);
+  return ct < CT;
+}
+
+// Host helper: grid size that covers every (mb, ct) under tile_of_block.
+static inline int grid_for_tiles(int MB, int CT) {
+  const int groups = (CT + 7) / 8;
+  const int groups_per_xcd = (groups + 7) / 8;
+  return 8 * groups_per_xcd * 8 * MB;
+}
+
+// One staged chunk: 16 reduction steps of four 32x32x2 fp32 MFMAs per wavefront.
+// As/Bs are [BK][lda]/[BK][ldb] with the reduction index as the row.  In
+// v_mfma_f32_32x32x2_f32 lane l supplies A[row l%32][k l/32] and B[k l/32][col l%32].
+__device__ __forceinline__ void mfma_chunk(const float* __restrict__ As, int lda,
+                                           const float* __restrict__ Bs, int ldb,
+                                           int wm, int wn, int lane, f32x16 (&acc)[2][2]) {
+  const float* ap = As + (lane >> 5) * lda + wm * 64 + (lane & 31);
+  const float* bp = Bs + (lane >> 5) * ldb + wn * 64 + (lane & 31);
+#pragma unroll
+  for (int ks = 0; ks < BK / 2; ++ks) {
+    const float a0 = ap[2 * ks * lda];
+    const float a1 = ap[2 * ks * lda + 32];
+    const float b0 = bp[2 * ks * ldb];
+    const float b1 = bp[2 * ks * ldb + 32];
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+  }
+}
+
+// Software-pipelined main loop shared by the three passes.  A loader stages one
+// operand: load(ch) issues the global reads of chunk ch into registers (chunks
+// are requested in increasing order, once each), store(buf) writes them to LDS.
+template <class LA, class LB>
+__device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
+                                              float* smem, f32x16 (&acc)[2][2]) {
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  float* sA[2] = {smem, smem + STAGE};
+  float* sB[2] = {smem + 2 * STAGE, smem + 3 * STAGE};
+  if (ch_begin >= ch_end) return;
+  la.load(ch_begin);
+  lb.load(ch_begin);
+  la.store(sA[0]);
+  lb.store(sB[0]);
+  __syncthreads();
+  int buf = 0;
+  for (int ch = ch_begin; ch < ch_end; ++ch) {
+    const bool more = ch + 1 < ch_end;
+    if (more) {
+      la.load(ch + 1);
+      lb.load(ch + 1);
+    }
+    mfma_chunk(sA[buf], LA::LD, sB[buf], LB::LD, wm, wn, lane, acc);
+    if (more) {
+      la.store(sA[buf ^ 1]);
+      lb.store(sB[buf ^ 1]);
+    }
+    __syncthreads();
+    buf ^= 1;
+  }
+}
+
+// Position of accumulator register v of a 32x32 MFMA block inside the block.
+__device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+}  // namespace cs

@@ -1,0 +1,343 @@
+// Host side of libconvslice.so: argument checks, workspace carving and kernel
+// launches for the three passes declared in include/convslice.h.
+#include "../../include/convslice.h"
+
+#include <hip/hip_runtime.h>
+
+#include "conv_common.h"
+#include "gemm_kernels.h"
+#include "pack_kernels.h"
+
+namespace {
+
+using cs::Geo;
+
+constexpr int64_t kMaxElems = (int64_t)1 << 31;
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+int out_extent(int in, int pad, int flt, int stride) {
+  const int64_t span = (int64_t)in + 2 * (int64_t)pad - flt;
+  if (span < 0) return 0;
+  return (int)(span / stride) + 1;
+}
+
+// Validates the descriptor and derives the geometry.  No GPU call.
+int make_geo(const conv_desc_t* d, Geo& g) {
+  if (!d) return CONV_ERR_NULL;
+  if (d->dtype != CONV_F32 && d->dtype != CONV_BF16) return CONV_ERR_DTYPE;
+  if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->K < 1 || d->R < 1 || d->S < 1)
+    return CONV_ERR_SHAPE;
+  if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return CONV_ERR_SHAPE;
+  if (d->k0 < 0 || d->k1 > d->K || d->k0 > d->k1) return CONV_ERR_SLICE;
+  const int P = out_extent(d->H, d->pad_h, d->R, d->stride_h);
+  const int Q = out_extent(d->W, d->pad_w, d->S, d->stride_w);
+  if (P < 1 || Q < 1) return CONV_ERR_SHAPE;
+  if ((int64_t)d->R * d->S > 1024) return CONV_ERR_SHAPE;
+  if (d->pad_h > (1 << 20) || d->pad_w > (1 << 20)) return CONV_ERR_SHAPE;
+  const int64_t Np = round_up(d->N, 32);
+  const int64_t HW = (int64_t)d->H * d->W, PQ = (int64_t)P * Q, RS = (int64_t)d->R * d->S;
+  const int64_t Cp = round_up(d->C, 4);
+  if ((int64_t)d->C * HW * Np >= kMaxElems) return CONV_ERR_SHAPE;       // x, x_t, dx_t
+  if ((int64_t)d->K * PQ * Np >= kMaxElems) return CONV_ERR_SHAPE;       // y, dy and work copies
+  if ((int64_t)d->K * Cp * RS + 4 * (int64_t)d->K >= kMaxElems) return CONV_ERR_SHAPE;  // w, w_t
+  g.N = d->N; g.Np = (int)Np; g.NB = (int)(Np / 32);
+  g.C = d->C; g.H = d->H; g.W = d->W; g.K = d->K; g.R = d->R; g.S = d->S; g.P = P; g.Q = Q;
+  g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
+  g.k0 = d->k0; g.Ks = d->k1 - d->k0;
+  g.HW = (int)HW; g.PQ = (int)PQ; g.RS = (int)RS; g.CRS = (int)(d->C * RS);
+  return CONV_OK;
+}
+
+inline size_t seg(int64_t floats) { return (size_t)round_up(floats * 4, 256); }
+
+struct FwdPlan {
+  bool repitch;      // filters copied to fp32 rows of pitch ldw (bf16 input or C*R*S not a multiple of 4)
+  int ldw, nch;
+  size_t off_xt, off_yt, off_tab, off_w, total;
+};
+
+FwdPlan plan_fwd(const Geo& g, int dtype) {
+  FwdPlan p;
+  p.repitch = dtype != CONV_F32 || (g.CRS % 4) != 0;
+  p.ldw = p.repitch ? (int)round_up(g.CRS, 4) : g.CRS;
+  p.nch = (g.CRS + cs::BK - 1) / cs::BK;
+  size_t o = 0;
+  p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
+  p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
+  p.off_tab = o; o += seg((int64_t)p.nch * cs::BK * 2);
+  p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
+  p.total = o;
+  return p;
+}
+
+struct BwdDataPlan {
+  int Cp;
+  size_t off_dyt, off_wt, off_dxt, off_perm, total;
+};
+
+BwdDataPlan plan_bwd_data(const Geo& g) {
+  BwdDataPlan p;
+  p.Cp = (int)round_up(g.C, 4);
+  size_t o = 0;
+  p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
+  p.off_wt = o;   o += seg((int64_t)g.RS * g.Ks * p.Cp);
+  p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
+  p.off_perm = o; o += seg(g.HW);
+  p.total = o;
+  return p;
+}
+
+struct BwdWeightPlan {
+  int MB, CT, nch, splits, chPerSplit;
+  size_t off_xt, off_dyt, off_part, total;
+};
+
+BwdWeightPlan plan_bwd_weight(const Geo& g) {
+  BwdWeightPlan p;
+  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
+  p.CT = (g.CRS + cs::BN - 1) / cs::BN;
+  p.nch = g.PQ * g.NB;
+  // Split the reduction until about four workgroups per compute unit exist, but keep
+  // at least four chunks per split so the pipeline prologue stays small.
+  const int64_t tiles = (int64_t)(p.MB > 0 ? p.MB : 1) * p.CT;
+  int64_t want = (1024 + tiles - 1) / tiles;
+  const int64_t cap = p.nch / 4 > 0 ? p.nch / 4 : 1;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  p.chPerSplit = (int)((p.nch + want - 1) / want);
+  p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;
+  size_t o = 0;
+  p.off_xt = o;   o += seg((int64_t)g.C * g.HW * g.Np);
+  p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
+  p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
+  p.total = o;
+  return p;
+}
+
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+int check_launch() { return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH; }
+
+template <typename K>
+int allow_big_lds(K kernel) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             cs::SMEM_BYTES) == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH;
+}
+
+// src[rows][cols] (pitch srcPitch, element type by dtype) -> dst[cols][rowsPad] fp32, batched.
+void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
+                         float* dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch,
+                         hipStream_t st) {
+  const size_t es = dtype == CONV_F32 ? 4 : 2;
+  for (int b0 = 0; b0 < batch; b0 += 32768) {  // grid.z is limited to 65535
+    const int nb = batch - b0 < 32768 ? batch - b0 : 32768;
+    const dim3 grid((cols + 63) / 64, (rowsPad + 63) / 64, nb);
+    const void* s = (const char*)src + (size_t)b0 * srcBatch * es;
+    float* d = dst + (size_t)b0 * dstBatch;
+    if (dtype == CONV_F32)
+      hipLaunchKernelGGL(cs::transpose_in_kernel<float>, grid, dim3(256), 0, st, (const float*)s, srcBatch,
+                         srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad);
+    else
+      hipLaunchKernelGGL(cs::transpose_in_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)s,
+                         srcBatch, srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad);
+  }
+}
+
+// src[cols][srcPitch] fp32 -> dst[rows][cols] (pitch dstPitch), optionally accumulating.
+void launch_transpose_out(int dtype, bool acc, const float* src, int64_t srcPitch, int rows, int cols,
+                          void* dst, int64_t dstPitch, hipStream_t st) {
+  const dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  if (dtype == CONV_F32) {
+    if (acc)
+      hipLaunchKernelGGL((cs::transpose_out_kernel<float, true>), grid, dim3(256), 0, st, src, srcPitch, rows,
+                         cols, (float*)dst, dstPitch);
+    else
+      hipLaunchKernelGGL((cs::transpose_out_kernel<float, false>), grid, dim3(256), 0, st, src, srcPitch, rows,
+                         cols, (float*)dst, dstPitch);
+  } else {
+    if (acc)
+      hipLaunchKernelGGL((cs::transpose_out_kernel<uint16_t, true>), grid, dim3(256), 0, st, src, srcPitch,
+                         rows, cols, (uint16_t*)dst, dstPitch);
+    else
+      hipLaunchKernelGGL((cs::transpose_out_kernel<uint16_t, false>), grid, dim3(256), 0, st, src, srcPitch,
+                         rows, cols, (uint16_t*)dst, dstPitch);
+  }
+}
+
+inline size_t elem_size(int dtype) { return dtype == CONV_F32 ? 4 : 2; }
+
+int check_ws(const void* ws, size_t ws_bytes, size_t need) {
+  if (need == 0) return CONV_OK;
+  if (!ws || ws_bytes < need || misaligned(ws, 256)) return CONV_ERR_WORKSPACE;
+  return CONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_output_dims(const conv_desc_t* desc, int32_t* P, int32_t* Q) {
+  if (!desc || !P || !Q) return CONV_ERR_NULL;
+  Geo g;
+  const int rc = make_geo(desc, g);
+  if (rc != CONV_OK) return rc;
+  *P = g.P;
+  *Q = g.Q;
+  return CONV_OK;
+}
+
+size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
+  Geo g;
+  if (make_geo(desc, g) != CONV_OK) return 0;
+  if (g.Ks == 0) return 0;
+  switch (pass) {
+    case CONV_PASS_FWD: return plan_fwd(g, desc->dtype).total;
+    case CONV_PASS_BWD_DATA: return plan_bwd_data(g).total;
+    case CONV_PASS_BWD_WEIGHT: return plan_bwd_weight(g).total;
+    default: return 0;
+  }
+}
+
+int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+             void* hip_stream) {
+  Geo g;
+  int rc = make_geo(desc, g);
+  if (rc != CONV_OK) return rc;
+  if (!x || !w || !y) return CONV_ERR_NULL;
+  if (misaligned(x, 16) || misaligned(w, 16) || misaligned(y, 16)) return CONV_ERR_ALIGN;
+  if (g.Ks == 0) return CONV_OK;
+  const FwdPlan p = plan_fwd(g, desc->dtype);
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* base = (char*)ws;
+  float* xt = (float*)(base + p.off_xt);
+  float* yt = (float*)(base + p.off_yt);
+  int2* tab = (int2*)(base + p.off_tab);
+  const size_t es = elem_size(desc->dtype);
+
+  // x[N][C*H*W] -> x_t[C*H*W][Np]
+  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, st);
+  const int entries = p.nch * cs::BK;
+  hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
+  const float* wmat;
+  if (p.repitch) {
+    float* wp = (float*)(base + p.off_w);
+    const int blocks = (int)((((int64_t)g.Ks * p.ldw + 255) / 256 < 4096) ? ((int64_t)g.Ks * p.ldw + 255) / 256 : 4096);
+    const char* wsrc = (const char*)w + (size_t)g.k0 * g.CRS * es;
+    if (desc->dtype == CONV_F32)
+      hipLaunchKernelGGL(cs::repitch_rows_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)wsrc,
+                         (int64_t)g.CRS, g.Ks, g.CRS, wp, p.ldw);
+    else
+      hipLaunchKernelGGL(cs::repitch_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st,
+                         (const uint16_t*)wsrc, (int64_t)g.CRS, g.Ks, g.CRS, wp, p.ldw);
+    wmat = wp;
+  } else {
+    wmat = (const float*)w + (size_t)g.k0 * g.CRS;
+  }
+  if ((rc = allow_big_lds(cs::fwd_gemm_kernel)) != CONV_OK) return rc;
+  const int MB = (g.Ks + cs::BM - 1) / cs::BM;
+  const int CT = (g.PQ * g.NB + 3) / 4;
+  hipLaunchKernelGGL(cs::fwd_gemm_kernel, dim3(cs::grid_for_tiles(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
+                     wmat, p.ldw, p.ldw, xt, tab, yt, MB, CT, p.nch);
+  // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
+  launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
+                       (char*)y + (size_t)g.k0 * g.PQ * es, (int64_t)g.K * g.PQ, st);
+  return check_launch();
+}
+
+int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+                  void* hip_stream) {
+  Geo g;
+  int rc = make_geo(desc, g);
+  if (rc != CONV_OK) return rc;
+  if (!dy || !w || !dx) return CONV_ERR_NULL;
+  if (misaligned(dy, 16) || misaligned(w, 16) || misaligned(dx, 16)) return CONV_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t es = elem_size(desc->dtype);
+  if (g.Ks == 0) {
+    if (!desc->accumulate) {
+      const int64_t count = (int64_t)g.N * g.C * g.HW;
+      const int blocks = (int)((count + 255) / 256 < 8192 ? (count + 255) / 256 : 8192);
+      if (desc->dtype == CONV_F32)
+        hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(blocks), dim3(256), 0, st, (float*)dx, count);
+      else
+        hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (uint16_t*)dx, count);
+      return check_launch();
+    }
+    return CONV_OK;
+  }
+  const BwdDataPlan p = plan_bwd_data(g);
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  char* base = (char*)ws;
+  float* dyt = (float*)(base + p.off_dyt);
+  float* wt = (float*)(base + p.off_wt);
+  float* dxt = (float*)(base + p.off_dxt);
+  int* perm = (int*)(base + p.off_perm);
+
+  // dy[n][k0*PQ ..] -> dy_t[Ks*P*Q][Np]
+  launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
+                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, st);
+  // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed
+  launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
+                      (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, st);
+  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
+  if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel)) != CONV_OK) return rc;
+  const int MB = (g.C + cs::BM - 1) / cs::BM;
+  const int CT = (g.HW * g.NB + 3) / 4;
+  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_for_tiles(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st,
+                     g, wt, p.Cp, dyt, perm, dxt, MB, CT);
+  // dx_t[C*H*W][Np] -> dx[N][C*H*W]
+  launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
+  return check_launch();
+}
+
+int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
+                    void* hip_stream) {
+  Geo g;
+  int rc = make_geo(desc, g);
+  if (rc != CONV_OK) return rc;
+  if (!x || !dy || !dw) return CONV_ERR_NULL;
+  if (misaligned(x, 16) || misaligned(dy, 16) || misaligned(dw, 16)) return CONV_ERR_ALIGN;
+  if (g.Ks == 0) return CONV_OK;
+  const BwdWeightPlan p = plan_bwd_weight(g);
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t es = elem_size(desc->dtype);
+  char* base = (char*)ws;
+  float* xt = (float*)(base + p.off_xt);
+  float* dyt = (float*)(base + p.off_dyt);
+  float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
+
+  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, st);
+  launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
+                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, st);
+  if ((rc = allow_big_lds(cs::bwd_weight_gemm_kernel)) != CONV_OK) return rc;
+  const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
+  float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
+  hipLaunchKernelGGL(cs::bwd_weight_gemm_kernel, dim3(cs::grid_for_tiles(p.MB, p.CT), p.splits), dim3(cs::NT),
+                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
+  if (p.splits > 1) {
+    const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);
+    hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, out, sliceElems, p.splits,
+                       dwslice, sliceElems);
+  }
+  return check_launch();
+}
+
+const char* conv_status_string(int status) {
+  switch (status) {
+    case CONV_OK: return "ok";
+    case CONV_ERR_NULL: return "a required pointer is NULL";
+    case CONV_ERR_SHAPE: return "invalid or unsupported tensor shape";
+    case CONV_ERR_SLICE: return "kernel slice must satisfy 0 <= k0 <= k1 <= K";
+    case CONV_ERR_DTYPE: return "unknown dtype";
+    case CONV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case CONV_ERR_LAUNCH: return "HIP launch failed";
+    case CONV_ERR_ALIGN: return "tensor pointer is not 16-byte aligned";
+    case CONV_ERR_PASS: return "unknown pass";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

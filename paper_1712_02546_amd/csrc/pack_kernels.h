@@ -1,0 +1,161 @@
+// Layout kernels around the matrix-core passes: tiled transposes between the
+// caller's NCHW / KCRS tensors and the batch-innermost work copies, plus the
+// small set-up kernels (filter-tap table, pixel ordering, fills, reductions).
+#pragma once
+#include "conv_common.h"
+
+namespace cs {
+
+// dst[b*dstBatch + l*dstPitch + n] = n < rows ? src[b*srcBatch + n*srcPitch + l] : 0
+// for 0 <= l < cols, 0 <= n < rowsPad.  64x64 tiles through LDS, both sides coalesced.
+// grid = (ceil(cols/64), ceil(rowsPad/64), batch).
+template <typename Tin>
+__global__ __launch_bounds__(256) void transpose_in_kernel(
+    const Tin* __restrict__ src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
+    float* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad) {
+  __shared__ float tile[64][65];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  src += (int64_t)blockIdx.z * srcBatch;
+  dst += (int64_t)blockIdx.z * dstBatch;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int nn = ty + 4 * i;
+    const int n = n0 + nn, l = l0 + tx;
+    float v = 0.f;
+    if (n < rows && l < cols) v = load_as_f32<Tin>(src + (int64_t)n * srcPitch + l);
+    tile[nn][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int ll = ty + 4 * i;
+    const int l = l0 + ll, n = n0 + tx;
+    if (l < cols && n < rowsPad) dst[(int64_t)l * dstPitch + n] = tile[tx][ll];
+  }
+}
+
+// dst[n*dstPitch + l] (+)= src[l*srcPitch + n] for 0 <= l < cols, 0 <= n < rows.
+// grid = (ceil(cols/64), ceil(rows/64)).
+template <typename Tout, bool ACC>
+__global__ __launch_bounds__(256) void transpose_out_kernel(
+    const float* __restrict__ src, int64_t srcPitch, int rows, int cols,
+    Tout* __restrict__ dst, int64_t dstPitch) {
+  __shared__ float tile[64][65];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int ll = ty + 4 * i;
+    const int l = l0 + ll, n = n0 + tx;
+    float v = 0.f;
+    if (l < cols && n < rows) v = src[(int64_t)l * srcPitch + n];
+    tile[ll][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int nn = ty + 4 * i;
+    const int n = n0 + nn, l = l0 + tx;
+    if (n < rows && l < cols) {
+      Tout* p = dst + (int64_t)n * dstPitch + l;
+      float v = tile[tx][nn];
+      if (ACC) v += load_as_f32<Tout>(p);
+      store_from_f32<Tout>(p, v);
+    }
+  }
+}
+
+// dst[r*dstPitch + c] = c < cols ? src[r*srcPitch + c] : 0 for c < dstPitch: rows of
+// the filter matrix converted to fp32 and re-pitched to a multiple of 4.
+template <typename Tin>
+__global__ __launch_bounds__(256) void repitch_rows_kernel(
+    const Tin* __restrict__ src, int64_t srcPitch, int rows, int cols,
+    float* __restrict__ dst, int dstPitch) {
+  const int64_t total = (int64_t)rows * dstPitch;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / dstPitch), c = (int)(i - (int64_t)r * dstPitch);
+    dst[i] = c < cols ? load_as_f32<Tin>(src + (int64_t)r * srcPitch + c) : 0.f;
+  }
+}
+
+// Forward pass: for reduction index kk = (c,r,s) the offset of that tap inside
+// x_t relative to a pixel's window origin, and (r,s) for the padding test.
+// Entries past C*R*S are marked invalid (y < 0).
+__global__ void fwd_tap_table_kernel(Geo g, int entries, int2* __restrict__ tab) {
+  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kk >= entries) return;
+  int2 e;
+  if (kk < g.CRS) {
+    const int c = kk / g.RS, rs = kk - c * g.RS;
+    const int r = rs / g.S, s = rs - r * g.S;
+    e.x = (c * g.HW + r * g.W + s) * g.Np;
+    e.y = (r << 16) | s;
+  } else {
+    e.x = 0;
+    e.y = -1;
+  }
+  tab[kk] = e;
+}
+
+// Input-gradient pass: number of filter taps that reach input pixel (h,v).
+__device__ __forceinline__ int taps_reaching(const Geo& g, int h, int v) {
+  int nr = 0, ns = 0;
+  for (int r = 0; r < g.R; ++r) {
+    const int hr = h + g.ph - r;
+    if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) ++nr;
+  }
+  for (int s = 0; s < g.S; ++s) {
+    const int vs = v + g.pw - s;
+    if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) ++ns;
+  }
+  return nr * ns;
+}
+
+// Orders the H*W input pixels by decreasing tap count (counting sort, one
+// workgroup), so that the heaviest tiles of the input-gradient pass are
+// dispatched first.  The order among equal counts is arbitrary; it only decides
+// where a tile runs, never what it computes.  perm has H*W entries.
+__global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm) {
+  __shared__ int bins[1026];
+  const int nb = g.RS + 1;
+  for (int i = threadIdx.x; i <= nb; i += blockDim.x) bins[i] = 0;
+  __syncthreads();
+  for (int px = threadIdx.x; px < g.HW; px += blockDim.x)
+    atomicAdd(&bins[taps_reaching(g, px / g.W, px % g.W)], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int wgt = g.RS; wgt >= 0; --wgt) {
+      const int cnt = bins[wgt];
+      bins[wgt] = run;
+      run += cnt;
+    }
+  }
+  __syncthreads();
+  for (int px = threadIdx.x; px < g.HW; px += blockDim.x) {
+    const int pos = atomicAdd(&bins[taps_reaching(g, px / g.W, px % g.W)], 1);
+    perm[pos] = px;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void fill_zero_kernel(T* __restrict__ p, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+       i += (int64_t)gridDim.x * blockDim.x)
+    p[i] = (T)0;
+}
+
+// dw[i] = sum_z part[z*stride + i], summed in increasing z (bit-stable).
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(
+    const float* __restrict__ part, int64_t stride, int splits, float* __restrict__ dw, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float acc = part[i];
+    for (int z = 1; z < splits; ++z) acc += part[(int64_t)z * stride + i];
+    dw[i] = acc;
+  }
+}
+
+}  // namespace cs

@@ -1,0 +1,107 @@
+"""The C-ABI library loads, exports what include/convslice.h declares, and rejects bad
+arguments before touching the GPU (none of these calls launches anything)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1712_02546_amd as cs
+from paper_1712_02546_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "convslice.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = cs.load()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    for code in range(-8, 1):
+        assert cs.status_string(code)
+    assert cs.status_string(0) == "ok"
+    assert "unknown" in cs.status_string(-99)
+
+
+GOOD = dict(N=8, C=3, H=32, W=32, K=16, R=5, S=5)
+
+
+def test_output_dims_and_workspace_query():
+    assert cs.conv_output_dims(cs.ConvDesc(**GOOD)) == (28, 28)
+    assert cs.conv_output_dims(cs.ConvDesc(64, 3, 224, 224, 96, 11, 11, 4, 4, 2, 2)) == (55, 55)
+    assert cs.conv_output_dims(cs.ConvDesc(1, 1, 34, 34, 1, 5, 5, 4, 4)) == (8, 8)
+    for p in (cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT):
+        assert cs.conv_workspace_bytes(cs.ConvDesc(**GOOD), p) > 0
+        assert cs.conv_workspace_bytes(cs.ConvDesc(**GOOD, k0=3, k1=3), p) == 0
+    assert cs.conv_workspace_bytes(cs.ConvDesc(**GOOD), 7) == 0
+
+
+class FakeBuf:
+    """Stands in for a device tensor: the calls below must fail before using it."""
+
+    def __init__(self, ptr, nbytes=1 << 20):
+        self._p, self._n = ptr, nbytes
+
+    def data_ptr(self):
+        return self._p
+
+    def numel(self):
+        return self._n
+
+    def element_size(self):
+        return 1
+
+
+A = FakeBuf(0x10000)
+WS = FakeBuf(0x20000, 1 << 30)
+
+
+@pytest.mark.parametrize("fn", [cs.conv_fwd, cs.conv_bwd_data, cs.conv_bwd_weight])
+@pytest.mark.parametrize("bad,code", [
+    (dict(N=0), -2), (dict(C=-1), -2), (dict(R=33, S=33), -2), (dict(H=4), -2), (dict(stride_h=0), -2),
+    (dict(pad_w=-1), -2), (dict(k0=-1), -3), (dict(k1=17), -3), (dict(k0=5, k1=4), -3), (dict(dtype=2), -4),
+    (dict(N=1 << 20, C=1 << 10), -2),
+])
+def test_bad_descriptors_are_rejected(fn, bad, code):
+    d = cs.ConvDesc(**{**GOOD, **bad})
+    assert fn(d, A, A, A, WS, stream=0, raw_status=True) == code
+
+
+@pytest.mark.parametrize("fn", [cs.conv_fwd, cs.conv_bwd_data, cs.conv_bwd_weight])
+def test_null_misaligned_and_workspace_errors(fn):
+    d = cs.ConvDesc(**GOOD)
+    assert fn(d, None, A, A, WS, stream=0, raw_status=True) == -1
+    assert fn(d, A, None, A, WS, stream=0, raw_status=True) == -1
+    assert fn(d, A, A, None, WS, stream=0, raw_status=True) == -1
+    assert fn(d, FakeBuf(0x10004), A, A, WS, stream=0, raw_status=True) == -7
+    assert fn(d, A, A, A, None, stream=0, raw_status=True) == -5
+    assert fn(d, A, A, A, FakeBuf(0x20000, 16), stream=0, raw_status=True) == -5
+    assert fn(d, A, A, A, FakeBuf(0x20010, 1 << 30), stream=0, raw_status=True) == -5
+    with pytest.raises(cs.ConvError):
+        fn(d, None, A, A, WS, stream=0)
+
+
+def test_null_descriptor():
+    lib = cs.load()
+    assert lib.conv_fwd(None, 1, 1, 1, 1, 0, None) == -1
+    assert lib.conv_workspace_bytes(None, 0) == 0
+    p = ctypes.c_int32()
+    assert lib.conv_output_dims(None, ctypes.byref(p), ctypes.byref(p)) == -1
+
+
+def test_empty_slice_needs_no_workspace_for_fwd_and_bwd_weight():
+    d = cs.ConvDesc(**GOOD, k0=4, k1=4)
+    assert cs.conv_fwd(d, A, A, A, None, stream=0, raw_status=True) == 0
+    assert cs.conv_bwd_weight(d, A, A, A, None, stream=0, raw_status=True) == 0
+    da = cs.ConvDesc(**GOOD, k0=4, k1=4, accumulate=1)
+    assert cs.conv_bwd_data(da, A, A, A, None, stream=0, raw_status=True) == 0

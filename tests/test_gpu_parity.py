@@ -1,0 +1,178 @@
+"""HIP path vs CPU oracle, element by element, on the same seeded inputs (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1712_02546_amd as cs
+from paper_1712_02546_amd import synth
+
+from helpers import BF16_TOL, FP32_TOL, Device, oracle_shape, rel_err, sample_indices
+
+pytestmark = pytest.mark.gpu
+
+# Small enough for the full oracle in seconds, large enough for several 128-wide tiles,
+# ragged tails in every GEMM dimension, batches that are not multiples of 32, strides,
+# padding, rectangular filters and interior slices.
+ADHOC = [
+    synth.random_layer(1, N=40, C=37, H=13, W=11, K=150, R=3, S=5),
+    synth.random_layer(2, N=40, C=37, H=13, W=11, K=150, R=3, S=5, stride=2, pad=2, k0=7, k1=141),
+    synth.random_layer(3, N=5, C=8, H=9, W=9, K=12, R=3, S=3, pad=1),
+    synth.random_layer(4, N=130, C=140, H=8, W=8, K=20, R=3, S=3, pad=1, k0=3, k1=20),
+    synth.random_layer(5, N=33, C=3, H=23, W=19, K=70, R=7, S=4, stride=3, pad=3),
+    synth.random_layer(6, N=64, C=16, H=6, W=6, K=300, R=6, S=6, k0=100, k1=290),      # P = Q = 1
+    synth.random_layer(7, N=32, C=20, H=10, W=10, K=33, R=1, S=1),                    # 1x1
+    synth.random_layer(8, N=9, C=5, H=34, W=34, K=6, R=5, S=5, stride=4),             # unread last row/col
+    synth.random_layer(9, N=1, C=1, H=5, W=5, K=1, R=2, S=2),
+]
+
+
+def check(got, ref, tol, what):
+    e = rel_err(got, ref)
+    assert e <= tol, f"{what}: max rel err {e:.3e} > {tol:.1e}"
+
+
+@pytest.mark.parametrize("cfg", ADHOC + [synth.CONFIGS["cfg1"]], ids=lambda c: c.name)
+def test_full_tensors_match_oracle_fp32(cfg):
+    x, w, dy = synth.make_inputs(cfg)
+    sh = oracle_shape(cfg)
+    k0, k1 = cfg.slice
+    dev = Device(cfg, x, w, dy)
+    y = dev.fwd(fill=7.0)
+    y_ref = oracle.conv_fwd(sh, x, w)
+    check(y[:, k0:k1], y_ref[:, k0:k1], FP32_TOL, "y")
+    assert np.all(y[:, :k0] == 7.0) and np.all(y[:, k1:] == 7.0), "channels outside the slice were written"
+    dx = dev.bwd_data()
+    check(dx, oracle.conv_bwd_data(sh, dy, w), FP32_TOL, "dx")
+    dw = dev.bwd_weight(fill=7.0)
+    dw_ref = oracle.conv_bwd_weight(sh, x, dy)
+    check(dw[k0:k1], dw_ref[k0:k1], FP32_TOL, "dw")
+    assert np.all(dw[:k0] == 7.0) and np.all(dw[k1:] == 7.0), "filters outside the slice were written"
+
+
+@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], synth.CONFIGS["cfg1"]], ids=lambda c: c.name)
+def test_full_tensors_match_oracle_bf16(cfg):
+    x, w, dy = (synth.round_to_bf16(a) for a in synth.make_inputs(cfg))
+    sh = oracle_shape(cfg)
+    k0, k1 = cfg.slice
+    dev = Device(cfg, x, w, dy, dtype=cs.CONV_BF16)
+    check(dev.fwd()[:, k0:k1], oracle.conv_fwd(sh, x, w)[:, k0:k1], BF16_TOL, "y")
+    check(dev.bwd_data(), oracle.conv_bwd_data(sh, dy, w), BF16_TOL, "dx")
+    # dw is stored in fp32, so it is held to the fp32 tolerance on the rounded inputs
+    check(dev.bwd_weight()[k0:k1], oracle.conv_bwd_weight(sh, x, dy)[k0:k1], FP32_TOL, "dw")
+
+
+def test_disjoint_slices_assemble_the_full_layer():
+    """Same inputs, different kernels per device, outputs side by side (Section 4.1.2):
+    slice calls into one y / dw give the full result; dx partial sums add up."""
+    import torch
+    cfg = synth.random_layer(20, N=36, C=24, H=12, W=12, K=200, R=5, S=5, pad=1)
+    x, w, dy = synth.make_inputs(cfg)
+    full = Device(cfg, x, w, dy)
+    y_full, dw_full, dx_full = full.fwd(), full.bwd_weight(), full.bwd_data()
+    y = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), device="cuda:0")
+    dw = torch.zeros((cfg.K, cfg.C, cfg.R, cfg.S), device="cuda:0")
+    dx = torch.empty((cfg.N, cfg.C, cfg.H, cfg.W), device="cuda:0")
+    cuts = [0, 37, 37, 128, 200]
+    from helpers import desc_of
+    for i, (k0, k1) in enumerate(zip(cuts[:-1], cuts[1:])):
+        part = cfg.with_slice(k0, k1)
+        cs.conv_fwd(desc_of(part), full.x, full.w, y, full.ws)
+        cs.conv_bwd_weight(desc_of(part), full.x, full.dy, dw, full.ws)
+        cs.conv_bwd_data(desc_of(part, accumulate=int(i > 0)), full.dy, full.w, dx, full.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), y_full), "slice-assembled y differs from the full-layer y"
+    check(dw.cpu().numpy(), dw_full, 1e-5, "dw assembled")
+    check(dx.cpu().numpy(), dx_full, 1e-5, "dx summed")
+    check(dx.cpu().numpy(), oracle.conv_bwd_data(oracle_shape(cfg), dy, w), FP32_TOL, "dx vs oracle")
+
+
+def test_empty_slice_and_accumulate():
+    cfg = synth.random_layer(21, N=7, C=6, H=9, W=9, K=10, R=3, S=3, k0=4, k1=4)
+    x, w, dy = synth.make_inputs(cfg)
+    dev = Device(cfg, x, w, dy)
+    assert np.all(dev.fwd(fill=3.0) == 3.0)
+    assert np.all(dev.bwd_weight(fill=3.0) == 3.0)
+    assert not dev.bwd_data().any()
+    init = np.full((cfg.N, cfg.C, cfg.H, cfg.W), 2.5, np.float32)
+    assert np.all(dev.bwd_data(accumulate=1, init=init) == 2.5)
+    cfg2 = cfg.with_slice(2, 9)
+    dev2 = Device(cfg2, x, w, dy)
+    ref = oracle.conv_bwd_data(oracle_shape(cfg2), dy, w)
+    check(dev2.bwd_data(accumulate=1, init=init), ref + 2.5, FP32_TOL, "dx accumulate")
+
+
+def test_results_are_bit_stable_run_to_run():
+    cfg = ADHOC[1]
+    x, w, dy = synth.make_inputs(cfg)
+    dev = Device(cfg, x, w, dy)
+    a = (dev.fwd(fill=0.0), dev.bwd_data(), dev.bwd_weight(fill=0.0))
+    b = (dev.fwd(fill=0.0), dev.bwd_data(), dev.bwd_weight(fill=0.0))
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+# ------------------------------------------------ full benchmark sizes, sampled outputs
+SAMPLED = ["cfg2", "cfg3", "cfg4", "cfg5a", "cfg5b"]
+
+
+def _sampled(cfg, dtype, tol, n=1500):
+    x, w, dy = synth.make_inputs(cfg)
+    if dtype == cs.CONV_BF16:
+        x, w, dy = (synth.round_to_bf16(a) for a in (x, w, dy))
+    sh = oracle_shape(cfg)
+    k0, k1 = cfg.slice
+    dev = Device(cfg, x, w, dy, dtype=dtype)
+    # forward: sample inside the slice
+    y = dev.fwd(fill=5.0)
+    ysl = y[:, k0:k1]
+    idx = sample_indices(ysl.size, n, 1)
+    nn, kk, pp, qq = np.unravel_index(idx, ysl.shape)
+    flat = np.ravel_multi_index((nn, kk + k0, pp, qq), y.shape)
+    ref = oracle.conv_fwd_at(sh, x, w, flat)
+    scale = float(np.sqrt(np.mean(ref * ref)))
+    err = np.max(np.abs(y.ravel()[flat] - ref) / np.maximum(np.abs(ref), scale))
+    assert err <= tol, f"y sampled: {err:.3e}"
+    if k0 > 0 or k1 < cfg.K:
+        assert np.all(y[:, :k0] == 5.0) and np.all(y[:, k1:] == 5.0)
+    del y, ysl
+    dx = dev.bwd_data()
+    idx = sample_indices(dx.size, n, 2)
+    ref = oracle.conv_bwd_data_at(sh, dy, w, idx)
+    scale = float(np.sqrt(np.mean(ref * ref)))
+    err = np.max(np.abs(dx.ravel()[idx] - ref) / np.maximum(np.abs(ref), scale))
+    assert err <= tol, f"dx sampled: {err:.3e}"
+    del dx
+    dw = dev.bwd_weight(fill=5.0)
+    dwsl = dw[k0:k1]
+    idx = sample_indices(dwsl.size, n, 3)
+    flat = idx + k0 * cfg.C * cfg.R * cfg.S
+    ref = oracle.conv_bwd_weight_at(sh, x, dy, flat)
+    scale = float(np.sqrt(np.mean(ref * ref)))
+    err = np.max(np.abs(dw.ravel()[flat] - ref) / np.maximum(np.abs(ref), scale))
+    assert err <= (tol if dtype == cs.CONV_F32 else FP32_TOL), f"dw sampled: {err:.3e}"
+    if k0 > 0 or k1 < cfg.K:
+        assert np.all(dw[:k0] == 5.0) and np.all(dw[k1:] == 5.0)
+
+
+@pytest.mark.parametrize("name", SAMPLED)
+def test_benchmark_configs_sampled_fp32(name):
+    _sampled(synth.CONFIGS[name], cs.CONV_F32, FP32_TOL)
+
+
+@pytest.mark.parametrize("name", ["cfg5a", "cfg5b"])
+def test_benchmark_configs_sampled_bf16(name):
+    _sampled(synth.CONFIGS[name], cs.CONV_BF16, BF16_TOL)
+
+
+def test_device_share_equals_slice_of_full_layer():
+    """cfg4 is kernels 500..999 of cfg3: its maps must be the same numbers as the
+    matching channels of the full-layer forward result."""
+    full, part = synth.CONFIGS["cfg3"], synth.CONFIGS["cfg4"]
+    x, w, dy = synth.make_inputs(full)
+    d_full = Device(full, x, w, dy)
+    y_full = d_full.fwd()
+    d_part = Device(part, None, None, None)
+    d_part.x, d_part.w, d_part.dy = d_full.x, d_full.w, d_full.dy
+    y_part = d_part.fwd(fill=0.0)
+    assert np.array_equal(y_part[:, 500:1000], y_full[:, 500:1000])
+    assert not y_part[:, :500].any() and not y_part[:, 1000:].any()
