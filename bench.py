@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the convolution hot path on one MI355X.
+
+One step = conv_fwd + conv_bwd_data + conv_bwd_weight through the C ABI on one batch of
+seeded synthetic tensors that are already resident in HBM.  Prints ONE JSON line:
+throughput in TFLOP/s on nominal FLOPs (3 * 2*N*Ks*P*Q*C*R*S per step), a roofline
+object for the slowest matrix-core kernel (timed live with HIP events placed around it by
+the library's one-shot probe), and the CPU oracle timed on a bounded sample of the same
+layer as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+# HBM bytes per launch of the slowest kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until such a run exists for the workload.
+TRAFFIC_BYTES = {}
+
+
+def find_hip_runtime():
+    """The libamdhip64 already mapped into this process (torch's and libconvslice's)."""
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                return ctypes.CDLL(line.split()[-1])
+    return ctypes.CDLL("libamdhip64.so")
+
+
+class HipEvents:
+    def __init__(self, count):
+        self.hip = find_hip_runtime()
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.ev = []
+        for _ in range(count):
+            e = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.ev.append(e)
+
+    def elapsed_ms(self, i, j):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.ev[i], self.ev[j])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def destroy(self):
+        for e in self.ev:
+            self.hip.hipEventDestroy(e)
+        self.ev = []
+
+
+def cpu_baseline(cfg, x, w, dy, images):
+    """The oracle as it stands on the first `images` images of the batch, all kernels of the slice."""
+    import oracle
+    k0, k1 = cfg.slice
+    n = min(images, cfg.N)
+    sh = oracle.Shape(n, cfg.C, cfg.H, cfg.W, cfg.K, cfg.R, cfg.S, cfg.stride, cfg.stride, cfg.pad, cfg.pad, k0, k1)
+    xs, dys = x[:n], dy[:n]
+    t0 = time.perf_counter()
+    oracle.conv_fwd(sh, xs, w)
+    oracle.conv_bwd_data(sh, dys, w)
+    oracle.conv_bwd_weight(sh, xs, dys)
+    dt = time.perf_counter() - t0
+    flops = 3 * 2 * n * (k1 - k0) * cfg.P * cfg.Q * cfg.C * cfg.R * cfg.S
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {n} of {cfg.N} images of {cfg.name}, all {k1 - k0} kernels of the slice, "
+                      f"fwd+bwd_data+bwd_weight, fp64 direct loops, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg3", help="cfg1..cfg5b (default: the 1500-kernel layer)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--cpu-images", type=int, default=8, help="images in the CPU-oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
+                 "(the kernel-slice argument is how the layer would be sharded across devices)")
+
+    import numpy as np
+    import torch
+
+    import paper_1712_02546_amd as cs
+    from paper_1712_02546_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cs.load()
+    cfg = synth.CONFIGS[args.config]
+    dtype = cs.CONV_F32 if args.dtype == "f32" else cs.CONV_BF16
+    k0, k1 = cfg.slice
+    x, w, dy = synth.make_inputs(cfg)
+    if dtype == cs.CONV_BF16:
+        x, w, dy = (synth.round_to_bf16(a) for a in (x, w, dy))
+    dev = torch.device("cuda:0")
+
+    def up(a):
+        if dtype == cs.CONV_BF16:
+            return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    xd, wd, dyd = up(x), up(w), up(dy)
+    tdt = torch.float32 if dtype == cs.CONV_F32 else torch.bfloat16
+    y = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=tdt, device=dev)
+    dx = torch.zeros((cfg.N, cfg.C, cfg.H, cfg.W), dtype=tdt, device=dev)
+    dw = torch.zeros((cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.float32, device=dev)
+    desc = cs.ConvDesc(cfg.N, cfg.C, cfg.H, cfg.W, cfg.K, cfg.R, cfg.S, cfg.stride, cfg.stride, cfg.pad, cfg.pad,
+                       k0, k1, dtype, 0)
+    ws = torch.empty(max(cs.conv_workspace_bytes(desc, p) for p in (0, 1, 2)), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    passes = (("conv_fwd", cs.conv_fwd, (xd, wd, y)),
+              ("conv_bwd_data", cs.conv_bwd_data, (dyd, wd, dx)),
+              ("conv_bwd_weight", cs.conv_bwd_weight, (xd, dyd, dw)))
+    kernel_names = {"conv_fwd": "fwd_gemm_kernel", "conv_bwd_data": "bwd_data_gemm_kernel",
+                    "conv_bwd_weight": "bwd_weight_gemm_kernel"}
+
+    def step(events=None, base=0):
+        for i, (_, fn, (a, b, out)) in enumerate(passes):
+            if events is not None:
+                cs.conv_probe_next_call(events.ev[base + 2 * i], events.ev[base + 2 * i + 1])
+            fn(desc, a, b, out, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    events = HipEvents(6 * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events, 6 * s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    F = cfg.flops_per_pass
+    value = 3 * F / (ms_per_step * 1e-3) / 1e12
+    kern = []
+    for i, (name, _, _) in enumerate(passes):
+        d = [events.elapsed_ms(6 * s + 2 * i, 6 * s + 2 * i + 1) for s in range(args.steps)]
+        avg = sum(d) / len(d)
+        kern.append({"entry": name, "kernel": kernel_names[name], "avg_ms": avg, "min_ms": min(d),
+                     "tflops": F / (avg * 1e-3) / 1e12})
+    events.destroy()
+    dom = max(kern, key=lambda k: k["avg_ms"])
+    peak = PEAK_TFLOPS[args.dtype]
+    roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s",
+                "frac": dom["tflops"] / peak, "avg_ms": dom["avg_ms"],
+                "traffic": TRAFFIC_BYTES.get((args.config, args.dtype, dom["kernel"]))}
+    out = {
+        "metric": "conv fwd+bwd TFLOP/s and % of MFMA peak, 1500-kernel 5x5 layer, batch 128",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: batch {cfg.N}, input {cfg.C}x{cfg.H}x{cfg.W}, {cfg.K} kernels "
+                               f"{cfg.R}x{cfg.S} stride {cfg.stride} pad {cfg.pad}, slice [{k0},{k1}), "
+                               "fwd + bwd_data + bwd_weight",
+                   "flops_per_step": 3 * F},
+        "frac_of_mfma_peak": value / peak,
+        "roofline": roofline,
+        "kernels": kern,
+    }
+    if args.cpu_images > 0:
+        out["cpu_baseline"] = cpu_baseline(cfg, x, w, dy, args.cpu_images)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -34,7 +34,7 @@
  * Execution.  Work is enqueued on hip_stream (a hipStream_t passed as void*,
  * NULL = default stream) and the call returns without synchronising.  The
  * library allocates no device memory and keeps no state between calls apart
- * from one-time kernel attribute set-up.
+ * from one-time kernel attribute set-up and the one-shot timing probe below.
  *
  * Errors.  Every entry point returns CONV_OK (0) or a negative conv_status_t.
  * All argument checks happen before the first launch; on an argument error
@@ -116,6 +116,18 @@ int conv_bwd_data(const conv_desc_t *desc, const void *dy, const void *w, void *
  */
 int conv_bwd_weight(const conv_desc_t *desc, const void *x, const void *dy, void *dw,
                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Measurement aid, not part of the method: arms a one-shot probe for the NEXT
+ * conv_fwd / conv_bwd_data / conv_bwd_weight call made by the calling host
+ * thread.  That call records start_event (a hipEvent_t passed as void*) on its
+ * stream right before its matrix-core kernel and stop_event right after it, so
+ * the kernel's duration can be read with hipEventElapsedTime once the stream
+ * has drained; the layout kernels around it are outside the bracket.  The probe
+ * is consumed by that call (also when it fails or has nothing to launch).
+ * Passing NULL for either event disarms it.  Always returns CONV_OK.
+ */
+int conv_probe_next_call(void *start_event, void *stop_event);
 
 /* Static, never-NULL description of a status code. */
 const char *conv_status_string(int status);

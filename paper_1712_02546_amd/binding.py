@@ -17,7 +17,7 @@ CONV_F32, CONV_BF16 = 0, 1
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_bwd_data",
-           "conv_bwd_weight", "conv_status_string")
+           "conv_bwd_weight", "conv_status_string", "conv_probe_next_call")
 
 
 class conv_desc_t(ctypes.Structure):
@@ -80,6 +80,8 @@ def load() -> ctypes.CDLL:
             f = getattr(lib, name)
             f.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
             f.restype = ctypes.c_int
+        lib.conv_probe_next_call.argtypes = [vp, vp]
+        lib.conv_probe_next_call.restype = ctypes.c_int
         lib.conv_status_string.argtypes = [ctypes.c_int]
         lib.conv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -88,6 +90,11 @@ def load() -> ctypes.CDLL:
 
 def status_string(status: int) -> str:
     return load().conv_status_string(int(status)).decode()
+
+
+def conv_probe_next_call(start_event, stop_event) -> int:
+    """Arm the one-shot matrix-core-kernel timing probe with two raw hipEvent_t handles (ints)."""
+    return int(load().conv_probe_next_call(start_event, stop_event))
 
 
 def conv_output_dims(desc: ConvDesc) -> tuple[int, int]:

@@ -77,6 +77,15 @@ static inline int grid_for_tiles(int MB, int CT) {
   return 8 * groups_per_xcd * 8 * MB;
 }
 
+__device__ __forceinline__ f32x4 masked(const f32x4& v, bool ok) {
+  f32x4 o;
+  o.x = ok ? v.x : 0.f;
+  o.y = ok ? v.y : 0.f;
+  o.z = ok ? v.z : 0.f;
+  o.w = ok ? v.w : 0.f;
+  return o;
+}
+
 // One staged chunk: 16 reduction steps of four 32x32x2 fp32 MFMAs per wavefront.
 // As/Bs are [BK][lda]/[BK][ldb] with the reduction index as the row.  In
 // v_mfma_f32_32x32x2_f32 lane l supplies A[row l%32][k l/32] and B[k l/32][col l%32].
@@ -85,16 +94,24 @@ __device__ __forceinline__ void mfma_chunk(const float* __restrict__ As, int lda
                                            int wm, int wn, int lane, f32x16 (&acc)[2][2]) {
   const float* ap = As + (lane >> 5) * lda + wm * 64 + (lane & 31);
   const float* bp = Bs + (lane >> 5) * ldb + wn * 64 + (lane & 31);
+  // Operands of step ks+1 are read from LDS before the MFMAs of step ks are issued.
+  float a0 = ap[0], a1 = ap[32], b0 = bp[0], b1 = bp[32];
 #pragma unroll
   for (int ks = 0; ks < BK / 2; ++ks) {
-    const float a0 = ap[2 * ks * lda];
-    const float a1 = ap[2 * ks * lda + 32];
-    const float b0 = bp[2 * ks * ldb];
-    const float b1 = bp[2 * ks * ldb + 32];
+    float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+    if (ks + 1 < BK / 2) {
+      na0 = ap[2 * (ks + 1) * lda];
+      na1 = ap[2 * (ks + 1) * lda + 32];
+      nb0 = bp[2 * (ks + 1) * ldb];
+      nb1 = bp[2 * (ks + 1) * ldb + 32];
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs they overlap with
     acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
     acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
     acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
     acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
   }
 }
 
@@ -107,28 +124,28 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  float* sA[2] = {smem, smem + STAGE};
-  float* sB[2] = {smem + 2 * STAGE, smem + 3 * STAGE};
+  // LDS map: [A buf0][A buf1][B buf0][B buf1]; offsets (not pointers) select the
+  // buffer so that every access stays a plain LDS instruction.
   if (ch_begin >= ch_end) return;
   la.load(ch_begin);
   lb.load(ch_begin);
-  la.store(sA[0]);
-  lb.store(sB[0]);
+  la.store(smem);
+  lb.store(smem + 2 * STAGE);
   __syncthreads();
-  int buf = 0;
+  int cur = 0;
   for (int ch = ch_begin; ch < ch_end; ++ch) {
     const bool more = ch + 1 < ch_end;
     if (more) {
       la.load(ch + 1);
       lb.load(ch + 1);
     }
-    mfma_chunk(sA[buf], LA::LD, sB[buf], LB::LD, wm, wn, lane, acc);
+    mfma_chunk(smem + cur, LA::LD, smem + 2 * STAGE + cur, LB::LD, wm, wn, lane, acc);
+    cur ^= STAGE;
     if (more) {
-      la.store(sA[buf ^ 1]);
-      lb.store(sB[buf ^ 1]);
+      la.store(smem + cur);
+      lb.store(smem + 2 * STAGE + cur);
     }
     __syncthreads();
-    buf ^= 1;
   }
 }
 

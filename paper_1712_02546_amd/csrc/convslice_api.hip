@@ -54,7 +54,7 @@ inline size_t seg(int64_t floats) { return (size_t)round_up(floats * 4, 256); }
 struct FwdPlan {
   bool repitch;      // filters copied to fp32 rows of pitch ldw (bf16 input or C*R*S not a multiple of 4)
   int ldw, nch;
-  size_t off_xt, off_yt, off_tab, off_w, total;
+  size_t off_xt, off_yt, off_w, total;
 };
 
 FwdPlan plan_fwd(const Geo& g, int dtype) {
@@ -65,7 +65,6 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   size_t o = 0;
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
-  p.off_tab = o; o += seg((int64_t)p.nch * cs::BK * 2);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
   p.total = o;
   return p;
@@ -114,6 +113,17 @@ BwdWeightPlan plan_bwd_weight(const Geo& g) {
   p.total = o;
   return p;
 }
+
+// One-shot timing probe, per host thread (see conv_probe_next_call).
+thread_local hipEvent_t tl_probe_start = nullptr;
+thread_local hipEvent_t tl_probe_stop = nullptr;
+
+struct Probe {
+  hipEvent_t start, stop;
+  Probe() : start(tl_probe_start), stop(tl_probe_stop) { tl_probe_start = tl_probe_stop = nullptr; }
+  void begin(hipStream_t st) const { if (start && stop) (void)hipEventRecord(start, st); }
+  void end(hipStream_t st) const { if (start && stop) (void)hipEventRecord(stop, st); }
+};
 
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
@@ -201,6 +211,7 @@ size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
 
 int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
              void* hip_stream) {
+  const Probe probe;
   Geo g;
   int rc = make_geo(desc, g);
   if (rc != CONV_OK) return rc;
@@ -213,13 +224,10 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   char* base = (char*)ws;
   float* xt = (float*)(base + p.off_xt);
   float* yt = (float*)(base + p.off_yt);
-  int2* tab = (int2*)(base + p.off_tab);
   const size_t es = elem_size(desc->dtype);
 
   // x[N][C*H*W] -> x_t[C*H*W][Np]
   launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, st);
-  const int entries = p.nch * cs::BK;
-  hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
   const float* wmat;
   if (p.repitch) {
     float* wp = (float*)(base + p.off_w);
@@ -238,8 +246,10 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   if ((rc = allow_big_lds(cs::fwd_gemm_kernel)) != CONV_OK) return rc;
   const int MB = (g.Ks + cs::BM - 1) / cs::BM;
   const int CT = (g.PQ * g.NB + 3) / 4;
+  probe.begin(st);
   hipLaunchKernelGGL(cs::fwd_gemm_kernel, dim3(cs::grid_for_tiles(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
-                     wmat, p.ldw, p.ldw, xt, tab, yt, MB, CT, p.nch);
+                     wmat, p.ldw, p.ldw, xt, yt, MB, CT, p.nch);
+  probe.end(st);
   // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
   launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
                        (char*)y + (size_t)g.k0 * g.PQ * es, (int64_t)g.K * g.PQ, st);
@@ -248,6 +258,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
 
 int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
                   void* hip_stream) {
+  const Probe probe;
   Geo g;
   int rc = make_geo(desc, g);
   if (rc != CONV_OK) return rc;
@@ -285,8 +296,10 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel)) != CONV_OK) return rc;
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
+  probe.begin(st);
   hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_for_tiles(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st,
                      g, wt, p.Cp, dyt, perm, dxt, MB, CT);
+  probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
   return check_launch();
@@ -294,6 +307,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
 
 int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
                     void* hip_stream) {
+  const Probe probe;
   Geo g;
   int rc = make_geo(desc, g);
   if (rc != CONV_OK) return rc;
@@ -315,14 +329,22 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   if ((rc = allow_big_lds(cs::bwd_weight_gemm_kernel)) != CONV_OK) return rc;
   const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
   float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
+  probe.begin(st);
   hipLaunchKernelGGL(cs::bwd_weight_gemm_kernel, dim3(cs::grid_for_tiles(p.MB, p.CT), p.splits), dim3(cs::NT),
                      cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
+  probe.end(st);
   if (p.splits > 1) {
     const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);
     hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, out, sliceElems, p.splits,
                        dwslice, sliceElems);
   }
   return check_launch();
+}
+
+int conv_probe_next_call(void* start_event, void* stop_event) {
+  tl_probe_start = (start_event && stop_event) ? (hipEvent_t)start_event : nullptr;
+  tl_probe_stop = (start_event && stop_event) ? (hipEvent_t)stop_event : nullptr;
+  return CONV_OK;
 }
 
 const char* conv_status_string(int status) {

@@ -19,6 +19,7 @@ struct FwdLoadA {
   bool rowok[4];
   int kq, cols;  // float offset of this thread's quad inside a chunk; valid row length
   f32x4 r[4];
+  bool okv[4];  // value mask, applied when the registers go to LDS
   __device__ FwdLoadA(const float* w, int ldw, int cols_, int m0, int Ks) {
     const int t = threadIdx.x;
     kq = 4 * (t & 7);
@@ -31,13 +32,14 @@ struct FwdLoadA {
     }
   }
   __device__ __forceinline__ void load(int ch) {
-    const int kk = ch * BK;
-    const bool kok = kk + kq < cols;
+    const bool kok = ch * BK + kq < cols;
+    const int kk = kok ? ch * BK : 0;  // keep the address inside the row; the value is masked below
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (kok && rowok[i]) v = *(const f32x4*)(base[i] + kk);
+      const f32x4 v = *(const f32x4*)(base[i] + kk);
+      const bool ok = kok && rowok[i];
       r[i] = v;
+      okv[i] = ok;
     }
   }
   __device__ __forceinline__ void store(float* s) const {
@@ -45,24 +47,28 @@ struct FwdLoadA {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float* d = s + kq * LD + (t >> 3) + 32 * i;
-      d[0] = r[i].x;
-      d[LD] = r[i].y;
-      d[2 * LD] = r[i].z;
-      d[3 * LD] = r[i].w;
+      const f32x4 v = masked(r[i], okv[i]);
+      d[0] = v.x;
+      d[LD] = v.y;
+      d[2 * LD] = v.z;
+      d[3 * LD] = v.w;
     }
   }
 };
 
 // B[kk][col] = x_t[tap kk of the column block's pixel][n], zero where the tap falls
-// into the padding.
+// into the padding.  Each thread walks its four reduction rows kk = (c,r,s) with
+// carry arithmetic (+32 per chunk), so no division or table sits in the loop.
 struct FwdLoadB {
   static constexpr int LD = LDV;
   const float* xt;
-  const int2* tab;
-  int base, h0, w0, H, W;
+  int base, h0, w0, H, W, C, R, S, HW, Np;
+  int dc, dr, ds;         // (c,r,s) increments of one chunk
+  int cc[4], rr[4], ss[4];
   bool cbok;
   f32x4 r[4];
-  __device__ FwdLoadB(const Geo& g, const float* xt_, const int2* tab_, int ct) : xt(xt_), tab(tab_) {
+  bool okv[4];  // value mask, applied when the registers go to LDS
+  __device__ FwdLoadB(const Geo& g, const float* xt_, int ct) : xt(xt_) {
     const int t = threadIdx.x;
     const int vcq = t & 31;
     const int gcb = ct * 4 + (vcq >> 3);
@@ -72,33 +78,48 @@ struct FwdLoadB {
     const int p = pix / g.Q, q = pix - p * g.Q;
     h0 = p * g.sh - g.ph;
     w0 = q * g.sw - g.pw;
-    H = g.H;
-    W = g.W;
-    base = (h0 * g.W + w0) * g.Np + nb * 32 + 4 * (vcq & 7);
-  }
-  __device__ __forceinline__ void load(int ch) {
-    const int t = threadIdx.x;
+    H = g.H; W = g.W; C = g.C; R = g.R; S = g.S; HW = g.HW; Np = g.Np;
+    base = nb * 32 + 4 * (vcq & 7);
+    dc = BK / g.RS;
+    const int rem = BK - dc * g.RS;
+    dr = rem / g.S;
+    ds = rem - dr * g.S;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int2 e = tab[ch * BK + (t >> 5) + 8 * i];
-      const int rr = e.y >> 16, ss = e.y & 0xffff;
-      const bool ok = cbok && e.y >= 0 && (unsigned)(h0 + rr) < (unsigned)H && (unsigned)(w0 + ss) < (unsigned)W;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (ok) v = *(const f32x4*)(xt + (base + e.x));
+      const int kk = (t >> 5) + 8 * i;
+      cc[i] = kk / g.RS;
+      const int rs = kk - cc[i] * g.RS;
+      rr[i] = rs / g.S;
+      ss[i] = rs - rr[i] * g.S;
+    }
+  }
+  __device__ __forceinline__ void load(int) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int hh = h0 + rr[i], vv = w0 + ss[i];
+      const bool ok = cbok && cc[i] < C && (unsigned)hh < (unsigned)H && (unsigned)vv < (unsigned)W;
+      const int off = ok ? (cc[i] * HW + hh * W + vv) * Np + base : 0;
+      const f32x4 v = *(const f32x4*)(xt + off);
       r[i] = v;
+      okv[i] = ok;
+      // advance (c,r,s) by one chunk
+      ss[i] += ds;
+      if (ss[i] >= S) { ss[i] -= S; rr[i] += 1; }
+      rr[i] += dr;
+      if (rr[i] >= R) { rr[i] -= R; cc[i] += 1; }
+      cc[i] += dc;
     }
   }
   __device__ __forceinline__ void store(float* s) const {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(f32x4*)(s + ((t >> 5) + 8 * i) * LD + 4 * (t & 31)) = r[i];
+    for (int i = 0; i < 4; ++i) *(f32x4*)(s + ((t >> 5) + 8 * i) * LD + 4 * (t & 31)) = masked(r[i], okv[i]);
   }
 };
 
 // y_t[k][pix][n] for the slice; one workgroup per 128 kernels x 4 column blocks.
 __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __restrict__ w, int ldw,
                                                       int wcols, const float* __restrict__ xt,
-                                                      const int2* __restrict__ tab,
                                                       float* __restrict__ yt, int MB, int CT, int nch) {
   extern __shared__ __align__(16) float smem[];
   int mb, ct;
@@ -112,7 +133,7 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   FwdLoadA la(w, ldw, wcols, m0, g.Ks);
-  FwdLoadB lb(g, xt, tab, ct);
+  FwdLoadB lb(g, xt, ct);
   gemm_mainloop(la, lb, 0, nch, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -143,6 +164,7 @@ struct BwdDataLoadA {
   int Ks, Cp, S, nkc, c, ti, kc;
   int64_t tapbase;
   f32x4 r[4];
+  bool okv[4];  // value mask, applied when the registers go to LDS
   __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_)
       : wt(wt_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), nkc(nkc_), ti(0), kc(0), tapbase(0) {
     c = m0 + 4 * (threadIdx.x & 31);
@@ -158,9 +180,10 @@ struct BwdDataLoadA {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int k = kc * BK + (t >> 5) + 8 * i;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (k < Ks && c < Cp) v = *(const f32x4*)(wt + tapbase + (int64_t)k * Cp + c);
+      const bool ok = k < Ks && c < Cp;
+      const f32x4 v = *(const f32x4*)(wt + (ok ? tapbase + (int64_t)k * Cp + c : 0));
       r[i] = v;
+      okv[i] = ok;
     }
     if (++kc == nkc) {
       kc = 0;
@@ -170,7 +193,7 @@ struct BwdDataLoadA {
   __device__ __forceinline__ void store(float* s) const {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(f32x4*)(s + ((t >> 5) + 8 * i) * LD + 4 * (t & 31)) = r[i];
+    for (int i = 0; i < 4; ++i) *(f32x4*)(s + ((t >> 5) + 8 * i) * LD + 4 * (t & 31)) = masked(r[i], okv[i]);
   }
 };
 
@@ -181,10 +204,11 @@ struct BwdDataLoadB {
   const float* dyt;
   const int* taps;
   int Ks, nkc, ti, kc;
-  int hp, vp, sh, sw, P, Q, PQNp, nboff;  // hp = h + pad_h, vp = v + pad_w of this thread's pixel
+  int hp, vp, sh, sw, P, Q, PQNp, nboff, Np_;  // hp = h + pad_h, vp = v + pad_w of this thread's pixel
   int off;
   bool cbok, tapok;
   f32x4 r[4];
+  bool okv[4];  // value mask, applied when the registers go to LDS
   __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* perm, int ct, const int* taps_, int nkc_)
       : dyt(dyt_), taps(taps_), Ks(g.Ks), nkc(nkc_), ti(0), kc(0), off(0), tapok(false) {
     const int vcq = threadIdx.x & 31;
@@ -203,7 +227,6 @@ struct BwdDataLoadB {
     nboff = nb * 32 + 4 * (vcq & 7);
     Np_ = g.Np;
   }
-  int Np_;
   __device__ __forceinline__ void set_tap() {
     const int e = taps[ti];
     const int hr = hp - (e >> 16), vs = vp - (e & 0xffff);
@@ -217,9 +240,10 @@ struct BwdDataLoadB {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int k = kc * BK + (t >> 5) + 8 * i;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (tapok && k < Ks) v = *(const f32x4*)(dyt + (int64_t)k * PQNp + off);
+      const bool ok = tapok && k < Ks;
+      const f32x4 v = *(const f32x4*)(dyt + (ok ? (int64_t)k * PQNp + off : 0));
       r[i] = v;
+      okv[i] = ok;
     }
     if (++kc == nkc) {
       kc = 0;
@@ -229,7 +253,7 @@ struct BwdDataLoadB {
   __device__ __forceinline__ void store(float* s) const {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(f32x4*)(s + ((t >> 5) + 8 * i) * LD + 4 * (t & 31)) = r[i];
+    for (int i = 0; i < 4; ++i) *(f32x4*)(s + ((t >> 5) + 8 * i) * LD + 4 * (t & 31)) = masked(r[i], okv[i]);
   }
 };
 
@@ -318,6 +342,7 @@ struct BwdWeightLoadA {
   const float* base[4];
   bool rowok[4];
   f32x4 r[4];
+  bool okv[4];  // value mask, applied when the registers go to LDS
   __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0) {
     const int t = threadIdx.x;
 #pragma unroll
@@ -330,9 +355,9 @@ struct BwdWeightLoadA {
   __device__ __forceinline__ void load(int ch) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (rowok[i]) v = *(const f32x4*)(base[i] + (int64_t)ch * BK);
+      const f32x4 v = *(const f32x4*)(base[i] + (int64_t)ch * BK);
       r[i] = v;
+      okv[i] = rowok[i];
     }
   }
   __device__ __forceinline__ void store(float* s) const {
@@ -340,10 +365,11 @@ struct BwdWeightLoadA {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float* d = s + 4 * (t & 7) * LD + (t >> 3) + 32 * i;
-      d[0] = r[i].x;
-      d[LD] = r[i].y;
-      d[2 * LD] = r[i].z;
-      d[3 * LD] = r[i].w;
+      const f32x4 v = masked(r[i], okv[i]);
+      d[0] = v.x;
+      d[LD] = v.y;
+      d[2 * LD] = v.z;
+      d[3 * LD] = v.w;
     }
   }
 };
@@ -356,6 +382,7 @@ struct BwdWeightLoadB {
   bool colok[4];
   int NB, Q, sh, sw, ph, pw, H, W, Np, nq;
   f32x4 r[4];
+  bool okv[4];  // value mask, applied when the registers go to LDS
   __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0) : xt(xt_) {
     const int t = threadIdx.x;
     NB = g.NB; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W; Np = g.Np;
@@ -378,10 +405,10 @@ struct BwdWeightLoadB {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int hh = h0 + rj[i], vv = v0 + sj[i];
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (colok[i] && (unsigned)hh < (unsigned)H && (unsigned)vv < (unsigned)W)
-        v = *(const f32x4*)(xt + (colbase[i] + (hh * W + vv) * Np + nb * 32 + nq));
+      const bool ok = colok[i] && (unsigned)hh < (unsigned)H && (unsigned)vv < (unsigned)W;
+      const f32x4 v = *(const f32x4*)(xt + (ok ? colbase[i] + (hh * W + vv) * Np + nb * 32 + nq : 0));
       r[i] = v;
+      okv[i] = ok;
     }
   }
   __device__ __forceinline__ void store(float* s) const {
@@ -389,10 +416,11 @@ struct BwdWeightLoadB {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float* d = s + nq * LD + (t >> 3) + 32 * i;
-      d[0] = r[i].x;
-      d[LD] = r[i].y;
-      d[2 * LD] = r[i].z;
-      d[3 * LD] = r[i].w;
+      const f32x4 v = masked(r[i], okv[i]);
+      d[0] = v.x;
+      d[LD] = v.y;
+      d[2 * LD] = v.z;
+      d[3 * LD] = v.w;
     }
   }
 };

@@ -1,6 +1,6 @@
 // Layout kernels around the matrix-core passes: tiled transposes between the
 // caller's NCHW / KCRS tensors and the batch-innermost work copies, plus the
-// small set-up kernels (filter-tap table, pixel ordering, fills, reductions).
+// small set-up kernels (pixel ordering, fills, reductions).
 #pragma once
 #include "conv_common.h"
 
@@ -78,25 +78,6 @@ __global__ __launch_bounds__(256) void repitch_rows_kernel(
     const int r = (int)(i / dstPitch), c = (int)(i - (int64_t)r * dstPitch);
     dst[i] = c < cols ? load_as_f32<Tin>(src + (int64_t)r * srcPitch + c) : 0.f;
   }
-}
-
-// Forward pass: for reduction index kk = (c,r,s) the offset of that tap inside
-// x_t relative to a pixel's window origin, and (r,s) for the padding test.
-// Entries past C*R*S are marked invalid (y < 0).
-__global__ void fwd_tap_table_kernel(Geo g, int entries, int2* __restrict__ tab) {
-  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
-  if (kk >= entries) return;
-  int2 e;
-  if (kk < g.CRS) {
-    const int c = kk / g.RS, rs = kk - c * g.RS;
-    const int r = rs / g.S, s = rs - r * g.S;
-    e.x = (c * g.HW + r * g.W + s) * g.Np;
-    e.y = (r << 16) | s;
-  } else {
-    e.x = 0;
-    e.y = -1;
-  }
-  tab[kk] = e;
 }
 
 // Input-gradient pass: number of filter taps that reach input pixel (h,v).
