@@ -11,7 +11,7 @@ import os
 from dataclasses import dataclass
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libconvslice.so")
+LIB_PATH = os.environ.get("CONVSLICE_LIB") or os.path.join(_HERE, "libconvslice.so")
 
 CONV_F32, CONV_BF16 = 0, 1
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2

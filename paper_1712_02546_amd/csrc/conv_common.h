@@ -55,27 +55,42 @@ template <> __device__ __forceinline__ void store_from_f32<float>(float* p, floa
 template <> __device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
 
 // Workgroup id -> (row tile mb, column tile ct).  Workgroups are dealt round-robin
-// to the 8 XCDs, each with its own L2.  Column tiles are taken in groups of 8; a
-// group and all MB row tiles against it stay on one XCD and are consecutive in
-// that XCD's dispatch order, so the tiles resident together share both operand
-// panels.  Returns false for the padding ids of a ragged last group.
-__device__ __forceinline__ bool tile_of_block(int g, int MB, int CT, int& mb, int& ct) {
-  const int xcd = g & 7;
+// to the 8 XCDs, each with its own L2, so id g runs on XCD g%8 as that XCD's
+// (g/8)-th workgroup.
+//
+// "Contiguous" map, for passes whose tiles all cost the same: tiles are put in a
+// line -- column tiles in groups of 8, all MB row tiles of a group together, so
+// that neighbours in the line share both operand panels -- and the line is cut
+// into 8 equal pieces, one per XCD.  Every XCD gets the same number of tiles
+// (+-1) and the tiles resident together on it are neighbours in the line.
+__device__ __forceinline__ bool tile_contiguous(int g, int MB, int CT, int& mb, int& ct) {
+  const int T = MB * CT;
+  const int per = (T + 7) >> 3;
   const int s = g >> 3;
-  const int per_group = 8 * MB;
-  const int gl = s / per_group;
-  const int rem = s - gl * per_group;
-  mb = rem >> 3;
-  ct = ((gl * 8 + xcd) << 3) + (rem & 7);
+  const int L = (g & 7) * per + s;
+  if (s >= per || L >= T) return false;
+  const int full = 8 * MB;                 // tiles in a full group
+  const int grp = L / full;
+  const int rem = L - grp * full;
+  const int gs = min(8, CT - 8 * grp);     // column tiles in this group (last may be ragged)
+  mb = rem / gs;
+  ct = 8 * grp + (rem - mb * gs);
+  return true;
+}
+static inline int grid_contiguous(int MB, int CT) { return 8 * ((MB * CT + 7) / 8); }
+
+// "Dealt" map, for the input-gradient pass whose column tiles are sorted by
+// decreasing cost: column tile ct goes to XCD ct%8 (so every XCD gets the same mix
+// of heavy and light tiles and starts with its heaviest), and the MB row tiles
+// that share its operand panel follow each other on that XCD.
+__device__ __forceinline__ bool tile_dealt(int g, int MB, int CT, int& mb, int& ct) {
+  const int s = g >> 3;
+  const int lc = s / MB;
+  mb = s - lc * MB;
+  ct = lc * 8 + (g & 7);
   return ct < CT;
 }
-
-// Host helper: grid size that covers every (mb, ct) under tile_of_block.
-static inline int grid_for_tiles(int MB, int CT) {
-  const int groups = (CT + 7) / 8;
-  const int groups_per_xcd = (groups + 7) / 8;
-  return 8 * groups_per_xcd * 8 * MB;
-}
+static inline int grid_dealt(int MB, int CT) { return 8 * ((CT + 7) / 8) * MB; }
 
 __device__ __forceinline__ f32x4 masked(const f32x4& v, bool ok) {
   f32x4 o;
@@ -133,19 +148,22 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   lb.store(smem + 2 * STAGE);
   __syncthreads();
   int cur = 0;
+#ifndef CS_EXP
+#define CS_EXP 0
+#endif
   for (int ch = ch_begin; ch < ch_end; ++ch) {
     const bool more = ch + 1 < ch_end;
-    if (more) {
+    if (more && !(CS_EXP & 1)) {
       la.load(ch + 1);
       lb.load(ch + 1);
     }
-    mfma_chunk(smem + cur, LA::LD, smem + 2 * STAGE + cur, LB::LD, wm, wn, lane, acc);
+    if (!(CS_EXP & 4)) mfma_chunk(smem + cur, LA::LD, smem + 2 * STAGE + cur, LB::LD, wm, wn, lane, acc);
     cur ^= STAGE;
-    if (more) {
+    if (more && !(CS_EXP & 1)) {
       la.store(smem + cur);
       lb.store(smem + 2 * STAGE + cur);
     }
-    __syncthreads();
+    if (!(CS_EXP & 2)) __syncthreads();
   }
 }
 

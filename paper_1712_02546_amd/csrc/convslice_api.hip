@@ -247,7 +247,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const int MB = (g.Ks + cs::BM - 1) / cs::BM;
   const int CT = (g.PQ * g.NB + 3) / 4;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::fwd_gemm_kernel, dim3(cs::grid_for_tiles(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
+  hipLaunchKernelGGL(cs::fwd_gemm_kernel, dim3(cs::grid_contiguous(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
                      wmat, p.ldw, p.ldw, xt, yt, MB, CT, p.nch);
   probe.end(st);
   // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
@@ -297,7 +297,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_for_tiles(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st,
+  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st,
                      g, wt, p.Cp, dyt, perm, dxt, MB, CT);
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
@@ -330,7 +330,7 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
   float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_weight_gemm_kernel, dim3(cs::grid_for_tiles(p.MB, p.CT), p.splits), dim3(cs::NT),
+  hipLaunchKernelGGL(cs::bwd_weight_gemm_kernel, dim3(cs::grid_contiguous(p.MB, p.CT), p.splits), dim3(cs::NT),
                      cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
   probe.end(st);
   if (p.splits > 1) {

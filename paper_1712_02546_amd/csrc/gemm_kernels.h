@@ -123,7 +123,7 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
                                                       float* __restrict__ yt, int MB, int CT, int nch) {
   extern __shared__ __align__(16) float smem[];
   int mb, ct;
-  if (!tile_of_block(blockIdx.x, MB, CT, mb, ct)) return;
+  if (!tile_contiguous(blockIdx.x, MB, CT, mb, ct)) return;
   const int m0 = mb * BM;
   f32x16 acc[2][2];
 #pragma unroll
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
   __shared__ int s_taps[1024];
   __shared__ int s_ntaps;
   int mb, ct;
-  if (!tile_of_block(blockIdx.x, MB, CT, mb, ct)) return;
+  if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
   const int m0 = mb * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
                                                              int MB, int CT, int nch, int chPerSplit) {
   extern __shared__ __align__(16) float smem[];
   int mb, ct;
-  if (!tile_of_block(blockIdx.x, MB, CT, mb, ct)) return;
+  if (!tile_contiguous(blockIdx.x, MB, CT, mb, ct)) return;
   const int m0 = mb * BM, j0 = ct * BN;
   const int z = blockIdx.y;
   const int ch0 = z * chPerSplit;
