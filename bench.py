@@ -88,7 +88,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg3", help="cfg1..cfg5b (default: the 1500-kernel layer)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--cpu-images", type=int, default=8, help="images in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-images", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
