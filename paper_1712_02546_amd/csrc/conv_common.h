@@ -21,10 +21,9 @@ constexpr int NT = 256;             // threads per workgroup: 4 wavefronts in a 
 constexpr int BM = 128;             // tile rows  (GEMM M)
 constexpr int BN = 128;             // tile cols  (GEMM N) = 4 column blocks of 32
 constexpr int BK = 32;              // reduction elements per staged chunk
-constexpr int LDT = 129;            // LDS row pitch for operands stored transposed (scalar stores)
-constexpr int LDV = 132;            // LDS row pitch for operands stored as float4 rows
-constexpr int STAGE = BK * LDV;     // floats per operand per buffer
-constexpr int SMEM_BYTES = 4 * STAGE * 4;  // A and B, double buffered
+constexpr int TILE_F = BM * BK;     // floats of one operand tile in LDS (16 KB)
+constexpr int SMEM_BYTES = 4 * TILE_F * 4;  // A and B, two stages each: 64 KB
+constexpr int ZERO_PAGE_FLOATS = 256;       // zero-filled scratch that masked lanes load from
 
 struct Geo {
   int N, Np, NB;                    // batch, padded batch, Np/32
@@ -92,78 +91,115 @@ __device__ __forceinline__ bool tile_dealt(int g, int MB, int CT, int& mb, int& 
 }
 static inline int grid_dealt(int MB, int CT) { return 8 * ((CT + 7) / 8) * MB; }
 
-__device__ __forceinline__ f32x4 masked(const f32x4& v, bool ok) {
-  f32x4 o;
-  o.x = ok ? v.x : 0.f;
-  o.y = ok ? v.y : 0.f;
-  o.z = ok ? v.z : 0.f;
-  o.w = ok ? v.w : 0.f;
-  return o;
+// ---------------------------------------------------------------------------
+// Staging.  Operand tiles go from global memory straight into LDS with the
+// gfx950 16-byte LDS-DMA load (global_load_lds_dwordx4): no staging registers,
+// no LDS store instructions.  One such instruction moves 64 x 16 bytes; lane l's
+// 16 bytes land at (wave-uniform LDS base) + 16*l, while each lane chooses its
+// own global address.  The LDS image of a tile is therefore fixed by lane order,
+// and a tile (128 x 32 floats = 1024 slots of 16 bytes) takes 16 wave-level
+// instructions: wavefront wv issues number i = 0..3 into slots
+// [(4*wv+i)*64, +64).  Two tile images are used:
+//
+//   row image  [kk][128]: reduction index kk is the row, 32 slots per row.
+//              slot = kk*32 + cq  ->  lane l of (wv,i) fetches row 8*wv+2*i+l/32,
+//              float columns 4*(l%32)..+3.  MFMA operands are read with 4-byte
+//              LDS reads along a row (conflict free).
+//   col image  [m][8 slots], XOR-swizzled: tile row m holds its 32 reduction
+//              elements as 8 slots, logical slot kq stored at position kq^(m&7).
+//              Lane l of (wv,i) fetches row 32*wv+8*i+l/8, logical slot
+//              (l%8)^(l/8).  MFMA operands are read with one 16-byte LDS read per
+//              four reduction steps; the swizzle makes 8 consecutive rows hit 8
+//              different 16-byte bank groups.
+//
+// Lanes whose element must be zero (padding tap, reduction tail, column block
+// past the end) fetch from a small zero-filled page instead.
+// ---------------------------------------------------------------------------
+#define CS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define CS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+__device__ __forceinline__ void dma16(const float* g, float* lds_uniform) {
+  __builtin_amdgcn_global_load_lds(CS_GPTR(g), CS_LPTR(lds_uniform), 16, 0, 0);
 }
 
-// One staged chunk: 16 reduction steps of four 32x32x2 fp32 MFMAs per wavefront.
-// As/Bs are [BK][lda]/[BK][ldb] with the reduction index as the row.  In
-// v_mfma_f32_32x32x2_f32 lane l supplies A[row l%32][k l/32] and B[k l/32][col l%32].
-__device__ __forceinline__ void mfma_chunk(const float* __restrict__ As, int lda,
-                                           const float* __restrict__ Bs, int ldb,
-                                           int wm, int wn, int lane, f32x16 (&acc)[2][2]) {
-  const float* ap = As + (lane >> 5) * lda + wm * 64 + (lane & 31);
-  const float* bp = Bs + (lane >> 5) * ldb + wn * 64 + (lane & 31);
-  // Operands of step ks+1 are read from LDS before the MFMAs of step ks are issued.
-  float a0 = ap[0], a1 = ap[32], b0 = bp[0], b1 = bp[32];
+// Reduction order inside a chunk.  MFMA step ks = 4*j + t (j, t in 0..3) multiplies
+// the element pair kk = 8*j + t (lanes 0..31) and kk = 8*j + 4 + t (lanes 32..63),
+// which is what a 16-byte read of col-image slot 2*j + lane/32 delivers.
+struct Frag {          // operands of four MFMA steps (one j) for the wavefront's two 32-wide blocks
+  f32x4 v[2];          // v[blk][t]
+};
+
+template <bool COL>
+__device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase, int lane, int j) {
+  if constexpr (COL) {
+    const int u = lane & 7, h = lane >> 5;
+    const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
+    f.v[0] = *(const f32x4*)(tile + slot * 4);
+    f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
+  } else {
+    const float* p = tile + (8 * j + 4 * (lane >> 5)) * BM + wbase + (lane & 31);
 #pragma unroll
-  for (int ks = 0; ks < BK / 2; ++ks) {
-    float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
-    if (ks + 1 < BK / 2) {
-      na0 = ap[2 * (ks + 1) * lda];
-      na1 = ap[2 * (ks + 1) * lda + 32];
-      nb0 = bp[2 * (ks + 1) * ldb];
-      nb1 = bp[2 * (ks + 1) * ldb + 32];
+    for (int t = 0; t < 4; ++t) {
+      f.v[0][t] = p[t * BM];
+      f.v[1][t] = p[t * BM + 32];
     }
-    __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs they overlap with
-    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
   }
 }
 
-// Software-pipelined main loop shared by the three passes.  A loader stages one
-// operand: load(ch) issues the global reads of chunk ch into registers (chunks
-// are requested in increasing order, once each), store(buf) writes them to LDS.
+// One staged chunk: 16 reduction steps of four 32x32x2 fp32 MFMAs per wavefront; the
+// LDS reads of group j+1 are issued before the 16 MFMAs of group j.
+template <bool ACOL, bool BCOL>
+__device__ __forceinline__ void mfma_chunk(const float* As, const float* Bs, int wm, int wn, int lane,
+                                           f32x16 (&acc)[2][2]) {
+  Frag a, na, b, nb;
+  read_frag<ACOL>(a, As, wm * 64, lane, 0);
+  read_frag<BCOL>(b, Bs, wn * 64, lane, 0);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j < 3) {
+      read_frag<ACOL>(na, As, wm * 64, lane, j + 1);
+      read_frag<BCOL>(nb, Bs, wn * 64, lane, j + 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs they overlap with
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[0][t], acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[1][t], acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[0][t], acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[1][t], acc[1][1], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (j < 3) {
+      a = na;
+      b = nb;
+    }
+  }
+}
+
+// Main loop shared by the three passes.  A loader's issue(ch, tile, wv) enqueues the
+// four LDS-DMA loads of this wavefront's share of chunk ch (chunks are requested in
+// increasing order, once each).  LDS holds [A stage0][A stage1][B stage0][B stage1];
+// the stage in use alternates per chunk.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
                                               float* smem, f32x16 (&acc)[2][2]) {
   const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  // LDS map: [A buf0][A buf1][B buf0][B buf1]; offsets (not pointers) select the
-  // buffer so that every access stays a plain LDS instruction.
+  const int lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wv >> 1, wn = wv & 1;
   if (ch_begin >= ch_end) return;
-  la.load(ch_begin);
-  lb.load(ch_begin);
-  la.store(smem);
-  lb.store(smem + 2 * STAGE);
-  __syncthreads();
-  int cur = 0;
-#ifndef CS_EXP
-#define CS_EXP 0
-#endif
+  la.issue(ch_begin, smem, wv);
+  lb.issue(ch_begin, smem + 2 * TILE_F, wv);
+  __syncthreads();  // includes the wait for this wavefront's own DMA loads
+  int cur = 0;  // float offset of the stage being computed on: 0 or TILE_F
   for (int ch = ch_begin; ch < ch_end; ++ch) {
-    const bool more = ch + 1 < ch_end;
-    if (more && !(CS_EXP & 1)) {
-      la.load(ch + 1);
-      lb.load(ch + 1);
+    if (ch + 1 < ch_end) {
+      la.issue(ch + 1, smem + (cur ^ TILE_F), wv);
+      lb.issue(ch + 1, smem + 2 * TILE_F + (cur ^ TILE_F), wv);
     }
-    if (!(CS_EXP & 4)) mfma_chunk(smem + cur, LA::LD, smem + 2 * STAGE + cur, LB::LD, wm, wn, lane, acc);
-    cur ^= STAGE;
-    if (more && !(CS_EXP & 1)) {
-      la.store(smem + cur);
-      lb.store(smem + 2 * STAGE + cur);
-    }
-    if (!(CS_EXP & 2)) __syncthreads();
+    mfma_chunk<LA::COL, LB::COL>(smem + cur, smem + 2 * TILE_F + cur, wm, wn, lane, acc);
+    __syncthreads();
+    cur ^= TILE_F;
   }
 }
 

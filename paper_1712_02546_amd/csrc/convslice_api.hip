@@ -54,7 +54,7 @@ inline size_t seg(int64_t floats) { return (size_t)round_up(floats * 4, 256); }
 struct FwdPlan {
   bool repitch;      // filters copied to fp32 rows of pitch ldw (bf16 input or C*R*S not a multiple of 4)
   int ldw, nch;
-  size_t off_xt, off_yt, off_w, total;
+  size_t off_xt, off_yt, off_w, off_zero, total;
 };
 
 FwdPlan plan_fwd(const Geo& g, int dtype) {
@@ -66,13 +66,14 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
+  p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
 }
 
 struct BwdDataPlan {
   int Cp;
-  size_t off_dyt, off_wt, off_dxt, off_perm, total;
+  size_t off_dyt, off_wt, off_dxt, off_perm, off_zero, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
@@ -83,13 +84,14 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_wt = o;   o += seg((int64_t)g.RS * g.Ks * p.Cp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
+  p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
 }
 
 struct BwdWeightPlan {
   int MB, CT, nch, splits, chPerSplit;
-  size_t off_xt, off_dyt, off_part, total;
+  size_t off_xt, off_dyt, off_part, off_zero, total;
 };
 
 BwdWeightPlan plan_bwd_weight(const Geo& g) {
@@ -110,6 +112,7 @@ BwdWeightPlan plan_bwd_weight(const Geo& g) {
   p.off_xt = o;   o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
+  p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
 }
@@ -138,7 +141,7 @@ int allow_big_lds(K kernel) {
 // src[rows][cols] (pitch srcPitch, element type by dtype) -> dst[cols][rowsPad] fp32, batched.
 void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
                          float* dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch,
-                         hipStream_t st) {
+                         float* zero_page, hipStream_t st) {
   const size_t es = dtype == CONV_F32 ? 4 : 2;
   for (int b0 = 0; b0 < batch; b0 += 32768) {  // grid.z is limited to 65535
     const int nb = batch - b0 < 32768 ? batch - b0 : 32768;
@@ -147,10 +150,10 @@ void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t s
     float* d = dst + (size_t)b0 * dstBatch;
     if (dtype == CONV_F32)
       hipLaunchKernelGGL(cs::transpose_in_kernel<float>, grid, dim3(256), 0, st, (const float*)s, srcBatch,
-                         srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad);
+                         srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad, b0 == 0 ? zero_page : nullptr);
     else
       hipLaunchKernelGGL(cs::transpose_in_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)s,
-                         srcBatch, srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad);
+                         srcBatch, srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad, b0 == 0 ? zero_page : nullptr);
   }
 }
 
@@ -227,7 +230,8 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const size_t es = elem_size(desc->dtype);
 
   // x[N][C*H*W] -> x_t[C*H*W][Np]
-  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, st);
+  float* zero = (float*)(base + p.off_zero);
+  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, zero, st);
   const float* wmat;
   if (p.repitch) {
     float* wp = (float*)(base + p.off_w);
@@ -248,7 +252,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const int CT = (g.PQ * g.NB + 3) / 4;
   probe.begin(st);
   hipLaunchKernelGGL(cs::fwd_gemm_kernel, dim3(cs::grid_contiguous(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
-                     wmat, p.ldw, p.ldw, xt, yt, MB, CT, p.nch);
+                     wmat, p.ldw, p.ldw, xt, zero, yt, MB, CT, p.nch);
   probe.end(st);
   // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
   launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
@@ -285,20 +289,21 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   float* wt = (float*)(base + p.off_wt);
   float* dxt = (float*)(base + p.off_dxt);
   int* perm = (int*)(base + p.off_perm);
+  float* zero = (float*)(base + p.off_zero);
 
   // dy[n][k0*PQ ..] -> dy_t[Ks*P*Q][Np]
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
-                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, st);
+                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, zero, st);
   // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
-                      (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, st);
+                      (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, nullptr, st);
   hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
   if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel)) != CONV_OK) return rc;
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
   probe.begin(st);
   hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st,
-                     g, wt, p.Cp, dyt, perm, dxt, MB, CT);
+                     g, wt, p.Cp, dyt, perm, zero, dxt, MB, CT);
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
@@ -323,15 +328,16 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   float* dyt = (float*)(base + p.off_dyt);
   float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
 
-  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, st);
+  float* zero = (float*)(base + p.off_zero);
+  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, zero, st);
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
-                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, st);
+                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, nullptr, st);
   if ((rc = allow_big_lds(cs::bwd_weight_gemm_kernel)) != CONV_OK) return rc;
   const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
   float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
   probe.begin(st);
   hipLaunchKernelGGL(cs::bwd_weight_gemm_kernel, dim3(cs::grid_contiguous(p.MB, p.CT), p.splits), dim3(cs::NT),
-                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
+                     cs::SMEM_BYTES, st, g, dyt, xt, zero, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
   probe.end(st);
   if (p.splits > 1) {
     const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);

@@ -8,14 +8,17 @@ namespace cs {
 
 // dst[b*dstBatch + l*dstPitch + n] = n < rows ? src[b*srcBatch + n*srcPitch + l] : 0
 // for 0 <= l < cols, 0 <= n < rowsPad.  64x64 tiles through LDS, both sides coalesced.
-// grid = (ceil(cols/64), ceil(rowsPad/64), batch).
+// grid = (ceil(cols/64), ceil(rowsPad/64), batch).  If zero_page is not null the first
+// workgroup also clears its ZERO_PAGE_FLOATS floats (the page masked DMA lanes read).
 template <typename Tin>
 __global__ __launch_bounds__(256) void transpose_in_kernel(
     const Tin* __restrict__ src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
-    float* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad) {
+    float* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, float* __restrict__ zero_page) {
   __shared__ float tile[64][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  if (zero_page && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+    for (int i = threadIdx.x; i < ZERO_PAGE_FLOATS; i += 256) zero_page[i] = 0.f;
   src += (int64_t)blockIdx.z * srcBatch;
   dst += (int64_t)blockIdx.z * dstBatch;
 #pragma unroll
