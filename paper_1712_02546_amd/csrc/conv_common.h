@@ -148,9 +148,15 @@ __device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase,
 
 // One staged chunk: 16 reduction steps of four 32x32x2 fp32 MFMAs per wavefront; the
 // LDS reads of group j+1 are issued before the 16 MFMAs of group j.
-template <bool ACOL, bool BCOL>
+// mid() -- the next chunk's address arithmetic and DMA issue -- is placed after the
+// first read group; its vector/scalar ALU and memory instructions may move across the
+// scheduling fences (LDS reads and MFMAs may not), so that they issue in the shadow of
+// the MFMAs instead of in front of them.
+constexpr int CS_FENCE = 0x0002 | 0x0004 | 0x0010;  // VALU, SALU and VMEM may cross
+
+template <bool ACOL, bool BCOL, class Mid>
 __device__ __forceinline__ void mfma_chunk(const float* As, const float* Bs, int wm, int wn, int lane,
-                                           f32x16 (&acc)[2][2]) {
+                                           f32x16 (&acc)[2][2], Mid&& mid) {
   Frag a, na, b, nb;
   read_frag<ACOL>(a, As, wm * 64, lane, 0);
   read_frag<BCOL>(b, Bs, wn * 64, lane, 0);
@@ -160,7 +166,8 @@ __device__ __forceinline__ void mfma_chunk(const float* As, const float* Bs, int
       read_frag<ACOL>(na, As, wm * 64, lane, j + 1);
       read_frag<BCOL>(nb, Bs, wn * 64, lane, j + 1);
     }
-    __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs they overlap with
+    if (j == 0) mid();
+    __builtin_amdgcn_sched_barrier(CS_FENCE);  // keep the reads ahead of the MFMAs they overlap with
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[0][t], acc[0][0], 0, 0, 0);
@@ -168,7 +175,7 @@ __device__ __forceinline__ void mfma_chunk(const float* As, const float* Bs, int
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[0][t], acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[1][t], acc[1][1], 0, 0, 0);
     }
-    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_sched_barrier(CS_FENCE);
     if (j < 3) {
       a = na;
       b = nb;
@@ -176,7 +183,7 @@ __device__ __forceinline__ void mfma_chunk(const float* As, const float* Bs, int
   }
 }
 
-// Main loop shared by the three passes.  A loader's issue(ch, tile, wv) enqueues the
+// Main loop shared by the three passes.  A loader's issue(ch, tile, wv, live) enqueues the
 // four LDS-DMA loads of this wavefront's share of chunk ch (chunks are requested in
 // increasing order, once each).  LDS holds [A stage0][A stage1][B stage0][B stage1];
 // the stage in use alternates per chunk.
@@ -188,16 +195,16 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wv >> 1, wn = wv & 1;
   if (ch_begin >= ch_end) return;
-  la.issue(ch_begin, smem, wv);
-  lb.issue(ch_begin, smem + 2 * TILE_F, wv);
+  la.issue(ch_begin, smem, wv, true);
+  lb.issue(ch_begin, smem + 2 * TILE_F, wv, true);
   __syncthreads();  // includes the wait for this wavefront's own DMA loads
   int cur = 0;  // float offset of the stage being computed on: 0 or TILE_F
   for (int ch = ch_begin; ch < ch_end; ++ch) {
-    if (ch + 1 < ch_end) {
-      la.issue(ch + 1, smem + (cur ^ TILE_F), wv);
-      lb.issue(ch + 1, smem + 2 * TILE_F + (cur ^ TILE_F), wv);
-    }
-    mfma_chunk<LA::COL, LB::COL>(smem + cur, smem + 2 * TILE_F + cur, wm, wn, lane, acc);
+    mfma_chunk<LA::COL, LB::COL>(smem + cur, smem + 2 * TILE_F + cur, wm, wn, lane, acc, [&]() {
+      const bool live = ch + 1 < ch_end;   // the last chunk issues dummy zero-page loads: no branch
+      la.issue(ch + 1, smem + (cur ^ TILE_F), wv, live);
+      lb.issue(ch + 1, smem + 2 * TILE_F + (cur ^ TILE_F), wv, live);
+    });
     __syncthreads();
     cur ^= TILE_F;
   }

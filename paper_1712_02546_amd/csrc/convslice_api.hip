@@ -50,11 +50,13 @@ int make_geo(const conv_desc_t* d, Geo& g) {
 }
 
 inline size_t seg(int64_t floats) { return (size_t)round_up(floats * 4, 256); }
+// A buffer that the DMA loaders read gets a zero page directly in front of it.
+constexpr size_t kZeroBytes = cs::ZERO_PAGE_FLOATS * 4;
 
 struct FwdPlan {
   bool repitch;      // filters copied to fp32 rows of pitch ldw (bf16 input or C*R*S not a multiple of 4)
   int ldw, nch;
-  size_t off_xt, off_yt, off_w, off_zero, total;
+  size_t off_xt, off_yt, off_w, off_tab, off_zero, total;
 };
 
 FwdPlan plan_fwd(const Geo& g, int dtype) {
@@ -63,9 +65,11 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.ldw = p.repitch ? (int)round_up(g.CRS, 4) : g.CRS;
   p.nch = (g.CRS + cs::BK - 1) / cs::BK;
   size_t o = 0;
+  o += kZeroBytes;
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
+  p.off_tab = o; o += seg((int64_t)(p.nch + 2) * cs::BK * 2);
   p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
@@ -73,25 +77,26 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
 
 struct BwdDataPlan {
   int Cp;
-  size_t off_dyt, off_wt, off_dxt, off_perm, off_zero, total;
+  size_t off_dyt, off_wt, off_dxt, off_perm, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
   BwdDataPlan p;
   p.Cp = (int)round_up(g.C, 4);
   size_t o = 0;
+  o += kZeroBytes;
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
+  o += kZeroBytes;
   p.off_wt = o;   o += seg((int64_t)g.RS * g.Ks * p.Cp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
-  p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
 }
 
 struct BwdWeightPlan {
   int MB, CT, nch, splits, chPerSplit;
-  size_t off_xt, off_dyt, off_part, off_zero, total;
+  size_t off_xt, off_dyt, off_part, total;
 };
 
 BwdWeightPlan plan_bwd_weight(const Geo& g) {
@@ -108,11 +113,10 @@ BwdWeightPlan plan_bwd_weight(const Geo& g) {
   if (want < 1) want = 1;
   p.chPerSplit = (int)((p.nch + want - 1) / want);
   p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;
-  size_t o = 0;
+  size_t o = kZeroBytes;
   p.off_xt = o;   o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
-  p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
 }
@@ -133,9 +137,14 @@ inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)
 int check_launch() { return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH; }
 
 template <typename K>
-int allow_big_lds(K kernel) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             cs::SMEM_BYTES) == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH;
+int allow_big_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
+             ? CONV_OK : CONV_ERR_LAUNCH;
+}
+
+// True when some window reaches outside the image, i.e. taps must be range-checked.
+bool needs_pad_checks(const Geo& g) {
+  return g.ph > 0 || g.pw > 0 || (g.P - 1) * g.sh - g.ph + g.R > g.H || (g.Q - 1) * g.sw - g.pw + g.S > g.W;
 }
 
 // src[rows][cols] (pitch srcPitch, element type by dtype) -> dst[cols][rowsPad] fp32, batched.
@@ -230,8 +239,10 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const size_t es = elem_size(desc->dtype);
 
   // x[N][C*H*W] -> x_t[C*H*W][Np]
-  float* zero = (float*)(base + p.off_zero);
-  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, zero, st);
+  float* zero = (float*)(base + p.off_zero);   // for the filter rows, which may be read in place
+  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
+                      xt - cs::ZERO_PAGE_FLOATS, st);
+  hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
   const float* wmat;
   if (p.repitch) {
     float* wp = (float*)(base + p.off_w);
@@ -247,12 +258,18 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   } else {
     wmat = (const float*)w + (size_t)g.k0 * g.CRS;
   }
-  if ((rc = allow_big_lds(cs::fwd_gemm_kernel)) != CONV_OK) return rc;
+  // two chunks more than needed: the loaders fetch entries one chunk ahead, also in the last (dummy) issue
+  int2* tab = (int2*)(base + p.off_tab);
+  const int entries = (p.nch + 2) * cs::BK;
+  hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
+  const bool pad = needs_pad_checks(g);
+  if ((rc = allow_big_lds(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK)
+    return rc;
   const int MB = (g.Ks + cs::BM - 1) / cs::BM;
   const int CT = (g.PQ * g.NB + 3) / 4;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::fwd_gemm_kernel, dim3(cs::grid_contiguous(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
-                     wmat, p.ldw, p.ldw, xt, zero, yt, MB, CT, p.nch);
+  hipLaunchKernelGGL(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(MB, CT)),
+                     dim3(cs::NT), cs::SMEM_BYTES, st, g, wmat, p.ldw, p.ldw, xt, tab, zero, yt, MB, CT, p.nch);
   probe.end(st);
   // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
   launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
@@ -289,21 +306,21 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   float* wt = (float*)(base + p.off_wt);
   float* dxt = (float*)(base + p.off_dxt);
   int* perm = (int*)(base + p.off_perm);
-  float* zero = (float*)(base + p.off_zero);
 
   // dy[n][k0*PQ ..] -> dy_t[Ks*P*Q][Np]
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
-                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, zero, st);
+                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, dyt - cs::ZERO_PAGE_FLOATS, st);
   // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
-                      (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, nullptr, st);
+                      (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, wt - cs::ZERO_PAGE_FLOATS, st);
   hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
-  if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel)) != CONV_OK) return rc;
+  const int lds = cs::SMEM_BYTES + (g.RS + 1) * 20;  // tiles + tap list + per-block tap offsets
+  if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel, lds)) != CONV_OK) return rc;
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES, st,
-                     g, wt, p.Cp, dyt, perm, zero, dxt, MB, CT);
+  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st,
+                     g, wt, p.Cp, dyt, perm, dxt, MB, CT);
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
@@ -328,16 +345,20 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   float* dyt = (float*)(base + p.off_dyt);
   float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
 
-  float* zero = (float*)(base + p.off_zero);
-  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1, zero, st);
+  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
+                      xt - cs::ZERO_PAGE_FLOATS, st);
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
                       g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, nullptr, st);
-  if ((rc = allow_big_lds(cs::bwd_weight_gemm_kernel)) != CONV_OK) return rc;
+  const bool pad = needs_pad_checks(g);
+  if ((rc = allow_big_lds(pad ? cs::bwd_weight_gemm_kernel<true> : cs::bwd_weight_gemm_kernel<false>,
+                          cs::SMEM_BYTES)) != CONV_OK)
+    return rc;
   const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
   float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_weight_gemm_kernel, dim3(cs::grid_contiguous(p.MB, p.CT), p.splits), dim3(cs::NT),
-                     cs::SMEM_BYTES, st, g, dyt, xt, zero, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
+  hipLaunchKernelGGL(pad ? cs::bwd_weight_gemm_kernel<true> : cs::bwd_weight_gemm_kernel<false>,
+                     dim3(cs::grid_contiguous(p.MB, p.CT), p.splits), dim3(cs::NT),
+                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
   probe.end(st);
   if (p.splits > 1) {
     const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);

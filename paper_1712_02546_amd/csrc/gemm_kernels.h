@@ -29,26 +29,29 @@ struct FwdLoadA {
       p[i] = w + (int64_t)m * ldw + kq4;
     }
   }
-  __device__ __forceinline__ void issue(int ch, float* tile, int wv) {
-    const bool kok = ch * BK + kq4 < cols;
+  // live = false turns the whole issue into harmless zero-page loads (keeps the loop branch free).
+  __device__ __forceinline__ void issue(int ch, float* tile, int wv, bool live) {
+    const bool ok = live && ch * BK + kq4 < cols;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(kok ? p[i] + ch * BK : zero, dma_dst(tile, wv, i));
+    for (int i = 0; i < 4; ++i) dma16(ok ? p[i] + ch * BK : zero, dma_dst(tile, wv, i));
   }
 };
 
 // B[kk][col] = x_t[tap kk of the column block's pixel][n] (row image), zero where the
-// tap falls into the padding.  Each lane walks its four reduction rows kk = (c,r,s)
-// with carry arithmetic (+32 per chunk), so no division or table sits in the loop.
+// tap falls into the padding.  tab[kk] = {offset of tap (c,r,s) inside x_t, (r<<16)|s}
+// (second word negative past C*R*S) is read with scalar loads: a DMA load covers two
+// consecutive reduction rows, one per half-wave.
+template <bool PAD>
 struct FwdLoadB {
   static constexpr bool COL = false;
-  const float* xt;
-  const float* zero;
-  int base, h0, w0, H, W, C, R, S, HW, Np;
-  int dc, dr, ds;         // (c,r,s) increments of one chunk
-  int cc[4], rr[4], ss[4];
-  bool cbok;
-  __device__ FwdLoadB(const Geo& g, const float* xt_, int ct, const float* zero_) : xt(xt_), zero(zero_) {
-    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const float* xt;       // a zero page sits ZERO_PAGE_FLOATS in front of x_t
+  const int4* tab2;
+  int4 nxt[4];           // table entries (two rows each) of the next chunk to issue; uniform
+  int pixbase, h0, w0, H, W;
+  bool cbok, upper;
+  __device__ FwdLoadB(const Geo& g, const float* xt_, const int2* tab, int ct) : xt(xt_), tab2((const int4*)tab) {
+    const int l = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cq = l & 31;
     const int gcb = ct * 4 + (cq >> 3);
     cbok = gcb < g.PQ * g.NB;
@@ -57,40 +60,35 @@ struct FwdLoadB {
     const int p = pix / g.Q, q = pix - p * g.Q;
     h0 = p * g.sh - g.ph;
     w0 = q * g.sw - g.pw;
-    H = g.H; W = g.W; C = g.C; R = g.R; S = g.S; HW = g.HW; Np = g.Np;
-    base = nb * 32 + 4 * (cq & 7);
-    dc = BK / g.RS;
-    const int rem = BK - dc * g.RS;
-    dr = rem / g.S;
-    ds = rem - dr * g.S;
+    H = g.H;
+    W = g.W;
+    pixbase = (h0 * g.W + w0) * g.Np + nb * 32 + 4 * (cq & 7);
+    upper = l >= 32;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int kk = 8 * wv + 2 * i + (l >> 5);
-      cc[i] = kk / g.RS;
-      const int rs = kk - cc[i] * g.RS;
-      rr[i] = rs / g.S;
-      ss[i] = rs - rr[i] * g.S;
-    }
+    for (int i = 0; i < 4; ++i) nxt[i] = tab2[4 * wv + i];
   }
-  __device__ __forceinline__ void issue(int, float* tile, int wv) {
+  __device__ __forceinline__ void issue(int ch, float* tile, int wv, bool live) {
+    int4 e[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) e[i] = nxt[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) nxt[i] = tab2[(ch + 1) * (BK / 2) + 4 * wv + i];  // rows 8*wv+2*i, +1 of chunk ch+1
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int hh = h0 + rr[i], vv = w0 + ss[i];
-      const bool ok = cbok && cc[i] < C && (unsigned)hh < (unsigned)H && (unsigned)vv < (unsigned)W;
-      dma16(ok ? xt + ((cc[i] * HW + hh * W + vv) * Np + base) : zero, dma_dst(tile, wv, i));
-      // advance (c,r,s) by one chunk
-      ss[i] += ds;
-      if (ss[i] >= S) { ss[i] -= S; rr[i] += 1; }
-      rr[i] += dr;
-      if (rr[i] >= R) { rr[i] -= R; cc[i] += 1; }
-      cc[i] += dc;
+      const int off = upper ? e[i].z : e[i].x;
+      const int rs = upper ? e[i].w : e[i].y;
+      bool ok = live & cbok & (rs >= 0);
+      if (PAD) ok = ok & ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
+      dma16(xt + (ok ? off + pixbase : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
     }
   }
 };
 
 // y_t[k][pix][n] for the slice; one workgroup per 128 kernels x 4 column blocks.
+template <bool PAD>
 __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __restrict__ w, int ldw,
                                                       int wcols, const float* __restrict__ xt,
+                                                      const int2* __restrict__ tab,
                                                       const float* __restrict__ zero,
                                                       float* __restrict__ yt, int MB, int CT, int nch) {
   extern __shared__ __align__(16) float smem[];
@@ -105,7 +103,7 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   FwdLoadA la(w, ldw, wcols, m0, g.Ks, zero);
-  FwdLoadB lb(g, xt, ct, zero);
+  FwdLoadB<PAD> lb(g, xt, tab, ct);
   gemm_mainloop(la, lb, 0, nch, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -128,85 +126,80 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
 
 // --------------------------------------------------------- input gradient ----
 // Reduction runs over (tap, k): only taps that reach the tile's pixels, k inner.
-// A^T[k][c] = w_t[tap][k][c] (filters re-laid with c innermost, pitch Cp), row image.
-struct BwdDataLoadA {
-  static constexpr bool COL = false;
-  const float* wt;
-  const float* zero;
-  const int* taps;
-  int Ks, Cp, S, nkc, c, krow, ti, kc;
-  int64_t tapbase;
-  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_,
-                          const float* zero_)
-      : wt(wt_), zero(zero_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), nkc(nkc_), ti(0), kc(0), tapbase(0) {
-    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    c = m0 + 4 * (l & 31);
-    krow = 8 * wv + (l >> 5);
-  }
-  __device__ __forceinline__ void issue(int, float* tile, int wv) {
-    if (kc == 0) {
-      const int e = taps[ti];
-      tapbase = (int64_t)((e >> 16) * S + (e & 0xffff)) * Ks * Cp;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int k = kc * BK + krow + 2 * i;
-      const bool ok = k < Ks && c < Cp;
-      dma16(ok ? wt + (tapbase + (int64_t)k * Cp + c) : zero, dma_dst(tile, wv, i));
-    }
-    if (++kc == nkc) {
+// Per tile, LDS holds the tap list s_taps[ti] = (r<<16)|s and, per tap and column
+// block, s_tapoff[ti][cb] = offset of the matching output pixel inside dy_t, or -1.
+// The (tap, k-chunk) counters are uniform and advance once per issue.
+struct TapWalk {
+  int ti, kc, nkc;
+  __device__ TapWalk(int nkc_) : ti(0), kc(0), nkc(nkc_) {}
+  __device__ __forceinline__ void next() {
+    ++kc;
+    if (kc == nkc) {
       kc = 0;
       ++ti;
     }
   }
 };
 
+// A^T[k][c] = w_t[tap][k][c] (filters re-laid with c innermost, pitch Cp), row image.
+// A zero page sits ZERO_PAGE_FLOATS in front of w_t.
+struct BwdDataLoadA {
+  static constexpr bool COL = false;
+  const float* wt;
+  const int* taps;
+  int Ks, Cp, S, krow, lane_off, tap;   // tap = flat (r*S+s) of walk.ti, fetched one call ahead
+  bool cok;
+  TapWalk walk;
+  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_)
+      : wt(wt_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), walk(nkc_) {
+    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int c = m0 + 4 * (l & 31);
+    cok = c < Cp;
+    krow = 8 * wv + (l >> 5);
+    lane_off = krow * Cp + c;
+    const int e = taps[0];
+    tap = (e >> 16) * S + (e & 0xffff);
+  }
+  __device__ __forceinline__ void issue(int, float* tile, int wv, bool live) {
+    const int base = (tap * Ks + walk.kc * BK) * Cp + lane_off;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool ok = live & cok & (walk.kc * BK + krow + 2 * i < Ks);
+      dma16(wt + (ok ? base + 2 * i * Cp : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
+    }
+    walk.next();
+    const int e = taps[walk.ti];   // one entry past the list is allocated, so this stays in bounds
+    tap = (e >> 16) * S + (e & 0xffff);
+  }
+};
+
 // B[k][col] = dy_t[k][p][q][n] (row image) with (p,q) the output pixel whose window
 // puts the current tap on the column block's input pixel; zero if there is none.
+// A zero page sits ZERO_PAGE_FLOATS in front of dy_t.
 struct BwdDataLoadB {
   static constexpr bool COL = false;
   const float* dyt;
-  const float* zero;
-  const int* taps;
-  int Ks, nkc, krow, ti, kc;
-  int hp, vp, sh, sw, P, Q, PQNp, nboff, Np;  // hp = h + pad_h, vp = v + pad_w of this lane's pixel
-  int off;
-  bool cbok, tapok;
-  __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* perm, int ct, const int* taps_, int nkc_,
-                          const float* zero_)
-      : dyt(dyt_), zero(zero_), taps(taps_), Ks(g.Ks), nkc(nkc_), ti(0), kc(0), off(0), tapok(false) {
+  const int* tapoff;
+  int Ks, PQNp, krow, cb, lane_off, toff;   // toff = tapoff[walk.ti][cb], fetched one call ahead
+  TapWalk walk;
+  __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* tapoff_, int nkc_)
+      : dyt(dyt_), tapoff(tapoff_), Ks(g.Ks), PQNp(g.PQ * g.Np), walk(nkc_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int cq = l & 31;
-    const int gcb = ct * 4 + (cq >> 3);
-    cbok = gcb < g.HW * g.NB;
-    const int sp = cbok ? gcb / g.NB : 0;
-    const int nb = cbok ? gcb - sp * g.NB : 0;
-    const int px = perm[sp];
-    hp = px / g.W + g.ph;
-    vp = px % g.W + g.pw;
-    sh = g.sh; sw = g.sw; P = g.P; Q = g.Q; Np = g.Np;
-    PQNp = g.PQ * g.Np;
-    nboff = nb * 32 + 4 * (cq & 7);
+    cb = cq >> 3;
     krow = 8 * wv + (l >> 5);
+    lane_off = 4 * (cq & 7);
+    toff = tapoff[cb];
   }
-  __device__ __forceinline__ void issue(int, float* tile, int wv) {
-    if (kc == 0) {
-      const int e = taps[ti];
-      const int hr = hp - (e >> 16), vs = vp - (e & 0xffff);
-      const int p = hr / sh, q = vs / sw;
-      tapok = cbok && hr >= 0 && vs >= 0 && p * sh == hr && q * sw == vs && p < P && q < Q;
-      off = (p * Q + q) * Np + nboff;
-    }
+  __device__ __forceinline__ void issue(int, float* tile, int wv, bool live) {
+    const int base = (walk.kc * BK + krow) * PQNp + toff + lane_off;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int k = kc * BK + krow + 2 * i;
-      const bool ok = tapok && k < Ks;
-      dma16(ok ? dyt + ((int64_t)k * PQNp + off) : zero, dma_dst(tile, wv, i));
+      const bool ok = live & (toff >= 0) & (walk.kc * BK + krow + 2 * i < Ks);
+      dma16(dyt + (ok ? base + 2 * i * PQNp : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
     }
-    if (++kc == nkc) {
-      kc = 0;
-      ++ti;
-    }
+    walk.next();
+    toff = tapoff[walk.ti * 4 + cb];
   }
 };
 
@@ -214,25 +207,28 @@ struct BwdDataLoadB {
 __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* __restrict__ wt, int Cp,
                                                            const float* __restrict__ dyt,
                                                            const int* __restrict__ perm,
-                                                           const float* __restrict__ zero,
                                                            float* __restrict__ dxt, int MB, int CT) {
   extern __shared__ __align__(16) float smem[];
-  __shared__ int s_taps[1024];
+  int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 1]
+  int* s_tapoff = s_taps + g.RS + 1;           // [RS + 1][4]
   __shared__ int s_ntaps;
   int mb, ct;
   if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
   const int m0 = mb * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-  // Taps that reach at least one of the tile's (up to four) pixels, in (r,s) order.
+  // Taps that reach at least one of the tile's (up to four) pixels, in (r,s) order, and
+  // for each of them where it lands in dy_t for every column block.
   if (wave == 0) {
-    int hp[4], vp[4];
+    int hp[4], vp[4], nbo[4];
     bool ok[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int gcb = ct * 4 + j;
       ok[j] = gcb < g.HW * g.NB;
-      const int px = perm[ok[j] ? gcb / g.NB : 0];
+      const int sp = ok[j] ? gcb / g.NB : 0;
+      const int px = perm[sp];
+      nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 : 0;
       hp[j] = px / g.W + g.ph;
       vp[j] = px % g.W + g.pw;
     }
@@ -241,19 +237,30 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
       const int tp = b + lane;
       const int rr = tp / g.S, ss = tp - rr * g.S;
       bool any = false;
-      if (tp < g.RS) {
+      int offs[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int hr = hp[j] - rr, vs = vp[j] - ss;
-          any |= ok[j] && hr >= 0 && vs >= 0 && hr % g.sh == 0 && vs % g.sw == 0 &&
-                 hr / g.sh < g.P && vs / g.sw < g.Q;
-        }
+      for (int j = 0; j < 4; ++j) {
+        const int hr = hp[j] - rr, vs = vp[j] - ss;
+        const int p = hr / g.sh, q = vs / g.sw;
+        const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
+                         p < g.P && q < g.Q;
+        offs[j] = hit ? (p * g.Q + q) * g.Np + nbo[j] : -1;
+        any |= hit;
       }
       const unsigned long long mask = __ballot(any);
-      if (any) s_taps[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = (rr << 16) | ss;
+      if (any) {
+        const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+        s_taps[pos] = (rr << 16) | ss;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
+      }
       cnt += __popcll(mask);
     }
-    if (lane == 0) s_ntaps = cnt;
+    if (lane < 4) s_tapoff[cnt * 4 + lane] = -1;   // the entry the loaders fetch after the last tap
+    if (lane == 0) {
+      s_taps[cnt] = 0;
+      s_ntaps = cnt;
+    }
   }
   __syncthreads();
   const int ntaps = s_ntaps;
@@ -266,8 +273,8 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  BwdDataLoadA la(g, wt, Cp, m0, s_taps, nkc, zero);
-  BwdDataLoadB lb(g, dyt, perm, ct, s_taps, nkc, zero);
+  BwdDataLoadA la(g, wt, Cp, m0, s_taps, nkc);
+  BwdDataLoadB lb(g, dyt, s_tapoff, nkc);
   gemm_mainloop(la, lb, 0, ntaps * nkc, smem, acc);
 
   const int wm = wave >> 1, wn = wave & 1;
@@ -303,25 +310,28 @@ struct BwdWeightLoadA {
       p[i] = dyt + (int64_t)m * g.PQ * g.Np + kq4;
     }
   }
-  __device__ __forceinline__ void issue(int ch, float* tile, int wv) {
+  __device__ __forceinline__ void issue(int ch, float* tile, int wv, bool live) {
+    const int64_t adv = (int64_t)(live ? ch : 0) * BK;   // the dummy issue re-reads chunk 0
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(p[i] + (int64_t)ch * BK, dma_dst(tile, wv, i));
+    for (int i = 0; i < 4; ++i) dma16(p[i] + adv, dma_dst(tile, wv, i));
   }
 };
 
 // B^T[j][kk] = x_t[c_j][p*sh-ph+r_j][q*sw-pw+s_j][n] (col image); zero where tap j is in
-// the padding or j is past C*R*S.
+// the padding or j is past C*R*S.  The chunk's output pixel (p,q) and image block nb are
+// uniform counters; a lane adds its constant column offset to their uniform offset.
+template <bool PAD>
 struct BwdWeightLoadB {
   static constexpr bool COL = true;
-  const float* xt;
-  const float* zero;
-  int colbase[4], rj[4], sj[4];
+  const float* xt;       // a zero page sits ZERO_PAGE_FLOATS in front of x_t
+  int coff[4], rj[4], sj[4];
   bool colok[4];
-  int NB, Q, sh, sw, ph, pw, H, W, Np, kq4;
-  __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, const float* zero_) : xt(xt_), zero(zero_) {
+  int NB, Q, sh, sw, ph, pw, H, W, Np;
+  int p, q, nb;   // uniform position of the next chunk to issue
+  __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, int ch0) : xt(xt_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     NB = g.NB; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W; Np = g.Np;
-    kq4 = 4 * ((l & 7) ^ (l >> 3));
+    const int kq4 = 4 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = j0 + 32 * wv + 8 * i + (l >> 3);
@@ -330,26 +340,36 @@ struct BwdWeightLoadB {
       const int c = jj / g.RS, rs = jj - c * g.RS;
       rj[i] = rs / g.S;
       sj[i] = rs - rj[i] * g.S;
-      colbase[i] = c * g.HW * g.Np;
+      coff[i] = c * g.HW * g.Np + (rj[i] * g.W + sj[i]) * g.Np + kq4;
     }
+    const int pix = ch0 / NB;
+    nb = ch0 - pix * NB;
+    p = pix / Q;
+    q = pix - p * Q;
   }
-  __device__ __forceinline__ void issue(int ch, float* tile, int wv) {
-    const int pix = ch / NB, nb = ch - pix * NB;
-    const int p = pix / Q, q = pix - p * Q;
+  __device__ __forceinline__ void issue(int, float* tile, int wv, bool live) {
     const int h0 = p * sh - ph, v0 = q * sw - pw;
+    const int uoff = (h0 * W + v0) * Np + nb * 32;   // uniform
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int hh = h0 + rj[i], vv = v0 + sj[i];
-      const bool ok = colok[i] && (unsigned)hh < (unsigned)H && (unsigned)vv < (unsigned)W;
-      dma16(ok ? xt + (colbase[i] + (hh * W + vv) * Np + nb * 32 + kq4) : zero, dma_dst(tile, wv, i));
+      bool ok = live & colok[i];
+      if (PAD) ok = ok & ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
+      dma16(xt + (ok ? coff[i] + uoff : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
+    }
+    if (++nb == NB) {
+      nb = 0;
+      if (++q == Q) {
+        q = 0;
+        ++p;
+      }
     }
   }
 };
 
 // out[z][m][j] partial (or final when one split) weight gradients of the slice.
+template <bool PAD>
 __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float* __restrict__ dyt,
                                                              const float* __restrict__ xt,
-                                                             const float* __restrict__ zero,
                                                              float* __restrict__ out, int64_t splitStride,
                                                              int MB, int CT, int nch, int chPerSplit) {
   extern __shared__ __align__(16) float smem[];
@@ -367,7 +387,7 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   BwdWeightLoadA la(g, dyt, m0);
-  BwdWeightLoadB lb(g, xt, j0, zero);
+  BwdWeightLoadB<PAD> lb(g, xt, j0, ch0);
   gemm_mainloop(la, lb, ch0, ch1, smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

@@ -83,6 +83,24 @@ __global__ __launch_bounds__(256) void repitch_rows_kernel(
   }
 }
 
+// Forward pass: for reduction index kk = (c,r,s), tab[kk] = {offset of that tap inside
+// x_t relative to a pixel's window origin, (r<<16)|s}; entries past C*R*S get {0, -1}.
+__global__ void fwd_tap_table_kernel(Geo g, int entries, int2* __restrict__ tab) {
+  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kk >= entries) return;
+  int2 e;
+  if (kk < g.CRS) {
+    const int c = kk / g.RS, rs = kk - c * g.RS;
+    const int r = rs / g.S, s = rs - r * g.S;
+    e.x = (c * g.HW + r * g.W + s) * g.Np;
+    e.y = (r << 16) | s;
+  } else {
+    e.x = 0;
+    e.y = -1;
+  }
+  tab[kk] = e;
+}
+
 // Input-gradient pass: number of filter taps that reach input pixel (h,v).
 __device__ __forceinline__ int taps_reaching(const Geo& g, int h, int v) {
   int nr = 0, ns = 0;
