@@ -146,68 +146,100 @@ __device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase,
   }
 }
 
-// One staged chunk: 16 reduction steps of four 32x32x2 fp32 MFMAs per wavefront; the
-// LDS reads of group j+1 are issued before the 16 MFMAs of group j.
-// mid() -- the next chunk's address arithmetic and DMA issue -- is placed after the
-// first read group; its vector/scalar ALU and memory instructions may move across the
-// scheduling fences (LDS reads and MFMAs may not), so that they issue in the shadow of
-// the MFMAs instead of in front of them.
-constexpr int CS_FENCE = 0x0002 | 0x0004 | 0x0010;  // VALU, SALU and VMEM may cross
-
-template <bool ACOL, bool BCOL, class Mid>
-__device__ __forceinline__ void mfma_chunk(const float* As, const float* Bs, int wm, int wn, int lane,
-                                           f32x16 (&acc)[2][2], Mid&& mid) {
-  Frag a, na, b, nb;
-  read_frag<ACOL>(a, As, wm * 64, lane, 0);
-  read_frag<BCOL>(b, Bs, wn * 64, lane, 0);
+// Sixteen MFMAs: four reduction steps on the wavefront's 2x2 accumulator blocks.
+__device__ __forceinline__ void mfma_group(const Frag& a, const Frag& b, f32x16 (&acc)[2][2]) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (j < 3) {
-      read_frag<ACOL>(na, As, wm * 64, lane, j + 1);
-      read_frag<BCOL>(nb, Bs, wn * 64, lane, j + 1);
-    }
-    if (j == 0) mid();
-    __builtin_amdgcn_sched_barrier(CS_FENCE);  // keep the reads ahead of the MFMAs they overlap with
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[0][t], acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[1][t], acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[0][t], acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[1][t], acc[1][1], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(CS_FENCE);
-    if (j < 3) {
-      a = na;
-      b = nb;
-    }
+  for (int t = 0; t < 4; ++t) {
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[0][t], acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[1][t], acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[0][t], acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[1][t], acc[1][1], 0, 0, 0);
   }
 }
 
+// Scheduling fence: LDS reads and MFMAs keep their order across it, while vector/scalar
+// ALU and memory instructions (the next chunk's address arithmetic and DMA issue) may
+// move, so that they issue in the shadow of the MFMAs instead of in front of them.
+#define CS_FENCE() __builtin_amdgcn_sched_barrier(0x0002 | 0x0004 | 0x0010)
+
 // Main loop shared by the three passes.  A loader's issue(ch, tile, wv, live) enqueues the
 // four LDS-DMA loads of this wavefront's share of chunk ch (chunks are requested in
-// increasing order, once each).  LDS holds [A stage0][A stage1][B stage0][B stage1];
-// the stage in use alternates per chunk.
+// increasing order, once each; live = false turns the call into harmless dummy loads so
+// that the loop body needs no branch).  LDS holds [A stage0][A stage1][B stage0][B stage1].
+//
+// A chunk is four groups G0..G3 of 16 MFMAs.  The loop is rotated across the barrier:
+// after the barrier that publishes chunk ch, a wavefront first issues the DMA loads of
+// chunk ch+1 (which then have a whole iteration to land), then runs G2,G3 of chunk ch-1
+// from registers while the LDS reads of G0,G1 of chunk ch are in flight, then G0,G1 of
+// chunk ch while G2,G3 are being read.  Every LDS read has 16 MFMAs to hide behind.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
                                               float* smem, f32x16 (&acc)[2][2]) {
+  constexpr bool AC = LA::COL, BC = LB::COL;
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wv >> 1, wn = wv & 1;
+  const int wa = (wv >> 1) * 64, wb = (wv & 1) * 64;
   if (ch_begin >= ch_end) return;
+  Frag a0, b0, a1, b1;
+  // prologue: chunk ch_begin into stage 0
   la.issue(ch_begin, smem, wv, true);
   lb.issue(ch_begin, smem + 2 * TILE_F, wv, true);
   __syncthreads();  // includes the wait for this wavefront's own DMA loads
-  int cur = 0;  // float offset of the stage being computed on: 0 or TILE_F
-  for (int ch = ch_begin; ch < ch_end; ++ch) {
-    mfma_chunk<LA::COL, LB::COL>(smem + cur, smem + 2 * TILE_F + cur, wm, wn, lane, acc, [&]() {
-      const bool live = ch + 1 < ch_end;   // the last chunk issues dummy zero-page loads: no branch
+  read_frag<AC>(a0, smem, wa, lane, 0);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0);
+  read_frag<AC>(a1, smem, wa, lane, 1);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1);
+  {
+    const bool live = ch_begin + 1 < ch_end;
+    la.issue(ch_begin + 1, smem + TILE_F, wv, live);
+    lb.issue(ch_begin + 1, smem + 3 * TILE_F, wv, live);
+  }
+  CS_FENCE();
+  mfma_group(a0, b0, acc);
+  CS_FENCE();
+  read_frag<AC>(a0, smem, wa, lane, 2);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 2);
+  CS_FENCE();
+  mfma_group(a1, b1, acc);
+  CS_FENCE();
+  read_frag<AC>(a1, smem, wa, lane, 3);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 3);
+  __syncthreads();
+  int cur = TILE_F;  // float offset of the stage that holds chunk ch: TILE_F or 0
+  for (int ch = ch_begin + 1; ch < ch_end; ++ch) {
+    const float* As = smem + cur;
+    const float* Bs = smem + 2 * TILE_F + cur;
+    {
+      const bool live = ch + 1 < ch_end;
       la.issue(ch + 1, smem + (cur ^ TILE_F), wv, live);
       lb.issue(ch + 1, smem + 2 * TILE_F + (cur ^ TILE_F), wv, live);
-    });
+    }
+    CS_FENCE();
+    mfma_group(a0, b0, acc);  // G2 of chunk ch-1
+    CS_FENCE();
+    read_frag<AC>(a0, As, wa, lane, 0);
+    read_frag<BC>(b0, Bs, wb, lane, 0);
+    CS_FENCE();
+    mfma_group(a1, b1, acc);  // G3 of chunk ch-1
+    CS_FENCE();
+    read_frag<AC>(a1, As, wa, lane, 1);
+    read_frag<BC>(b1, Bs, wb, lane, 1);
+    CS_FENCE();
+    mfma_group(a0, b0, acc);  // G0 of chunk ch
+    CS_FENCE();
+    read_frag<AC>(a0, As, wa, lane, 2);
+    read_frag<BC>(b0, Bs, wb, lane, 2);
+    CS_FENCE();
+    mfma_group(a1, b1, acc);  // G1 of chunk ch
+    CS_FENCE();
+    read_frag<AC>(a1, As, wa, lane, 3);
+    read_frag<BC>(b1, Bs, wb, lane, 3);
     __syncthreads();
     cur ^= TILE_F;
   }
+  mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
+  mfma_group(a1, b1, acc);
 }
 
 // Position of accumulator register v of a 32x32 MFMA block inside the block.
