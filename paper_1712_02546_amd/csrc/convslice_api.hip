@@ -76,14 +76,32 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
 }
 
 struct BwdDataPlan {
-  int Cp;
-  size_t off_dyt, off_wt, off_dxt, off_perm, total;
+  bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
+  int Cp, Ks4, nch;
+  size_t off_dyt, off_wt, off_dxt, off_perm, off_tab, off_zero, off_T, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
   BwdDataPlan p;
   p.Cp = (int)round_up(g.C, 4);
+  p.Ks4 = (int)round_up(g.Ks, 4);
+  p.nch = (g.Ks + cs::BK - 1) / cs::BK;
+  // With C input channels the per-pixel form fills C of a tile's 128 rows; the scatter form
+  // fills C*R*S of them and pays one round trip of T through memory instead.
+  p.scatter = g.C <= 32 && (int64_t)g.CRS * g.PQ * g.Np < kMaxElems;
   size_t o = 0;
+  if (p.scatter) {
+    o += kZeroBytes;
+    p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
+    p.off_wt = o;   o += seg((int64_t)g.CRS * p.Ks4);          // w'[(c,r,s)][k]
+    p.off_tab = o;  o += seg((int64_t)(p.nch + 2) * cs::BK * 2);
+    p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
+    p.off_T = o;    o += seg((int64_t)g.CRS * g.PQ * g.Np);
+    p.off_dxt = p.off_perm = 0;
+    p.total = o;
+    return p;
+  }
+  p.off_tab = p.off_zero = p.off_T = 0;
   o += kZeroBytes;
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   o += kZeroBytes;
@@ -310,6 +328,39 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   // dy[n][k0*PQ ..] -> dy_t[Ks*P*Q][Np]
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
                       g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, dyt - cs::ZERO_PAGE_FLOATS, st);
+  if (p.scatter) {
+    // T[(c,r,s)][p][q][n] = sum_k w'[(c,r,s)][k] * dy_t[k][p][q][n] is the forward kernel of a 1x1 layer
+    // with Ks input channels, C*R*S kernels and dy_t as its input.
+    Geo g1 = g;
+    g1.C = g.Ks; g1.H = g.P; g1.W = g.Q; g1.K = g.CRS; g1.R = g1.S = 1; g1.sh = g1.sw = 1; g1.ph = g1.pw = 0;
+    g1.k0 = 0; g1.Ks = g.CRS; g1.HW = g.PQ; g1.RS = 1; g1.CRS = g.Ks;
+    float* T = (float*)(base + p.off_T);
+    float* zero = (float*)(base + p.off_zero);
+    int2* tab = (int2*)(base + p.off_tab);
+    // w[k][(c,r,s)] -> w'[(c,r,s)][Ks4]
+    launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0,
+                        p.Ks4, p.Ks4, 1, nullptr, st);
+    hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
+    const int entries = (p.nch + 2) * cs::BK;
+    hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g1, entries, tab);
+    if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    const int MB = (g1.Ks + cs::BM - 1) / cs::BM;
+    const int CT = (g1.PQ * g1.NB + 3) / 4;
+    probe.begin(st);
+    hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES,
+                       st, g1, wt, p.Ks4, p.Ks4, dyt, tab, zero, T, MB, CT, p.nch);
+    probe.end(st);
+    const dim3 grid((g.C * g.HW + 63) / 64, (g.N + 63) / 64);
+    const bool acc = desc->accumulate != 0;
+    if (desc->dtype == CONV_F32) {
+      if (acc) hipLaunchKernelGGL((cs::col2im_out_kernel<float, true>), grid, dim3(256), 0, st, g, T, (float*)dx);
+      else hipLaunchKernelGGL((cs::col2im_out_kernel<float, false>), grid, dim3(256), 0, st, g, T, (float*)dx);
+    } else {
+      if (acc) hipLaunchKernelGGL((cs::col2im_out_kernel<uint16_t, true>), grid, dim3(256), 0, st, g, T, (uint16_t*)dx);
+      else hipLaunchKernelGGL((cs::col2im_out_kernel<uint16_t, false>), grid, dim3(256), 0, st, g, T, (uint16_t*)dx);
+    }
+    return check_launch();
+  }
   // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
                       (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, wt - cs::ZERO_PAGE_FLOATS, st);

@@ -69,6 +69,58 @@ __global__ __launch_bounds__(256) void transpose_out_kernel(
   }
 }
 
+// Input gradient of layers with few input channels, second step.  The matrix-core step
+// leaves T[(c,r,s)][p][q][n] = sum_k w[k,c,r,s] * dy[n,k,p,q]; every input pixel (h,v)
+// collects the (r,s,p,q) combinations whose window position lands on it:
+//   dx[n][c][h][v] (+)= sum_{r,s : p*sh-ph+r = h, q*sw-pw+s = v} T[(c,r,s)][p][q][n]
+// in increasing (r,s) order.  Same tiling as transpose_out_kernel: a wavefront reads
+// T rows along n (coalesced) and the tile is written out along (c,h,v).
+// grid = (ceil(C*H*W/64), ceil(N/64)).
+template <typename Tout, bool ACC>
+__global__ __launch_bounds__(256) void col2im_out_kernel(Geo g, const float* __restrict__ T,
+                                                         Tout* __restrict__ dx) {
+  __shared__ float tile[64][65];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  const int CHW = g.C * g.HW;
+#pragma unroll 1
+  for (int i = 0; i < 16; ++i) {
+    const int ll = ty + 4 * i;
+    const int l = l0 + ll, n = n0 + tx;
+    float acc = 0.f;
+    if (l < CHW && n < g.Np) {
+      const int c = l / g.HW, hw = l - c * g.HW;
+      const int h = hw / g.W, v = hw - h * g.W;
+      for (int r = 0; r < g.R; ++r) {
+        const int hr = h + g.ph - r;
+        if (hr < 0) break;
+        const int p = hr / g.sh;
+        if (p * g.sh != hr || p >= g.P) continue;
+        for (int s = 0; s < g.S; ++s) {
+          const int vs = v + g.pw - s;
+          if (vs < 0) break;
+          const int q = vs / g.sw;
+          if (q * g.sw != vs || q >= g.Q) continue;
+          acc += T[((int64_t)(c * g.RS + r * g.S + s) * g.PQ + p * g.Q + q) * g.Np + n];
+        }
+      }
+    }
+    tile[ll][tx] = acc;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int nn = ty + 4 * i;
+    const int n = n0 + nn, l = l0 + tx;
+    if (n < g.N && l < CHW) {
+      Tout* p = dx + (int64_t)n * CHW + l;
+      float v = tile[tx][nn];
+      if (ACC) v += load_as_f32<Tout>(p);
+      store_from_f32<Tout>(p, v);
+    }
+  }
+}
+
 // dst[r*dstPitch + c] = c < cols ? src[r*srcPitch + c] : 0 for c < dstPitch: rows of
 // the filter matrix converted to fp32 and re-pitched to a multiple of 4.
 template <typename Tin>

@@ -61,11 +61,12 @@ def test_full_tensors_match_oracle_bf16(cfg):
     check(dev.bwd_weight()[k0:k1], oracle.conv_bwd_weight(sh, x, dy)[k0:k1], FP32_TOL, "dw")
 
 
-def test_disjoint_slices_assemble_the_full_layer():
+@pytest.mark.parametrize("C", [24, 48])
+def test_disjoint_slices_assemble_the_full_layer(C):
     """Same inputs, different kernels per device, outputs side by side (Section 4.1.2):
     slice calls into one y / dw give the full result; dx partial sums add up."""
     import torch
-    cfg = synth.random_layer(20, N=36, C=24, H=12, W=12, K=200, R=5, S=5, pad=1)
+    cfg = synth.random_layer(20, N=36, C=C, H=12, W=12, K=200, R=5, S=5, pad=1)
     x, w, dy = synth.make_inputs(cfg)
     full = Device(cfg, x, w, dy)
     y_full, dw_full, dx_full = full.fwd(), full.bwd_weight(), full.bwd_data()
@@ -86,8 +87,9 @@ def test_disjoint_slices_assemble_the_full_layer():
     check(dx.cpu().numpy(), oracle.conv_bwd_data(oracle_shape(cfg), dy, w), FP32_TOL, "dx vs oracle")
 
 
-def test_empty_slice_and_accumulate():
-    cfg = synth.random_layer(21, N=7, C=6, H=9, W=9, K=10, R=3, S=3, k0=4, k1=4)
+@pytest.mark.parametrize("C", [6, 40])   # few channels: scatter form; many: per-pixel form
+def test_empty_slice_and_accumulate(C):
+    cfg = synth.random_layer(21, N=7, C=C, H=9, W=9, K=10, R=3, S=3, k0=4, k1=4)
     x, w, dy = synth.make_inputs(cfg)
     dev = Device(cfg, x, w, dy)
     assert np.all(dev.fwd(fill=3.0) == 3.0)
