@@ -7,6 +7,10 @@ throughput in TFLOP/s on nominal FLOPs (3 * 2*N*Ks*P*Q*C*R*S per step), a roofli
 object for the slowest matrix-core kernel (timed live with HIP events placed around it by
 the library's one-shot probe), and the CPU oracle timed on a bounded sample of the same
 layer as a reported baseline.
+
+`--table` instead measures every benchmark configuration (fp32, and bf16 for the
+larger-image layers) and prints one JSON line per configuration plus a markdown table
+on stderr; it is not the default contract line.
 """
 from __future__ import annotations
 
@@ -22,9 +26,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
-# HBM bytes per launch of the slowest kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until such a run exists for the workload.
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of a matrix-core kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# scaled by a copy kernel of known size (profiles/cfg3_f32_hbm_traffic.md).  None where not measured.
 TRAFFIC_BYTES = {}
+
+METRIC = "conv fwd+bwd TFLOP/s and % of MFMA peak, 1500-kernel 5x5 layer, batch 128"
 
 
 def find_hip_runtime():
@@ -81,30 +88,20 @@ def cpu_baseline(cfg, x, w, dy, images):
                       f"fwd+bwd_data+bwd_weight, fp64 direct loops, {dt:.1f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg3", help="cfg1..cfg5b (default: the 1500-kernel layer)")
-    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--cpu-images", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
-                 "(the kernel-slice argument is how the layer would be sharded across devices)")
+KERNEL_OF = {"conv_fwd": "fwd_gemm_kernel", "conv_bwd_data": "bwd_data_gemm_kernel",
+             "conv_bwd_weight": "bwd_weight_gemm_kernel"}
 
+
+def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
+    """Times `steps` steps of one configuration; returns the result dictionary."""
     import numpy as np
     import torch
 
     import paper_1712_02546_amd as cs
     from paper_1712_02546_amd import synth
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    cs.load()
-    cfg = synth.CONFIGS[args.config]
-    dtype = cs.CONV_F32 if args.dtype == "f32" else cs.CONV_BF16
+    cfg = synth.CONFIGS[cfg_name]
+    dtype = cs.CONV_F32 if dtype_name == "f32" else cs.CONV_BF16
     k0, k1 = cfg.slice
     x, w, dy = synth.make_inputs(cfg)
     if dtype == cs.CONV_BF16:
@@ -129,8 +126,6 @@ def main():
     passes = (("conv_fwd", cs.conv_fwd, (xd, wd, y)),
               ("conv_bwd_data", cs.conv_bwd_data, (dyd, wd, dx)),
               ("conv_bwd_weight", cs.conv_bwd_weight, (xd, dyd, dw)))
-    kernel_names = {"conv_fwd": "fwd_gemm_kernel", "conv_bwd_data": "bwd_data_gemm_kernel",
-                    "conv_bwd_weight": "bwd_weight_gemm_kernel"}
 
     def step(events=None, base=0):
         for i, (_, fn, (a, b, out)) in enumerate(passes):
@@ -138,47 +133,116 @@ def main():
                 cs.conv_probe_next_call(events.ev[base + 2 * i], events.ev[base + 2 * i + 1])
             fn(desc, a, b, out, ws, stream)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
-    events = HipEvents(6 * args.steps)
+    events = HipEvents(6 * steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for s in range(args.steps):
+    for s in range(steps):
         step(events, 6 * s)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     F = cfg.flops_per_pass
     value = 3 * F / (ms_per_step * 1e-3) / 1e12
     kern = []
     for i, (name, _, _) in enumerate(passes):
-        d = [events.elapsed_ms(6 * s + 2 * i, 6 * s + 2 * i + 1) for s in range(args.steps)]
+        d = [events.elapsed_ms(6 * s + 2 * i, 6 * s + 2 * i + 1) for s in range(steps)]
         avg = sum(d) / len(d)
-        kern.append({"entry": name, "kernel": kernel_names[name], "avg_ms": avg, "min_ms": min(d),
+        kern.append({"entry": name, "kernel": KERNEL_OF[name], "avg_ms": avg, "min_ms": min(d),
                      "tflops": F / (avg * 1e-3) / 1e12})
     events.destroy()
+    if per_pass:  # whole entry point (layout kernels included), each pass timed on its own
+        for k, (name, fn, (a, b, out)) in zip(kern, passes):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn(desc, a, b, out, ws, stream)
+            torch.cuda.synchronize()
+            k["entry_ms"] = (time.perf_counter() - t0) * 1e3 / steps
     dom = max(kern, key=lambda k: k["avg_ms"])
-    peak = PEAK_TFLOPS[args.dtype]
+    peak = PEAK_TFLOPS[dtype_name]
+    es = 4 if dtype == cs.CONV_F32 else 2
+    min_bytes = 3 * ((x.size + y.numel() * (k1 - k0) // cfg.K) * es + w.size * (k1 - k0) // cfg.K * es)
     roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s",
                 "frac": dom["tflops"] / peak, "avg_ms": dom["avg_ms"],
-                "traffic": TRAFFIC_BYTES.get((args.config, args.dtype, dom["kernel"]))}
+                "traffic": TRAFFIC_BYTES.get((cfg_name, dtype_name, dom["kernel"]))}
     out = {
-        "metric": "conv fwd+bwd TFLOP/s and % of MFMA peak, 1500-kernel 5x5 layer, batch 128",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": METRIC,
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": args.dtype, "data": "synthetic",
+        "dtype": dtype_name, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: batch {cfg.N}, input {cfg.C}x{cfg.H}x{cfg.W}, {cfg.K} kernels "
                                f"{cfg.R}x{cfg.S} stride {cfg.stride} pad {cfg.pad}, slice [{k0},{k1}), "
                                "fwd + bwd_data + bwd_weight",
                    "flops_per_step": 3 * F},
         "frac_of_mfma_peak": value / peak,
+        "min_hbm_bytes_per_step": min_bytes,
+        "hbm_gbs_on_min_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "roofline": roofline,
         "kernels": kern,
     }
-    if args.cpu_images > 0:
-        out["cpu_baseline"] = cpu_baseline(cfg, x, w, dy, args.cpu_images)
-    print(json.dumps(out))
+    if cpu_images > 0:
+        out["cpu_baseline"] = cpu_baseline(cfg, x, w, dy, cpu_images)
+    del xd, wd, dyd, y, dx, dw, ws
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg3", help="cfg1..cfg5b (default: the 1500-kernel layer)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--cpu-images", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--table", action="store_true", help="measure all configurations (not the contract line)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="first run one plain device copy of this many MiB (a kernel of known HBM traffic "
+                         "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings with)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
+                 "(the kernel-slice argument is how the layer would be sharded across devices)")
+
+    import torch
+
+    import paper_1712_02546_amd as cs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cs.load()
+
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib * (1 << 18), dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
+    if not args.table:
+        print(json.dumps(measure(args.config, args.dtype, args.steps, args.warmup, args.cpu_images)))
+        return
+
+    runs = [("cfg1", "f32"), ("cfg2", "f32"), ("cfg3", "f32"), ("cfg4", "f32"), ("cfg5a", "f32"), ("cfg5b", "f32"),
+            ("cfg5a", "bf16"), ("cfg5b", "bf16")]
+    rows = []
+    for name, dt in runs:
+        r = measure(name, dt, args.steps, args.warmup, 0, per_pass=True)
+        print(json.dumps(r), flush=True)
+        rows.append((name, dt, r))
+    print("| cfg | dtype | fwd ms | bwd_data ms | bwd_weight ms | step ms | TFLOP/s | % MFMA peak | GB/s on minimal bytes |",
+          file=sys.stderr)
+    print("|---|---|---|---|---|---|---|---|---|", file=sys.stderr)
+    for name, dt, r in rows:
+        k = {x["entry"]: x for x in r["kernels"]}
+        print(f"| {name} | {dt} | {k['conv_fwd']['entry_ms']:.3f} | {k['conv_bwd_data']['entry_ms']:.3f} | "
+              f"{k['conv_bwd_weight']['entry_ms']:.3f} | {r['ms_per_step']:.3f} | {r['value']:.2f} | "
+              f"{100 * r['frac_of_mfma_peak']:.1f} | {r['hbm_gbs_on_min_bytes']:.0f} |", file=sys.stderr)
 
 
 if __name__ == "__main__":

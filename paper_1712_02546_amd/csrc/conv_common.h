@@ -162,16 +162,31 @@ __device__ __forceinline__ void mfma_group(const Frag& a, const Frag& b, f32x16 
 // move, so that they issue in the shadow of the MFMAs instead of in front of them.
 #define CS_FENCE() __builtin_amdgcn_sched_barrier(0x0002 | 0x0004 | 0x0010)
 
-// Main loop shared by the three passes.  A loader's issue(ch, tile, wv, live) enqueues the
-// four LDS-DMA loads of this wavefront's share of chunk ch (chunks are requested in
-// increasing order, once each; live = false turns the call into harmless dummy loads so
-// that the loop body needs no branch).  LDS holds [A stage0][A stage1][B stage0][B stage1].
+// Main loop shared by the three passes.  A loader stages one operand; per chunk it is
+// driven as begin(ch, live), addr(0..3), end(): addr(i) is this lane's global address
+// for LDS-DMA load number i of this wavefront's share of chunk ch (chunks are requested
+// in increasing order, once each; live = false marks the chunk past the last one, whose
+// loads must stay harmless so that the loop body needs no branch).  LDS holds
+// [A stage0][A stage1][B stage0][B stage1].
 //
 // A chunk is four groups G0..G3 of 16 MFMAs.  The loop is rotated across the barrier:
 // after the barrier that publishes chunk ch, a wavefront first issues the DMA loads of
 // chunk ch+1 (which then have a whole iteration to land), then runs G2,G3 of chunk ch-1
 // from registers while the LDS reads of G0,G1 of chunk ch are in flight, then G0,G1 of
 // chunk ch while G2,G3 are being read.  Every LDS read has 16 MFMAs to hide behind.
+template <class LA, class LB>
+__device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, float* tb, int wv, bool live) {
+  la.begin(ch, live);
+  lb.begin(ch, live);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    dma16(la.addr(i), ta + (wv * 4 + i) * 256);
+    dma16(lb.addr(i), tb + (wv * 4 + i) * 256);
+  }
+  la.end();
+  lb.end();
+}
+
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
                                               float* smem, f32x16 (&acc)[2][2]) {
@@ -183,18 +198,13 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   if (ch_begin >= ch_end) return;
   Frag a0, b0, a1, b1;
   // prologue: chunk ch_begin into stage 0
-  la.issue(ch_begin, smem, wv, true);
-  lb.issue(ch_begin, smem + 2 * TILE_F, wv, true);
+  issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
   __syncthreads();  // includes the wait for this wavefront's own DMA loads
   read_frag<AC>(a0, smem, wa, lane, 0);
   read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0);
   read_frag<AC>(a1, smem, wa, lane, 1);
   read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1);
-  {
-    const bool live = ch_begin + 1 < ch_end;
-    la.issue(ch_begin + 1, smem + TILE_F, wv, live);
-    lb.issue(ch_begin + 1, smem + 3 * TILE_F, wv, live);
-  }
+  issue_all(la, lb, ch_begin + 1, smem + TILE_F, smem + 3 * TILE_F, wv, ch_begin + 1 < ch_end);
   CS_FENCE();
   mfma_group(a0, b0, acc);
   CS_FENCE();
@@ -210,11 +220,7 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   for (int ch = ch_begin + 1; ch < ch_end; ++ch) {
     const float* As = smem + cur;
     const float* Bs = smem + 2 * TILE_F + cur;
-    {
-      const bool live = ch + 1 < ch_end;
-      la.issue(ch + 1, smem + (cur ^ TILE_F), wv, live);
-      lb.issue(ch + 1, smem + 2 * TILE_F + (cur ^ TILE_F), wv, live);
-    }
+    issue_all(la, lb, ch + 1, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F), wv, ch + 1 < ch_end);
     CS_FENCE();
     mfma_group(a0, b0, acc);  // G2 of chunk ch-1
     CS_FENCE();

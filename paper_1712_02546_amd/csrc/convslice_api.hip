@@ -69,7 +69,7 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
-  p.off_tab = o; o += seg((int64_t)(p.nch + 2) * cs::BK * 2);
+  p.off_tab = o; o += seg((int64_t)(p.nch + 3) * cs::BK * 2);
   p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.total = o;
   return p;
@@ -94,7 +94,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     o += kZeroBytes;
     p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
     p.off_wt = o;   o += seg((int64_t)g.CRS * p.Ks4);          // w'[(c,r,s)][k]
-    p.off_tab = o;  o += seg((int64_t)(p.nch + 2) * cs::BK * 2);
+    p.off_tab = o;  o += seg((int64_t)(p.nch + 3) * cs::BK * 2);
     p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
     p.off_T = o;    o += seg((int64_t)g.CRS * g.PQ * g.Np);
     p.off_dxt = p.off_perm = 0;
@@ -276,9 +276,9 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   } else {
     wmat = (const float*)w + (size_t)g.k0 * g.CRS;
   }
-  // two chunks more than needed: the loaders fetch entries one chunk ahead, also in the last (dummy) issue
+  // three chunks more than needed: addresses are computed two chunks ahead and the table is read one further
   int2* tab = (int2*)(base + p.off_tab);
-  const int entries = (p.nch + 2) * cs::BK;
+  const int entries = (p.nch + 3) * cs::BK;
   hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
   const bool pad = needs_pad_checks(g);
   if ((rc = allow_big_lds(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK)
@@ -341,7 +341,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0,
                         p.Ks4, p.Ks4, 1, nullptr, st);
     hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
-    const int entries = (p.nch + 2) * cs::BK;
+    const int entries = (p.nch + 3) * cs::BK;
     hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g1, entries, tab);
     if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
     const int MB = (g1.Ks + cs::BM - 1) / cs::BM;
@@ -365,7 +365,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
                       (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, wt - cs::ZERO_PAGE_FLOATS, st);
   hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
-  const int lds = cs::SMEM_BYTES + (g.RS + 1) * 20;  // tiles + tap list + per-block tap offsets
+  const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;  // tiles + tap list + per-block tap offsets
   if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel, lds)) != CONV_OK) return rc;
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;

@@ -19,6 +19,8 @@ struct FwdLoadA {
   const float* p[4];
   const float* zero;
   int kq4, cols;  // float offset of this lane's slot inside a chunk; valid row length
+  int adv;        // uniform: float offset of the chunk being issued
+  bool ok;
   __device__ FwdLoadA(const float* w, int ldw, int cols_, int m0, int Ks, const float* zero_)
       : zero(zero_), cols(cols_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -29,12 +31,14 @@ struct FwdLoadA {
       p[i] = w + (int64_t)m * ldw + kq4;
     }
   }
-  // live = false turns the whole issue into harmless zero-page loads (keeps the loop branch free).
-  __device__ __forceinline__ void issue(int ch, float* tile, int wv, bool live) {
-    const bool ok = live && ch * BK + kq4 < cols;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(ok ? p[i] + ch * BK : zero, dma_dst(tile, wv, i));
+  // begin/addr/end: the addresses of one chunk's four DMA loads.  live = false (chunks past
+  // the last one) must stay harmless: such loads read the zero page.
+  __device__ __forceinline__ void begin(int ch, bool live) {
+    adv = ch * BK;
+    ok = live & (adv + kq4 < cols);   // past the row end the operand must be zero
   }
+  __device__ __forceinline__ const float* addr(int i) const { return ok ? p[i] + adv : zero; }
+  __device__ __forceinline__ void end() {}
 };
 
 // B[kk][col] = x_t[tap kk of the column block's pixel][n] (row image), zero where the
@@ -46,17 +50,17 @@ struct FwdLoadB {
   static constexpr bool COL = false;
   const float* xt;       // a zero page sits ZERO_PAGE_FLOATS in front of x_t
   const int4* tab2;
-  int4 nxt[4];           // table entries (two rows each) of the next chunk to issue; uniform
+  int4 cur[4], nxt[4];   // table entries (two rows each) of the chunk being issued / the next one; uniform
   int pixbase, h0, w0, H, W;
-  bool cbok, upper;
+  bool upper;
   __device__ FwdLoadB(const Geo& g, const float* xt_, const int2* tab, int ct) : xt(xt_), tab2((const int4*)tab) {
     const int l = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cq = l & 31;
-    const int gcb = ct * 4 + (cq >> 3);
-    cbok = gcb < g.PQ * g.NB;
-    const int pix = cbok ? gcb / g.NB : 0;
-    const int nb = cbok ? gcb - pix * g.NB : 0;
+    // column blocks past the end are computed like block 0 and never stored
+    const int gcb = ct * 4 + (cq >> 3) < g.PQ * g.NB ? ct * 4 + (cq >> 3) : 0;
+    const int pix = gcb / g.NB;
+    const int nb = gcb - pix * g.NB;
     const int p = pix / g.Q, q = pix - p * g.Q;
     h0 = p * g.sh - g.ph;
     w0 = q * g.sw - g.pw;
@@ -67,21 +71,26 @@ struct FwdLoadB {
 #pragma unroll
     for (int i = 0; i < 4; ++i) nxt[i] = tab2[4 * wv + i];
   }
-  __device__ __forceinline__ void issue(int ch, float* tile, int wv, bool live) {
-    int4 e[4];
+  // Table rows past C*R*S repeat row 0 (the filter operand is zero there), and the table
+  // runs three chunks past the end, so neither the tail nor the dummy chunks need a test.
+  __device__ __forceinline__ void begin(int ch, bool) {
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) e[i] = nxt[i];
+    for (int i = 0; i < 4; ++i) cur[i] = nxt[i];
 #pragma unroll
     for (int i = 0; i < 4; ++i) nxt[i] = tab2[(ch + 1) * (BK / 2) + 4 * wv + i];  // rows 8*wv+2*i, +1 of chunk ch+1
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int off = upper ? e[i].z : e[i].x;
-      const int rs = upper ? e[i].w : e[i].y;
-      bool ok = live & cbok & (rs >= 0);
-      if (PAD) ok = ok & ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
-      dma16(xt + (ok ? off + pixbase : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
-    }
   }
+  __device__ __forceinline__ const float* addr(int i) const {
+    const int off = upper ? cur[i].z : cur[i].x;
+    int idx = off + pixbase;
+    if (PAD) {
+      const int rs = upper ? cur[i].w : cur[i].y;
+      const bool ok = ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
+      idx = ok ? idx : -ZERO_PAGE_FLOATS;
+    }
+    return xt + idx;
+  }
+  __device__ __forceinline__ void end() {}
 };
 
 // y_t[k][pix][n] for the slice; one workgroup per 128 kernels x 4 column blocks.
@@ -132,12 +141,11 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
 struct TapWalk {
   int ti, kc, nkc;
   __device__ TapWalk(int nkc_) : ti(0), kc(0), nkc(nkc_) {}
-  __device__ __forceinline__ void next() {
+  __device__ __forceinline__ void next() {   // branch-free carry
     ++kc;
-    if (kc == nkc) {
-      kc = 0;
-      ++ti;
-    }
+    const int c = kc == nkc;
+    kc = c ? 0 : kc;
+    ti += c;
   }
 };
 
@@ -148,7 +156,8 @@ struct BwdDataLoadA {
   const float* wt;
   const int* taps;
   int Ks, Cp, S, krow, lane_off, tap;   // tap = flat (r*S+s) of walk.ti, fetched one call ahead
-  bool cok;
+  int base;
+  bool cok, live;
   TapWalk walk;
   __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_)
       : wt(wt_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), walk(nkc_) {
@@ -160,15 +169,17 @@ struct BwdDataLoadA {
     const int e = taps[0];
     tap = (e >> 16) * S + (e & 0xffff);
   }
-  __device__ __forceinline__ void issue(int, float* tile, int wv, bool live) {
-    const int base = (tap * Ks + walk.kc * BK) * Cp + lane_off;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool ok = live & cok & (walk.kc * BK + krow + 2 * i < Ks);
-      dma16(wt + (ok ? base + 2 * i * Cp : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
-    }
+  __device__ __forceinline__ void begin(int, bool live_) {
+    live = live_ & cok;
+    base = (tap * Ks + walk.kc * BK) * Cp + lane_off;
+  }
+  __device__ __forceinline__ const float* addr(int i) const {
+    const bool ok = live & (walk.kc * BK + krow + 2 * i < Ks);
+    return wt + (ok ? base + 2 * i * Cp : -ZERO_PAGE_FLOATS);
+  }
+  __device__ __forceinline__ void end() {
     walk.next();
-    const int e = taps[walk.ti];   // one entry past the list is allocated, so this stays in bounds
+    const int e = taps[walk.ti];   // entries past the list are allocated, so this stays in bounds
     tap = (e >> 16) * S + (e & 0xffff);
   }
 };
@@ -181,6 +192,8 @@ struct BwdDataLoadB {
   const float* dyt;
   const int* tapoff;
   int Ks, PQNp, krow, cb, lane_off, toff;   // toff = tapoff[walk.ti][cb], fetched one call ahead
+  int base;
+  bool live;
   TapWalk walk;
   __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* tapoff_, int nkc_)
       : dyt(dyt_), tapoff(tapoff_), Ks(g.Ks), PQNp(g.PQ * g.Np), walk(nkc_) {
@@ -191,13 +204,15 @@ struct BwdDataLoadB {
     lane_off = 4 * (cq & 7);
     toff = tapoff[cb];
   }
-  __device__ __forceinline__ void issue(int, float* tile, int wv, bool live) {
-    const int base = (walk.kc * BK + krow) * PQNp + toff + lane_off;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool ok = live & (toff >= 0) & (walk.kc * BK + krow + 2 * i < Ks);
-      dma16(dyt + (ok ? base + 2 * i * PQNp : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
-    }
+  __device__ __forceinline__ void begin(int, bool live_) {
+    live = live_ & (toff >= 0);
+    base = (walk.kc * BK + krow) * PQNp + toff + lane_off;
+  }
+  __device__ __forceinline__ const float* addr(int i) const {
+    const bool ok = live & (walk.kc * BK + krow + 2 * i < Ks);
+    return dyt + (ok ? base + 2 * i * PQNp : -ZERO_PAGE_FLOATS);
+  }
+  __device__ __forceinline__ void end() {
     walk.next();
     toff = tapoff[walk.ti * 4 + cb];
   }
@@ -209,8 +224,8 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
                                                            const int* __restrict__ perm,
                                                            float* __restrict__ dxt, int MB, int CT) {
   extern __shared__ __align__(16) float smem[];
-  int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 1]
-  int* s_tapoff = s_taps + g.RS + 1;           // [RS + 1][4]
+  int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 3]: the loaders run up to three entries past the list
+  int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][4]
   __shared__ int s_ntaps;
   int mb, ct;
   if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
@@ -256,11 +271,9 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
       }
       cnt += __popcll(mask);
     }
-    if (lane < 4) s_tapoff[cnt * 4 + lane] = -1;   // the entry the loaders fetch after the last tap
-    if (lane == 0) {
-      s_taps[cnt] = 0;
-      s_ntaps = cnt;
-    }
+    if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;   // the entries the loaders fetch after the last tap
+    if (lane < 3) s_taps[cnt + lane] = 0;
+    if (lane == 0) s_ntaps = cnt;
   }
   __syncthreads();
   const int ntaps = s_ntaps;
@@ -301,6 +314,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
 struct BwdWeightLoadA {
   static constexpr bool COL = true;
   const float* p[4];
+  int64_t adv;   // uniform
   __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int kq4 = 4 * ((l & 7) ^ (l >> 3));
@@ -310,24 +324,23 @@ struct BwdWeightLoadA {
       p[i] = dyt + (int64_t)m * g.PQ * g.Np + kq4;
     }
   }
-  __device__ __forceinline__ void issue(int ch, float* tile, int wv, bool live) {
-    const int64_t adv = (int64_t)(live ? ch : 0) * BK;   // the dummy issue re-reads chunk 0
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(p[i] + adv, dma_dst(tile, wv, i));
-  }
+  __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK; }  // dummy: chunk 0
+  __device__ __forceinline__ const float* addr(int i) const { return p[i] + adv; }
+  __device__ __forceinline__ void end() {}
 };
 
 // B^T[j][kk] = x_t[c_j][p*sh-ph+r_j][q*sw-pw+s_j][n] (col image); zero where tap j is in
-// the padding or j is past C*R*S.  The chunk's output pixel (p,q) and image block nb are
-// uniform counters; a lane adds its constant column offset to their uniform offset.
+// the padding.  Columns j past C*R*S are computed like column 0 and never stored.  The
+// chunk's output pixel (p,q) and image block nb are uniform counters; a lane adds its
+// constant column offset to their uniform offset.
 template <bool PAD>
 struct BwdWeightLoadB {
   static constexpr bool COL = true;
   const float* xt;       // a zero page sits ZERO_PAGE_FLOATS in front of x_t
   int coff[4], rj[4], sj[4];
-  bool colok[4];
   int NB, Q, sh, sw, ph, pw, H, W, Np;
-  int p, q, nb;   // uniform position of the next chunk to issue
+  int p, q, nb;          // uniform position of the next chunk to issue
+  int h0, v0, uoff;      // uniform, of the chunk being issued
   __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, int ch0) : xt(xt_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     NB = g.NB; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W; Np = g.Np;
@@ -335,8 +348,7 @@ struct BwdWeightLoadB {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = j0 + 32 * wv + 8 * i + (l >> 3);
-      colok[i] = j < g.CRS;
-      const int jj = colok[i] ? j : 0;
+      const int jj = j < g.CRS ? j : 0;
       const int c = jj / g.RS, rs = jj - c * g.RS;
       rj[i] = rs / g.S;
       sj[i] = rs - rj[i] * g.S;
@@ -347,22 +359,27 @@ struct BwdWeightLoadB {
     p = pix / Q;
     q = pix - p * Q;
   }
-  __device__ __forceinline__ void issue(int, float* tile, int wv, bool live) {
-    const int h0 = p * sh - ph, v0 = q * sw - pw;
-    const int uoff = (h0 * W + v0) * Np + nb * 32;   // uniform
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      bool ok = live & colok[i];
-      if (PAD) ok = ok & ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
-      dma16(xt + (ok ? coff[i] + uoff : -ZERO_PAGE_FLOATS), dma_dst(tile, wv, i));
+  __device__ __forceinline__ void begin(int, bool live) {
+    h0 = live ? p * sh - ph : 0;       // the dummy issue re-reads the first pixel
+    v0 = live ? q * sw - pw : 0;
+    uoff = (h0 * W + v0) * Np + (live ? nb * 32 : 0);
+  }
+  __device__ __forceinline__ const float* addr(int i) const {
+    int idx = coff[i] + uoff;
+    if (PAD) {
+      const bool ok = ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
+      idx = ok ? idx : -ZERO_PAGE_FLOATS;
     }
-    if (++nb == NB) {
-      nb = 0;
-      if (++q == Q) {
-        q = 0;
-        ++p;
-      }
-    }
+    return xt + idx;
+  }
+  __device__ __forceinline__ void end() {   // branch-free carry: (nb, q, p) += 1 chunk
+    ++nb;
+    const int cq = nb == NB;
+    nb = cq ? 0 : nb;
+    q += cq;
+    const int cp = q == Q;
+    q = cp ? 0 : q;
+    p += cp;
   }
 };
 

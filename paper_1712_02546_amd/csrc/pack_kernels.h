@@ -136,21 +136,18 @@ __global__ __launch_bounds__(256) void repitch_rows_kernel(
 }
 
 // Forward pass: for reduction index kk = (c,r,s), tab[kk] = {offset of that tap inside
-// x_t relative to a pixel's window origin, (r<<16)|s}; entries past C*R*S get {0, -1}.
+// x_t relative to a pixel's window origin, (r<<16)|s}.  Entries past C*R*S repeat entry 0:
+// the filter operand is zero there, so any finite input value will do.
 __global__ void fwd_tap_table_kernel(Geo g, int entries, int2* __restrict__ tab) {
-  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
-  if (kk >= entries) return;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= entries) return;
+  const int kk = i < g.CRS ? i : 0;
+  const int c = kk / g.RS, rs = kk - c * g.RS;
+  const int r = rs / g.S, s = rs - r * g.S;
   int2 e;
-  if (kk < g.CRS) {
-    const int c = kk / g.RS, rs = kk - c * g.RS;
-    const int r = rs / g.S, s = rs - r * g.S;
-    e.x = (c * g.HW + r * g.W + s) * g.Np;
-    e.y = (r << 16) | s;
-  } else {
-    e.x = 0;
-    e.y = -1;
-  }
-  tab[kk] = e;
+  e.x = (c * g.HW + r * g.W + s) * g.Np;
+  e.y = (r << 16) | s;
+  tab[i] = e;
 }
 
 // Input-gradient pass: number of filter taps that reach input pixel (h,v).
