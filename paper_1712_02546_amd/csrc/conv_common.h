@@ -62,21 +62,34 @@ template <> __device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p
 // that neighbours in the line share both operand panels -- and the line is cut
 // into 8 equal pieces, one per XCD.  Every XCD gets the same number of tiles
 // (+-1) and the tiles resident together on it are neighbours in the line.
-__device__ __forceinline__ bool tile_contiguous(int g, int MB, int CT, int& mb, int& ct) {
-  const int T = MB * CT;
-  const int per = (T + 7) >> 3;
-  const int s = g >> 3;
-  const int L = (g & 7) * per + s;
-  if (s >= per || L >= T) return false;
+__device__ __forceinline__ void tile_from_line(int L, int MB, int CT, int& mb, int& ct) {
   const int full = 8 * MB;                 // tiles in a full group
   const int grp = L / full;
   const int rem = L - grp * full;
   const int gs = min(8, CT - 8 * grp);     // column tiles in this group (last may be ragged)
   mb = rem / gs;
   ct = 8 * grp + (rem - mb * gs);
-  return true;
 }
-static inline int grid_contiguous(int MB, int CT) { return 8 * ((MB * CT + 7) / 8); }
+// Workgroup g of a grid of grid_contiguous(n) -> position in the line, for the first n tiles.
+__device__ __forceinline__ bool line_contiguous(int g, int n, int& L) {
+  const int per = (n + 7) >> 3;
+  const int s = g >> 3;
+  L = (g & 7) * per + s;
+  return s < per && L < n;
+}
+__host__ __device__ static inline int grid_contiguous(int n) { return 8 * ((n + 7) / 8); }
+
+// Tail plan for the equal-cost passes.  With S workgroup slots on the chip (two per CU)
+// and T tiles, the first nFull = S*floor(T/S) tiles are computed whole, one workgroup
+// each, in full rounds.  The remaining nTail tiles would occupy only part of the chip for
+// a whole tile time; instead their nTail*nch reduction chunks are dealt out in equal runs
+// of `units` consecutive chunks to nTailWg workgroups (a run covers at most two tiles).
+// Each run writes its accumulators to a scratch slot and a fix-up kernel adds the slots
+// of a tile in run order, so the result does not depend on timing.
+struct TailPlan {
+  int nFull, nTail, units, nTailWg;
+};
+constexpr int TAIL_SLOT_FLOATS = 64 * NT;   // one wavefront-layout accumulator image (64 KB)
 
 // "Dealt" map, for the input-gradient pass whose column tiles are sorted by
 // decreasing cost: column tile ct goes to XCD ct%8 (so every XCD gets the same mix

@@ -53,10 +53,46 @@ inline size_t seg(int64_t floats) { return (size_t)round_up(floats * 4, 256); }
 // A buffer that the DMA loaders read gets a zero page directly in front of it.
 constexpr size_t kZeroBytes = cs::ZERO_PAGE_FLOATS * 4;
 
+// Workgroup slots on the chip: two 64 KB workgroups fit a compute unit's 160 KB of LDS.
+int chip_slots() {
+  static int slots = 0;
+  if (slots == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      slots = 2 * cus;
+    else
+      return 512;   // no device visible (workspace queries on a CPU-only host): MI355X has 256 CUs
+  }
+  return slots;
+}
+
+// Splits T equal tiles of nch chunks into whole-tile rounds and an evenly shared tail.
+cs::TailPlan plan_tail(int T, int nch) {
+  cs::TailPlan tp;
+  const int S = chip_slots();
+  const int rem = T % S;
+  if (rem == 0 || nch < 16) {   // nothing left over, or reductions too short to be worth splitting
+    tp.nFull = T; tp.nTail = 0; tp.units = 1; tp.nTailWg = 0;
+    return tp;
+  }
+  tp.nFull = T - rem;
+  tp.nTail = rem;
+  const int64_t work = (int64_t)rem * nch;
+  tp.units = (int)((work + S - 1) / S);
+  tp.nTailWg = (int)((work + tp.units - 1) / tp.units);
+  return tp;
+}
+inline size_t tail_bytes(const cs::TailPlan& tp) {
+  return tp.nTailWg > 0 ? (size_t)tp.nTailWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
+}
+
 struct FwdPlan {
   bool repitch;      // filters copied to fp32 rows of pitch ldw (bf16 input or C*R*S not a multiple of 4)
   int ldw, nch;
-  size_t off_xt, off_yt, off_w, off_tab, off_zero, total;
+  int MB, CT;
+  cs::TailPlan tail;
+  size_t off_xt, off_yt, off_w, off_tab, off_zero, off_tail, total;
 };
 
 FwdPlan plan_fwd(const Geo& g, int dtype) {
@@ -64,6 +100,9 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.repitch = dtype != CONV_F32 || (g.CRS % 4) != 0;
   p.ldw = p.repitch ? (int)round_up(g.CRS, 4) : g.CRS;
   p.nch = (g.CRS + cs::BK - 1) / cs::BK;
+  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
+  p.CT = (g.PQ * g.NB + 3) / 4;
+  p.tail = plan_tail(p.MB * p.CT, p.nch);
   size_t o = 0;
   o += kZeroBytes;
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
@@ -71,14 +110,16 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
   p.off_tab = o; o += seg((int64_t)(p.nch + 3) * cs::BK * 2);
   p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
+  p.off_tail = o; o += tail_bytes(p.tail);
   p.total = o;
   return p;
 }
 
 struct BwdDataPlan {
   bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
-  int Cp, Ks4, nch;
-  size_t off_dyt, off_wt, off_dxt, off_perm, off_tab, off_zero, off_T, total;
+  int Cp, Ks4, nch, MB1, CT1;
+  cs::TailPlan tail;
+  size_t off_dyt, off_wt, off_dxt, off_perm, off_tab, off_zero, off_T, off_tail, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
@@ -97,6 +138,10 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     p.off_tab = o;  o += seg((int64_t)(p.nch + 3) * cs::BK * 2);
     p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
     p.off_T = o;    o += seg((int64_t)g.CRS * g.PQ * g.Np);
+    p.MB1 = (g.CRS + cs::BM - 1) / cs::BM;
+    p.CT1 = (g.PQ * g.NB + 3) / 4;
+    p.tail = plan_tail(p.MB1 * p.CT1, p.nch);
+    p.off_tail = o; o += tail_bytes(p.tail);
     p.off_dxt = p.off_perm = 0;
     p.total = o;
     return p;
@@ -114,7 +159,8 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
 
 struct BwdWeightPlan {
   int MB, CT, nch, splits, chPerSplit;
-  size_t off_xt, off_dyt, off_part, total;
+  cs::TailPlan tail;
+  size_t off_xt, off_dyt, off_part, off_tail, total;
 };
 
 BwdWeightPlan plan_bwd_weight(const Geo& g) {
@@ -135,6 +181,12 @@ BwdWeightPlan plan_bwd_weight(const Geo& g) {
   p.off_xt = o;   o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
+  if (p.splits > 1) {   // already split over gridDim.y: whole tiles only
+    p.tail.nFull = (int)tiles; p.tail.nTail = 0; p.tail.units = 1; p.tail.nTailWg = 0;
+  } else {
+    p.tail = plan_tail((int)tiles, p.nch);
+  }
+  p.off_tail = o; o += tail_bytes(p.tail);
   p.total = o;
   return p;
 }
@@ -283,11 +335,14 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const bool pad = needs_pad_checks(g);
   if ((rc = allow_big_lds(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK)
     return rc;
-  const int MB = (g.Ks + cs::BM - 1) / cs::BM;
-  const int CT = (g.PQ * g.NB + 3) / 4;
+  float* partial = (float*)(base + p.off_tail);
   probe.begin(st);
-  hipLaunchKernelGGL(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(MB, CT)),
-                     dim3(cs::NT), cs::SMEM_BYTES, st, g, wmat, p.ldw, p.ldw, xt, tab, zero, yt, MB, CT, p.nch);
+  hipLaunchKernelGGL(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>,
+                     dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg), dim3(cs::NT), cs::SMEM_BYTES, st, g,
+                     wmat, p.ldw, p.ldw, xt, tab, zero, yt, p.MB, p.CT, p.nch, p.tail, partial);
+  if (p.tail.nTail > 0)
+    hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
+                       p.CT, p.nch, p.tail);
   probe.end(st);
   // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
   launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
@@ -344,11 +399,14 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     const int entries = (p.nch + 3) * cs::BK;
     hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g1, entries, tab);
     if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
-    const int MB = (g1.Ks + cs::BM - 1) / cs::BM;
-    const int CT = (g1.PQ * g1.NB + 3) / 4;
+    float* partial = (float*)(base + p.off_tail);
     probe.begin(st);
-    hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(MB, CT)), dim3(cs::NT), cs::SMEM_BYTES,
-                       st, g1, wt, p.Ks4, p.Ks4, dyt, tab, zero, T, MB, CT, p.nch);
+    hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg),
+                       dim3(cs::NT), cs::SMEM_BYTES, st, g1, wt, p.Ks4, p.Ks4, dyt, tab, zero, T, p.MB1, p.CT1, p.nch,
+                       p.tail, partial);
+    if (p.tail.nTail > 0)
+      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g1, partial, T, p.MB1,
+                         p.CT1, p.nch, p.tail);
     probe.end(st);
     const dim3 grid((g.C * g.HW + 63) / 64, (g.N + 63) / 64);
     const bool acc = desc->accumulate != 0;
@@ -407,9 +465,13 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
   float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
   probe.begin(st);
+  float* partial = (float*)(base + p.off_tail);
   hipLaunchKernelGGL(pad ? cs::bwd_weight_gemm_kernel<true> : cs::bwd_weight_gemm_kernel<false>,
-                     dim3(cs::grid_contiguous(p.MB, p.CT), p.splits), dim3(cs::NT),
-                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit);
+                     dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg, p.splits), dim3(cs::NT),
+                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit, p.tail, partial);
+  if (p.tail.nTail > 0)
+    hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
+                       p.MB, p.CT, p.nch, p.tail);
   probe.end(st);
   if (p.splits > 1) {
     const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);

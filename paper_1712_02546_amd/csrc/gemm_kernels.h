@@ -53,7 +53,8 @@ struct FwdLoadB {
   int4 cur[4], nxt[4];   // table entries (two rows each) of the chunk being issued / the next one; uniform
   int pixbase, h0, w0, H, W;
   bool upper;
-  __device__ FwdLoadB(const Geo& g, const float* xt_, const int2* tab, int ct) : xt(xt_), tab2((const int4*)tab) {
+  __device__ FwdLoadB(const Geo& g, const float* xt_, const int2* tab, int ct, int ch0)
+      : xt(xt_), tab2((const int4*)tab) {
     const int l = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cq = l & 31;
@@ -69,7 +70,7 @@ struct FwdLoadB {
     pixbase = (h0 * g.W + w0) * g.Np + nb * 32 + 4 * (cq & 7);
     upper = l >= 32;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) nxt[i] = tab2[4 * wv + i];
+    for (int i = 0; i < 4; ++i) nxt[i] = tab2[ch0 * (BK / 2) + 4 * wv + i];
   }
   // Table rows past C*R*S repeat row 0 (the filter operand is zero there), and the table
   // runs three chunks past the end, so neither the tail nor the dummy chunks need a test.
@@ -93,44 +94,119 @@ struct FwdLoadB {
   __device__ __forceinline__ void end() {}
 };
 
-// y_t[k][pix][n] for the slice; one workgroup per 128 kernels x 4 column blocks.
-template <bool PAD>
-__global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __restrict__ w, int ldw,
-                                                      int wcols, const float* __restrict__ xt,
-                                                      const int2* __restrict__ tab,
-                                                      const float* __restrict__ zero,
-                                                      float* __restrict__ yt, int MB, int CT, int nch) {
-  extern __shared__ __align__(16) float smem[];
-  int mb, ct;
-  if (!tile_contiguous(blockIdx.x, MB, CT, mb, ct)) return;
-  const int m0 = mb * BM;
-  f32x16 acc[2][2];
+// Accumulator images in wavefront layout: element e = (i*2+j)*16+v of thread t at [e*NT + t].
+__device__ __forceinline__ void store_partial(float* slot, const f32x16 (&acc)[2][2]) {
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  FwdLoadA la(w, ldw, wcols, m0, g.Ks, zero);
-  FwdLoadB<PAD> lb(g, xt, tab, ct);
-  gemm_mainloop(la, lb, 0, nch, smem, acc);
+      for (int v = 0; v < 16; ++v) slot[((i * 2 + j) * 16 + v) * NT + threadIdx.x] = acc[i][j][v];
+}
 
+// Sum of the scratch slots of tail tile tl, in run order, for accumulator block (bi,bj).
+__device__ __forceinline__ void gather_partials(const float* partial, const TailPlan& tp, int nch, int tl,
+                                                int bi, int bj, f32x16& acc) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  const int wfirst = (tl * nch) / tp.units;
+  const int wlast = min(tp.nTailWg - 1, (tl * nch + nch - 1) / tp.units);
+  for (int w = wfirst; w <= wlast; ++w) {
+    const int slot = (w * tp.units) / nch == tl ? 0 : 1;   // a run's first tile uses slot 0, its second slot 1
+    const float* p = partial + (int64_t)(w * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];
+  }
+}
+
+// One workgroup's share of an equal-cost pass: a whole tile, or a run of the tail.
+// body(L, ch_begin, ch_end, direct, slot) computes chunks [ch_begin, ch_end) of the tile at
+// line position L and stores them as the final result (direct) or into a scratch slot.
+template <class Body>
+__device__ __forceinline__ void for_each_segment(const TailPlan& tp, int nch, Body&& body) {
+  const int gid = blockIdx.x;
+  const int gfull = grid_contiguous(tp.nFull);
+  if (gid < gfull) {
+    int L;
+    if (line_contiguous(gid, tp.nFull, L)) body(L, 0, nch, true, 0);
+    return;
+  }
+  const int w = gid - gfull;
+  int u0 = w * tp.units;
+  const int u1 = min(u0 + tp.units, tp.nTail * nch);
+  int tl = u0 / nch;
+  int c = u0 - tl * nch;
+  for (int slot = 0; slot < 2 && u0 < u1; ++slot) {
+    const int ce = min(nch, c + (u1 - u0));
+    body(tp.nFull + tl, c, ce, false, w * 2 + slot);
+    u0 += ce - c;
+    ++tl;
+    c = 0;
+  }
+}
+
+// Stores accumulator block (i,j) of this wavefront: 32 kernels x 32 images of one pixel.
+__device__ __forceinline__ void fwd_store_block(const Geo& g, float* __restrict__ yt, int mb, int ct, int i, int j,
+                                                const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  const int gcb = ct * 4 + wn * 2 + j;
+  if (gcb >= g.PQ * g.NB) return;
+  const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
+  const int n = nb * 32 + (lane & 31);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int gcb = ct * 4 + wn * 2 + j;
-    if (gcb >= g.PQ * g.NB) continue;
-    const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
-    const int n = nb * 32 + (lane & 31);
+  for (int v = 0; v < 16; ++v) {
+    const int m = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
+    if (m < g.Ks) yt[((int64_t)m * g.PQ + pix) * g.Np + n] = acc[v];
+  }
+}
+
+__device__ __forceinline__ void fwd_store_tile(const Geo& g, float* __restrict__ yt, int mb, int ct,
+                                               const f32x16 (&acc)[2][2]) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) fwd_store_block(g, yt, mb, ct, i, j, acc[i][j]);
+}
+
+// y_t[k][pix][n] for the slice; a tile is 128 kernels x 4 column blocks.
+template <bool PAD>
+__global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __restrict__ w, int ldw,
+                                                      int wcols, const float* __restrict__ xt,
+                                                      const int2* __restrict__ tab,
+                                                      const float* __restrict__ zero,
+                                                      float* __restrict__ yt, int MB, int CT, int nch,
+                                                      TailPlan tp, float* __restrict__ partial) {
+  extern __shared__ __align__(16) float smem[];
+  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+    int mb, ct;
+    tile_from_line(L, MB, CT, mb, ct);
+    f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 64 + i * 32 + acc_row(v, lane);
-        if (m < g.Ks) yt[((int64_t)m * g.PQ + pix) * g.Np + n] = acc[i][j][v];
-      }
-  }
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    FwdLoadA la(w, ldw, wcols, mb * BM, g.Ks, zero);
+    FwdLoadB<PAD> lb(g, xt, tab, ct, cb);
+    gemm_mainloop(la, lb, cb, ce, smem, acc);
+    if (direct) fwd_store_tile(g, yt, mb, ct, acc);
+    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+  });
+}
+
+// Adds up the scratch slots of each tail tile and stores the tile.  grid = (nTail, 4): one
+// workgroup per tile and accumulator block.
+__global__ __launch_bounds__(NT) void fwd_tail_fixup_kernel(Geo g, const float* __restrict__ partial,
+                                                            float* __restrict__ yt, int MB, int CT, int nch,
+                                                            TailPlan tp) {
+  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  f32x16 acc;
+  gather_partials(partial, tp, nch, blockIdx.x, bi, bj, acc);
+  int mb, ct;
+  tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
+  fwd_store_block(g, yt, mb, ct, bi, bj, acc);
 }
 
 // --------------------------------------------------------- input gradient ----
@@ -383,45 +459,72 @@ struct BwdWeightLoadB {
   }
 };
 
-// out[z][m][j] partial (or final when one split) weight gradients of the slice.
+__device__ __forceinline__ void bwd_weight_store_block(const Geo& g, float* __restrict__ o, int mb, int ct, int i,
+                                                       int j, const f32x16& acc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
+  if (col >= g.CRS) return;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
+    if (m < g.Ks) o[(int64_t)m * g.CRS + col] = acc[v];
+  }
+}
+
+__device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __restrict__ o, int mb, int ct,
+                                                      const f32x16 (&acc)[2][2]) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) bwd_weight_store_block(g, o, mb, ct, i, j, acc[i][j]);
+}
+
+// out[z][m][j]: partial (or final when one split) weight gradients of the slice.  Either
+// the reduction is split evenly over gridDim.y (small outputs; tp then has no tail) or
+// gridDim.y is 1 and tp shares out the tail tiles.
 template <bool PAD>
 __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float* __restrict__ dyt,
                                                              const float* __restrict__ xt,
                                                              float* __restrict__ out, int64_t splitStride,
-                                                             int MB, int CT, int nch, int chPerSplit) {
+                                                             int MB, int CT, int nch, int chPerSplit,
+                                                             TailPlan tp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
-  int mb, ct;
-  if (!tile_contiguous(blockIdx.x, MB, CT, mb, ct)) return;
-  const int m0 = mb * BM, j0 = ct * BN;
   const int z = blockIdx.y;
   const int ch0 = z * chPerSplit;
   const int ch1 = min(nch, ch0 + chPerSplit);
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  BwdWeightLoadA la(g, dyt, m0);
-  BwdWeightLoadB<PAD> lb(g, xt, j0, ch0);
-  gemm_mainloop(la, lb, ch0, ch1, smem, acc);
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
   float* o = out + (int64_t)z * splitStride;
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = j0 + wn * 64 + j * 32 + (lane & 31);
-    if (col >= g.CRS) continue;
+  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+    int mb, ct;
+    tile_from_line(L, MB, CT, mb, ct);
+    if (direct) {   // whole tile: this split's chunk range
+      cb = ch0;
+      ce = ch1;
+    }
+    f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 64 + i * 32 + acc_row(v, lane);
-        if (m < g.Ks) o[(int64_t)m * g.CRS + col] = acc[i][j][v];
-      }
-  }
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    BwdWeightLoadA la(g, dyt, mb * BM);
+    BwdWeightLoadB<PAD> lb(g, xt, ct * BN, cb);
+    gemm_mainloop(la, lb, cb, ce, smem, acc);
+    if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
+    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+  });
+}
+
+__global__ __launch_bounds__(NT) void bwd_weight_tail_fixup_kernel(Geo g, const float* __restrict__ partial,
+                                                                   float* __restrict__ out, int MB, int CT,
+                                                                   int nch, TailPlan tp) {
+  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  f32x16 acc;
+  gather_partials(partial, tp, nch, blockIdx.x, bi, bj, acc);
+  int mb, ct;
+  tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
+  bwd_weight_store_block(g, out, mb, ct, bi, bj, acc);
 }
 
 }  // namespace cs
