@@ -108,7 +108,7 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
-  p.off_tab = o; o += seg((int64_t)(p.nch + 3) * cs::BK * 2);
+  p.off_tab = o; o += seg((int64_t)(p.nch + 4) * cs::BK * 2);
   p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.off_tail = o; o += tail_bytes(p.tail);
   p.total = o;
@@ -135,7 +135,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     o += kZeroBytes;
     p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
     p.off_wt = o;   o += seg((int64_t)g.CRS * p.Ks4);          // w'[(c,r,s)][k]
-    p.off_tab = o;  o += seg((int64_t)(p.nch + 3) * cs::BK * 2);
+    p.off_tab = o;  o += seg((int64_t)(p.nch + 4) * cs::BK * 2);
     p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
     p.off_T = o;    o += seg((int64_t)g.CRS * g.PQ * g.Np);
     p.MB1 = (g.CRS + cs::BM - 1) / cs::BM;
@@ -330,7 +330,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   }
   // three chunks more than needed: addresses are computed two chunks ahead and the table is read one further
   int2* tab = (int2*)(base + p.off_tab);
-  const int entries = (p.nch + 3) * cs::BK;
+  const int entries = (p.nch + 4) * cs::BK;
   hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
   const bool pad = needs_pad_checks(g);
   if ((rc = allow_big_lds(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK)
@@ -396,7 +396,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0,
                         p.Ks4, p.Ks4, 1, nullptr, st);
     hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
-    const int entries = (p.nch + 3) * cs::BK;
+    const int entries = (p.nch + 4) * cs::BK;
     hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g1, entries, tab);
     if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
     float* partial = (float*)(base + p.off_tail);

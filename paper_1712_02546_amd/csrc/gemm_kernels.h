@@ -16,6 +16,7 @@ __device__ __forceinline__ float* dma_dst(float* tile, int wv, int i) { return t
 // A[m][kk] = w[k0+m0+m][kk]: rows of the (re-pitched) filter matrix, col image.
 struct FwdLoadA {
   static constexpr bool COL = true;
+  static constexpr bool DEEP = false;
   const float* p[4];
   const float* zero;
   int kq4, cols;  // float offset of this lane's slot inside a chunk; valid row length
@@ -229,6 +230,7 @@ struct TapWalk {
 // A zero page sits ZERO_PAGE_FLOATS in front of w_t.
 struct BwdDataLoadA {
   static constexpr bool COL = false;
+  static constexpr bool DEEP = false;
   const float* wt;
   const int* taps;
   int Ks, Cp, S, krow, lane_off, tap;   // tap = flat (r*S+s) of walk.ti, fetched one call ahead
@@ -389,6 +391,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
 // A[m][kk] = dy_t[m0+m][pix][n]: dense rows, col image.
 struct BwdWeightLoadA {
   static constexpr bool COL = true;
+  static constexpr bool DEEP = true;
   const float* p[4];
   int64_t adv;   // uniform
   __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0) {
