@@ -6,6 +6,7 @@
 
 #include "conv_common.h"
 #include "gemm_kernels.h"
+#include "gemm_bf16_kernels.h"
 #include "pack_kernels.h"
 
 namespace {
@@ -202,6 +203,94 @@ struct Probe {
   void end(hipStream_t st) const { if (start && stop) (void)hipEventRecord(stop, st); }
 };
 
+// ---- bfloat16 matrix-core paths (packed bf16 work copies, see gemm_bf16_kernels.h) ----
+inline size_t seg16(int64_t halves) { return (size_t)round_up(halves * 2, 256); }
+
+// Forward and input gradient need >= 32 input channels to fill the channel-innermost copies.
+bool bf16_mfma_fwd_ok(const Geo& g, int dtype) {
+  const int64_t Cp = round_up(g.C, 64);
+  return dtype == CONV_BF16 && g.C >= 32 && (int64_t)g.HW * g.Np * Cp < kMaxElems &&
+         (int64_t)g.Ks * g.RS * Cp < kMaxElems;
+}
+bool bf16_mfma_bwd_data_ok(const Geo& g, int dtype) {
+  const int64_t Ksp = round_up(g.Ks, 64);
+  return dtype == CONV_BF16 && g.C > 32 && (int64_t)g.PQ * g.Np * Ksp < kMaxElems &&
+         (int64_t)g.RS * g.C * Ksp < kMaxElems;
+}
+bool bf16_mfma_bwd_weight_ok(const Geo& g, int dtype) {
+  const int64_t Np64 = round_up(g.N, 64);
+  return dtype == CONV_BF16 && (int64_t)g.C * g.HW * Np64 < kMaxElems && (int64_t)g.Ks * g.PQ * Np64 < kMaxElems;
+}
+
+struct Fwd16Plan {
+  int Cp, nch, MB, CT;
+  cs::TailPlan tail;
+  size_t off_x, off_w, off_yt, off_tail, total;
+};
+Fwd16Plan plan_fwd16(const Geo& g) {
+  Fwd16Plan p;
+  p.Cp = (int)round_up(g.C, 64);
+  p.nch = g.RS * (p.Cp / cs::BK16);
+  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
+  p.CT = (g.PQ * g.NB + 3) / 4;
+  p.tail = plan_tail(p.MB * p.CT, p.nch);
+  size_t o = kZeroBytes;
+  p.off_x = o;    o += seg16((int64_t)g.HW * g.Np * p.Cp);
+  p.off_w = o;    o += seg16((int64_t)g.Ks * g.RS * p.Cp);
+  p.off_yt = o;   o += seg((int64_t)g.Ks * g.PQ * g.Np);
+  p.off_tail = o; o += tail_bytes(p.tail);
+  p.total = o;
+  return p;
+}
+
+struct BwdData16Plan {
+  int Ksp;
+  size_t off_dy, off_w, off_dxt, off_perm, total;
+};
+BwdData16Plan plan_bwd_data16(const Geo& g) {
+  BwdData16Plan p;
+  p.Ksp = (int)round_up(g.Ks, 64);
+  size_t o = kZeroBytes;
+  p.off_dy = o;   o += seg16((int64_t)g.PQ * g.Np * p.Ksp);
+  p.off_w = o;    o += seg16((int64_t)g.RS * g.C * p.Ksp);
+  p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
+  p.off_perm = o; o += seg(g.HW);
+  p.total = o;
+  return p;
+}
+
+struct BwdWeight16Plan {
+  int Np64, MB, CT, nch, splits, chPerSplit;
+  cs::TailPlan tail;
+  size_t off_xt, off_dyt, off_part, off_tail, total;
+};
+BwdWeight16Plan plan_bwd_weight16(const Geo& g) {
+  BwdWeight16Plan p;
+  p.Np64 = (int)round_up(g.N, 64);
+  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
+  p.CT = (g.CRS + cs::BN - 1) / cs::BN;
+  p.nch = g.PQ * (p.Np64 / cs::BK16);
+  const int64_t tiles = (int64_t)p.MB * p.CT;
+  int64_t want = (1024 + tiles - 1) / tiles;
+  const int64_t cap = p.nch / 4 > 0 ? p.nch / 4 : 1;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  p.chPerSplit = (int)((p.nch + want - 1) / want);
+  p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;
+  if (p.splits > 1) {
+    p.tail.nFull = (int)tiles; p.tail.nTail = 0; p.tail.units = 1; p.tail.nTailWg = 0;
+  } else {
+    p.tail = plan_tail((int)tiles, p.nch);
+  }
+  size_t o = kZeroBytes;
+  p.off_xt = o;   o += seg16((int64_t)g.C * g.HW * p.Np64);
+  p.off_dyt = o;  o += seg16((int64_t)g.Ks * g.PQ * p.Np64);
+  p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
+  p.off_tail = o; o += tail_bytes(p.tail);
+  p.total = o;
+  return p;
+}
+
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
 int check_launch() { return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH; }
@@ -217,22 +306,29 @@ bool needs_pad_checks(const Geo& g) {
   return g.ph > 0 || g.pw > 0 || (g.P - 1) * g.sh - g.ph + g.R > g.H || (g.Q - 1) * g.sw - g.pw + g.S > g.W;
 }
 
-// src[rows][cols] (pitch srcPitch, element type by dtype) -> dst[cols][rowsPad] fp32, batched.
+// src[rows][cols] (pitch srcPitch, element type by dtype) -> dst[cols][rowsPad] (fp32, or bf16 when
+// out16), for batches 0..batch-1; batches at or past batchValid are written as zeros.
 void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
-                         float* dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch,
-                         float* zero_page, hipStream_t st) {
-  const size_t es = dtype == CONV_F32 ? 4 : 2;
+                         void* dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch,
+                         float* zero_page, hipStream_t st, bool out16 = false, int batchValid = -1) {
+  if (batchValid < 0) batchValid = batch;
   for (int b0 = 0; b0 < batch; b0 += 32768) {  // grid.z is limited to 65535
     const int nb = batch - b0 < 32768 ? batch - b0 : 32768;
     const dim3 grid((cols + 63) / 64, (rowsPad + 63) / 64, nb);
-    const void* s = (const char*)src + (size_t)b0 * srcBatch * es;
-    float* d = dst + (size_t)b0 * dstBatch;
-    if (dtype == CONV_F32)
-      hipLaunchKernelGGL(cs::transpose_in_kernel<float>, grid, dim3(256), 0, st, (const float*)s, srcBatch,
-                         srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad, b0 == 0 ? zero_page : nullptr);
+    float* zp = b0 == 0 ? zero_page : nullptr;
+    if (dtype == CONV_F32 && !out16)
+      hipLaunchKernelGGL((cs::transpose_in_kernel<float, float>), grid, dim3(256), 0, st, (const float*)src,
+                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp);
+    else if (dtype == CONV_F32)
+      hipLaunchKernelGGL((cs::transpose_in_kernel<float, uint16_t>), grid, dim3(256), 0, st, (const float*)src,
+                         srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp);
+    else if (!out16)
+      hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, float>), grid, dim3(256), 0, st, (const uint16_t*)src,
+                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp);
     else
-      hipLaunchKernelGGL(cs::transpose_in_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)s,
-                         srcBatch, srcPitch, rows, cols, d, dstBatch, dstPitch, rowsPad, b0 == 0 ? zero_page : nullptr);
+      hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st,
+                         (const uint16_t*)src, srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch,
+                         rowsPad, b0, batchValid, zp);
   }
 }
 
@@ -284,9 +380,12 @@ size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
   if (make_geo(desc, g) != CONV_OK) return 0;
   if (g.Ks == 0) return 0;
   switch (pass) {
-    case CONV_PASS_FWD: return plan_fwd(g, desc->dtype).total;
-    case CONV_PASS_BWD_DATA: return plan_bwd_data(g).total;
-    case CONV_PASS_BWD_WEIGHT: return plan_bwd_weight(g).total;
+    case CONV_PASS_FWD:
+      return bf16_mfma_fwd_ok(g, desc->dtype) ? plan_fwd16(g).total : plan_fwd(g, desc->dtype).total;
+    case CONV_PASS_BWD_DATA:
+      return bf16_mfma_bwd_data_ok(g, desc->dtype) ? plan_bwd_data16(g).total : plan_bwd_data(g).total;
+    case CONV_PASS_BWD_WEIGHT:
+      return bf16_mfma_bwd_weight_ok(g, desc->dtype) ? plan_bwd_weight16(g).total : plan_bwd_weight(g).total;
     default: return 0;
   }
 }
@@ -300,6 +399,33 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   if (!x || !w || !y) return CONV_ERR_NULL;
   if (misaligned(x, 16) || misaligned(w, 16) || misaligned(y, 16)) return CONV_ERR_ALIGN;
   if (g.Ks == 0) return CONV_OK;
+  if (bf16_mfma_fwd_ok(g, desc->dtype)) {
+    const Fwd16Plan p = plan_fwd16(g);
+    if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* base = (char*)ws;
+    cs::bf16_t* xp = (cs::bf16_t*)(base + p.off_x);
+    cs::bf16_t* wp = (cs::bf16_t*)(base + p.off_w);
+    float* yt = (float*)(base + p.off_yt);
+    float* partial = (float*)(base + p.off_tail);
+    // per image: x[n] as a C x HW matrix -> x_hwnc[hw][n][Cp]; images N..Np-1 are zero
+    launch_transpose_in(CONV_BF16, x, (int64_t)g.C * g.HW, g.HW, g.C, g.HW, xp, p.Cp, (int64_t)g.Np * p.Cp, p.Cp,
+                        g.Np, (float*)(base + p.off_x - kZeroBytes), st, true, g.N);
+    // per kernel: w[k] as a C x RS matrix -> w_krsc[k][rs][Cp]
+    launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.CRS, g.RS, g.C, g.RS, wp,
+                        (int64_t)g.RS * p.Cp, p.Cp, p.Cp, g.Ks, nullptr, st, true);
+    if ((rc = allow_big_lds(cs::fwd16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    probe.begin(st);
+    hipLaunchKernelGGL(cs::fwd16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg), dim3(cs::NT),
+                       cs::SMEM_BYTES, st, g, wp, p.Cp, xp, yt, p.MB, p.CT, p.nch, p.tail, partial);
+    if (p.tail.nTail > 0)
+      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
+                         p.CT, p.nch, p.tail);
+    probe.end(st);
+    launch_transpose_out(CONV_BF16, false, yt, g.Np, g.N, g.Ks * g.PQ, (char*)y + (size_t)g.k0 * g.PQ * 2,
+                         (int64_t)g.K * g.PQ, st);
+    return check_launch();
+  }
   const FwdPlan p = plan_fwd(g, desc->dtype);
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -371,6 +497,33 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
       return check_launch();
     }
     return CONV_OK;
+  }
+  if (bf16_mfma_bwd_data_ok(g, desc->dtype)) {
+    const BwdData16Plan p = plan_bwd_data16(g);
+    if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+    char* base = (char*)ws;
+    cs::bf16_t* dyp = (cs::bf16_t*)(base + p.off_dy);
+    cs::bf16_t* wp = (cs::bf16_t*)(base + p.off_w);
+    float* dxt = (float*)(base + p.off_dxt);
+    int* perm = (int*)(base + p.off_perm);
+    // per image: dy[n][k0..k1) as a Ks x PQ matrix -> dy_pqnk[pq][n][Ksp]; images N..Np-1 are zero
+    launch_transpose_in(CONV_BF16, (const char*)dy + (size_t)g.k0 * g.PQ * 2, (int64_t)g.K * g.PQ, g.PQ, g.Ks, g.PQ,
+                        dyp, p.Ksp, (int64_t)g.Np * p.Ksp, p.Ksp, g.Np, (float*)(base + p.off_dy - kZeroBytes), st,
+                        true, g.N);
+    // per channel c: w[k0..k1)[c] as a Ks x RS matrix -> w_rsck[rs][c][Ksp]
+    launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.RS, g.CRS, g.Ks, g.RS, wp, p.Ksp,
+                        (int64_t)g.C * p.Ksp, p.Ksp, g.C, nullptr, st, true);
+    hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
+    const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
+    if ((rc = allow_big_lds(cs::bwd_data16_gemm_kernel, lds)) != CONV_OK) return rc;
+    const int MB = (g.C + cs::BM - 1) / cs::BM;
+    const int CT = (g.HW * g.NB + 3) / 4;
+    probe.begin(st);
+    hipLaunchKernelGGL(cs::bwd_data16_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st, g, wp, p.Ksp,
+                       dyp, perm, dxt, MB, CT);
+    probe.end(st);
+    launch_transpose_out(CONV_BF16, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
+    return check_launch();
   }
   const BwdDataPlan p = plan_bwd_data(g);
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
@@ -445,6 +598,37 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   if (!x || !dy || !dw) return CONV_ERR_NULL;
   if (misaligned(x, 16) || misaligned(dy, 16) || misaligned(dw, 16)) return CONV_ERR_ALIGN;
   if (g.Ks == 0) return CONV_OK;
+  if (bf16_mfma_bwd_weight_ok(g, desc->dtype)) {
+    const BwdWeight16Plan p = plan_bwd_weight16(g);
+    if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* base = (char*)ws;
+    cs::bf16_t* xt = (cs::bf16_t*)(base + p.off_xt);
+    cs::bf16_t* dyt = (cs::bf16_t*)(base + p.off_dyt);
+    float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
+    launch_transpose_in(CONV_BF16, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, p.Np64, p.Np64, 1,
+                        (float*)(base + p.off_xt - kZeroBytes), st, true);
+    launch_transpose_in(CONV_BF16, (const char*)dy + (size_t)g.k0 * g.PQ * 2, 0, (int64_t)g.K * g.PQ, g.N,
+                        g.Ks * g.PQ, dyt, 0, p.Np64, p.Np64, 1, nullptr, st, true);
+    if ((rc = allow_big_lds(cs::bwd_weight16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
+    float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
+    float* partial = (float*)(base + p.off_tail);
+    probe.begin(st);
+    hipLaunchKernelGGL(cs::bwd_weight16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg, p.splits),
+                       dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt, p.Np64, out, sliceElems, p.MB, p.CT, p.nch,
+                       p.chPerSplit, p.tail, partial);
+    if (p.tail.nTail > 0)
+      hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
+                         p.MB, p.CT, p.nch, p.tail);
+    probe.end(st);
+    if (p.splits > 1) {
+      const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);
+      hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, out, sliceElems, p.splits,
+                         dwslice, sliceElems);
+    }
+    return check_launch();
+  }
   const BwdWeightPlan p = plan_bwd_weight(g);
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;

@@ -1,0 +1,419 @@
+// bfloat16 matrix-core passes: v_mfma_f32_32x32x16_bf16 with fp32 accumulation.
+//
+// In that instruction lane l supplies the eight consecutive reduction elements
+// k = 8*(l/32) .. +7 of row (or column) l%32, i.e. 16 bytes.  So both operands are staged
+// as col images (see conv_common.h): a tile row holds 64 reduction elements as eight
+// 16-byte slots, and one 16-byte LDS read is one MFMA operand.  To make every operand
+// contiguous along the reduction, each pass gets its own packed bf16 copies:
+//
+//   fwd        reduction (r,s,c):  w_krsc[Ks][R*S][Cp]          x_hwnc[H][W][Np][Cp]
+//   bwd_data   reduction (tap,k):  w_rsck[R*S][C][Ksp]          dy_pqnk[P][Q][Np][Ksp]
+//   bwd_weight reduction (pix,n):  dy_t[Ks][P*Q][Np64]          x_t[C][H][W][Np64]
+//
+// with Cp, Ksp, Np64 rounded up to 64 and zero filled, so a chunk (64 reduction elements)
+// never needs a tail mask.  Tiles, column blocks, tap lists, XCD maps and epilogues are
+// those of the fp32 kernels; outputs leave the kernels as fp32 (y_t, dx_t, dw).
+#pragma once
+#include "conv_common.h"
+#include "gemm_kernels.h"
+
+namespace cs {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint16_t bf16_t;                  // storage type of a bfloat16 element
+constexpr int BK16 = 64;                  // reduction elements per chunk
+constexpr int ZERO_PAGE_BF16 = ZERO_PAGE_FLOATS * 2;   // the zero page counted in bf16 elements
+
+__device__ __forceinline__ void dma16h(const bf16_t* g, float* lds_uniform) {
+  __builtin_amdgcn_global_load_lds(CS_GPTR(g), CS_LPTR(lds_uniform), 16, 0, 0);
+}
+
+struct Frag16 {
+  f32x4 v[2];   // one MFMA operand (8 bf16) for each of the wavefront's two 32-wide blocks
+};
+
+// Operands of MFMA step j (0..3) of a chunk from a col image: logical slot 2*j + lane/32.
+__device__ __forceinline__ void read_frag16(Frag16& f, const float* tile, int wbase, int lane, int j) {
+  const int u = lane & 7, h = lane >> 5;
+  const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
+  f.v[0] = *(const f32x4*)(tile + slot * 4);
+  f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
+}
+
+__device__ __forceinline__ void mfma16_group(const Frag16& a, const Frag16& b, f32x16 (&acc)[2][2]) {
+  const bf16x8 a0 = __builtin_bit_cast(bf16x8, a.v[0]), a1 = __builtin_bit_cast(bf16x8, a.v[1]);
+  const bf16x8 b0 = __builtin_bit_cast(bf16x8, b.v[0]), b1 = __builtin_bit_cast(bf16x8, b.v[1]);
+  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+}
+
+// Main loop: same driving protocol as the fp32 loops (begin / addr(0..3) / end, dummy
+// loads past the last chunk), one barrier per chunk, all four operand reads of a chunk
+// issued up front, DMA loads of the next chunk issued right after the barrier.
+template <class LA, class LB>
+__device__ __forceinline__ void gemm16_mainloop(LA& la, LB& lb, int ch_begin, int ch_end, float* smem,
+                                                f32x16 (&acc)[2][2]) {
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wa = (wv >> 1) * 64, wb = (wv & 1) * 64;
+  if (ch_begin >= ch_end) return;
+  auto issue = [&](int ch, float* ta, float* tb, bool live) {
+    la.begin(ch, live);
+    lb.begin(ch, live);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      dma16h(la.addr(i), ta + (wv * 4 + i) * 256);
+      dma16h(lb.addr(i), tb + (wv * 4 + i) * 256);
+    }
+    la.end();
+    lb.end();
+  };
+  issue(ch_begin, smem, smem + 2 * TILE_F, true);
+  __syncthreads();
+  int cur = 0;
+  for (int ch = ch_begin; ch < ch_end; ++ch) {
+    const float* As = smem + cur;
+    const float* Bs = smem + 2 * TILE_F + cur;
+    issue(ch + 1, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F), ch + 1 < ch_end);
+    Frag16 a[4], b[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      read_frag16(a[j], As, wa, lane, j);
+      read_frag16(b[j], Bs, wb, lane, j);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) mfma16_group(a[j], b[j], acc);
+    __syncthreads();
+    cur ^= TILE_F;
+  }
+}
+
+// ------------------------------------------------------------------ forward ----
+// A[m][kk] = w_krsc[m0+m][kk]: dense rows of R*S*Cp elements.
+struct Fwd16LoadA {
+  const bf16_t* p[4];
+  int64_t adv;
+  __device__ Fwd16LoadA(const bf16_t* w, int64_t ldw, int m0, int Ks) {
+    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = min(m0 + 32 * wv + 8 * i + (l >> 3), Ks - 1);  // rows past the slice repeat the last one
+      p[i] = w + (int64_t)m * ldw + kq8;
+    }
+  }
+  __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK16; }
+  __device__ __forceinline__ const bf16_t* addr(int i) const { return p[i] + adv; }
+  __device__ __forceinline__ void end() {}
+};
+
+// B^T[(block,n)][kk] = x_hwnc[h0+r][w0+s][n][c]: chunk = (r, s, 64 channels); the pixel of
+// a column block is uniform per wavefront (wavefront wv stages block wv of the tile).
+struct Fwd16LoadB {
+  const bf16_t* x;      // a zero page sits ZERO_PAGE_BF16 in front of it
+  int lane_off[4];
+  int h0, w0, H, W, S, R, NpCp, ncc;
+  int r, s, cc;         // uniform walk over the next chunk to issue
+  int uoff;
+  bool ok;
+  __device__ Fwd16LoadB(const Geo& g, const bf16_t* x_, int Cp, int ct, int ch0) : x(x_) {
+    const int l = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
+    const int gcb = ct * 4 + wv < g.PQ * g.NB ? ct * 4 + wv : 0;   // blocks past the end: computed, never stored
+    const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
+    const int p = pix / g.Q, q = pix - p * g.Q;
+    h0 = p * g.sh - g.ph;
+    w0 = q * g.sw - g.pw;
+    H = g.H; W = g.W; S = g.S; R = g.R;
+    NpCp = g.Np * Cp;
+    ncc = Cp / BK16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lane_off[i] = (nb * 32 + 8 * i + (l >> 3)) * Cp + kq8;
+    const int tap = ch0 / ncc;
+    cc = ch0 - tap * ncc;
+    r = tap / S;
+    s = tap - r * S;
+  }
+  __device__ __forceinline__ void begin(int, bool live) {
+    const int hh = h0 + r, vv = w0 + s;
+    ok = live & ((unsigned)hh < (unsigned)H) & ((unsigned)vv < (unsigned)W);
+    uoff = (hh * W + vv) * NpCp + cc * BK16;
+  }
+  __device__ __forceinline__ const bf16_t* addr(int i) const { return x + (ok ? uoff + lane_off[i] : -ZERO_PAGE_BF16); }
+  __device__ __forceinline__ void end() {   // branch-free carry over (cc, s, r)
+    ++cc;
+    const int c1 = cc == ncc;
+    cc = c1 ? 0 : cc;
+    s += c1;
+    const int c2 = s == S;
+    s = c2 ? 0 : s;
+    r += c2;
+  }
+};
+
+__global__ __launch_bounds__(NT) void fwd16_gemm_kernel(Geo g, const bf16_t* __restrict__ w, int Cp,
+                                                        const bf16_t* __restrict__ x, float* __restrict__ yt,
+                                                        int MB, int CT, int nch, TailPlan tp,
+                                                        float* __restrict__ partial) {
+  extern __shared__ __align__(16) float smem[];
+  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+    int mb, ct;
+    tile_from_line(L, MB, CT, mb, ct);
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    Fwd16LoadA la(w, (int64_t)g.RS * Cp, mb * BM, g.Ks);
+    Fwd16LoadB lb(g, x, Cp, ct, cb);
+    gemm16_mainloop(la, lb, cb, ce, smem, acc);
+    if (direct) fwd_store_tile(g, yt, mb, ct, acc);
+    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+  });
+}
+
+// ----------------------------------------------------------- input gradient ----
+// A[c][kk] = w_rsck[tap][c][k]: chunk = (tap, 64 kernels).
+struct BwdData16LoadA {
+  const bf16_t* wt;
+  const int* taps;
+  int S, CKsp, tap, lane_off[4];
+  int uoff;
+  TapWalk walk;
+  __device__ BwdData16LoadA(const Geo& g, const bf16_t* wt_, int Ksp, int m0, const int* taps_, int nkc_)
+      : wt(wt_), taps(taps_), S(g.S), CKsp(g.C * Ksp), walk(nkc_) {
+    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = min(m0 + 32 * wv + 8 * i + (l >> 3), g.C - 1);   // rows past C repeat the last one
+      lane_off[i] = c * Ksp + kq8;
+    }
+    const int e = taps[0];
+    tap = (e >> 16) * S + (e & 0xffff);
+  }
+  __device__ __forceinline__ void begin(int, bool live) { uoff = live ? tap * CKsp + walk.kc * BK16 : 0; }
+  __device__ __forceinline__ const bf16_t* addr(int i) const { return wt + (uoff + lane_off[i]); }
+  __device__ __forceinline__ void end() {
+    walk.next();
+    const int e = taps[walk.ti];
+    tap = (e >> 16) * S + (e & 0xffff);
+  }
+};
+
+// B^T[(block,n)][kk] = dy_pqnk[p][q][n][k] with (p,q) the output pixel the current tap maps
+// the block's input pixel to (from the per-tile LDS table), zero if there is none.
+struct BwdData16LoadB {
+  const bf16_t* dy;     // a zero page sits ZERO_PAGE_BF16 in front of it
+  const int* tapoff;
+  int lane_off[4], toff, wvb;
+  int uoff;
+  bool ok;
+  TapWalk walk;
+  __device__ BwdData16LoadB(const bf16_t* dy_, int Ksp, const int* tapoff_, int nkc_)
+      : dy(dy_), tapoff(tapoff_), walk(nkc_) {
+    const int l = threadIdx.x & 63;
+    wvb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lane_off[i] = (8 * i + (l >> 3)) * Ksp + kq8;
+    toff = tapoff[wvb];
+  }
+  __device__ __forceinline__ void begin(int, bool live) {
+    ok = live & (toff >= 0);
+    uoff = toff + walk.kc * BK16;
+  }
+  __device__ __forceinline__ const bf16_t* addr(int i) const { return dy + (ok ? uoff + lane_off[i] : -ZERO_PAGE_BF16); }
+  __device__ __forceinline__ void end() {
+    walk.next();
+    toff = tapoff[walk.ti * 4 + wvb];
+  }
+};
+
+__global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t* __restrict__ wt, int Ksp,
+                                                             const bf16_t* __restrict__ dy,
+                                                             const int* __restrict__ perm,
+                                                             float* __restrict__ dxt, int MB, int CT) {
+  extern __shared__ __align__(16) float smem[];
+  int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 3]
+  int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][4]
+  __shared__ int s_ntaps;
+  int mb, ct;
+  if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (wave == 0) {   // tap list of the tile, as in the fp32 kernel; offsets are into dy_pqnk
+    int hp[4], vp[4], nbo[4];
+    bool ok[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gcb = ct * 4 + j;
+      ok[j] = gcb < g.HW * g.NB;
+      const int sp = ok[j] ? gcb / g.NB : 0;
+      const int px = perm[sp];
+      nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 * Ksp : 0;
+      hp[j] = px / g.W + g.ph;
+      vp[j] = px % g.W + g.pw;
+    }
+    int cnt = 0;
+    for (int b = 0; b < g.RS; b += 64) {
+      const int tp = b + lane;
+      const int rr = tp / g.S, ss = tp - rr * g.S;
+      bool any = false;
+      int offs[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int hr = hp[j] - rr, vs = vp[j] - ss;
+        const int p = hr / g.sh, q = vs / g.sw;
+        const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
+                         p < g.P && q < g.Q;
+        offs[j] = hit ? (p * g.Q + q) * g.Np * Ksp + nbo[j] : -1;
+        any |= hit;
+      }
+      const unsigned long long mask = __ballot(any);
+      if (any) {
+        const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+        s_taps[pos] = (rr << 16) | ss;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
+      }
+      cnt += __popcll(mask);
+    }
+    if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;
+    if (lane < 3) s_taps[cnt + lane] = 0;
+    if (lane == 0) s_ntaps = cnt;
+  }
+  __syncthreads();
+  const int ntaps = s_ntaps;
+  const int nkc = Ksp / BK16;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  BwdData16LoadA la(g, wt, Ksp, mb * BM, s_taps, nkc);
+  BwdData16LoadB lb(dy, Ksp, s_tapoff, nkc);
+  gemm16_mainloop(la, lb, 0, ntaps * nkc, smem, acc);
+
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int gcb = ct * 4 + wn * 2 + j;
+    if (gcb >= g.HW * g.NB) continue;
+    const int sp = gcb / g.NB, nb = gcb - sp * g.NB;
+    const int px = perm[sp];
+    const int n = nb * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int c = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
+        if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[i][j][v];
+      }
+  }
+}
+
+// ---------------------------------------------------------- weight gradient ----
+// A[k][kk] = dy_t[k][pix][n]: dense rows of P*Q*Np64 elements; chunk = 64 images of one pixel.
+struct BwdWeight16LoadA {
+  const bf16_t* p[4];
+  int64_t adv;
+  __device__ BwdWeight16LoadA(const bf16_t* dyt, int64_t ld, int m0, int Ks) {
+    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = min(m0 + 32 * wv + 8 * i + (l >> 3), Ks - 1);
+      p[i] = dyt + (int64_t)m * ld + kq8;
+    }
+  }
+  __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK16; }
+  __device__ __forceinline__ const bf16_t* addr(int i) const { return p[i] + adv; }
+  __device__ __forceinline__ void end() {}
+};
+
+// B^T[(c,r,s)][kk] = x_t[c][p*sh-ph+r][q*sw-pw+s][n]; zero where the tap is in the padding.
+struct BwdWeight16LoadB {
+  const bf16_t* xt;     // a zero page sits ZERO_PAGE_BF16 in front of it
+  int coff[4], rj[4], sj[4];
+  int NB64, Q, sh, sw, ph, pw, H, W, Np64;
+  int p, q, nb;
+  int h0, v0, uoff;
+  __device__ BwdWeight16LoadB(const Geo& g, const bf16_t* xt_, int Np64_, int j0, int ch0) : xt(xt_) {
+    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    Np64 = Np64_; NB64 = Np64_ / BK16; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W;
+    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = j0 + 32 * wv + 8 * i + (l >> 3);
+      const int jj = j < g.CRS ? j : 0;
+      const int c = jj / g.RS, rs = jj - c * g.RS;
+      rj[i] = rs / g.S;
+      sj[i] = rs - rj[i] * g.S;
+      coff[i] = c * g.HW * Np64 + (rj[i] * g.W + sj[i]) * Np64 + kq8;
+    }
+    const int pix = ch0 / NB64;
+    nb = ch0 - pix * NB64;
+    p = pix / Q;
+    q = pix - p * Q;
+  }
+  __device__ __forceinline__ void begin(int, bool live) {
+    h0 = live ? p * sh - ph : 0;
+    v0 = live ? q * sw - pw : 0;
+    uoff = (h0 * W + v0) * Np64 + (live ? nb * BK16 : 0);
+  }
+  __device__ __forceinline__ const bf16_t* addr(int i) const {
+    const bool ok = ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
+    return xt + (ok ? coff[i] + uoff : -ZERO_PAGE_BF16);
+  }
+  __device__ __forceinline__ void end() {
+    ++nb;
+    const int cq = nb == NB64;
+    nb = cq ? 0 : nb;
+    q += cq;
+    const int cp = q == Q;
+    q = cp ? 0 : q;
+    p += cp;
+  }
+};
+
+__global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16_t* __restrict__ dyt,
+                                                               const bf16_t* __restrict__ xt, int Np64,
+                                                               float* __restrict__ out, int64_t splitStride,
+                                                               int MB, int CT, int nch, int chPerSplit,
+                                                               TailPlan tp, float* __restrict__ partial) {
+  extern __shared__ __align__(16) float smem[];
+  const int z = blockIdx.y;
+  const int ch0 = z * chPerSplit;
+  const int ch1 = min(nch, ch0 + chPerSplit);
+  float* o = out + (int64_t)z * splitStride;
+  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+    int mb, ct;
+    tile_from_line(L, MB, CT, mb, ct);
+    if (direct) {
+      cb = ch0;
+      ce = ch1;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    BwdWeight16LoadA la(dyt, (int64_t)g.PQ * Np64, mb * BM, g.Ks);
+    BwdWeight16LoadB lb(g, xt, Np64, ct * BN, cb);
+    gemm16_mainloop(la, lb, cb, ce, smem, acc);
+    if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
+    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+  });
+}
+
+}  // namespace cs

@@ -6,27 +6,31 @@
 
 namespace cs {
 
-// dst[b*dstBatch + l*dstPitch + n] = n < rows ? src[b*srcBatch + n*srcPitch + l] : 0
-// for 0 <= l < cols, 0 <= n < rowsPad.  64x64 tiles through LDS, both sides coalesced.
-// grid = (ceil(cols/64), ceil(rowsPad/64), batch).  If zero_page is not null the first
-// workgroup also clears its ZERO_PAGE_FLOATS floats (the page masked DMA lanes read).
-template <typename Tin>
+// dst[b*dstBatch + l*dstPitch + n] = (n < rows && b < batchValid) ? src[b*srcBatch + n*srcPitch + l] : 0
+// for 0 <= l < cols, 0 <= n < rowsPad, b = batch0 + blockIdx.z.  64x64 tiles through LDS,
+// both sides coalesced.  grid = (ceil(cols/64), ceil(rowsPad/64), batches).  If zero_page is
+// not null the first workgroup also clears its ZERO_PAGE_FLOATS floats (the page masked DMA
+// lanes read).  Tin/Tout are float or uint16_t (bfloat16 bits).
+template <typename Tin, typename Tout>
 __global__ __launch_bounds__(256) void transpose_in_kernel(
     const Tin* __restrict__ src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
-    float* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, float* __restrict__ zero_page) {
+    Tout* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch0, int batchValid,
+    float* __restrict__ zero_page) {
   __shared__ float tile[64][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
   if (zero_page && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
     for (int i = threadIdx.x; i < ZERO_PAGE_FLOATS; i += 256) zero_page[i] = 0.f;
-  src += (int64_t)blockIdx.z * srcBatch;
-  dst += (int64_t)blockIdx.z * dstBatch;
+  const int b = batch0 + blockIdx.z;
+  const bool bok = b < batchValid;
+  src += (int64_t)(bok ? b : 0) * srcBatch;
+  dst += (int64_t)b * dstBatch;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int nn = ty + 4 * i;
     const int n = n0 + nn, l = l0 + tx;
     float v = 0.f;
-    if (n < rows && l < cols) v = load_as_f32<Tin>(src + (int64_t)n * srcPitch + l);
+    if (bok && n < rows && l < cols) v = load_as_f32<Tin>(src + (int64_t)n * srcPitch + l);
     tile[nn][tx] = v;
   }
   __syncthreads();
@@ -34,7 +38,7 @@ __global__ __launch_bounds__(256) void transpose_in_kernel(
   for (int i = 0; i < 16; ++i) {
     const int ll = ty + 4 * i;
     const int l = l0 + ll, n = n0 + tx;
-    if (l < cols && n < rowsPad) dst[(int64_t)l * dstPitch + n] = tile[tx][ll];
+    if (l < cols && n < rowsPad) store_from_f32<Tout>(dst + (int64_t)l * dstPitch + n, tile[tx][ll]);
   }
 }
 
