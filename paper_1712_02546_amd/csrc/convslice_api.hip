@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "conv_common.h"
 #include "gemm_kernels.h"
 #include "gemm_bf16_kernels.h"
@@ -295,10 +297,23 @@ inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)
 
 int check_launch() { return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH; }
 
+// Raises a kernel's dynamic-LDS limit (needed above 64 KB).  The attribute is per kernel and
+// device, so it is set once per (kernel, device, size) and remembered.
 template <typename K>
 int allow_big_lds(K kernel, int bytes) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
-             ? CONV_OK : CONV_ERR_LAUNCH;
+  struct Done { const void* fn; int dev; int bytes; };
+  static Done done[32];
+  static int ndone = 0;
+  static std::mutex mu;
+  const std::lock_guard<std::mutex> lock(mu);
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  for (int i = 0; i < ndone; ++i)
+    if (done[i].fn == (const void*)kernel && done[i].dev == dev && done[i].bytes >= bytes) return CONV_OK;
+  if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return CONV_ERR_LAUNCH;
+  if (ndone < 32) done[ndone++] = Done{(const void*)kernel, dev, bytes};
+  return CONV_OK;
 }
 
 // True when some window reaches outside the image, i.e. taps must be range-checked.

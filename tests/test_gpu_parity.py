@@ -23,6 +23,11 @@ ADHOC = [
     synth.random_layer(7, N=32, C=20, H=10, W=10, K=33, R=1, S=1),                    # 1x1
     synth.random_layer(8, N=9, C=5, H=34, W=34, K=6, R=5, S=5, stride=4),             # unread last row/col
     synth.random_layer(9, N=1, C=1, H=5, W=5, K=1, R=2, S=2),
+    # more than 512 tiles with a long reduction: the tail tiles are shared out in runs
+    synth.random_layer(10, N=32, C=64, H=34, W=34, K=200, R=3, S=3, k0=9, k1=200),
+    synth.random_layer(11, N=3, C=2, H=33, W=34, K=3, R=32, S=32),                   # R*S at the limit
+    synth.random_layer(12, N=65, C=32, H=9, W=7, K=70, R=3, S=2, stride=2, pad=1),    # bf16: C = 32, batch 65
+    synth.random_layer(13, N=20, C=72, H=10, W=10, K=130, R=5, S=5, pad=2, k0=1, k1=130),
 ]
 
 
@@ -53,7 +58,8 @@ def test_full_tensors_match_oracle_fp32(cfg):
     assert np.all(dw[:k0] == 7.0) and np.all(dw[k1:] == 7.0), "filters outside the slice were written"
 
 
-@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], synth.CONFIGS["cfg1"]], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], synth.CONFIGS["cfg1"]],
+                         ids=lambda c: c.name)
 def test_full_tensors_match_oracle_bf16(cfg):
     x, w, dy = (synth.round_to_bf16(a) for a in synth.make_inputs(cfg))
     sh = oracle_shape(cfg)
@@ -109,10 +115,12 @@ def test_empty_slice_and_accumulate(C):
     check(dev2.bwd_data(accumulate=1, init=init), ref + 2.5, FP32_TOL, "dx accumulate")
 
 
-def test_results_are_bit_stable_run_to_run():
-    cfg = ADHOC[1]
+@pytest.mark.parametrize("which,dtype", [(1, "f32"), (9, "f32"), (12, "bf16")])
+def test_results_are_bit_stable_run_to_run(which, dtype):
+    """No atomics anywhere: split reductions and shared tails are summed in a fixed order."""
+    cfg = ADHOC[which]
     x, w, dy = synth.make_inputs(cfg)
-    dev = Device(cfg, x, w, dy)
+    dev = Device(cfg, x, w, dy, dtype=cs.CONV_F32 if dtype == "f32" else cs.CONV_BF16)
     a = (dev.fwd(fill=0.0), dev.bwd_data(), dev.bwd_weight(fill=0.0))
     b = (dev.fwd(fill=0.0), dev.bwd_data(), dev.bwd_weight(fill=0.0))
     for u, v in zip(a, b):
