@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <vector>
 
 #include "conv_common.h"
 #include "gemm_kernels.h"
@@ -118,11 +119,52 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   return p;
 }
 
+// Even sharing of the input-gradient pass: possible when every column tile holds one pixel
+// (Np a multiple of 128).  The length of the tile line is computed here exactly as the
+// ordering kernel counts it: sum over pixels of max(taps,1) chunks-of-Ks, times the tiles per pixel.
+cs::RunPlan plan_runs(const Geo& g, int MB) {
+  cs::RunPlan rp;
+  rp.enabled = 0; rp.units = 1; rp.nWg = 0; rp.tilesPerPix = 1; rp.total = 0;
+  if (g.NB % 4 != 0) return rp;
+  const int nkc = (g.Ks + cs::BK - 1) / cs::BK;
+  std::vector<int64_t> rowh(g.R + 1, 0), colh(g.S + 1, 0);
+  for (int h = 0; h < g.H; ++h) {
+    int n = 0;
+    for (int r = 0; r < g.R; ++r) {
+      const int hr = h + g.ph - r;
+      if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) ++n;
+    }
+    ++rowh[n];
+  }
+  for (int v = 0; v < g.W; ++v) {
+    int n = 0;
+    for (int s = 0; s < g.S; ++s) {
+      const int vs = v + g.pw - s;
+      if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) ++n;
+    }
+    ++colh[n];
+  }
+  int64_t taps = 0;
+  for (int a = 0; a <= g.R; ++a)
+    for (int b = 0; b <= g.S; ++b) taps += rowh[a] * colh[b] * (a * b > 0 ? a * b : 1);
+  const int tilesPerPix = (g.NB / 4) * MB;
+  const int64_t total = taps * tilesPerPix * nkc;
+  const int S = chip_slots();
+  if (total >= (int64_t)1 << 30 || total < (int64_t)16 * S) return rp;   // too long for int, or too little work
+  rp.enabled = 1;
+  rp.tilesPerPix = tilesPerPix;
+  rp.total = (int)total;
+  rp.nWg = S & ~7;
+  rp.units = (int)((total + rp.nWg - 1) / rp.nWg);
+  return rp;
+}
+
 struct BwdDataPlan {
   bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
   int Cp, Ks4, nch, MB1, CT1;
   cs::TailPlan tail;
-  size_t off_dyt, off_wt, off_dxt, off_perm, off_tab, off_zero, off_T, off_tail, total;
+  cs::RunPlan run;
+  size_t off_dyt, off_wt, off_dxt, off_perm, off_cls, off_scratch, off_tab, off_zero, off_T, off_tail, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
@@ -156,6 +198,10 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_wt = o;   o += seg((int64_t)g.RS * g.Ks * p.Cp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
+  p.off_cls = o;  o += seg(2 * (g.RS + 1));
+  p.off_scratch = o; o += seg((int64_t)g.H + g.W);
+  p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM);
+  p.off_tail = o; o += p.run.enabled ? (size_t)p.run.nWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
   p.total = o;
   return p;
 }
@@ -247,7 +293,7 @@ Fwd16Plan plan_fwd16(const Geo& g) {
 
 struct BwdData16Plan {
   int Ksp;
-  size_t off_dy, off_w, off_dxt, off_perm, total;
+  size_t off_dy, off_w, off_dxt, off_perm, off_cls, off_scratch, total;
 };
 BwdData16Plan plan_bwd_data16(const Geo& g) {
   BwdData16Plan p;
@@ -257,6 +303,8 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   p.off_w = o;    o += seg16((int64_t)g.RS * g.C * p.Ksp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
+  p.off_cls = o;  o += seg(2 * (g.RS + 1));
+  p.off_scratch = o; o += seg((int64_t)g.H + g.W);
   p.total = o;
   return p;
 }
@@ -528,7 +576,8 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     // per channel c: w[k0..k1)[c] as a Ks x RS matrix -> w_rsck[rs][c][Ksp]
     launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.RS, g.CRS, g.Ks, g.RS, wp, p.Ksp,
                         (int64_t)g.C * p.Ksp, p.Ksp, g.C, nullptr, st, true);
-    hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
+    hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm,
+                       (int*)(base + p.off_cls), (int*)(base + p.off_scratch));
     const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
     if ((rc = allow_big_lds(cs::bwd_data16_gemm_kernel, lds)) != CONV_OK) return rc;
     const int MB = (g.C + cs::BM - 1) / cs::BM;
@@ -590,14 +639,21 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
                       (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, wt - cs::ZERO_PAGE_FLOATS, st);
-  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm);
-  const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;  // tiles + tap list + per-block tap offsets
+  int* cls = (int*)(base + p.off_cls);
+  int* scratch = (int*)(base + p.off_scratch);
+  float* partial = (float*)(base + p.off_tail);
+  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm, cls, scratch);
+  // tiles + tap list + per-block tap offsets + copy of the class table
+  const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20 + (g.RS + 1) * 8;
   if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel, lds)) != CONV_OK) return rc;
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st,
-                     g, wt, p.Cp, dyt, perm, dxt, MB, CT);
+  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(p.run.enabled ? p.run.nWg : cs::grid_dealt(MB, CT)), dim3(cs::NT),
+                     lds, st, g, wt, p.Cp, dyt, perm, cls, dxt, MB, CT, p.run, partial);
+  if (p.run.enabled)
+    hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, cls, partial, dxt,
+                       MB, p.run);
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);

@@ -187,7 +187,7 @@ struct BwdData16LoadA {
   int uoff;
   TapWalk walk;
   __device__ BwdData16LoadA(const Geo& g, const bf16_t* wt_, int Ksp, int m0, const int* taps_, int nkc_)
-      : wt(wt_), taps(taps_), S(g.S), CKsp(g.C * Ksp), walk(nkc_) {
+      : wt(wt_), taps(taps_), S(g.S), CKsp(g.C * Ksp), walk(nkc_, 0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int kq8 = 8 * ((l & 7) ^ (l >> 3));
 #pragma unroll
@@ -217,7 +217,7 @@ struct BwdData16LoadB {
   bool ok;
   TapWalk walk;
   __device__ BwdData16LoadB(const bf16_t* dy_, int Ksp, const int* tapoff_, int nkc_)
-      : dy(dy_), tapoff(tapoff_), walk(nkc_) {
+      : dy(dy_), tapoff(tapoff_), walk(nkc_, 0) {
     const int l = threadIdx.x & 63;
     wvb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kq8 = 8 * ((l & 7) ^ (l >> 3));

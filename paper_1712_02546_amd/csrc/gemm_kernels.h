@@ -217,7 +217,7 @@ __global__ __launch_bounds__(NT) void fwd_tail_fixup_kernel(Geo g, const float* 
 // The (tap, k-chunk) counters are uniform and advance once per issue.
 struct TapWalk {
   int ti, kc, nkc;
-  __device__ TapWalk(int nkc_) : ti(0), kc(0), nkc(nkc_) {}
+  __device__ TapWalk(int nkc_, int ch0) : ti(ch0 / nkc_), kc(ch0 - (ch0 / nkc_) * nkc_), nkc(nkc_) {}
   __device__ __forceinline__ void next() {   // branch-free carry
     ++kc;
     const int c = kc == nkc;
@@ -237,14 +237,14 @@ struct BwdDataLoadA {
   int base;
   bool cok, live;
   TapWalk walk;
-  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_)
-      : wt(wt_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), walk(nkc_) {
+  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_, int ch0)
+      : wt(wt_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int c = m0 + 4 * (l & 31);
     cok = c < Cp;
     krow = 8 * wv + (l >> 5);
     lane_off = krow * Cp + c;
-    const int e = taps[0];
+    const int e = taps[walk.ti];
     tap = (e >> 16) * S + (e & 0xffff);
   }
   __device__ __forceinline__ void begin(int, bool live_) {
@@ -273,14 +273,14 @@ struct BwdDataLoadB {
   int base;
   bool live;
   TapWalk walk;
-  __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* tapoff_, int nkc_)
-      : dyt(dyt_), tapoff(tapoff_), Ks(g.Ks), PQNp(g.PQ * g.Np), walk(nkc_) {
+  __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* tapoff_, int nkc_, int ch0)
+      : dyt(dyt_), tapoff(tapoff_), Ks(g.Ks), PQNp(g.PQ * g.Np), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int cq = l & 31;
     cb = cq >> 3;
     krow = 8 * wv + (l >> 5);
     lane_off = 4 * (cq & 7);
-    toff = tapoff[cb];
+    toff = tapoff[walk.ti * 4 + cb];
   }
   __device__ __forceinline__ void begin(int, bool live_) {
     live = live_ & (toff >= 0);
@@ -296,94 +296,203 @@ struct BwdDataLoadB {
   }
 };
 
-// dx_t[c][pixel][n]; column tiles follow the pixel order in perm (heaviest first).
+// Even sharing of the input-gradient pass (tiles of unequal cost).  With every column tile
+// holding one pixel (Np a multiple of 128) the tiles form a line: pixels by decreasing tap
+// count (perm / cls from the ordering kernel), per pixel its Np/128 column tiles, per column
+// tile its MB row tiles.  A tile with t taps is max(t,1)*nkc chunks long.  The line is cut
+// into nWg equal runs of `units` chunks; a workgroup computes the tiles inside its run
+// whole and the (at most two) tiles that stick out at either end partially, into scratch
+// slot 2*run (the tile its run starts in) or 2*run+1; a fix-up kernel adds the slots of a
+// cut tile in run order.  enabled = 0: one workgroup per tile, heaviest first (tile_dealt).
+struct RunPlan {
+  int enabled, units, nWg, tilesPerPix, total;
+};
+
+__device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __restrict__ dxt,
+                                                     const int* __restrict__ perm, int mb, int ct, int i, int j,
+                                                     const f32x16& acc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int gcb = ct * 4 + wn * 2 + j;
+  if (gcb >= g.HW * g.NB) return;
+  const int sp = gcb / g.NB, nb = gcb - sp * g.NB;
+  const int px = perm[sp];
+  const int n = nb * 32 + (lane & 31);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int c = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
+    if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[v];
+  }
+}
+
+// dx_t[c][pixel][n]; column tiles follow the pixel order in perm.
 __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* __restrict__ wt, int Cp,
                                                            const float* __restrict__ dyt,
                                                            const int* __restrict__ perm,
-                                                           float* __restrict__ dxt, int MB, int CT) {
+                                                           const int* __restrict__ cls,
+                                                           float* __restrict__ dxt, int MB, int CT, RunPlan rp,
+                                                           float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
   int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 3]: the loaders run up to three entries past the list
   int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][4]
+  int* s_cls = s_tapoff + 4 * (g.RS + 3);      // [RS + 1][2], run mode only
   __shared__ int s_ntaps;
-  int mb, ct;
-  if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
-  const int m0 = mb * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-  // Taps that reach at least one of the tile's (up to four) pixels, in (r,s) order, and
-  // for each of them where it lands in dy_t for every column block.
-  if (wave == 0) {
-    int hp[4], vp[4], nbo[4];
-    bool ok[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int gcb = ct * 4 + j;
-      ok[j] = gcb < g.HW * g.NB;
-      const int sp = ok[j] ? gcb / g.NB : 0;
-      const int px = perm[sp];
-      nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 : 0;
-      hp[j] = px / g.W + g.ph;
-      vp[j] = px % g.W + g.pw;
-    }
-    int cnt = 0;
-    for (int b = 0; b < g.RS; b += 64) {
-      const int tp = b + lane;
-      const int rr = tp / g.S, ss = tp - rr * g.S;
-      bool any = false;
-      int offs[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int hr = hp[j] - rr, vs = vp[j] - ss;
-        const int p = hr / g.sh, q = vs / g.sw;
-        const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
-                         p < g.P && q < g.Q;
-        offs[j] = hit ? (p * g.Q + q) * g.Np + nbo[j] : -1;
-        any |= hit;
-      }
-      const unsigned long long mask = __ballot(any);
-      if (any) {
-        const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-        s_taps[pos] = (rr << 16) | ss;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
-      }
-      cnt += __popcll(mask);
-    }
-    if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;   // the entries the loaders fetch after the last tap
-    if (lane < 3) s_taps[cnt + lane] = 0;
-    if (lane == 0) s_ntaps = cnt;
-  }
-  __syncthreads();
-  const int ntaps = s_ntaps;
   const int nkc = (g.Ks + BK - 1) / BK;
 
-  f32x16 acc[2][2];
+  // Chunks [c0, c1) of tile (mb, ct), stored as the result (direct) or into a scratch slot.
+  auto segment = [&](int mb, int ct, int c0, int c1, bool direct, int slot) {
+    // Taps that reach at least one of the tile's (up to four) pixels, in (r,s) order, and
+    // for each of them where it lands in dy_t for every column block.
+    if (wave == 0) {
+      int hp[4], vp[4], nbo[4];
+      bool ok[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < 4; ++j) {
+        const int gcb = ct * 4 + j;
+        ok[j] = gcb < g.HW * g.NB;
+        const int sp = ok[j] ? gcb / g.NB : 0;
+        const int px = perm[sp];
+        nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 : 0;
+        hp[j] = px / g.W + g.ph;
+        vp[j] = px % g.W + g.pw;
+      }
+      int cnt = 0;
+      for (int b = 0; b < g.RS; b += 64) {
+        const int tp = b + lane;
+        const int rr = tp / g.S, ss = tp - rr * g.S;
+        bool any = false;
+        int offs[4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j) {
+          const int hr = hp[j] - rr, vs = vp[j] - ss;
+          const int p = hr / g.sh, q = vs / g.sw;
+          const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
+                           p < g.P && q < g.Q;
+          offs[j] = hit ? (p * g.Q + q) * g.Np + nbo[j] : -1;
+          any |= hit;
+        }
+        const unsigned long long mask = __ballot(any);
+        if (any) {
+          const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+          s_taps[pos] = (rr << 16) | ss;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  BwdDataLoadA la(g, wt, Cp, m0, s_taps, nkc);
-  BwdDataLoadB lb(g, dyt, s_tapoff, nkc);
-  gemm_mainloop(la, lb, 0, ntaps * nkc, smem, acc);
-
-  const int wm = wave >> 1, wn = wave & 1;
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int gcb = ct * 4 + wn * 2 + j;
-    if (gcb >= g.HW * g.NB) continue;
-    const int sp = gcb / g.NB, nb = gcb - sp * g.NB;
-    const int px = perm[sp];
-    const int n = nb * 32 + (lane & 31);
+          for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
+        }
+        cnt += __popcll(mask);
+      }
+      if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;   // the entries the loaders fetch after the last tap
+      if (lane < 3) s_taps[cnt + lane] = 0;
+      if (lane == 0) s_ntaps = cnt;
+    }
+    __syncthreads();
+    const int nchunks = s_ntaps * nkc;
+    const int cb = min(c0, nchunks), ce = min(c1, nchunks);
+    f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int c = m0 + wm * 64 + i * 32 + acc_row(v, lane);
-        if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[i][j][v];
-      }
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    BwdDataLoadA la(g, wt, Cp, mb * BM, s_taps, nkc, cb);
+    BwdDataLoadB lb(g, dyt, s_tapoff, nkc, cb);
+    gemm_mainloop(la, lb, cb, ce, smem, acc);
+    if (direct) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) bwd_data_store_block(g, dxt, perm, mb, ct, i, j, acc[i][j]);
+    } else {
+      store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+    }
+    __syncthreads();   // the next segment rewrites the tap list
+  };
+
+  if (!rp.enabled) {
+    int mb, ct;
+    if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
+    segment(mb, ct, 0, 0x7fffffff, true, 0);
+    return;
   }
+
+  // run mode: runs are dealt to the XCDs in contiguous blocks (run = xcd * nWg/8 + sequence)
+  const int run = (blockIdx.x & 7) * (rp.nWg >> 3) + (blockIdx.x >> 3);
+  int pos = run * rp.units;
+  const int end = min(pos + rp.units, rp.total);
+  if (pos >= end) return;
+  for (int i = threadIdx.x; i < 2 * (g.RS + 1); i += NT) s_cls[i] = cls[i];
+  __syncthreads();
+  // locate pos: tap-count class wc (descending), tile index t inside the class, chunk c inside the tile
+  int wc = g.RS, t = 0, c = 0;
+  {
+    int rest = pos;
+    for (;; --wc) {
+      const int len = max(wc, 1) * nkc;
+      const int span = s_cls[2 * wc + 1] * rp.tilesPerPix * len;
+      if (rest < span) {
+        t = rest / len;
+        c = rest - t * len;
+        break;
+      }
+      if (wc == 0) return;   // cannot happen when the host's total matches the class table
+      rest -= span;
+    }
+  }
+  const int NBq = g.NB >> 2;
+  bool first = true;
+  while (pos < end) {
+    const int len = max(wc, 1) * nkc;
+    const int ce = min(len, c + (end - pos));
+    const int pi = t / rp.tilesPerPix, sub = t - pi * rp.tilesPerPix;
+    const int nbq = sub / MB, mb = sub - nbq * MB;
+    const int ct = (s_cls[2 * wc] + pi) * NBq + nbq;
+    segment(mb, ct, c, ce, c == 0 && ce == len, run * 2 + (first ? 0 : 1));
+    pos += ce - c;
+    c = 0;
+    first = false;
+    if (++t == s_cls[2 * wc + 1] * rp.tilesPerPix) {
+      t = 0;
+      do --wc; while (wc > 0 && s_cls[2 * wc + 1] == 0);
+      if (wc < 0 || s_cls[2 * wc + 1] == 0) break;   // end of the line
+    }
+  }
+}
+
+// Adds up the scratch slots of every tile that was cut by a run boundary.  grid = (CT*MB, 4).
+__global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __restrict__ perm,
+                                                            const int* __restrict__ cls,
+                                                            const float* __restrict__ partial,
+                                                            float* __restrict__ dxt, int MB, RunPlan rp) {
+  const int nkc = (g.Ks + BK - 1) / BK;
+  const int NBq = g.NB >> 2;
+  const int ct = blockIdx.x / MB, mb = blockIdx.x - ct * MB;
+  const int sp = ct / NBq, nbq = ct - sp * NBq;
+  // position of the tile in the line
+  int a = 0, len = 0;
+  for (int wc = g.RS; wc >= 0; --wc) {
+    const int start = cls[2 * wc], cnt = cls[2 * wc + 1];
+    len = max(wc, 1) * nkc;
+    if (sp >= start && sp < start + cnt) {
+      a += ((sp - start) * rp.tilesPerPix + nbq * MB + mb) * len;
+      break;
+    }
+    a += cnt * rp.tilesPerPix * len;
+  }
+  const int b = a + len;
+  const int r0 = a / rp.units, r1 = (b - 1) / rp.units;
+  if (r0 == r1) return;   // inside one run: stored directly
+  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int r = r0; r <= r1; ++r) {
+    const int slot = r * rp.units >= a ? 0 : 1;   // a run that starts inside the tile used its first slot
+    const float* p = partial + (int64_t)(r * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];
+  }
+  bwd_data_store_block(g, dxt, perm, mb, ct, bi, bj, acc);
 }
 
 // -------------------------------------------------------- weight gradient ----

@@ -154,44 +154,65 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int2* __restrict__ tab)
   tab[i] = e;
 }
 
-// Input-gradient pass: number of filter taps that reach input pixel (h,v).
-__device__ __forceinline__ int taps_reaching(const Geo& g, int h, int v) {
-  int nr = 0, ns = 0;
-  for (int r = 0; r < g.R; ++r) {
-    const int hr = h + g.ph - r;
-    if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) ++nr;
+// Orders the H*W input pixels by decreasing tap count, ties in row-major order (a stable
+// counting sort by one workgroup, no atomics in the placement, so the order is the same
+// on every run).  perm[position] = pixel.  cls[2*w] = first position of tap count w,
+// cls[2*w+1] = number of pixels with tap count w, for w = 0..R*S.  scratch holds H + W ints.
+// A pixel's tap count is rows(h) * cols(v), so its rank among equal counts is a sum over the
+// earlier image rows of "columns with the matching factor" plus a scan of its own row.
+__global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
+                                                                    int* __restrict__ cls,
+                                                                    int* __restrict__ scratch) {
+  __shared__ int bins[1026];    // pixels per tap count, then first position per tap count
+  __shared__ int ncolhist[1026];  // image columns per column-tap count
+  int* nrow = scratch;
+  int* ncol = scratch + g.H;
+  for (int i = threadIdx.x; i <= g.RS + 1; i += blockDim.x) bins[i] = 0;
+  for (int i = threadIdx.x; i <= g.S + 1; i += blockDim.x) ncolhist[i] = 0;
+  for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
+    int n = 0;
+    for (int r = 0; r < g.R; ++r) {
+      const int hr = h + g.ph - r;
+      if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) ++n;
+    }
+    nrow[h] = n;
   }
-  for (int s = 0; s < g.S; ++s) {
-    const int vs = v + g.pw - s;
-    if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) ++ns;
+  for (int v = threadIdx.x; v < g.W; v += blockDim.x) {
+    int n = 0;
+    for (int s = 0; s < g.S; ++s) {
+      const int vs = v + g.pw - s;
+      if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) ++n;
+    }
+    ncol[v] = n;
   }
-  return nr * ns;
-}
-
-// Orders the H*W input pixels by decreasing tap count (counting sort, one
-// workgroup), so that the heaviest tiles of the input-gradient pass are
-// dispatched first.  The order among equal counts is arbitrary; it only decides
-// where a tile runs, never what it computes.  perm has H*W entries.
-__global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm) {
-  __shared__ int bins[1026];
-  const int nb = g.RS + 1;
-  for (int i = threadIdx.x; i <= nb; i += blockDim.x) bins[i] = 0;
+  __threadfence_block();
   __syncthreads();
-  for (int px = threadIdx.x; px < g.HW; px += blockDim.x)
-    atomicAdd(&bins[taps_reaching(g, px / g.W, px % g.W)], 1);
+  for (int v = threadIdx.x; v < g.W; v += blockDim.x) atomicAdd(&ncolhist[ncol[v]], 1);   // counts only
+  for (int px = threadIdx.x; px < g.HW; px += blockDim.x) atomicAdd(&bins[nrow[px / g.W] * ncol[px % g.W]], 1);
   __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0;
     for (int wgt = g.RS; wgt >= 0; --wgt) {
       const int cnt = bins[wgt];
       bins[wgt] = run;
+      cls[2 * wgt] = run;
+      cls[2 * wgt + 1] = cnt;
       run += cnt;
     }
   }
   __syncthreads();
   for (int px = threadIdx.x; px < g.HW; px += blockDim.x) {
-    const int pos = atomicAdd(&bins[taps_reaching(g, px / g.W, px % g.W)], 1);
-    perm[pos] = px;
+    const int h = px / g.W, v = px - h * g.W;
+    const int nr = nrow[h];
+    const int wgt = nr * ncol[v];
+    int rank = 0;
+    for (int hh = 0; hh < h; ++hh) {   // pixels of earlier rows with the same tap count
+      const int a = nrow[hh];
+      if (a == 0) rank += wgt == 0 ? g.W : 0;
+      else if (wgt % a == 0 && wgt / a <= g.S) rank += ncolhist[wgt / a];
+    }
+    for (int vv = 0; vv < v; ++vv) rank += nr * ncol[vv] == wgt;
+    perm[bins[wgt] + rank] = px;
   }
 }
 

@@ -28,6 +28,10 @@ ADHOC = [
     synth.random_layer(11, N=3, C=2, H=33, W=34, K=3, R=32, S=32),                   # R*S at the limit
     synth.random_layer(12, N=65, C=32, H=9, W=7, K=70, R=3, S=2, stride=2, pad=1),    # bf16: C = 32, batch 65
     synth.random_layer(13, N=20, C=72, H=10, W=10, K=130, R=5, S=5, pad=2, k0=1, k1=130),
+    # input-gradient tiles of unequal length shared out in equal runs (batch fills whole column tiles)
+    synth.random_layer(14, N=128, C=130, H=12, W=12, K=100, R=3, S=3, pad=1, k0=2, k1=100),
+    # the same with pixels no tap reaches (1x1, stride 2)
+    synth.random_layer(15, N=100, C=130, H=24, W=24, K=260, R=1, S=1, stride=2),
 ]
 
 
@@ -115,7 +119,7 @@ def test_empty_slice_and_accumulate(C):
     check(dev2.bwd_data(accumulate=1, init=init), ref + 2.5, FP32_TOL, "dx accumulate")
 
 
-@pytest.mark.parametrize("which,dtype", [(1, "f32"), (9, "f32"), (12, "bf16")])
+@pytest.mark.parametrize("which,dtype", [(1, "f32"), (9, "f32"), (14, "f32"), (12, "bf16")])
 def test_results_are_bit_stable_run_to_run(which, dtype):
     """No atomics anywhere: split reductions and shared tails are summed in a fixed order."""
     cfg = ADHOC[which]
