@@ -68,7 +68,8 @@ typedef enum {
   CONV_ERR_WORKSPACE = -5, /* ws_bytes too small, or ws missing / misaligned     */
   CONV_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch                   */
   CONV_ERR_ALIGN = -7,     /* a tensor pointer is not 16-byte aligned            */
-  CONV_ERR_PASS = -8       /* pass is not a conv_pass_t                          */
+  CONV_ERR_PASS = -8,      /* pass is not a conv_pass_t                          */
+  CONV_ERR_PARTITION = -9  /* convlayer.h: bad times, device count or k-bounds   */
 } conv_status_t;
 
 typedef enum { CONV_F32 = 0, CONV_BF16 = 1 } conv_dtype_t;

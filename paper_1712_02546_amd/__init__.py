@@ -1,11 +1,16 @@
-"""MI355X-native convolution over a kernel slice (arXiv 1712.02546, Section 4.1.2).
+"""MI355X-native convolution over a kernel slice (arXiv 1712.02546, Section 4.1.2), the Eq. (1)
+workload partition and the partitioned-layer driver (Section 3.1.1, Algorithm 1).
 
-Thin Python front end of libconvslice.so; see include/convslice.h for the ABI.
+Thin Python front end of libconvslice.so; see include/convslice.h and include/convlayer.h for the ABI.
 """
-from .binding import (CONV_BF16, CONV_F32, PASS_BWD_DATA, PASS_BWD_WEIGHT, PASS_FWD, ConvDesc,
-                      ConvError, conv_bwd_data, conv_bwd_weight, conv_fwd, conv_output_dims, conv_probe_next_call,
-                      conv_workspace_bytes, load, status_string)
+from .binding import (CONV_BF16, CONV_F32, MAX_DEVICES, PASS_BWD_DATA, PASS_BWD_WEIGHT, PASS_FWD, ConvDesc,
+                      ConvError, conv_bwd_data, conv_bwd_weight, conv_calibrate, conv_calibrate_workspace_bytes,
+                      conv_fwd, conv_layer_bwd_data, conv_layer_bwd_weight, conv_layer_fwd,
+                      conv_layer_workspace_bytes, conv_output_dims, conv_partition, conv_partition_estimate,
+                      conv_probe_next_call, conv_workspace_bytes, load, pass_mask, status_string)
 
-__all__ = ["CONV_BF16", "CONV_F32", "PASS_BWD_DATA", "PASS_BWD_WEIGHT", "PASS_FWD", "ConvDesc",
-           "ConvError", "conv_bwd_data", "conv_bwd_weight", "conv_fwd", "conv_output_dims", "conv_probe_next_call",
-           "conv_workspace_bytes", "load", "status_string"]
+__all__ = ["CONV_BF16", "CONV_F32", "MAX_DEVICES", "PASS_BWD_DATA", "PASS_BWD_WEIGHT", "PASS_FWD", "ConvDesc",
+           "ConvError", "conv_bwd_data", "conv_bwd_weight", "conv_calibrate", "conv_calibrate_workspace_bytes",
+           "conv_fwd", "conv_layer_bwd_data", "conv_layer_bwd_weight", "conv_layer_fwd",
+           "conv_layer_workspace_bytes", "conv_output_dims", "conv_partition", "conv_partition_estimate",
+           "conv_probe_next_call", "conv_workspace_bytes", "load", "pass_mask", "status_string"]

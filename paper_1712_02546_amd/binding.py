@@ -17,7 +17,11 @@ CONV_F32, CONV_BF16 = 0, 1
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_bwd_data",
-           "conv_bwd_weight", "conv_status_string", "conv_probe_next_call")
+           "conv_bwd_weight", "conv_status_string", "conv_probe_next_call",
+           "conv_partition", "conv_partition_estimate", "conv_calibrate_workspace_bytes",
+           "conv_calibrate", "conv_layer_workspace_bytes", "conv_layer_fwd",
+           "conv_layer_bwd_data", "conv_layer_bwd_weight")
+MAX_DEVICES = 64
 
 
 class conv_desc_t(ctypes.Structure):
@@ -69,6 +73,10 @@ def load() -> ctypes.CDLL:
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_1712_02546_amd.build` "
                 "(hipcc, gfx950). There is no CPU or PyTorch fallback.")
+        # PyTorch-ROCm carries its own copy of the HIP runtime.  If this library were loaded
+        # first it would pull in the system copy, a later `import torch` would add a second
+        # one, and the first kernel launch would crash inside the duplicated runtime.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         dp = ctypes.POINTER(conv_desc_t)
         vp = ctypes.c_void_p
@@ -84,6 +92,21 @@ def load() -> ctypes.CDLL:
         lib.conv_probe_next_call.restype = ctypes.c_int
         lib.conv_status_string.argtypes = [ctypes.c_int]
         lib.conv_status_string.restype = ctypes.c_char_p
+        pd, pi = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+        lib.conv_partition.argtypes = [pd, ctypes.c_int32, ctypes.c_int32, pd, pi]
+        lib.conv_partition.restype = ctypes.c_int
+        lib.conv_partition_estimate.argtypes = [pd, pd, ctypes.c_int32, pd, pd]
+        lib.conv_partition_estimate.restype = ctypes.c_int
+        lib.conv_calibrate_workspace_bytes.argtypes = [dp, ctypes.c_int]
+        lib.conv_calibrate_workspace_bytes.restype = ctypes.c_size_t
+        lib.conv_calibrate.argtypes = [dp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp, pd]
+        lib.conv_calibrate.restype = ctypes.c_int
+        lib.conv_layer_workspace_bytes.argtypes = [dp, pi, ctypes.c_int32, ctypes.c_int]
+        lib.conv_layer_workspace_bytes.restype = ctypes.c_size_t
+        for name in ("conv_layer_fwd", "conv_layer_bwd_data", "conv_layer_bwd_weight"):
+            f = getattr(lib, name)
+            f.argtypes = [dp, pi, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+            f.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -147,3 +170,96 @@ def conv_bwd_data(desc: ConvDesc, dy, w, dx, ws=None, stream=None, raw_status=Fa
 def conv_bwd_weight(desc: ConvDesc, x, dy, dw, ws=None, stream=None, raw_status=False):
     """dw[k0:k1] = weight gradient from x and dy[:, k0:k1]; returns dw (fp32)."""
     return _call("conv_bwd_weight", desc, x, dy, dw, ws, stream, raw_status)
+
+
+# ---- convlayer.h: Eq. (1) partition, calibration probe, partitioned layer --------------------
+
+def _doubles(v):
+    return (ctypes.c_double * len(v))(*[float(a) for a in v])
+
+
+def _ints(v):
+    return (ctypes.c_int32 * len(v))(*[int(a) for a in v])
+
+
+def conv_partition(t, K: int, raw_status=False):
+    """Eq. (1) shares and contiguous k-bounds for probe times t; returns (shares, bounds)."""
+    n = len(t)
+    shares = (ctypes.c_double * max(n, 1))()
+    bounds = (ctypes.c_int32 * (max(n, 0) + 1))()
+    rc = load().conv_partition(_doubles(t) if n else None, n, int(K), shares, bounds)
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_partition")
+    return [float(v) for v in shares[:n]], [int(v) for v in bounds[:n + 1]]
+
+
+def conv_partition_estimate(t, shares, raw_status=False):
+    """(finish time of the slowest device, speed-up over the fastest device alone)."""
+    fin, sp = ctypes.c_double(), ctypes.c_double()
+    rc = load().conv_partition_estimate(_doubles(t), _doubles(shares), len(t), ctypes.byref(fin),
+                                        ctypes.byref(sp))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_partition_estimate")
+    return float(fin.value), float(sp.value)
+
+
+def pass_mask(*passes: int) -> int:
+    m = 0
+    for p in passes:
+        m |= 1 << p
+    return m
+
+
+def conv_calibrate_workspace_bytes(desc: ConvDesc, mask: int) -> int:
+    cd = desc.c_struct()
+    return int(load().conv_calibrate_workspace_bytes(ctypes.byref(cd), int(mask)))
+
+
+def conv_calibrate(desc: ConvDesc, mask: int, reps: int, ws, stream=None, raw_status=False):
+    """Seconds per repetition of the selected passes on random data (blocks until measured)."""
+    cd = desc.c_struct()
+    sec = ctypes.c_double()
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load().conv_calibrate(ctypes.byref(cd), int(mask), int(reps), _ptr(ws), ws_bytes,
+                               _stream(stream), ctypes.byref(sec))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_calibrate")
+    return float(sec.value)
+
+
+def conv_layer_workspace_bytes(desc: ConvDesc, bounds, which: int) -> int:
+    cd = desc.c_struct()
+    return int(load().conv_layer_workspace_bytes(ctypes.byref(cd), _ints(bounds), len(bounds) - 1, int(which)))
+
+
+def _layer_call(name: str, desc: ConvDesc, bounds, a, b, out, ws, stream, raw_status: bool):
+    cd = desc.c_struct()
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = getattr(load(), name)(ctypes.byref(cd), _ints(bounds), len(bounds) - 1, _ptr(a), _ptr(b), _ptr(out),
+                               _ptr(ws), ws_bytes, _stream(stream))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, name)
+    return out
+
+
+def conv_layer_fwd(desc: ConvDesc, bounds, x, w, y, ws=None, stream=None, raw_status=False):
+    """All slices of the partition `bounds` write their channel blocks of y; returns y."""
+    return _layer_call("conv_layer_fwd", desc, bounds, x, w, y, ws, stream, raw_status)
+
+
+def conv_layer_bwd_data(desc: ConvDesc, bounds, dy, w, dx, ws=None, stream=None, raw_status=False):
+    """dx (+)= sum of the slices' partial input gradients, in slice order; returns dx."""
+    return _layer_call("conv_layer_bwd_data", desc, bounds, dy, w, dx, ws, stream, raw_status)
+
+
+def conv_layer_bwd_weight(desc: ConvDesc, bounds, x, dy, dw, ws=None, stream=None, raw_status=False):
+    """All slices of the partition write their blocks of dw; returns dw (fp32)."""
+    return _layer_call("conv_layer_bwd_weight", desc, bounds, x, dy, dw, ws, stream, raw_status)

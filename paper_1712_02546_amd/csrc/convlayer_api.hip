@@ -1,0 +1,379 @@
+// convlayer_api.hip -- the master's side on one GPU: Eq. (1) partition, calibration probe
+// and the driver that runs every slice of a partitioned layer (Section 3.1.1, Algorithm 1).
+// Everything here is host code on top of the per-slice entry points, plus one fill kernel.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "../../include/convlayer.h"
+
+namespace {
+
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+int check_times(const double* t, int32_t n) {
+  if (!t) return CONV_ERR_NULL;
+  if (n < 1 || n > CONV_MAX_DEVICES) return CONV_ERR_PARTITION;
+  for (int i = 0; i < n; ++i)
+    if (!(t[i] > 0.0) || !std::isfinite(t[i])) return CONV_ERR_PARTITION;
+  return CONV_OK;
+}
+
+// w_i of Eq. (1): performance value max(t)/t_i over the sum of all performance values.
+void eq1_shares(const double* t, int n, double* w) {
+  double tmax = t[0];
+  for (int i = 1; i < n; ++i) tmax = std::max(tmax, t[i]);
+  double sum = 0.0;
+  for (int i = 0; i < n; ++i) {
+    w[i] = tmax / t[i];
+    sum += w[i];
+  }
+  for (int i = 0; i < n; ++i) w[i] /= sum;
+}
+
+int check_bounds(const int32_t* bounds, int32_t n, int32_t K) {
+  if (!bounds) return CONV_ERR_NULL;
+  if (n < 1 || n > CONV_MAX_DEVICES) return CONV_ERR_PARTITION;
+  if (bounds[0] != 0 || bounds[n] != K) return CONV_ERR_PARTITION;
+  for (int i = 0; i < n; ++i)
+    if (bounds[i] > bounds[i + 1]) return CONV_ERR_PARTITION;
+  return CONV_OK;
+}
+
+conv_desc_t slice_of(const conv_desc_t& layer, int32_t k0, int32_t k1) {
+  conv_desc_t d = layer;
+  d.k0 = k0;
+  d.k1 = k1;
+  return d;
+}
+
+// Validates the layer descriptor itself (whole layer as the slice).
+int check_layer(const conv_desc_t* desc) {
+  if (!desc) return CONV_ERR_NULL;
+  const conv_desc_t full = slice_of(*desc, 0, desc->K);
+  int32_t P, Q;
+  return conv_output_dims(&full, &P, &Q);
+}
+
+// ---- internal streams of the layer driver, one set per device ----------------------------
+constexpr int kStreams = 4;
+constexpr int kMaxGpus = 16;
+struct StreamSet {
+  bool ready = false;
+  hipStream_t s[kStreams];
+  hipEvent_t fork;
+  hipEvent_t join[kStreams];
+};
+StreamSet g_sets[kMaxGpus];
+std::mutex g_sets_mutex;
+
+StreamSet* stream_set() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxGpus) return nullptr;
+  std::lock_guard<std::mutex> lock(g_sets_mutex);
+  StreamSet& ss = g_sets[dev];
+  if (!ss.ready) {
+    if (hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+    for (int i = 0; i < kStreams; ++i) {
+      if (hipStreamCreateWithFlags(&ss.s[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
+      if (hipEventCreateWithFlags(&ss.join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+    }
+    ss.ready = true;
+  }
+  return &ss;
+}
+
+typedef int (*slice_fn)(const conv_desc_t*, const void*, const void*, void*, void*, size_t, void*);
+
+// Slices with disjoint outputs: fork from the caller's stream, one region of ws per slice, join.
+int run_disjoint(slice_fn fn, int pass, const conv_desc_t* desc, const int32_t* bounds, int32_t n, const void* a,
+                 const void* b, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_layer(desc);
+  if (rc != CONV_OK) return rc;
+  if ((rc = check_bounds(bounds, n, desc->K)) != CONV_OK) return rc;
+  if (!a || !b || !out) return CONV_ERR_NULL;
+  if (ws_bytes < conv_layer_workspace_bytes(desc, bounds, n, pass)) return CONV_ERR_WORKSPACE;
+  int live = 0;
+  for (int i = 0; i < n; ++i) live += bounds[i + 1] > bounds[i];
+  if (live == 0) return CONV_OK;
+  hipStream_t user = (hipStream_t)hip_stream;
+  char* base = (char*)ws;
+  size_t off = 0;
+  if (live == 1) {
+    for (int i = 0; i < n; ++i) {
+      if (bounds[i + 1] == bounds[i]) continue;
+      const conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
+      return fn(&d, a, b, out, base, ws_bytes, hip_stream);
+    }
+  }
+  StreamSet* ss = stream_set();
+  if (!ss) return CONV_ERR_LAUNCH;
+  const int used = std::min(live, kStreams);
+  if (hipEventRecord(ss->fork, user) != hipSuccess) return CONV_ERR_LAUNCH;
+  for (int s = 0; s < used; ++s)
+    if (hipStreamWaitEvent(ss->s[s], ss->fork, 0) != hipSuccess) rc = CONV_ERR_LAUNCH;
+  int turn = 0;
+  for (int i = 0; i < n && rc == CONV_OK; ++i) {
+    if (bounds[i + 1] == bounds[i]) continue;
+    const conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
+    const size_t need = round256(conv_workspace_bytes(&d, pass));
+    rc = fn(&d, a, b, out, need ? base + off : nullptr, need, (void*)ss->s[turn % used]);
+    off += need;
+    ++turn;
+  }
+  // always join what was forked, also after an error
+  for (int s = 0; s < used; ++s) {
+    if (hipEventRecord(ss->join[s], ss->s[s]) != hipSuccess) rc = rc == CONV_OK ? CONV_ERR_LAUNCH : rc;
+    if (hipStreamWaitEvent(user, ss->join[s], 0) != hipSuccess) rc = rc == CONV_OK ? CONV_ERR_LAUNCH : rc;
+  }
+  return rc;
+}
+
+// ---- calibration probe --------------------------------------------------------------------
+// Uniform in (-1,1) from a hash of the element index (values only need to be ordinary numbers).
+__device__ __forceinline__ float probe_value(uint64_t i) {
+  uint64_t z = i + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return ((float)(uint32_t)(z >> 40) + 0.5f) * (2.0f / 16777216.0f) - 1.0f;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void probe_fill_kernel(T* __restrict__ p, int64_t count, uint64_t salt) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) {
+    const float v = probe_value((uint64_t)i + salt);
+    if constexpr (sizeof(T) == 4) {
+      p[i] = v;
+    } else {
+      p[i] = (T)(__float_as_uint(v) >> 16);   // truncation is fine for probe data
+    }
+  }
+}
+
+void probe_fill(int dtype, void* p, int64_t count, uint64_t salt, hipStream_t st) {
+  if (count <= 0) return;
+  const int blocks = (int)std::min<int64_t>((count + 255) / 256, 8192);
+  if (dtype == CONV_F32)
+    hipLaunchKernelGGL(probe_fill_kernel<float>, dim3(blocks), dim3(256), 0, st, (float*)p, count, salt);
+  else
+    hipLaunchKernelGGL(probe_fill_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (uint16_t*)p, count, salt);
+}
+
+struct CalibPlan {
+  conv_desc_t d;   // the probed slice as a packed layer of its own: K = k1 - k0
+  size_t off_x, off_w, off_y, off_dx, off_dw, off_ws, ws_pass, total;
+  int64_t nx, nw, ny;
+  bool ok;
+};
+
+CalibPlan plan_calib(const conv_desc_t* desc, int mask) {
+  CalibPlan p{};
+  p.ok = false;
+  if (!desc) return p;
+  int32_t P, Q;
+  if (conv_output_dims(desc, &P, &Q) != CONV_OK) return p;
+  if (mask & ~7) return p;
+  if (mask == 0) mask = 1 << CONV_PASS_FWD;
+  p.d = *desc;
+  p.d.K = desc->k1 - desc->k0;
+  p.d.k0 = 0;
+  p.d.k1 = p.d.K;
+  p.d.accumulate = 0;
+  if (p.d.K < 1) return p;
+  const size_t es = desc->dtype == CONV_BF16 ? 2 : 4;
+  p.nx = (int64_t)desc->N * desc->C * desc->H * desc->W;
+  p.nw = (int64_t)p.d.K * desc->C * desc->R * desc->S;
+  p.ny = (int64_t)desc->N * p.d.K * P * Q;
+  size_t o = 0;
+  p.off_x = o; o += round256(p.nx * es);
+  p.off_w = o; o += round256(p.nw * es);
+  p.off_y = o; o += round256(p.ny * es);
+  p.off_dx = o; o += (mask & (1 << CONV_PASS_BWD_DATA)) ? round256(p.nx * es) : 0;
+  p.off_dw = o; o += (mask & (1 << CONV_PASS_BWD_WEIGHT)) ? round256(p.nw * 4) : 0;
+  p.ws_pass = 0;
+  for (int pass = 0; pass < 3; ++pass)
+    if (mask & (1 << pass)) p.ws_pass = std::max(p.ws_pass, conv_workspace_bytes(&p.d, pass));
+  p.off_ws = o; o += round256(p.ws_pass);
+  p.total = o;
+  p.ok = true;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_partition(const double* t, int32_t n, int32_t K, double* shares, int32_t* bounds) {
+  int rc = check_times(t, n);
+  if (rc != CONV_OK) return rc;
+  if (K < 0) return CONV_ERR_PARTITION;
+  double w[CONV_MAX_DEVICES];
+  eq1_shares(t, n, w);
+  if (shares)
+    for (int i = 0; i < n; ++i) shares[i] = w[i];
+  if (!bounds) return CONV_OK;
+  // Largest remainder.  Quotas within tol of an integer count as that integer and
+  // fractional parts within tol of each other as equal, so rounding noise in the
+  // doubles cannot reorder what is a tie in exact arithmetic.
+  const double tol = std::ldexp((double)std::max(K, 1), -40);
+  int32_t cnt[CONV_MAX_DEVICES];
+  double frac[CONV_MAX_DEVICES];
+  int64_t given = 0;
+  for (int i = 0; i < n; ++i) {
+    const double q = w[i] * (double)K;
+    double f = std::floor(q + tol);
+    if (f > (double)K) f = (double)K;
+    cnt[i] = (int32_t)f;
+    frac[i] = std::max(q - f, 0.0);
+    given += cnt[i];
+  }
+  // The kernels left over (fewer than n) go to the largest fractional parts; the scan keeps
+  // the lower index unless a later part is larger by more than tol.
+  bool taken[CONV_MAX_DEVICES] = {false};
+  for (int64_t left = (int64_t)K - given; left > 0; --left) {
+    int best = -1;
+    for (int i = 0; i < n; ++i)
+      if (!taken[i] && (best < 0 || frac[i] > frac[best] + tol)) best = i;
+    if (best < 0) {   // every device already got one: start another round
+      for (int i = 0; i < n; ++i) taken[i] = false;
+      best = 0;
+    }
+    taken[best] = true;
+    ++cnt[best];
+  }
+  // The floors cannot add up to more than K unless rounding lifted several quotas at once;
+  // hand such kernels back from the last devices that hold any.
+  for (int64_t over = given - (int64_t)K; over > 0; --over)
+    for (int i = n - 1; i >= 0; --i)
+      if (cnt[i] > 0) {
+        --cnt[i];
+        break;
+      }
+  bounds[0] = 0;
+  for (int i = 0; i < n; ++i) bounds[i + 1] = bounds[i] + cnt[i];
+  return CONV_OK;
+}
+
+int conv_partition_estimate(const double* t, const double* shares, int32_t n, double* finish, double* speedup) {
+  int rc = check_times(t, n);
+  if (rc != CONV_OK) return rc;
+  if (!shares) return CONV_ERR_NULL;
+  double worst = 0.0, tmin = t[0];
+  for (int i = 0; i < n; ++i) {
+    if (!(shares[i] >= 0.0) || !std::isfinite(shares[i])) return CONV_ERR_PARTITION;
+    worst = std::max(worst, t[i] * shares[i]);
+    tmin = std::min(tmin, t[i]);
+  }
+  if (finish) *finish = worst;
+  if (speedup) *speedup = worst > 0.0 ? tmin / worst : 0.0;
+  return CONV_OK;
+}
+
+size_t conv_calibrate_workspace_bytes(const conv_desc_t* desc, int pass_mask) {
+  const CalibPlan p = plan_calib(desc, pass_mask);
+  return p.ok ? p.total : 0;
+}
+
+int conv_calibrate(const conv_desc_t* desc, int pass_mask, int reps, void* ws, size_t ws_bytes, void* hip_stream,
+                   double* seconds) {
+  if (!desc || !seconds) return CONV_ERR_NULL;
+  int32_t P, Q;
+  int rc = conv_output_dims(desc, &P, &Q);
+  if (rc != CONV_OK) return rc;
+  if (pass_mask & ~7) return CONV_ERR_PASS;
+  if (reps < 1) return CONV_ERR_SHAPE;
+  if (desc->k1 - desc->k0 < 1) return CONV_ERR_SLICE;
+  if (pass_mask == 0) pass_mask = 1 << CONV_PASS_FWD;
+  const CalibPlan p = plan_calib(desc, pass_mask);
+  if (!p.ok) return CONV_ERR_SHAPE;
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.total) return CONV_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* base = (char*)ws;
+  void* x = base + p.off_x;
+  void* w = base + p.off_w;
+  void* y = base + p.off_y;
+  void* dx = base + p.off_dx;
+  void* dw = base + p.off_dw;
+  void* pws = p.ws_pass ? base + p.off_ws : nullptr;
+  probe_fill(desc->dtype, x, p.nx, 0, st);
+  probe_fill(desc->dtype, w, p.nw, 1ull << 40, st);
+  probe_fill(desc->dtype, y, p.ny, 2ull << 40, st);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return CONV_ERR_LAUNCH;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return CONV_ERR_LAUNCH;
+  }
+  // bwd passes first so that dy is still the random pattern; fwd (which rewrites y) last
+  auto once = [&]() -> int {
+    int r = CONV_OK;
+    if (r == CONV_OK && (pass_mask & (1 << CONV_PASS_BWD_DATA))) r = conv_bwd_data(&p.d, y, w, dx, pws, p.ws_pass, hip_stream);
+    if (r == CONV_OK && (pass_mask & (1 << CONV_PASS_BWD_WEIGHT))) r = conv_bwd_weight(&p.d, x, y, dw, pws, p.ws_pass, hip_stream);
+    if (r == CONV_OK && (pass_mask & (1 << CONV_PASS_FWD))) r = conv_fwd(&p.d, x, w, y, pws, p.ws_pass, hip_stream);
+    return r;
+  };
+  rc = once();   // untimed
+  if (rc == CONV_OK && hipEventRecord(e0, st) != hipSuccess) rc = CONV_ERR_LAUNCH;
+  for (int i = 0; i < reps && rc == CONV_OK; ++i) rc = once();
+  if (rc == CONV_OK && hipEventRecord(e1, st) != hipSuccess) rc = CONV_ERR_LAUNCH;
+  if (rc == CONV_OK && hipEventSynchronize(e1) != hipSuccess) rc = CONV_ERR_LAUNCH;
+  float ms = 0.f;
+  if (rc == CONV_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = CONV_ERR_LAUNCH;
+  if (rc != CONV_OK) (void)hipStreamSynchronize(st);   // nothing of ours may be in flight when the events go
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc == CONV_OK) *seconds = (double)ms * 1e-3 / reps;
+  return rc;
+}
+
+size_t conv_layer_workspace_bytes(const conv_desc_t* desc, const int32_t* bounds, int32_t n_slices, int pass) {
+  if (check_layer(desc) != CONV_OK || check_bounds(bounds, n_slices, desc->K) != CONV_OK) return 0;
+  if (pass < CONV_PASS_FWD || pass > CONV_PASS_BWD_WEIGHT) return 0;
+  size_t sum = 0, biggest = 0;
+  for (int i = 0; i < n_slices; ++i) {
+    if (bounds[i + 1] == bounds[i]) continue;
+    const conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
+    const size_t b = round256(conv_workspace_bytes(&d, pass));
+    sum += b;
+    biggest = std::max(biggest, b);
+  }
+  return pass == CONV_PASS_BWD_DATA ? biggest : sum;
+}
+
+int conv_layer_fwd(const conv_desc_t* desc, const int32_t* bounds, int32_t n_slices, const void* x, const void* w,
+                   void* y, void* ws, size_t ws_bytes, void* hip_stream) {
+  return run_disjoint(conv_fwd, CONV_PASS_FWD, desc, bounds, n_slices, x, w, y, ws, ws_bytes, hip_stream);
+}
+
+int conv_layer_bwd_weight(const conv_desc_t* desc, const int32_t* bounds, int32_t n_slices, const void* x,
+                          const void* dy, void* dw, void* ws, size_t ws_bytes, void* hip_stream) {
+  return run_disjoint(conv_bwd_weight, CONV_PASS_BWD_WEIGHT, desc, bounds, n_slices, x, dy, dw, ws, ws_bytes,
+                      hip_stream);
+}
+
+int conv_layer_bwd_data(const conv_desc_t* desc, const int32_t* bounds, int32_t n_slices, const void* dy,
+                        const void* w, void* dx, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_layer(desc);
+  if (rc != CONV_OK) return rc;
+  if ((rc = check_bounds(bounds, n_slices, desc->K)) != CONV_OK) return rc;
+  if (!dy || !w || !dx) return CONV_ERR_NULL;
+  if (ws_bytes < conv_layer_workspace_bytes(desc, bounds, n_slices, CONV_PASS_BWD_DATA)) return CONV_ERR_WORKSPACE;
+  // dx = sum over slices, added in slice order on the caller's stream.  If every slice is
+  // empty (K = 0 cannot be described, so this needs n_slices slices of a zero-kernel range,
+  // which check_bounds only admits for K = 0) nothing runs.
+  bool first = true;
+  for (int i = 0; i < n_slices; ++i) {
+    if (bounds[i + 1] == bounds[i]) continue;
+    conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
+    d.accumulate = first ? desc->accumulate : 1;
+    first = false;
+    if ((rc = conv_bwd_data(&d, dy, w, dx, ws, ws_bytes, hip_stream)) != CONV_OK) return rc;
+  }
+  return CONV_OK;
+}
+
+}  // extern "C"

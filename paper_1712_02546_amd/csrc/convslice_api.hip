@@ -753,6 +753,7 @@ const char* conv_status_string(int status) {
     case CONV_ERR_LAUNCH: return "HIP launch failed";
     case CONV_ERR_ALIGN: return "tensor pointer is not 16-byte aligned";
     case CONV_ERR_PASS: return "unknown pass";
+    case CONV_ERR_PARTITION: return "invalid times, device count or kernel bounds";
     default: return "unknown status";
   }
 }

@@ -1,4 +1,4 @@
-"""The C-ABI library loads, exports what include/convslice.h declares, and rejects bad
+"""The C-ABI library loads, exports what include/*.h declare, and rejects bad
 arguments before touching the GPU (none of these calls launches anything)."""
 import ctypes
 import os
@@ -13,9 +13,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "convslice.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(conv_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(conv_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -27,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    for code in range(-8, 1):
+    for code in range(-9, 1):
         assert cs.status_string(code)
     assert cs.status_string(0) == "ok"
     assert "unknown" in cs.status_string(-99)
@@ -105,3 +111,16 @@ def test_empty_slice_needs_no_workspace_for_fwd_and_bwd_weight():
     assert cs.conv_bwd_weight(d, A, A, A, None, stream=0, raw_status=True) == 0
     da = cs.ConvDesc(**GOOD, k0=4, k1=4, accumulate=1)
     assert cs.conv_bwd_data(da, A, A, A, None, stream=0, raw_status=True) == 0
+
+
+def test_loading_the_library_brings_in_torch_first():
+    """PyTorch-ROCm ships its own HIP runtime; the binding must not let the system copy in
+    ahead of it (two runtimes in one process crash at the first kernel launch)."""
+    import subprocess
+    import sys
+    code = ("import sys; import paper_1712_02546_amd as cs; assert 'torch' not in sys.modules; "
+            "cs.load(); assert 'torch' in sys.modules; "
+            "maps = open('/proc/self/maps').read(); "
+            "libs = {l.split()[-1] for l in maps.splitlines() if 'libamdhip64' in l}; "
+            "assert len(libs) == 1, libs")
+    subprocess.check_call([sys.executable, "-c", code], cwd=ROOT)
