@@ -194,6 +194,70 @@ def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
     return out
 
 
+def measure_partition(cfg_name, dtype_name, times, steps, warmup):
+    """Times the layer split by Eq. (1) for the given probe times (all slices on this one GPU,
+    conv_layer_*) next to the same layer as one slice; also runs the calibration probe."""
+    import numpy as np
+    import torch
+
+    import paper_1712_02546_amd as cs
+    from paper_1712_02546_amd import synth
+
+    cfg = synth.CONFIGS[cfg_name]
+    cfg = cfg.with_slice(0, cfg.K)
+    dtype = cs.CONV_F32 if dtype_name == "f32" else cs.CONV_BF16
+    x, w, dy = synth.make_inputs(cfg)
+    dev = torch.device("cuda:0")
+
+    def up(a):
+        if dtype == cs.CONV_BF16:
+            return torch.from_numpy(synth.f32_to_bf16_bits(synth.round_to_bf16(a)).view(np.int16)).to(dev).view(
+                torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    xd, wd, dyd = up(x), up(w), up(dy)
+    tdt = torch.float32 if dtype == cs.CONV_F32 else torch.bfloat16
+    y = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=tdt, device=dev)
+    dx = torch.zeros((cfg.N, cfg.C, cfg.H, cfg.W), dtype=tdt, device=dev)
+    dw = torch.zeros((cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.float32, device=dev)
+    desc = cs.ConvDesc(cfg.N, cfg.C, cfg.H, cfg.W, cfg.K, cfg.R, cfg.S, cfg.stride, cfg.stride, cfg.pad, cfg.pad,
+                       0, cfg.K, dtype, 0)
+    shares, bounds = cs.conv_partition(times, cfg.K)
+    mask = cs.pass_mask(cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT)
+    need = max([cs.conv_layer_workspace_bytes(desc, bounds, p) for p in (0, 1, 2)] +
+               [cs.conv_layer_workspace_bytes(desc, [0, cfg.K], p) for p in (0, 1, 2)] +
+               [cs.conv_calibrate_workspace_bytes(desc, mask)])
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def layer(b):
+        cs.conv_layer_fwd(desc, b, xd, wd, y, ws, stream)
+        cs.conv_layer_bwd_data(desc, b, dyd, wd, dx, ws, stream)
+        cs.conv_layer_bwd_weight(desc, b, xd, dyd, dw, ws, stream)
+
+    def timed(b):
+        for _ in range(warmup):
+            layer(b)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            layer(b)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    one = timed([0, cfg.K])
+    split = timed(bounds)
+    probe_s = cs.conv_calibrate(desc, mask, max(steps // 2, 1), ws, stream)
+    finish, speedup = cs.conv_partition_estimate(times, shares)
+    F3 = 3 * cfg.flops_per_pass
+    return {"what": "layer split by Eq. (1), all slices on one GPU", "config": cfg.name, "dtype": dtype_name,
+            "probe_times": times, "shares": shares, "bounds": bounds,
+            "estimated_finish_of_slowest": finish, "estimated_speedup_over_fastest_alone": speedup,
+            "ms_one_slice": one, "ms_partitioned": split, "partitioned_over_one": split / one,
+            "tflops_one_slice": F3 / (one * 1e-3) / 1e12, "tflops_partitioned": F3 / (split * 1e-3) / 1e12,
+            "calibration_probe_ms": probe_s * 1e3, "steps": steps, "warmup": warmup}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +270,9 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="first run one plain device copy of this many MiB (a kernel of known HBM traffic "
                          "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings with)")
+    ap.add_argument("--partition", default="",
+                    help="comma-separated probe times of pretend devices: time the layer split by Eq. (1) "
+                         "(all slices on this GPU) against one slice (not the contract line)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
@@ -227,6 +294,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.partition:
+        times = [float(v) for v in args.partition.split(",")]
+        print(json.dumps(measure_partition(args.config, args.dtype, times, args.steps, args.warmup)))
+        return
 
     if not args.table:
         print(json.dumps(measure(args.config, args.dtype, args.steps, args.warmup, args.cpu_images)))

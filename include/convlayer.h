@@ -70,10 +70,12 @@ int conv_calibrate(const conv_desc_t *desc, int pass_mask, int reps, void *ws, s
  * call on the full layer.
  *
  *   conv_layer_fwd / conv_layer_bwd_weight: the slices write disjoint channel
- *     blocks of y / dw; they are enqueued on up to four internal streams (default
- *     priority, created on first use and kept for the life of the process) that
- *     fork from and join back into hip_stream with events, so small slices can
- *     share the GPU.  Work enqueued on hip_stream after the call sees all of y / dw.
+ *     blocks of y / dw.  Slices that are too small to fill the GPU (< 2e10 FLOP per
+ *     pass) are enqueued on up to four internal streams (default priority, created
+ *     on first use and kept for the life of the process) that fork from and join
+ *     back into hip_stream with events, so they share the GPU; if every slice is
+ *     large they run one after the other on hip_stream.  Either way, work enqueued
+ *     on hip_stream after the call sees all of y / dw.
  *   conv_layer_bwd_data: dx is the sum of the slices' partial gradients, added in
  *     slice order on hip_stream itself (slice 0 honours desc->accumulate, the
  *     others accumulate), so the result does not depend on timing.

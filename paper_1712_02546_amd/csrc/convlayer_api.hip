@@ -60,6 +60,7 @@ int check_layer(const conv_desc_t* desc) {
 
 // ---- internal streams of the layer driver, one set per device ----------------------------
 constexpr int kStreams = 4;
+constexpr double kFillsGpuFlop = 2e10;   // a slice pass of this size keeps 256 CUs busy for >0.1 ms
 constexpr int kMaxGpus = 16;
 struct StreamSet {
   bool ready = false;
@@ -108,6 +109,23 @@ int run_disjoint(slice_fn fn, int pass, const conv_desc_t* desc, const int32_t* 
       const conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
       return fn(&d, a, b, out, base, ws_bytes, hip_stream);
     }
+  }
+  // A slice with enough work fills the GPU by itself (its tiles are shared out evenly over all
+  // compute units), and two such kernels side by side only get in each other's way: those
+  // run one after the other on the caller's stream.  Small slices share the GPU.
+  int32_t P = 0, Q = 0;
+  const conv_desc_t whole = slice_of(*desc, 0, desc->K);
+  (void)conv_output_dims(&whole, &P, &Q);
+  const double flop_per_kernel = 2.0 * desc->N * P * Q * (double)desc->C * desc->R * desc->S;
+  int big = 0;
+  for (int i = 0; i < n; ++i) big += (bounds[i + 1] - bounds[i]) * flop_per_kernel >= kFillsGpuFlop;
+  if (big == live) {
+    for (int i = 0; i < n; ++i) {
+      if (bounds[i + 1] == bounds[i]) continue;
+      const conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
+      if ((rc = fn(&d, a, b, out, base, ws_bytes, hip_stream)) != CONV_OK) return rc;
+    }
+    return CONV_OK;
   }
   StreamSet* ss = stream_set();
   if (!ss) return CONV_ERR_LAUNCH;
