@@ -97,6 +97,41 @@ int conv_layer_bwd_weight(const conv_desc_t *desc, const int32_t *bounds, int32_
                           const void *x, const void *dy, void *dw, void *ws, size_t ws_bytes,
                           void *hip_stream);
 
+/*
+ * Scalability model of Section 4.2.  All host code.
+ *
+ * conv_comm_elements: Eq. (2) -- elements the master exchanges with the slaves for one
+ *   batch, summed over the distributed layers: in^2*inCh*batch (input maps) +
+ *   k^2*numK*inCh (kernels) + out^2*numK*batch (output maps) per layer.
+ * conv_comm_elements_partition: the same count for one layer split at `bounds` among
+ *   n_devices when device `master` keeps its own block at home.  The paper does not
+ *   spell this case out; here every other device receives all input maps and its own
+ *   kernels and returns its own maps (one slave holding every kernel gives Eq. (2)).
+ * conv_scaling_estimate: time of one batch = t_comm + max_i(shares[i]*t_conv[i]) + t_comp
+ *   ("Comm. time", "Conv. time" of the slowest node, "Comp. time" of the other layers),
+ *   with t_comm = elements * bytes_per_element * 8 / bits_per_second (the paper:
+ *   doubles at about 5 Mbps); *speedup compares with device `master` doing all
+ *   convolutions alone without communication; *amdahl is the bound
+ *   1 / (1 - conv fraction of that single-device time).  Outputs may be NULL.
+ * Counts are returned as doubles (exact below 2^53).  Errors: CONV_ERR_NULL,
+ * CONV_ERR_SHAPE (negative extents or batch), CONV_ERR_PARTITION (bounds, times,
+ * shares, master index, non-positive bandwidth).
+ */
+typedef struct {
+  int32_t in;    /* input width = height  */
+  int32_t inCh;  /* input channels        */
+  int32_t k;     /* kernel width = height */
+  int32_t numK;  /* kernels               */
+  int32_t out;   /* output width = height */
+} conv_comm_layer_t;
+
+int conv_comm_elements(const conv_comm_layer_t *layers, int32_t n_layers, int64_t batch, double *elements);
+int conv_comm_elements_partition(const conv_comm_layer_t *layer, int64_t batch, const int32_t *bounds,
+                                 int32_t n_devices, int32_t master, double *elements);
+int conv_scaling_estimate(const double *t_conv, const double *shares, int32_t n_devices, int32_t master,
+                          double t_comp, double elements, double bytes_per_element, double bits_per_second,
+                          double *batch_seconds, double *speedup, double *amdahl);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,12 +5,14 @@ Thin Python front end of libconvslice.so; see include/convslice.h and include/co
 """
 from .binding import (CONV_BF16, CONV_F32, MAX_DEVICES, PASS_BWD_DATA, PASS_BWD_WEIGHT, PASS_FWD, ConvDesc,
                       ConvError, conv_bwd_data, conv_bwd_weight, conv_calibrate, conv_calibrate_workspace_bytes,
+                      conv_comm_elements, conv_comm_elements_partition, conv_scaling_estimate,
                       conv_fwd, conv_layer_bwd_data, conv_layer_bwd_weight, conv_layer_fwd,
                       conv_layer_workspace_bytes, conv_output_dims, conv_partition, conv_partition_estimate,
                       conv_probe_next_call, conv_workspace_bytes, load, pass_mask, status_string)
 
 __all__ = ["CONV_BF16", "CONV_F32", "MAX_DEVICES", "PASS_BWD_DATA", "PASS_BWD_WEIGHT", "PASS_FWD", "ConvDesc",
            "ConvError", "conv_bwd_data", "conv_bwd_weight", "conv_calibrate", "conv_calibrate_workspace_bytes",
+           "conv_comm_elements", "conv_comm_elements_partition", "conv_scaling_estimate",
            "conv_fwd", "conv_layer_bwd_data", "conv_layer_bwd_weight", "conv_layer_fwd",
            "conv_layer_workspace_bytes", "conv_output_dims", "conv_partition", "conv_partition_estimate",
            "conv_probe_next_call", "conv_workspace_bytes", "load", "pass_mask", "status_string"]

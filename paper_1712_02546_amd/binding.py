@@ -20,7 +20,8 @@ EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_bwd_dat
            "conv_bwd_weight", "conv_status_string", "conv_probe_next_call",
            "conv_partition", "conv_partition_estimate", "conv_calibrate_workspace_bytes",
            "conv_calibrate", "conv_layer_workspace_bytes", "conv_layer_fwd",
-           "conv_layer_bwd_data", "conv_layer_bwd_weight")
+           "conv_layer_bwd_data", "conv_layer_bwd_weight", "conv_comm_elements",
+           "conv_comm_elements_partition", "conv_scaling_estimate")
 MAX_DEVICES = 64
 
 
@@ -28,6 +29,10 @@ class conv_desc_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
         "k0", "k1", "dtype", "accumulate")]
+
+
+class conv_comm_layer_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("inp", "inCh", "k", "numK", "out")]
 
 
 @dataclass(frozen=True)
@@ -103,6 +108,13 @@ def load() -> ctypes.CDLL:
         lib.conv_calibrate.restype = ctypes.c_int
         lib.conv_layer_workspace_bytes.argtypes = [dp, pi, ctypes.c_int32, ctypes.c_int]
         lib.conv_layer_workspace_bytes.restype = ctypes.c_size_t
+        pl = ctypes.POINTER(conv_comm_layer_t)
+        lib.conv_comm_elements.argtypes = [pl, ctypes.c_int32, ctypes.c_int64, pd]
+        lib.conv_comm_elements.restype = ctypes.c_int
+        lib.conv_comm_elements_partition.argtypes = [pl, ctypes.c_int64, pi, ctypes.c_int32, ctypes.c_int32, pd]
+        lib.conv_comm_elements_partition.restype = ctypes.c_int
+        lib.conv_scaling_estimate.argtypes = [pd, pd, ctypes.c_int32, ctypes.c_int32] + [ctypes.c_double] * 4 + [pd] * 3
+        lib.conv_scaling_estimate.restype = ctypes.c_int
         for name in ("conv_layer_fwd", "conv_layer_bwd_data", "conv_layer_bwd_weight"):
             f = getattr(lib, name)
             f.argtypes = [dp, pi, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -263,3 +275,44 @@ def conv_layer_bwd_data(desc: ConvDesc, bounds, dy, w, dx, ws=None, stream=None,
 def conv_layer_bwd_weight(desc: ConvDesc, bounds, x, dy, dw, ws=None, stream=None, raw_status=False):
     """All slices of the partition write their blocks of dw; returns dw (fp32)."""
     return _layer_call("conv_layer_bwd_weight", desc, bounds, x, dy, dw, ws, stream, raw_status)
+
+
+# ---- convlayer.h: Eq. (2) communication volume and the scalability estimate -------------------
+
+def conv_comm_elements(layers, batch: int, raw_status=False):
+    """Eq. (2): elements exchanged per batch; layers are (in, inCh, k, numK, out) tuples."""
+    arr = (conv_comm_layer_t * max(len(layers), 1))(*[conv_comm_layer_t(*l) for l in layers])
+    out = ctypes.c_double()
+    rc = load().conv_comm_elements(arr, len(layers), int(batch), ctypes.byref(out))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_comm_elements")
+    return float(out.value)
+
+
+def conv_comm_elements_partition(layer, batch: int, bounds, master: int = 0, raw_status=False):
+    """Elements the master exchanges for one layer split at `bounds` (its own block stays home)."""
+    l = conv_comm_layer_t(*layer)
+    out = ctypes.c_double()
+    rc = load().conv_comm_elements_partition(ctypes.byref(l), int(batch), _ints(bounds), len(bounds) - 1,
+                                             int(master), ctypes.byref(out))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_comm_elements_partition")
+    return float(out.value)
+
+
+def conv_scaling_estimate(t_conv, shares, t_comp: float, elements: float, bytes_per_element: float,
+                          bits_per_second: float, master: int = 0, raw_status=False):
+    """(seconds per batch, speed-up over the master alone, Amdahl bound) of Section 4.2's model."""
+    sec, sp, am = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    rc = load().conv_scaling_estimate(_doubles(t_conv), _doubles(shares), len(t_conv), int(master), float(t_comp),
+                                      float(elements), float(bytes_per_element), float(bits_per_second),
+                                      ctypes.byref(sec), ctypes.byref(sp), ctypes.byref(am))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_scaling_estimate")
+    return float(sec.value), float(sp.value), float(am.value)

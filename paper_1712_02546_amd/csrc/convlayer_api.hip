@@ -348,6 +348,65 @@ int conv_calibrate(const conv_desc_t* desc, int pass_mask, int reps, void* ws, s
   return rc;
 }
 
+int conv_comm_elements(const conv_comm_layer_t* layers, int32_t n_layers, int64_t batch, double* elements) {
+  if (!layers || !elements) return CONV_ERR_NULL;
+  if (n_layers < 0 || batch < 0) return CONV_ERR_SHAPE;
+  double total = 0.0;
+  for (int i = 0; i < n_layers; ++i) {
+    const conv_comm_layer_t& l = layers[i];
+    if (l.in < 0 || l.inCh < 0 || l.k < 0 || l.numK < 0 || l.out < 0) return CONV_ERR_SHAPE;
+    total += (double)l.in * l.in * l.inCh * (double)batch;     // input maps
+    total += (double)l.k * l.k * l.numK * (double)l.inCh;      // kernels
+    total += (double)l.out * l.out * l.numK * (double)batch;   // output maps
+  }
+  *elements = total;
+  return CONV_OK;
+}
+
+int conv_comm_elements_partition(const conv_comm_layer_t* layer, int64_t batch, const int32_t* bounds,
+                                 int32_t n_devices, int32_t master, double* elements) {
+  if (!layer || !elements) return CONV_ERR_NULL;
+  if (layer->in < 0 || layer->inCh < 0 || layer->k < 0 || layer->numK < 0 || layer->out < 0 || batch < 0)
+    return CONV_ERR_SHAPE;
+  const int rc = check_bounds(bounds, n_devices, layer->numK);
+  if (rc != CONV_OK) return rc;
+  if (master < 0 || master >= n_devices) return CONV_ERR_PARTITION;
+  double total = 0.0;
+  for (int d = 0; d < n_devices; ++d) {
+    if (d == master) continue;
+    const double own = (double)(bounds[d + 1] - bounds[d]);
+    total += (double)layer->in * layer->in * layer->inCh * (double)batch;
+    total += (double)layer->k * layer->k * own * (double)layer->inCh;
+    total += (double)layer->out * layer->out * own * (double)batch;
+  }
+  *elements = total;
+  return CONV_OK;
+}
+
+int conv_scaling_estimate(const double* t_conv, const double* shares, int32_t n_devices, int32_t master,
+                          double t_comp, double elements, double bytes_per_element, double bits_per_second,
+                          double* batch_seconds, double* speedup, double* amdahl) {
+  const int rc = check_times(t_conv, n_devices);
+  if (rc != CONV_OK) return rc;
+  if (!shares) return CONV_ERR_NULL;
+  if (master < 0 || master >= n_devices) return CONV_ERR_PARTITION;
+  if (!(t_comp >= 0.0) || !(elements >= 0.0) || !(bytes_per_element >= 0.0) || !(bits_per_second > 0.0) ||
+      !std::isfinite(t_comp) || !std::isfinite(elements) || !std::isfinite(bytes_per_element))
+    return CONV_ERR_PARTITION;
+  double conv = 0.0;
+  for (int i = 0; i < n_devices; ++i) {
+    if (!(shares[i] >= 0.0) || !std::isfinite(shares[i])) return CONV_ERR_PARTITION;
+    conv = std::max(conv, shares[i] * t_conv[i]);
+  }
+  const double comm = elements * bytes_per_element * 8.0 / bits_per_second;
+  const double total = comm + conv + t_comp;
+  const double alone = t_conv[master] + t_comp;
+  if (batch_seconds) *batch_seconds = total;
+  if (speedup) *speedup = total > 0.0 ? alone / total : 0.0;
+  if (amdahl) *amdahl = t_comp > 0.0 ? alone / t_comp : INFINITY;
+  return CONV_OK;
+}
+
 size_t conv_layer_workspace_bytes(const conv_desc_t* desc, const int32_t* bounds, int32_t n_slices, int pass) {
   if (check_layer(desc) != CONV_OK || check_bounds(bounds, n_slices, desc->K) != CONV_OK) return 0;
   if (pass < CONV_PASS_FWD || pass > CONV_PASS_BWD_WEIGHT) return 0;
