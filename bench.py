@@ -258,6 +258,41 @@ def measure_partition(cfg_name, dtype_name, times, steps, warmup):
             "calibration_probe_ms": probe_s * 1e3, "steps": steps, "warmup": warmup}
 
 
+def scaling_study(cfg_name, dtype_name, max_devices, link_gbytes, comp_fraction, reps):
+    """The form of the paper's scalability study (Section 4.2) with this GPU's numbers: the
+    calibration probe gives the convolution time of one device, Eq. (1) the blocks of n equal
+    devices, Eq. (2) (per-partition form) the elements the master exchanges, and one xGMI link
+    of the master the bandwidth.  Returns one row per device count."""
+    import torch
+
+    import paper_1712_02546_amd as cs
+    from paper_1712_02546_amd import synth
+
+    cfg = synth.CONFIGS[cfg_name]
+    dtype = cs.CONV_F32 if dtype_name == "f32" else cs.CONV_BF16
+    desc = cs.ConvDesc(cfg.N, cfg.C, cfg.H, cfg.W, cfg.K, cfg.R, cfg.S, cfg.stride, cfg.stride, cfg.pad, cfg.pad,
+                       0, cfg.K, dtype, 0)
+    mask = cs.pass_mask(cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT)
+    ws = torch.empty(cs.conv_calibrate_workspace_bytes(desc, mask), dtype=torch.uint8, device="cuda:0")
+    t_conv = cs.conv_calibrate(desc, mask, reps, ws)
+    t_comp = t_conv * comp_fraction / (1.0 - comp_fraction)
+    layer = (cfg.H, cfg.C, cfg.R, cfg.K, cfg.P)
+    es = 4 if dtype == cs.CONV_F32 else 2
+    rows = []
+    n = 1
+    while n <= max_devices:
+        shares, bounds = cs.conv_partition([t_conv] * n, cfg.K)
+        # forward traffic of Eq. (2); the backward passes move the same maps the other way
+        elements = 2 * cs.conv_comm_elements_partition(layer, cfg.N, bounds, 0)
+        sec, sp, am = cs.conv_scaling_estimate([t_conv] * n, shares, t_comp, elements, es, link_gbytes * 8e9)
+        rows.append({"devices": n, "kernels_per_device": bounds[1] - bounds[0], "elements": elements,
+                     "batch_ms": sec * 1e3, "speedup": sp, "amdahl_bound": am})
+        n *= 2
+    return {"what": "scalability estimate in the form of Section 4.2", "config": cfg.name, "dtype": dtype_name,
+            "probe_ms_fwd_bwd": t_conv * 1e3, "other_layers_fraction": comp_fraction,
+            "link_GB_per_s": link_gbytes, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -273,6 +308,12 @@ def main():
     ap.add_argument("--partition", default="",
                     help="comma-separated probe times of pretend devices: time the layer split by Eq. (1) "
                          "(all slices on this GPU) against one slice (not the contract line)")
+    ap.add_argument("--scaling", type=int, default=0,
+                    help="largest device count of a scalability estimate in the form of the paper's "
+                         "(measured probe time, Eq. (1), Eq. (2), one xGMI link; not the contract line)")
+    ap.add_argument("--link-gbytes", type=float, default=153.0, help="bandwidth of the master's link, GB/s")
+    ap.add_argument("--comp-fraction", type=float, default=0.13,
+                    help="share of the other layers in the single-device time (the paper measured 13-25 %%)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
@@ -294,6 +335,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.scaling > 0:
+        print(json.dumps(scaling_study(args.config, args.dtype, args.scaling, args.link_gbytes, args.comp_fraction,
+                                       max(args.steps // 2, 1))))
+        return
 
     if args.partition:
         times = [float(v) for v in args.partition.split(",")]

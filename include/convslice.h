@@ -46,7 +46,8 @@
  * fp32, round-to-nearest-even on output), accumulation is fp32, dw is fp32.
  *
  * Limits.  Each tensor (and each internal transposed copy, whose batch extent
- * is rounded up to a multiple of 32) must have fewer than 2^31 elements;
+ * is rounded up to a multiple of 32) must have fewer than 2^30 - 4096 elements
+ * (the kernels address their work copies with 32-bit byte offsets);
  * R*S <= 1024.  Otherwise CONV_ERR_SHAPE.
  */
 #ifndef CONVSLICE_H

@@ -15,6 +15,7 @@
 namespace cs {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int NT = 256;             // threads per workgroup: 4 wavefronts in a 2x2 grid
@@ -130,9 +131,31 @@ static inline int grid_dealt(int MB, int CT) { return 8 * ((CT + 7) / 8) * MB; }
 // ---------------------------------------------------------------------------
 #define CS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define CS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+// Tables a kernel only reads and whose address is wave-uniform: loads through a pointer
+// to the constant address space are scalar loads.
+#define CS_CONST __attribute__((address_space(4)))
 
 __device__ __forceinline__ void dma16(const float* g, float* lds_uniform) {
   __builtin_amdgcn_global_load_lds(CS_GPTR(g), CS_LPTR(lds_uniform), 16, 0, 0);
+}
+
+// A pointer the compiler must treat as an opaque wave-uniform value (no folding of the
+// arithmetic that produced it into later address computations).
+__device__ __forceinline__ const char* opaque_uniform(const void* p) {
+  const unsigned long long v = (unsigned long long)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (const char*)(((unsigned long long)hi << 32) | lo);
+}
+
+// The same load with the address split into a wave-uniform base and a 32-bit per-lane byte
+// offset.  The instruction then takes the base from scalar registers and the lane offset as
+// it is, so an operand whose lanes keep their offsets from chunk to chunk costs no vector
+// ALU work at all: only the scalar base moves.  (The empty asm keeps the zero-extension of
+// the offset next to the addition, which is the form the instruction selector recognises.)
+__device__ __forceinline__ void dma16_uv(const char* base_uniform, unsigned& lane_off, float* lds_uniform) {
+  asm volatile("" : "+v"(lane_off));
+  __builtin_amdgcn_global_load_lds(CS_GPTR(base_uniform + lane_off), CS_LPTR(lds_uniform), 16, 0, 0);
 }
 
 // Reduction order inside a chunk.  MFMA step ks = 4*j + t (j, t in 0..3) multiplies
@@ -200,8 +223,8 @@ __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, flo
   lb.begin(ch, live);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    dma16(la.addr(i), ta + (wv * 4 + i) * 256);
-    dma16(lb.addr(i), tb + (wv * 4 + i) * 256);
+    la.issue(i, ta + (wv * 4 + i) * 256);
+    lb.issue(i, tb + (wv * 4 + i) * 256);
   }
   la.end();
   lb.end();

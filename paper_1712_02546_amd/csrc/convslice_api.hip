@@ -16,7 +16,8 @@ namespace {
 
 using cs::Geo;
 
-constexpr int64_t kMaxElems = (int64_t)1 << 31;
+// Work copies are addressed with 32-bit byte offsets from a base a little in front of them.
+constexpr int64_t kMaxElems = ((int64_t)1 << 30) - 4096;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
@@ -92,17 +93,17 @@ inline size_t tail_bytes(const cs::TailPlan& tp) {
 }
 
 struct FwdPlan {
-  bool repitch;      // filters copied to fp32 rows of pitch ldw (bf16 input or C*R*S not a multiple of 4)
+  bool repitch;      // filters copied to zero-padded fp32 rows of pitch ldw (bf16 input, or C*R*S not a multiple of BK)
   int ldw, nch;
   int MB, CT;
   cs::TailPlan tail;
-  size_t off_xt, off_yt, off_w, off_tab, off_zero, off_tail, total;
+  size_t off_xt, off_yt, off_w, off_tab, off_tail, total;
 };
 
 FwdPlan plan_fwd(const Geo& g, int dtype) {
   FwdPlan p;
-  p.repitch = dtype != CONV_F32 || (g.CRS % 4) != 0;
-  p.ldw = p.repitch ? (int)round_up(g.CRS, 4) : g.CRS;
+  p.repitch = dtype != CONV_F32 || (g.CRS % cs::BK) != 0;
+  p.ldw = p.repitch ? (int)round_up(g.CRS, cs::BK) : g.CRS;
   p.nch = (g.CRS + cs::BK - 1) / cs::BK;
   p.MB = (g.Ks + cs::BM - 1) / cs::BM;
   p.CT = (g.PQ * g.NB + 3) / 4;
@@ -113,7 +114,6 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
   p.off_tab = o; o += seg((int64_t)(p.nch + 4) * cs::BK * 2);
-  p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
   p.off_tail = o; o += tail_bytes(p.tail);
   p.total = o;
   return p;
@@ -161,16 +161,16 @@ cs::RunPlan plan_runs(const Geo& g, int MB) {
 
 struct BwdDataPlan {
   bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
-  int Cp, Ks4, nch, MB1, CT1;
+  int Cp, Ksp, nch, MB1, CT1;   // Ksp: pitch of w' in the scatter form, a multiple of BK
   cs::TailPlan tail;
   cs::RunPlan run;
-  size_t off_dyt, off_wt, off_dxt, off_perm, off_cls, off_scratch, off_tab, off_zero, off_T, off_tail, total;
+  size_t off_dyt, off_wt, off_dxt, off_perm, off_cls, off_scratch, off_tab, off_T, off_tail, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
   BwdDataPlan p;
   p.Cp = (int)round_up(g.C, 4);
-  p.Ks4 = (int)round_up(g.Ks, 4);
+  p.Ksp = (int)round_up(g.Ks, cs::BK);
   p.nch = (g.Ks + cs::BK - 1) / cs::BK;
   // With C input channels the per-pixel form fills C of a tile's 128 rows; the scatter form
   // fills C*R*S of them and pays one round trip of T through memory instead.
@@ -179,9 +179,8 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   if (p.scatter) {
     o += kZeroBytes;
     p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
-    p.off_wt = o;   o += seg((int64_t)g.CRS * p.Ks4);          // w'[(c,r,s)][k]
+    p.off_wt = o;   o += seg((int64_t)g.CRS * p.Ksp);          // w'[(c,r,s)][k], zero past Ks
     p.off_tab = o;  o += seg((int64_t)(p.nch + 4) * cs::BK * 2);
-    p.off_zero = o; o += seg(cs::ZERO_PAGE_FLOATS);
     p.off_T = o;    o += seg((int64_t)g.CRS * g.PQ * g.Np);
     p.MB1 = (g.CRS + cs::BM - 1) / cs::BM;
     p.CT1 = (g.PQ * g.NB + 3) / 4;
@@ -191,7 +190,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     p.total = o;
     return p;
   }
-  p.off_tab = p.off_zero = p.off_T = 0;
+  p.off_tab = p.off_T = 0;
   o += kZeroBytes;
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   o += kZeroBytes;
@@ -498,10 +497,8 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const size_t es = elem_size(desc->dtype);
 
   // x[N][C*H*W] -> x_t[C*H*W][Np]
-  float* zero = (float*)(base + p.off_zero);   // for the filter rows, which may be read in place
   launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
                       xt - cs::ZERO_PAGE_FLOATS, st);
-  hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
   const float* wmat;
   if (p.repitch) {
     float* wp = (float*)(base + p.off_w);
@@ -518,7 +515,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
     wmat = (const float*)w + (size_t)g.k0 * g.CRS;
   }
   // three chunks more than needed: addresses are computed two chunks ahead and the table is read one further
-  int2* tab = (int2*)(base + p.off_tab);
+  int* tab = (int*)(base + p.off_tab);
   const int entries = (p.nch + 4) * cs::BK;
   hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
   const bool pad = needs_pad_checks(g);
@@ -528,7 +525,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   probe.begin(st);
   hipLaunchKernelGGL(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>,
                      dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg), dim3(cs::NT), cs::SMEM_BYTES, st, g,
-                     wmat, p.ldw, p.ldw, xt, tab, zero, yt, p.MB, p.CT, p.nch, p.tail, partial);
+                     wmat, p.ldw, xt, tab, entries, yt, p.MB, p.CT, p.nch, p.tail, partial);
   if (p.tail.nTail > 0)
     hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
                        p.CT, p.nch, p.tail);
@@ -607,19 +604,17 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     g1.C = g.Ks; g1.H = g.P; g1.W = g.Q; g1.K = g.CRS; g1.R = g1.S = 1; g1.sh = g1.sw = 1; g1.ph = g1.pw = 0;
     g1.k0 = 0; g1.Ks = g.CRS; g1.HW = g.PQ; g1.RS = 1; g1.CRS = g.Ks;
     float* T = (float*)(base + p.off_T);
-    float* zero = (float*)(base + p.off_zero);
-    int2* tab = (int2*)(base + p.off_tab);
-    // w[k][(c,r,s)] -> w'[(c,r,s)][Ks4]
+    int* tab = (int*)(base + p.off_tab);
+    // w[k][(c,r,s)] -> w'[(c,r,s)][Ksp], zero past Ks
     launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0,
-                        p.Ks4, p.Ks4, 1, nullptr, st);
-    hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
+                        p.Ksp, p.Ksp, 1, nullptr, st);
     const int entries = (p.nch + 4) * cs::BK;
     hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g1, entries, tab);
     if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
     float* partial = (float*)(base + p.off_tail);
     probe.begin(st);
     hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg),
-                       dim3(cs::NT), cs::SMEM_BYTES, st, g1, wt, p.Ks4, p.Ks4, dyt, tab, zero, T, p.MB1, p.CT1, p.nch,
+                       dim3(cs::NT), cs::SMEM_BYTES, st, g1, wt, p.Ksp, dyt, tab, entries, T, p.MB1, p.CT1, p.nch,
                        p.tail, partial);
     if (p.tail.nTail > 0)
       hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g1, partial, T, p.MB1,

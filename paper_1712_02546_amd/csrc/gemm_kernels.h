@@ -13,51 +13,51 @@ namespace cs {
 __device__ __forceinline__ float* dma_dst(float* tile, int wv, int i) { return tile + (wv * 4 + i) * 256; }
 
 // ---------------------------------------------------------------- forward ----
-// A[m][kk] = w[k0+m0+m][kk]: rows of the (re-pitched) filter matrix, col image.
+// A[m][kk] = w[k0+m0+m][kk]: rows of the filter matrix, col image.  The row pitch ldw is a
+// multiple of BK and rows are zero past C*R*S, so no lane ever needs a mask: a lane's byte
+// offset from the tile's first row is fixed and only the uniform base moves along the rows.
 struct FwdLoadA {
   static constexpr bool COL = true;
   static constexpr bool DEEP = false;
-  const float* p[4];
-  const float* zero;
-  int kq4, cols;  // float offset of this lane's slot inside a chunk; valid row length
-  int adv;        // uniform: float offset of the chunk being issued
-  bool ok;
-  __device__ FwdLoadA(const float* w, int ldw, int cols_, int m0, int Ks, const float* zero_)
-      : zero(zero_), cols(cols_) {
+  const char* tile;   // uniform: row m0 of the filter matrix
+  const char* ub;     // uniform: tile + the chunk being issued
+  unsigned off[4];
+  __device__ FwdLoadA(const float* w, int ldw, int m0, int Ks) : tile((const char*)(w + (int64_t)m0 * ldw)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    kq4 = 4 * ((l & 7) ^ (l >> 3));
+    const int kq4 = 4 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int m = min(m0 + 32 * wv + 8 * i + (l >> 3), Ks - 1);  // rows past the slice repeat the last one
-      p[i] = w + (int64_t)m * ldw + kq4;
+      const int m = min(32 * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
+      off[i] = ((unsigned)m * (unsigned)ldw + kq4) * 4u;
     }
   }
-  // begin/addr/end: the addresses of one chunk's four DMA loads.  live = false (chunks past
-  // the last one) must stay harmless: such loads read the zero page.
-  __device__ __forceinline__ void begin(int ch, bool live) {
-    adv = ch * BK;
-    ok = live & (adv + kq4 < cols);   // past the row end the operand must be zero
-  }
-  __device__ __forceinline__ const float* addr(int i) const { return ok ? p[i] + adv : zero; }
+  // Chunks past the last one (live = false) re-read the row start, which is always there.
+  __device__ __forceinline__ void begin(int ch, bool live) { ub = tile + (live ? ch : 0) * (BK * 4); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {}
 };
 
 // B[kk][col] = x_t[tap kk of the column block's pixel][n] (row image), zero where the
-// tap falls into the padding.  tab[kk] = {offset of tap (c,r,s) inside x_t, (r<<16)|s}
-// (second word negative past C*R*S) is read with scalar loads: a DMA load covers two
-// consecutive reduction rows, one per half-wave.
+// tap falls into the padding.  A zero page sits ZERO_PAGE_FLOATS in front of x_t and is the
+// uniform base of every load; off_tab[kk] = byte offset of tap (c,r,s) from that base,
+// rs_tab[kk] = (r<<16)|s (read only when the layer has padding).  Both are read with scalar
+// loads one chunk ahead; a DMA load covers two consecutive reduction rows, one per half-wave,
+// so a lane's offset is "its row's table entry + its pixel": three vector instructions.
 template <bool PAD>
 struct FwdLoadB {
   static constexpr bool COL = false;
-  const float* xt;       // a zero page sits ZERO_PAGE_FLOATS in front of x_t
-  const int4* tab2;
-  int4 cur[4], nxt[4];   // table entries (two rows each) of the chunk being issued / the next one; uniform
-  int pixbase, h0, w0, H, W;
+  const char* zp;        // uniform: the zero page in front of x_t
+  const CS_CONST int* off_tab;   // constant address space: read with scalar loads
+  const CS_CONST int* rs_tab;
+  i32x4 cur[2], nxt[2];   // offsets of rows 8*wv .. 8*wv+7 of the chunk being issued / the next one; uniform
+  i32x4 cur_rs[2], nxt_rs[2];
+  unsigned pixbase;      // byte offset of the lane's pixel, image block and 16-byte piece (may wrap below zero)
+  int h0, w0, H, W;
   bool upper;
-  __device__ FwdLoadB(const Geo& g, const float* xt_, const int2* tab, int ct, int ch0)
-      : xt(xt_), tab2((const int4*)tab) {
+  __device__ FwdLoadB(const Geo& g, const float* xt, const int* tab, int entries, int ct, int ch0)
+      : zp(opaque_uniform(xt - ZERO_PAGE_FLOATS)), off_tab((const CS_CONST int*)tab),
+        rs_tab((const CS_CONST int*)tab + entries) {
     const int l = threadIdx.x & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cq = l & 31;
     // column blocks past the end are computed like block 0 and never stored
     const int gcb = ct * 4 + (cq >> 3) < g.PQ * g.NB ? ct * 4 + (cq >> 3) : 0;
@@ -68,29 +68,41 @@ struct FwdLoadB {
     w0 = q * g.sw - g.pw;
     H = g.H;
     W = g.W;
-    pixbase = (h0 * g.W + w0) * g.Np + nb * 32 + 4 * (cq & 7);
+    pixbase = (unsigned)((h0 * g.W + w0) * g.Np + nb * 32 + 4 * (cq & 7)) * 4u;
     upper = l >= 32;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) nxt[i] = tab2[ch0 * (BK / 2) + 4 * wv + i];
+    fetch(ch0);
   }
   // Table rows past C*R*S repeat row 0 (the filter operand is zero there), and the table
   // runs three chunks past the end, so neither the tail nor the dummy chunks need a test.
   __device__ __forceinline__ void begin(int ch, bool) {
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) cur[i] = nxt[i];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) nxt[i] = tab2[(ch + 1) * (BK / 2) + 4 * wv + i];  // rows 8*wv+2*i, +1 of chunk ch+1
-  }
-  __device__ __forceinline__ const float* addr(int i) const {
-    const int off = upper ? cur[i].z : cur[i].x;
-    int idx = off + pixbase;
+    cur[0] = nxt[0];
+    cur[1] = nxt[1];
     if (PAD) {
-      const int rs = upper ? cur[i].w : cur[i].y;
-      const bool ok = ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
-      idx = ok ? idx : -ZERO_PAGE_FLOATS;
+      cur_rs[0] = nxt_rs[0];
+      cur_rs[1] = nxt_rs[1];
     }
-    return xt + idx;
+    fetch(ch + 1);
+  }
+  __device__ __forceinline__ void fetch(int ch) {   // rows 8*wv .. 8*wv+7 of chunk ch
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const CS_CONST i32x4* po = (const CS_CONST i32x4*)(off_tab + ch * BK + 8 * wv);
+    nxt[0] = po[0];
+    nxt[1] = po[1];
+    if (PAD) {
+      const CS_CONST i32x4* pr = (const CS_CONST i32x4*)(rs_tab + ch * BK + 8 * wv);
+      nxt_rs[0] = pr[0];
+      nxt_rs[1] = pr[1];
+    }
+  }
+  static __device__ __forceinline__ int pick(const i32x4 (&v)[2], int r) { return v[r >> 2][r & 3]; }  // r: compile-time row 0..7
+  __device__ __forceinline__ void issue(int i, float* dst) {
+    unsigned off = (unsigned)(upper ? pick(cur, 2 * i + 1) : pick(cur, 2 * i)) + pixbase;
+    if (PAD) {
+      const int rs = upper ? pick(cur_rs, 2 * i + 1) : pick(cur_rs, 2 * i);
+      const bool ok = ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
+      off = ok ? off : 0u;
+    }
+    dma16_uv(zp, off, dst);
   }
   __device__ __forceinline__ void end() {}
 };
@@ -173,9 +185,8 @@ __device__ __forceinline__ void fwd_store_tile(const Geo& g, float* __restrict__
 // y_t[k][pix][n] for the slice; a tile is 128 kernels x 4 column blocks.
 template <bool PAD>
 __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __restrict__ w, int ldw,
-                                                      int wcols, const float* __restrict__ xt,
-                                                      const int2* __restrict__ tab,
-                                                      const float* __restrict__ zero,
+                                                      const float* __restrict__ xt,
+                                                      const int* __restrict__ tab, int entries,
                                                       float* __restrict__ yt, int MB, int CT, int nch,
                                                       TailPlan tp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
@@ -189,8 +200,8 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    FwdLoadA la(w, ldw, wcols, mb * BM, g.Ks, zero);
-    FwdLoadB<PAD> lb(g, xt, tab, ct, cb);
+    FwdLoadA la(w, ldw, mb * BM, g.Ks);
+    FwdLoadB<PAD> lb(g, xt, tab, entries, ct, cb);
     gemm_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) fwd_store_tile(g, yt, mb, ct, acc);
     else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
@@ -255,6 +266,7 @@ struct BwdDataLoadA {
     const bool ok = live & (walk.kc * BK + krow + 2 * i < Ks);
     return wt + (ok ? base + 2 * i * Cp : -ZERO_PAGE_FLOATS);
   }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
   __device__ __forceinline__ void end() {
     walk.next();
     const int e = taps[walk.ti];   // entries past the list are allocated, so this stays in bounds
@@ -290,6 +302,7 @@ struct BwdDataLoadB {
     const bool ok = live & (walk.kc * BK + krow + 2 * i < Ks);
     return dyt + (ok ? base + 2 * i * PQNp : -ZERO_PAGE_FLOATS);
   }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
   __device__ __forceinline__ void end() {
     walk.next();
     toff = tapoff[walk.ti * 4 + cb];
@@ -514,6 +527,7 @@ struct BwdWeightLoadA {
   }
   __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK; }  // dummy: chunk 0
   __device__ __forceinline__ const float* addr(int i) const { return p[i] + adv; }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
   __device__ __forceinline__ void end() {}
 };
 
@@ -560,6 +574,7 @@ struct BwdWeightLoadB {
     }
     return xt + idx;
   }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
   __device__ __forceinline__ void end() {   // branch-free carry: (nb, q, p) += 1 chunk
     ++nb;
     const int cq = nb == NB;

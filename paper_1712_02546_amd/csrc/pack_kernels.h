@@ -139,19 +139,18 @@ __global__ __launch_bounds__(256) void repitch_rows_kernel(
   }
 }
 
-// Forward pass: for reduction index kk = (c,r,s), tab[kk] = {offset of that tap inside
-// x_t relative to a pixel's window origin, (r<<16)|s}.  Entries past C*R*S repeat entry 0:
-// the filter operand is zero there, so any finite input value will do.
-__global__ void fwd_tap_table_kernel(Geo g, int entries, int2* __restrict__ tab) {
+// Forward pass: for reduction index kk = (c,r,s), tab[kk] = byte offset of that tap inside
+// x_t relative to a pixel's window origin, counted from the zero page in front of x_t, and
+// tab[entries + kk] = (r<<16)|s.  Entries past C*R*S repeat entry 0: the filter operand is
+// zero there, so any finite input value will do.
+__global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= entries) return;
   const int kk = i < g.CRS ? i : 0;
   const int c = kk / g.RS, rs = kk - c * g.RS;
   const int r = rs / g.S, s = rs - r * g.S;
-  int2 e;
-  e.x = (c * g.HW + r * g.W + s) * g.Np;
-  e.y = (r << 16) | s;
-  tab[i] = e;
+  tab[i] = (int)(((unsigned)((c * g.HW + r * g.W + s) * g.Np) + (unsigned)ZERO_PAGE_FLOATS) * 4u);
+  tab[entries + i] = (r << 16) | s;
 }
 
 // Orders the H*W input pixels by decreasing tap count, ties in row-major order (a stable
