@@ -166,20 +166,30 @@ struct Frag {          // operands of four MFMA steps (one j) for the wavefront'
 };
 
 template <bool COL>
-__device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase, int lane, int j) {
+__device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase, int lane, int j, int blk1) {
   if constexpr (COL) {
     const int u = lane & 7, h = lane >> 5;
     const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
     f.v[0] = *(const f32x4*)(tile + slot * 4);
     f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
   } else {
+    // The second block lies blk1 = 32 floats to the right.  blk1 is an opaque register (see
+    // opaque_block_offset), so the two blocks keep separate base registers and the reads of
+    // rows t, t+1 of one block (512 bytes apart) pair up into LDS reads with 256-byte offset
+    // units, which reach every j and t from that one base.
     const float* p = tile + (8 * j + 4 * (lane >> 5)) * BM + wbase + (lane & 31);
+    const float* q = p + blk1;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      f.v[0][t] = p[t * BM];
-      f.v[1][t] = p[t * BM + 32];
-    }
+    for (int t = 0; t < 4; ++t) f.v[0][t] = p[t * BM];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) f.v[1][t] = q[t * BM];
   }
+}
+
+__device__ __forceinline__ int opaque_block_offset() {
+  int o = 32;
+  asm volatile("" : "+v"(o));
+  return o;
 }
 
 // Sixteen MFMAs: four reduction steps on the wavefront's 2x2 accumulator blocks.
@@ -245,19 +255,20 @@ __device__ __forceinline__ void gemm_mainloop_two_barriers(LA& la, LB& lb, int c
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wa = (wv >> 1) * 64, wb = (wv & 1) * 64;
   if (ch_begin >= ch_end) return;
+  const int blk1 = opaque_block_offset();
   Frag a0, b0, a1, b1, a2, b2, a3, b3;
   // prologue: chunks ch_begin and ch_begin+1 into stages 0 and 1
   issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
   issue_all(la, lb, ch_begin + 1, smem + TILE_F, smem + 3 * TILE_F, wv, ch_begin + 1 < ch_end);
   barrier_chunk_landed();                                   // A(ch_begin)
-  read_frag<AC>(a0, smem, wa, lane, 0);
-  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0);
-  read_frag<AC>(a1, smem, wa, lane, 1);
-  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1);
-  read_frag<AC>(a2, smem, wa, lane, 2);
-  read_frag<BC>(b2, smem + 2 * TILE_F, wb, lane, 2);
-  read_frag<AC>(a3, smem, wa, lane, 3);
-  read_frag<BC>(b3, smem + 2 * TILE_F, wb, lane, 3);
+  read_frag<AC>(a0, smem, wa, lane, 0, blk1);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0, blk1);
+  read_frag<AC>(a1, smem, wa, lane, 1, blk1);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1, blk1);
+  read_frag<AC>(a2, smem, wa, lane, 2, blk1);
+  read_frag<BC>(b2, smem + 2 * TILE_F, wb, lane, 2, blk1);
+  read_frag<AC>(a3, smem, wa, lane, 3, blk1);
+  read_frag<BC>(b3, smem + 2 * TILE_F, wb, lane, 3, blk1);
   __builtin_amdgcn_sched_barrier(0);
   mfma_group(a0, b0, acc);
   __builtin_amdgcn_sched_barrier(0);
@@ -270,18 +281,18 @@ __device__ __forceinline__ void gemm_mainloop_two_barriers(LA& la, LB& lb, int c
     const float* As = smem + cur;
     const float* Bs = smem + 2 * TILE_F + cur;
     barrier_chunk_landed();                                 // A(ch)
-    read_frag<AC>(a0, As, wa, lane, 0);
-    read_frag<BC>(b0, Bs, wb, lane, 0);
-    read_frag<AC>(a1, As, wa, lane, 1);
-    read_frag<BC>(b1, Bs, wb, lane, 1);
+    read_frag<AC>(a0, As, wa, lane, 0, blk1);
+    read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
+    read_frag<AC>(a1, As, wa, lane, 1, blk1);
+    read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
     __builtin_amdgcn_sched_barrier(0);
     mfma_group(a2, b2, acc);  // G2 of chunk ch-1
     mfma_group(a3, b3, acc);  // G3 of chunk ch-1
     __builtin_amdgcn_sched_barrier(0);
-    read_frag<AC>(a2, As, wa, lane, 2);
-    read_frag<BC>(b2, Bs, wb, lane, 2);
-    read_frag<AC>(a3, As, wa, lane, 3);
-    read_frag<BC>(b3, Bs, wb, lane, 3);
+    read_frag<AC>(a2, As, wa, lane, 2, blk1);
+    read_frag<BC>(b2, Bs, wb, lane, 2, blk1);
+    read_frag<AC>(a3, As, wa, lane, 3, blk1);
+    read_frag<BC>(b3, Bs, wb, lane, 3, blk1);
     __builtin_amdgcn_sched_barrier(0);
     mfma_group(a0, b0, acc);  // G0 of chunk ch
     __builtin_amdgcn_sched_barrier(0);
@@ -313,25 +324,26 @@ __device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wa = (wv >> 1) * 64, wb = (wv & 1) * 64;
   if (ch_begin >= ch_end) return;
+  const int blk1 = opaque_block_offset();
   Frag a0, b0, a1, b1;
   // prologue: chunk ch_begin into stage 0
   issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
   __syncthreads();  // includes the wait for this wavefront's own DMA loads
-  read_frag<AC>(a0, smem, wa, lane, 0);
-  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0);
-  read_frag<AC>(a1, smem, wa, lane, 1);
-  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1);
+  read_frag<AC>(a0, smem, wa, lane, 0, blk1);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0, blk1);
+  read_frag<AC>(a1, smem, wa, lane, 1, blk1);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1, blk1);
   issue_all(la, lb, ch_begin + 1, smem + TILE_F, smem + 3 * TILE_F, wv, ch_begin + 1 < ch_end);
   CS_FENCE();
   mfma_group(a0, b0, acc);
   CS_FENCE();
-  read_frag<AC>(a0, smem, wa, lane, 2);
-  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 2);
+  read_frag<AC>(a0, smem, wa, lane, 2, blk1);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 2, blk1);
   CS_FENCE();
   mfma_group(a1, b1, acc);
   CS_FENCE();
-  read_frag<AC>(a1, smem, wa, lane, 3);
-  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 3);
+  read_frag<AC>(a1, smem, wa, lane, 3, blk1);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 3, blk1);
   __syncthreads();
   int cur = TILE_F;  // float offset of the stage that holds chunk ch: TILE_F or 0
   for (int ch = ch_begin + 1; ch < ch_end; ++ch) {
@@ -341,23 +353,23 @@ __device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch
     CS_FENCE();
     mfma_group(a0, b0, acc);  // G2 of chunk ch-1
     CS_FENCE();
-    read_frag<AC>(a0, As, wa, lane, 0);
-    read_frag<BC>(b0, Bs, wb, lane, 0);
+    read_frag<AC>(a0, As, wa, lane, 0, blk1);
+    read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
     CS_FENCE();
     mfma_group(a1, b1, acc);  // G3 of chunk ch-1
     CS_FENCE();
-    read_frag<AC>(a1, As, wa, lane, 1);
-    read_frag<BC>(b1, Bs, wb, lane, 1);
+    read_frag<AC>(a1, As, wa, lane, 1, blk1);
+    read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
     CS_FENCE();
     mfma_group(a0, b0, acc);  // G0 of chunk ch
     CS_FENCE();
-    read_frag<AC>(a0, As, wa, lane, 2);
-    read_frag<BC>(b0, Bs, wb, lane, 2);
+    read_frag<AC>(a0, As, wa, lane, 2, blk1);
+    read_frag<BC>(b0, Bs, wb, lane, 2, blk1);
     CS_FENCE();
     mfma_group(a1, b1, acc);  // G1 of chunk ch
     CS_FENCE();
-    read_frag<AC>(a1, As, wa, lane, 3);
-    read_frag<BC>(b1, Bs, wb, lane, 3);
+    read_frag<AC>(a1, As, wa, lane, 3, blk1);
+    read_frag<BC>(b1, Bs, wb, lane, 3, blk1);
     __syncthreads();
     cur ^= TILE_F;
   }

@@ -53,6 +53,7 @@ struct FwdLoadB {
   i32x4 cur_rs[2], nxt_rs[2];
   unsigned pixbase;      // byte offset of the lane's pixel, image block and 16-byte piece (may wrap below zero)
   int h0, w0, H, W;
+  unsigned upmask;
   bool upper;
   __device__ FwdLoadB(const Geo& g, const float* xt, const int* tab, int entries, int ct, int ch0)
       : zp(opaque_uniform(xt - ZERO_PAGE_FLOATS)), off_tab((const CS_CONST int*)tab),
@@ -70,6 +71,8 @@ struct FwdLoadB {
     W = g.W;
     pixbase = (unsigned)((h0 * g.W + w0) * g.Np + nb * 32 + 4 * (cq & 7)) * 4u;
     upper = l >= 32;
+    upmask = upper ? ~0u : 0u;
+    asm volatile("" : "+v"(upmask));
     fetch(ch0);
   }
   // Table rows past C*R*S repeat row 0 (the filter operand is zero there), and the table
@@ -96,7 +99,10 @@ struct FwdLoadB {
   }
   static __device__ __forceinline__ int pick(const i32x4 (&v)[2], int r) { return v[r >> 2][r & 3]; }  // r: compile-time row 0..7
   __device__ __forceinline__ void issue(int i, float* dst) {
-    unsigned off = (unsigned)(upper ? pick(cur, 2 * i + 1) : pick(cur, 2 * i)) + pixbase;
+    // lower half-wave: row 2i, upper half-wave: row 2i+1.  Written as "a + ((b - a) & mask)"
+    // with an opaque all-ones/all-zeros lane mask: two vector instructions, the difference is scalar.
+    const unsigned a = (unsigned)pick(cur, 2 * i), b = (unsigned)pick(cur, 2 * i + 1);
+    unsigned off = ((b - a) & upmask) + a + pixbase;
     if (PAD) {
       const int rs = upper ? pick(cur_rs, 2 * i + 1) : pick(cur_rs, 2 * i);
       const bool ok = ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
