@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -44,7 +45,8 @@ int make_geo(const conv_desc_t* d, Geo& g) {
   const int64_t HW = (int64_t)d->H * d->W, PQ = (int64_t)P * Q, RS = (int64_t)d->R * d->S;
   const int64_t Cp = round_up(d->C, 4);
   if ((int64_t)d->C * HW * Np >= kMaxElems) return CONV_ERR_SHAPE;       // x, x_t, dx_t
-  if ((int64_t)d->K * PQ * Np >= kMaxElems) return CONV_ERR_SHAPE;       // y, dy and work copies
+  if (((int64_t)d->K + 32) * (PQ + 1) * Np >= kMaxElems) return CONV_ERR_SHAPE;   // y, dy and work copies (padded)
+  if (((int64_t)PQ + 1) * Np >= ((int64_t)1 << 29)) return CONV_ERR_SHAPE;          // two rows of a work copy in 32 bits
   if ((int64_t)d->K * Cp * RS + 4 * (int64_t)d->K >= kMaxElems) return CONV_ERR_SHAPE;  // w, w_t
   g.N = d->N; g.Np = (int)Np; g.NB = (int)(Np / 32);
   g.C = d->C; g.H = d->H; g.W = d->W; g.K = d->K; g.R = d->R; g.S = d->S; g.P = P; g.Q = Q;
@@ -191,10 +193,9 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     return p;
   }
   p.off_tab = p.off_T = 0;
-  o += kZeroBytes;
-  p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
-  o += kZeroBytes;
-  p.off_wt = o;   o += seg((int64_t)g.RS * g.Ks * p.Cp);
+  // dy_t[Ksp][PQ+1][Np] (one zero pixel per row, zero rows past Ks), w_t[RS][Ksp][Cp] (zero rows past Ks)
+  p.off_dyt = o;  o += seg((int64_t)p.Ksp * (g.PQ + 1) * g.Np);
+  p.off_wt = o;   o += seg((int64_t)g.RS * p.Ksp * p.Cp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
   p.off_cls = o;  o += seg(2 * (g.RS + 1));
@@ -372,7 +373,7 @@ bool needs_pad_checks(const Geo& g) {
 // out16), for batches 0..batch-1; batches at or past batchValid are written as zeros.
 void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
                          void* dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch,
-                         float* zero_page, hipStream_t st, bool out16 = false, int batchValid = -1) {
+                         float* zero_page, hipStream_t st, bool out16 = false, int batchValid = -1, int group = 0) {
   if (batchValid < 0) batchValid = batch;
   for (int b0 = 0; b0 < batch; b0 += 32768) {  // grid.z is limited to 65535
     const int nb = batch - b0 < 32768 ? batch - b0 : 32768;
@@ -380,17 +381,17 @@ void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t s
     float* zp = b0 == 0 ? zero_page : nullptr;
     if (dtype == CONV_F32 && !out16)
       hipLaunchKernelGGL((cs::transpose_in_kernel<float, float>), grid, dim3(256), 0, st, (const float*)src,
-                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp);
+                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group);
     else if (dtype == CONV_F32)
       hipLaunchKernelGGL((cs::transpose_in_kernel<float, uint16_t>), grid, dim3(256), 0, st, (const float*)src,
-                         srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp);
+                         srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group);
     else if (!out16)
       hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, float>), grid, dim3(256), 0, st, (const uint16_t*)src,
-                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp);
+                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group);
     else
       hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st,
                          (const uint16_t*)src, srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch,
-                         rowsPad, b0, batchValid, zp);
+                         rowsPad, b0, batchValid, zp, group);
   }
 }
 
@@ -594,10 +595,10 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   float* dxt = (float*)(base + p.off_dxt);
   int* perm = (int*)(base + p.off_perm);
 
-  // dy[n][k0*PQ ..] -> dy_t[Ks*P*Q][Np]
-  launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
-                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, dyt - cs::ZERO_PAGE_FLOATS, st);
   if (p.scatter) {
+    // dy[n][k0*PQ ..] -> dy_t[Ks*P*Q][Np]
+    launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
+                        g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, dyt - cs::ZERO_PAGE_FLOATS, st);
     // T[(c,r,s)][p][q][n] = sum_k w'[(c,r,s)][k] * dy_t[k][p][q][n] is the forward kernel of a 1x1 layer
     // with Ks input channels, C*R*S kernels and dy_t as its input.
     Geo g1 = g;
@@ -631,9 +632,19 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     }
     return check_launch();
   }
-  // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed
+  // dy[n][k0*PQ ..] -> dy_t[k][P*Q + 1][Np]: one row left free after the P*Q pixels of every kernel.  That
+  // pixel and the rows of kernels Ks .. Ksp-1 are cleared: taps that miss read the one, the reduction tail the other.
+  const int64_t kPitch = (int64_t)(g.PQ + 1) * g.Np;
+  launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
+                      g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, nullptr, st, false, -1, g.PQ);
+  hipLaunchKernelGGL(cs::fill_zero_rows_kernel, dim3(std::min(1024, (g.Ks * g.Np + 255) / 256)), dim3(256), 0, st,
+                     dyt + (int64_t)g.PQ * g.Np, kPitch, g.Ks, g.Np);
+  if (p.Ksp > g.Ks)
+    hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1024), dim3(256), 0, st, dyt + (int64_t)g.Ks * kPitch,
+                       (int64_t)(p.Ksp - g.Ks) * kPitch);
+  // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed; kernels Ks .. Ksp-1 are written as zeros
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
-                      (int64_t)g.Ks * p.Cp, p.Cp, g.Ks, wt - cs::ZERO_PAGE_FLOATS, st);
+                      (int64_t)p.Ksp * p.Cp, p.Cp, p.Ksp, nullptr, st, false, g.Ks);
   int* cls = (int*)(base + p.off_cls);
   int* scratch = (int*)(base + p.off_scratch);
   float* partial = (float*)(base + p.off_tail);

@@ -243,72 +243,70 @@ struct TapWalk {
   }
 };
 
-// A^T[k][c] = w_t[tap][k][c] (filters re-laid with c innermost, pitch Cp), row image.
-// A zero page sits ZERO_PAGE_FLOATS in front of w_t.
+// A^T[k][c] = w_t[tap][k][c] (filters re-laid with c innermost, pitch Cp; Ksp = 32*nkc rows
+// per tap, zero past Ks), row image.  The uniform base is the chunk's (tap, k) row at the
+// tile's first channel; a lane's offset from it never changes.
 struct BwdDataLoadA {
   static constexpr bool COL = false;
   static constexpr bool DEEP = false;
-  const float* wt;
+  const char* wt;     // uniform: w_t at channel m0
+  const char* ub;     // uniform base of the chunk being issued
   const int* taps;
-  int Ks, Cp, S, krow, lane_off, tap;   // tap = flat (r*S+s) of walk.ti, fetched one call ahead
-  int base;
-  bool cok, live;
+  unsigned off[4];
+  int S, rowBytes, tap;   // tap = flat (r*S+s) of walk.ti, fetched one call ahead (uniform, held in a vector register)
   TapWalk walk;
-  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp_, int m0, const int* taps_, int nkc_, int ch0)
-      : wt(wt_), taps(taps_), Ks(g.Ks), Cp(Cp_), S(g.S), walk(nkc_, ch0) {
+  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp, int m0, const int* taps_, int nkc_, int ch0)
+      : wt((const char*)(wt_ + m0)), taps(taps_), S(g.S), rowBytes(Cp * 4), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int c = m0 + 4 * (l & 31);
-    cok = c < Cp;
-    krow = 8 * wv + (l >> 5);
-    lane_off = krow * Cp + c;
+    const int c = min(4 * (l & 31), Cp - 4 - m0);   // channels past the end repeat the last four (never stored)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) off[i] = (unsigned)((8 * wv + 2 * i + (l >> 5)) * Cp + c) * 4u;
     const int e = taps[walk.ti];
     tap = (e >> 16) * S + (e & 0xffff);
   }
-  __device__ __forceinline__ void begin(int, bool live_) {
-    live = live_ & cok;
-    base = (tap * Ks + walk.kc * BK) * Cp + lane_off;
+  __device__ __forceinline__ void begin(int, bool) {
+    const int t = __builtin_amdgcn_readfirstlane(tap);
+    ub = wt + (int64_t)((t * walk.nkc + walk.kc) * BK) * rowBytes;
   }
-  __device__ __forceinline__ const float* addr(int i) const {
-    const bool ok = live & (walk.kc * BK + krow + 2 * i < Ks);
-    return wt + (ok ? base + 2 * i * Cp : -ZERO_PAGE_FLOATS);
-  }
-  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {
     walk.next();
-    const int e = taps[walk.ti];   // entries past the list are allocated, so this stays in bounds
+    const int e = taps[walk.ti];   // entries past the list are allocated and hold tap 0, so this stays in bounds
     tap = (e >> 16) * S + (e & 0xffff);
   }
 };
 
-// B[k][col] = dy_t[k][p][q][n] (row image) with (p,q) the output pixel whose window
-// puts the current tap on the column block's input pixel; zero if there is none.
-// A zero page sits ZERO_PAGE_FLOATS in front of dy_t.
+// B[k][col] = dy_t[k][pixel][n] (row image; Ksp rows of P*Q+1 pixels, the extra pixel and
+// the rows past Ks are zero) with `pixel` the output pixel whose window puts the current tap
+// on the column block's input pixel, or the zero pixel if there is none.  The uniform base
+// is the k row of each load; a lane adds its half-wave's row, its block's pixel and its piece.
 struct BwdDataLoadB {
   static constexpr bool COL = false;
-  const float* dyt;
+  const char* dyt;    // uniform
+  const char* ub;     // uniform: rows of the chunk being issued
   const int* tapoff;
-  int Ks, PQNp, krow, cb, lane_off, toff;   // toff = tapoff[walk.ti][cb], fetched one call ahead
-  int base;
-  bool live;
+  int64_t pairBytes;  // two k rows
+  int64_t kBytes;     // one k row
+  unsigned lane_const, off;
+  int cb, wv8, toff;   // toff = tapoff[walk.ti][cb], fetched one call ahead
   TapWalk walk;
   __device__ BwdDataLoadB(const Geo& g, const float* dyt_, const int* tapoff_, int nkc_, int ch0)
-      : dyt(dyt_), tapoff(tapoff_), Ks(g.Ks), PQNp(g.PQ * g.Np), walk(nkc_, ch0) {
-    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+      : dyt((const char*)dyt_), tapoff(tapoff_), walk(nkc_, ch0) {
+    const int l = threadIdx.x & 63;
     const int cq = l & 31;
+    const int pitchK = (g.PQ + 1) * g.Np;
+    kBytes = (int64_t)pitchK * 4;
+    pairBytes = 2 * kBytes;
     cb = cq >> 3;
-    krow = 8 * wv + (l >> 5);
-    lane_off = 4 * (cq & 7);
+    wv8 = 8 * __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    lane_const = (unsigned)((l >> 5) * pitchK + 4 * (cq & 7)) * 4u;
     toff = tapoff[walk.ti * 4 + cb];
   }
-  __device__ __forceinline__ void begin(int, bool live_) {
-    live = live_ & (toff >= 0);
-    base = (walk.kc * BK + krow) * PQNp + toff + lane_off;
+  __device__ __forceinline__ void begin(int, bool) {
+    ub = dyt + (walk.kc * BK + wv8) * kBytes;
+    off = lane_const + (unsigned)toff * 4u;
   }
-  __device__ __forceinline__ const float* addr(int i) const {
-    const bool ok = live & (walk.kc * BK + krow + 2 * i < Ks);
-    return dyt + (ok ? base + 2 * i * PQNp : -ZERO_PAGE_FLOATS);
-  }
-  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub + i * pairBytes, off, dst); }
   __device__ __forceinline__ void end() {
     walk.next();
     toff = tapoff[walk.ti * 4 + cb];
@@ -388,7 +386,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
           const int p = hr / g.sh, q = vs / g.sw;
           const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
                            p < g.P && q < g.Q;
-          offs[j] = hit ? (p * g.Q + q) * g.Np + nbo[j] : -1;
+          offs[j] = (hit ? p * g.Q + q : g.PQ) * g.Np + nbo[j];   // no hit: the zero pixel
           any |= hit;
         }
         const unsigned long long mask = __ballot(any);
@@ -400,7 +398,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
         }
         cnt += __popcll(mask);
       }
-      if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;   // the entries the loaders fetch after the last tap
+      if (lane < 12) s_tapoff[cnt * 4 + lane] = g.PQ * g.Np;   // the entries the loaders fetch after the last tap
       if (lane < 3) s_taps[cnt + lane] = 0;
       if (lane == 0) s_ntaps = cnt;
     }
@@ -514,42 +512,50 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
   bwd_data_store_block(g, dxt, perm, mb, ct, bi, bj, acc);
 }
 
-// -------------------------------------------------------- weight gradient ----
-// Reduction runs over (pixel, n) in chunks of 32 images of one output pixel.
-// A[m][kk] = dy_t[m0+m][pix][n]: dense rows, col image.
+// ---------------------------------------------------------- weight gradient ----
+// Reduction index = (output pixel, image block, image): chunk ch covers output pixel
+// ch / NB, images nb*32 .. nb*32+31 with nb = ch % NB.
+// A[m][kk] = dy_t[m0+m][ch*32 + kk]: rows of dy_t, col image.  A lane's offset from the
+// tile's first row never changes; the uniform base advances by one chunk.
 struct BwdWeightLoadA {
   static constexpr bool COL = true;
   static constexpr bool DEEP = true;
-  const float* p[4];
-  int64_t adv;   // uniform
-  __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0) {
+  const char* tile;   // uniform: row m0 of dy_t
+  const char* ub;     // uniform: tile + the chunk being issued
+  unsigned off[4];
+  __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0)
+      : tile((const char*)(dyt + (int64_t)m0 * g.PQ * g.Np)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int kq4 = 4 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int m = min(m0 + 32 * wv + 8 * i + (l >> 3), g.Ks - 1);  // rows past the slice repeat the last one
-      p[i] = dyt + (int64_t)m * g.PQ * g.Np + kq4;
+      const int m = min(32 * wv + 8 * i + (l >> 3), g.Ks - 1 - m0);  // rows past the slice repeat the last one
+      off[i] = ((unsigned)m * (unsigned)(g.PQ * g.Np) + kq4) * 4u;
     }
   }
-  __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK; }  // dummy: chunk 0
-  __device__ __forceinline__ const float* addr(int i) const { return p[i] + adv; }
-  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
+  __device__ __forceinline__ void begin(int ch, bool live) { ub = tile + (int64_t)(live ? ch : 0) * (BK * 4); }  // dummy: chunk 0
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {}
 };
 
 // B^T[j][kk] = x_t[c_j][p*sh-ph+r_j][q*sw-pw+s_j][n] (col image); zero where tap j is in
 // the padding.  Columns j past C*R*S are computed like column 0 and never stored.  The
-// chunk's output pixel (p,q) and image block nb are uniform counters; a lane adds its
-// constant column offset to their uniform offset.
+// chunk's output pixel (p,q) and image block nb are uniform counters.  Without padding the
+// window origin goes into the uniform base and a lane's offset is its constant column
+// offset; with padding the base is the zero page in front of x_t, which out-of-range taps read.
 template <bool PAD>
 struct BwdWeightLoadB {
   static constexpr bool COL = true;
-  const float* xt;       // a zero page sits ZERO_PAGE_FLOATS in front of x_t
-  int coff[4], rj[4], sj[4];
+  const char* xt;        // uniform; a zero page sits ZERO_PAGE_FLOATS in front of x_t
+  const char* ub;        // uniform base of the chunk being issued
+  unsigned coff[4];      // bytes
+  int rj[4], sj[4];
   int NB, Q, sh, sw, ph, pw, H, W, Np;
   int p, q, nb;          // uniform position of the next chunk to issue
-  int h0, v0, uoff;      // uniform, of the chunk being issued
-  __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, int ch0) : xt(xt_) {
+  int h0, v0;            // uniform, of the chunk being issued
+  unsigned uoff;
+  __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, int ch0)
+      : xt(PAD ? opaque_uniform(xt_ - ZERO_PAGE_FLOATS) : (const char*)xt_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     NB = g.NB; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W; Np = g.Np;
     const int kq4 = 4 * ((l & 7) ^ (l >> 3));
@@ -560,7 +566,7 @@ struct BwdWeightLoadB {
       const int c = jj / g.RS, rs = jj - c * g.RS;
       rj[i] = rs / g.S;
       sj[i] = rs - rj[i] * g.S;
-      coff[i] = c * g.HW * g.Np + (rj[i] * g.W + sj[i]) * g.Np + kq4;
+      coff[i] = (unsigned)(c * g.HW * g.Np + (rj[i] * g.W + sj[i]) * g.Np + kq4 + (PAD ? ZERO_PAGE_FLOATS : 0)) * 4u;
     }
     const int pix = ch0 / NB;
     nb = ch0 - pix * NB;
@@ -570,17 +576,19 @@ struct BwdWeightLoadB {
   __device__ __forceinline__ void begin(int, bool live) {
     h0 = live ? p * sh - ph : 0;       // the dummy issue re-reads the first pixel
     v0 = live ? q * sw - pw : 0;
-    uoff = (h0 * W + v0) * Np + (live ? nb * 32 : 0);
+    const int u = (h0 * W + v0) * Np + (live ? nb * 32 : 0);
+    if (PAD) uoff = (unsigned)u * 4u;          // may wrap below zero; the sum with coff does not
+    else ub = xt + (int64_t)u * 4;
   }
-  __device__ __forceinline__ const float* addr(int i) const {
-    int idx = coff[i] + uoff;
+  __device__ __forceinline__ void issue(int i, float* dst) {
     if (PAD) {
       const bool ok = ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
-      idx = ok ? idx : -ZERO_PAGE_FLOATS;
+      unsigned o = ok ? coff[i] + uoff : 0u;
+      dma16_uv(xt, o, dst);
+    } else {
+      dma16_uv(ub, coff[i], dst);
     }
-    return xt + idx;
   }
-  __device__ __forceinline__ void issue(int i, float* dst) { dma16(addr(i), dst); }
   __device__ __forceinline__ void end() {   // branch-free carry: (nb, q, p) += 1 chunk
     ++nb;
     const int cq = nb == NB;

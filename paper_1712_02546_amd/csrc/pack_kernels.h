@@ -10,12 +10,13 @@ namespace cs {
 // for 0 <= l < cols, 0 <= n < rowsPad, b = batch0 + blockIdx.z.  64x64 tiles through LDS,
 // both sides coalesced.  grid = (ceil(cols/64), ceil(rowsPad/64), batches).  If zero_page is
 // not null the first workgroup also clears its ZERO_PAGE_FLOATS floats (the page masked DMA
-// lanes read).  Tin/Tout are float or uint16_t (bfloat16 bits).
+// lanes read).  group > 0 leaves one destination row free after every group rows (row l goes
+// to l + l/group).  Tin/Tout are float or uint16_t (bfloat16 bits).
 template <typename Tin, typename Tout>
 __global__ __launch_bounds__(256) void transpose_in_kernel(
     const Tin* __restrict__ src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
     Tout* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch0, int batchValid,
-    float* __restrict__ zero_page) {
+    float* __restrict__ zero_page, int group) {
   __shared__ float tile[64][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
@@ -38,7 +39,8 @@ __global__ __launch_bounds__(256) void transpose_in_kernel(
   for (int i = 0; i < 16; ++i) {
     const int ll = ty + 4 * i;
     const int l = l0 + ll, n = n0 + tx;
-    if (l < cols && n < rowsPad) store_from_f32<Tout>(dst + (int64_t)l * dstPitch + n, tile[tx][ll]);
+    const int lrow = group > 0 ? l + l / group : l;
+    if (l < cols && n < rowsPad) store_from_f32<Tout>(dst + (int64_t)lrow * dstPitch + n, tile[tx][ll]);
   }
 }
 
@@ -220,6 +222,15 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(T* __restrict__ p, int64
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
        i += (int64_t)gridDim.x * blockDim.x)
     p[i] = (T)0;
+}
+
+// Clears `rows` runs of `len` floats that start `stride` floats apart.
+__global__ __launch_bounds__(256) void fill_zero_rows_kernel(float* __restrict__ p, int64_t stride, int rows, int len) {
+  const int64_t total = (int64_t)rows * len;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / len);
+    p[(int64_t)r * stride + (i - (int64_t)r * len)] = 0.f;
+  }
 }
 
 // dw[i] = sum_z part[z*stride + i], summed in increasing z (bit-stable).
