@@ -209,24 +209,11 @@ __device__ __forceinline__ void mfma_group(const Frag& a, const Frag& b, f32x16 
 #define CS_FENCE() __builtin_amdgcn_sched_barrier(0x0002 | 0x0004 | 0x0010)
 
 // Main loop shared by the three passes.  A loader stages one operand; per chunk it is
-// driven as begin(ch, live), addr(0..3), end(): addr(i) is this lane's global address
-// for LDS-DMA load number i of this wavefront's share of chunk ch (chunks are requested
-// in increasing order, once each; live = false marks chunks past the last one, whose
-// loads must stay harmless so that the loop body needs no branch).  LDS holds
-// [A stage0][A stage1][B stage0][B stage1].
-//
-// A chunk is four groups G0..G3 of 16 MFMAs whose operands are read from LDS into four
-// register fragments.  Two barriers per chunk make two LDS stages behave like three:
-//   barrier A(ch): chunk ch has landed in its stage.  Each wavefront first waits for its
-//                  own eight DMA loads of chunk ch (the eight newer ones, of chunk ch+1,
-//                  may still be in flight: s_waitcnt vmcnt(8)).
-//   barrier B(ch): every wavefront has the whole of chunk ch in registers, so the stage
-//                  is free and the DMA loads of chunk ch+2 are issued into it at once.
-// A load is thus issued about one and a half chunk times before it is waited for, which
-// hides the long latency of the DMA path.  The loop is also rotated: G2,G3 of chunk ch-1
-// run while the first reads of chunk ch are in flight, so no MFMA waits for LDS.  The
-// barriers are written as asm (with a "memory" clobber as compiler fence) because the
-// fenced __syncthreads() would wait for all DMA loads.
+// driven as begin(ch, live), issue(0..3, dst), end(): issue(i, dst) starts LDS-DMA load
+// number i of this wavefront's share of chunk ch into the wave-uniform LDS address dst
+// (chunks are requested in increasing order, once each; live = false marks chunks past the
+// last one, whose loads must stay harmless so that the loop body needs no branch).  LDS
+// holds [A stage0][A stage1][B stage0][B stage1].
 template <class LA, class LB>
 __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, float* tb, int wv, bool live) {
   la.begin(ch, live);
@@ -240,78 +227,8 @@ __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, flo
   lb.end();
 }
 
-__device__ __forceinline__ void barrier_chunk_landed() { asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory"); }
-__device__ __forceinline__ void barrier_stage_free() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-__device__ __forceinline__ void barrier_all_done() {
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
-template <class LA, class LB>
-__device__ __forceinline__ void gemm_mainloop_two_barriers(LA& la, LB& lb, int ch_begin, int ch_end,
-                                              float* smem, f32x16 (&acc)[2][2]) {
-  constexpr bool AC = LA::COL, BC = LB::COL;
-  const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wa = (wv >> 1) * 64, wb = (wv & 1) * 64;
-  if (ch_begin >= ch_end) return;
-  const int blk1 = opaque_block_offset();
-  Frag a0, b0, a1, b1, a2, b2, a3, b3;
-  // prologue: chunks ch_begin and ch_begin+1 into stages 0 and 1
-  issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
-  issue_all(la, lb, ch_begin + 1, smem + TILE_F, smem + 3 * TILE_F, wv, ch_begin + 1 < ch_end);
-  barrier_chunk_landed();                                   // A(ch_begin)
-  read_frag<AC>(a0, smem, wa, lane, 0, blk1);
-  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0, blk1);
-  read_frag<AC>(a1, smem, wa, lane, 1, blk1);
-  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1, blk1);
-  read_frag<AC>(a2, smem, wa, lane, 2, blk1);
-  read_frag<BC>(b2, smem + 2 * TILE_F, wb, lane, 2, blk1);
-  read_frag<AC>(a3, smem, wa, lane, 3, blk1);
-  read_frag<BC>(b3, smem + 2 * TILE_F, wb, lane, 3, blk1);
-  __builtin_amdgcn_sched_barrier(0);
-  mfma_group(a0, b0, acc);
-  __builtin_amdgcn_sched_barrier(0);
-  barrier_stage_free();                                     // B(ch_begin)
-  issue_all(la, lb, ch_begin + 2, smem, smem + 2 * TILE_F, wv, ch_begin + 2 < ch_end);
-  mfma_group(a1, b1, acc);
-  __builtin_amdgcn_sched_barrier(0);
-  int cur = TILE_F;  // float offset of the stage that holds chunk ch: TILE_F or 0
-  for (int ch = ch_begin + 1; ch < ch_end; ++ch) {
-    const float* As = smem + cur;
-    const float* Bs = smem + 2 * TILE_F + cur;
-    barrier_chunk_landed();                                 // A(ch)
-    read_frag<AC>(a0, As, wa, lane, 0, blk1);
-    read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
-    read_frag<AC>(a1, As, wa, lane, 1, blk1);
-    read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(a2, b2, acc);  // G2 of chunk ch-1
-    mfma_group(a3, b3, acc);  // G3 of chunk ch-1
-    __builtin_amdgcn_sched_barrier(0);
-    read_frag<AC>(a2, As, wa, lane, 2, blk1);
-    read_frag<BC>(b2, Bs, wb, lane, 2, blk1);
-    read_frag<AC>(a3, As, wa, lane, 3, blk1);
-    read_frag<BC>(b3, Bs, wb, lane, 3, blk1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(a0, b0, acc);  // G0 of chunk ch
-    __builtin_amdgcn_sched_barrier(0);
-    barrier_stage_free();                                   // B(ch)
-    issue_all(la, lb, ch + 2, smem + cur, smem + 2 * TILE_F + cur, wv, ch + 2 < ch_end);
-    mfma_group(a1, b1, acc);  // G1 of chunk ch; the address arithmetic above hides in its shadow
-    __builtin_amdgcn_sched_barrier(0);
-    cur ^= TILE_F;
-  }
-  mfma_group(a2, b2, acc);  // G2, G3 of the last chunk
-  mfma_group(a3, b3, acc);
-  barrier_all_done();       // the dummy loads past the last chunk have landed: LDS may be reused
-}
-
-// Scheduling fence for the one-barrier loop: LDS reads and MFMAs keep their order across
-// it, vector/scalar ALU and memory instructions may move.
-#define CS_FENCE() __builtin_amdgcn_sched_barrier(0x0002 | 0x0004 | 0x0010)
-
-// One-barrier variant: after the barrier that publishes chunk ch, a wavefront issues the
+// One barrier per chunk: after the barrier that publishes chunk ch, a wavefront issues the
 // DMA loads of chunk ch+1 (they have one chunk time to land), runs G2,G3 of chunk ch-1
 // from registers while the LDS reads of G0,G1 of chunk ch are in flight, then G0,G1 of
 // chunk ch while G2,G3 are being read.
@@ -377,14 +294,10 @@ __device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch
   mfma_group(a1, b1, acc);
 }
 
-// Which loop a pass uses is a measured choice (LA::DEEP): the weight-gradient pass, whose
-// two operands are both 16-byte-read col images, gains from the deeper prefetch; the
-// other two passes are faster with a single barrier per chunk.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
                                               float* smem, f32x16 (&acc)[2][2]) {
-  if constexpr (LA::DEEP) gemm_mainloop_two_barriers(la, lb, ch_begin, ch_end, smem, acc);
-  else gemm_mainloop_one_barrier(la, lb, ch_begin, ch_end, smem, acc);
+  gemm_mainloop_one_barrier(la, lb, ch_begin, ch_end, smem, acc);
 }
 
 // Position of accumulator register v of a 32x32 MFMA block inside the block.

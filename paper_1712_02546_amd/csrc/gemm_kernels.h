@@ -18,7 +18,6 @@ __device__ __forceinline__ float* dma_dst(float* tile, int wv, int i) { return t
 // offset from the tile's first row is fixed and only the uniform base moves along the rows.
 struct FwdLoadA {
   static constexpr bool COL = true;
-  static constexpr bool DEEP = false;
   const char* tile;   // uniform: row m0 of the filter matrix
   const char* ub;     // uniform: tile + the chunk being issued
   unsigned off[4];
@@ -104,7 +103,8 @@ struct FwdLoadB {
     const unsigned a = (unsigned)pick(cur, 2 * i), b = (unsigned)pick(cur, 2 * i + 1);
     unsigned off = ((b - a) & upmask) + a + pixbase;
     if (PAD) {
-      const int rs = upper ? pick(cur_rs, 2 * i + 1) : pick(cur_rs, 2 * i);
+      const unsigned ra = (unsigned)pick(cur_rs, 2 * i), rb = (unsigned)pick(cur_rs, 2 * i + 1);
+      const int rs = (int)(ra + ((rb - ra) & upmask));   // same half-wave choice, again without a select
       const bool ok = ((unsigned)(h0 + (rs >> 16)) < (unsigned)H) & ((unsigned)(w0 + (rs & 0xffff)) < (unsigned)W);
       off = ok ? off : 0u;
     }
@@ -248,7 +248,6 @@ struct TapWalk {
 // tile's first channel; a lane's offset from it never changes.
 struct BwdDataLoadA {
   static constexpr bool COL = false;
-  static constexpr bool DEEP = false;
   const char* wt;     // uniform: w_t at channel m0
   const char* ub;     // uniform base of the chunk being issued
   const int* taps;
@@ -519,7 +518,6 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
 // tile's first row never changes; the uniform base advances by one chunk.
 struct BwdWeightLoadA {
   static constexpr bool COL = true;
-  static constexpr bool DEEP = true;
   const char* tile;   // uniform: row m0 of dy_t
   const char* ub;     // uniform: tile + the chunk being issued
   unsigned off[4];
