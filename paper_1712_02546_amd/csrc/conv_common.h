@@ -161,6 +161,11 @@ __device__ __forceinline__ void dma16_uv(const char* base_uniform, unsigned& lan
 // Reduction order inside a chunk.  MFMA step ks = 4*j + t (j, t in 0..3) multiplies
 // the element pair kk = 8*j + t (lanes 0..31) and kk = 8*j + 4 + t (lanes 32..63),
 // which is what a 16-byte read of col-image slot 2*j + lane/32 delivers.
+// Col image: tile row m keeps its eight 16-byte slots (four reduction steps each) in the
+// order slot = kq ^ col_key(m).  The key is chosen by measurement: with (m >> 1) & 7 a
+// wavefront's 16-byte LDS reads run at 256 bytes per clock, with m & 7 at half of that.
+__device__ __forceinline__ int col_key(int row) { return (row >> 1) & 7; }
+
 struct Frag {          // operands of four MFMA steps (one j) for the wavefront's two 32-wide blocks
   f32x4 v[2];          // v[blk][t]
 };
@@ -168,7 +173,7 @@ struct Frag {          // operands of four MFMA steps (one j) for the wavefront'
 template <bool COL>
 __device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase, int lane, int j, int blk1) {
   if constexpr (COL) {
-    const int u = lane & 7, h = lane >> 5;
+    const int u = col_key(lane & 31), h = lane >> 5;
     const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
     f.v[0] = *(const f32x4*)(tile + slot * 4);
     f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);

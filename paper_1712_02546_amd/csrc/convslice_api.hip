@@ -157,7 +157,11 @@ cs::RunPlan plan_runs(const Geo& g, int MB) {
   rp.tilesPerPix = tilesPerPix;
   rp.total = (int)total;
   rp.nWg = S & ~7;
-  rp.units = (int)((total + rp.nWg - 1) / rp.nWg);
+  // Runs are whole numbers of taps (nkc chunks each), so that every workgroup starts a tap at the same time and
+  // all of them sweep the kernel range together: what one compute die needs at any moment is then one k-chunk
+  // of every tap's filters and of every output pixel, which its L2 holds.
+  const int64_t pieces = total / nkc;
+  rp.units = (int)((pieces + rp.nWg - 1) / rp.nWg) * nkc;
   return rp;
 }
 

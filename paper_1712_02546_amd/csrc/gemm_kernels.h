@@ -23,9 +23,9 @@ struct FwdLoadA {
   unsigned off[4];
   __device__ FwdLoadA(const float* w, int ldw, int m0, int Ks) : tile((const char*)(w + (int64_t)m0 * ldw)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int kq4 = 4 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
       const int m = min(32 * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
       off[i] = ((unsigned)m * (unsigned)ldw + kq4) * 4u;
     }
@@ -524,9 +524,9 @@ struct BwdWeightLoadA {
   __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0)
       : tile((const char*)(dyt + (int64_t)m0 * g.PQ * g.Np)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int kq4 = 4 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
       const int m = min(32 * wv + 8 * i + (l >> 3), g.Ks - 1 - m0);  // rows past the slice repeat the last one
       off[i] = ((unsigned)m * (unsigned)(g.PQ * g.Np) + kq4) * 4u;
     }
@@ -556,9 +556,9 @@ struct BwdWeightLoadB {
       : xt(PAD ? opaque_uniform(xt_ - ZERO_PAGE_FLOATS) : (const char*)xt_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     NB = g.NB; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W; Np = g.Np;
-    const int kq4 = 4 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
       const int j = j0 + 32 * wv + 8 * i + (l >> 3);
       const int jj = j < g.CRS ? j : 0;
       const int c = jj / g.RS, rs = jj - c * g.RS;
