@@ -199,7 +199,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_tab = p.off_T = 0;
   // dy_t[Ksp][PQ+1][Np] (one zero pixel per row, zero rows past Ks), w_t[RS][Ksp][Cp] (zero rows past Ks)
   p.off_dyt = o;  o += seg((int64_t)p.Ksp * (g.PQ + 1) * g.Np);
-  p.off_wt = o;   o += seg((int64_t)g.RS * p.Ksp * p.Cp);
+  p.off_wt = o;   o += seg((int64_t)g.RS * g.C * p.Ksp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
   p.off_cls = o;  o += seg(2 * (g.RS + 1));
@@ -377,7 +377,8 @@ bool needs_pad_checks(const Geo& g) {
 // out16), for batches 0..batch-1; batches at or past batchValid are written as zeros.
 void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
                          void* dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch,
-                         float* zero_page, hipStream_t st, bool out16 = false, int batchValid = -1, int group = 0) {
+                         float* zero_page, hipStream_t st, bool out16 = false, int batchValid = -1, int group = 0,
+                         int interleave = 0) {
   if (batchValid < 0) batchValid = batch;
   for (int b0 = 0; b0 < batch; b0 += 32768) {  // grid.z is limited to 65535
     const int nb = batch - b0 < 32768 ? batch - b0 : 32768;
@@ -385,17 +386,17 @@ void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t s
     float* zp = b0 == 0 ? zero_page : nullptr;
     if (dtype == CONV_F32 && !out16)
       hipLaunchKernelGGL((cs::transpose_in_kernel<float, float>), grid, dim3(256), 0, st, (const float*)src,
-                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group);
+                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave);
     else if (dtype == CONV_F32)
       hipLaunchKernelGGL((cs::transpose_in_kernel<float, uint16_t>), grid, dim3(256), 0, st, (const float*)src,
-                         srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group);
+                         srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave);
     else if (!out16)
       hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, float>), grid, dim3(256), 0, st, (const uint16_t*)src,
-                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group);
+                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave);
     else
       hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st,
                          (const uint16_t*)src, srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch,
-                         rowsPad, b0, batchValid, zp, group);
+                         rowsPad, b0, batchValid, zp, group, interleave);
   }
 }
 
@@ -646,9 +647,10 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   if (p.Ksp > g.Ks)
     hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1024), dim3(256), 0, st, dyt + (int64_t)g.Ks * kPitch,
                        (int64_t)(p.Ksp - g.Ks) * kPitch);
-  // w[k][c][rs] -> w_t[rs][k][Cp]: per kernel k a C x RS matrix transposed; kernels Ks .. Ksp-1 are written as zeros
-  launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, g.CRS, g.RS, g.C, g.RS, wt, p.Cp,
-                      (int64_t)p.Ksp * p.Cp, p.Cp, p.Ksp, nullptr, st, false, g.Ks);
+  // w[k][(c,rs)] -> w_t[rs][c][Ksp]: the slice's filter matrix transposed, its rows (c,rs) re-ordered tap-major,
+  // zero past Ks.  A tap's C rows are then a dense C x Ksp matrix, contiguous along the reduction.
+  launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0, p.Ksp,
+                      p.Ksp, 1, nullptr, st, false, -1, g.RS, g.C);
   int* cls = (int*)(base + p.off_cls);
   int* scratch = (int*)(base + p.off_scratch);
   float* partial = (float*)(base + p.off_tail);
@@ -660,7 +662,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   const int CT = (g.HW * g.NB + 3) / 4;
   probe.begin(st);
   hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(p.run.enabled ? p.run.nWg : cs::grid_dealt(MB, CT)), dim3(cs::NT),
-                     lds, st, g, wt, p.Cp, dyt, perm, cls, dxt, MB, CT, p.run, partial);
+                     lds, st, g, wt, p.Ksp, dyt, perm, cls, dxt, MB, CT, p.run, partial);
   if (p.run.enabled)
     hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, cls, partial, dxt,
                        MB, p.run);

@@ -243,35 +243,36 @@ struct TapWalk {
   }
 };
 
-// A^T[k][c] = w_t[tap][k][c] (filters re-laid with c innermost, pitch Cp; Ksp = 32*nkc rows
-// per tap, zero past Ks), row image.  The uniform base is the chunk's (tap, k) row at the
-// tile's first channel; a lane's offset from it never changes.
+// A[c][k] = w_t[tap][c][k] (filters re-laid tap-major with k innermost, pitch Ksp = 32*nkc,
+// zero past Ks), col image, like the forward pass's filter operand: the uniform base is the
+// chunk's (tap, k) position in the tile's first channel row, a lane's offset never changes.
 struct BwdDataLoadA {
-  static constexpr bool COL = false;
-  const char* wt;     // uniform: w_t at channel m0
+  static constexpr bool COL = true;
+  const char* wt;     // uniform: w_t at channel m0 of tap 0
   const char* ub;     // uniform base of the chunk being issued
   const int* taps;
   unsigned off[4];
-  int S, rowBytes, tap;   // tap = flat (r*S+s) of walk.ti, fetched one call ahead (uniform, held in a vector register)
+  unsigned tapBytes;  // one tap: C rows (a whole work copy is below 4 GiB)
+  int tap;            // flat tap r*S+s of walk.ti, fetched one call ahead (uniform, held in a vector register)
   TapWalk walk;
-  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Cp, int m0, const int* taps_, int nkc_, int ch0)
-      : wt((const char*)(wt_ + m0)), taps(taps_), S(g.S), rowBytes(Cp * 4), walk(nkc_, ch0) {
+  __device__ BwdDataLoadA(const Geo& g, const float* wt_, int Ksp, int m0, const int* taps_, int nkc_, int ch0)
+      : wt((const char*)(wt_ + (int64_t)m0 * Ksp)), taps(taps_), tapBytes((unsigned)g.C * (unsigned)Ksp * 4u), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int c = min(4 * (l & 31), Cp - 4 - m0);   // channels past the end repeat the last four (never stored)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) off[i] = (unsigned)((8 * wv + 2 * i + (l >> 5)) * Cp + c) * 4u;
-    const int e = taps[walk.ti];
-    tap = (e >> 16) * S + (e & 0xffff);
+    for (int i = 0; i < 4; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
+      const int c = min(32 * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // channels past the end repeat the last one (never stored)
+      off[i] = ((unsigned)c * (unsigned)Ksp + kq4) * 4u;
+    }
+    tap = taps[walk.ti];
   }
   __device__ __forceinline__ void begin(int, bool) {
-    const int t = __builtin_amdgcn_readfirstlane(tap);
-    ub = wt + (int64_t)((t * walk.nkc + walk.kc) * BK) * rowBytes;
+    ub = wt + ((unsigned)__builtin_amdgcn_readfirstlane(tap) * tapBytes + (unsigned)walk.kc * (BK * 4u));
   }
   __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {
     walk.next();
-    const int e = taps[walk.ti];   // entries past the list are allocated and hold tap 0, so this stays in bounds
-    tap = (e >> 16) * S + (e & 0xffff);
+    tap = taps[walk.ti];   // entries past the list are allocated and hold tap 0, so this stays in bounds
   }
 };
 
@@ -284,8 +285,8 @@ struct BwdDataLoadB {
   const char* dyt;    // uniform
   const char* ub;     // uniform: rows of the chunk being issued
   const int* tapoff;
-  int64_t pairBytes;  // two k rows
-  int64_t kBytes;     // one k row
+  unsigned pairBytes; // two k rows
+  unsigned kBytes;    // one k row (a whole work copy is below 4 GiB)
   unsigned lane_const, off;
   int cb, wv8, toff;   // toff = tapoff[walk.ti][cb], fetched one call ahead
   TapWalk walk;
@@ -294,18 +295,18 @@ struct BwdDataLoadB {
     const int l = threadIdx.x & 63;
     const int cq = l & 31;
     const int pitchK = (g.PQ + 1) * g.Np;
-    kBytes = (int64_t)pitchK * 4;
-    pairBytes = 2 * kBytes;
+    kBytes = (unsigned)pitchK * 4u;
+    pairBytes = 2u * kBytes;
     cb = cq >> 3;
     wv8 = 8 * __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     lane_const = (unsigned)((l >> 5) * pitchK + 4 * (cq & 7)) * 4u;
     toff = tapoff[walk.ti * 4 + cb];
   }
   __device__ __forceinline__ void begin(int, bool) {
-    ub = dyt + (walk.kc * BK + wv8) * kBytes;
+    ub = dyt + (unsigned)(walk.kc * BK + wv8) * kBytes;
     off = lane_const + (unsigned)toff * 4u;
   }
-  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub + i * pairBytes, off, dst); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub + (unsigned)i * pairBytes, off, dst); }
   __device__ __forceinline__ void end() {
     walk.next();
     toff = tapoff[walk.ti * 4 + cb];
@@ -342,7 +343,7 @@ __device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __rest
 }
 
 // dx_t[c][pixel][n]; column tiles follow the pixel order in perm.
-__global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* __restrict__ wt, int Cp,
+__global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* __restrict__ wt, int Ksp,
                                                            const float* __restrict__ dyt,
                                                            const int* __restrict__ perm,
                                                            const int* __restrict__ cls,
@@ -391,7 +392,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
         const unsigned long long mask = __ballot(any);
         if (any) {
           const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-          s_taps[pos] = (rr << 16) | ss;
+          s_taps[pos] = tp;   // flat r*S+s
 #pragma unroll
           for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
         }
@@ -411,7 +412,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    BwdDataLoadA la(g, wt, Cp, mb * BM, s_taps, nkc, cb);
+    BwdDataLoadA la(g, wt, Ksp, mb * BM, s_taps, nkc, cb);
     BwdDataLoadB lb(g, dyt, s_tapoff, nkc, cb);
     gemm_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) {

@@ -10,13 +10,15 @@ namespace cs {
 // for 0 <= l < cols, 0 <= n < rowsPad, b = batch0 + blockIdx.z.  64x64 tiles through LDS,
 // both sides coalesced.  grid = (ceil(cols/64), ceil(rowsPad/64), batches).  If zero_page is
 // not null the first workgroup also clears its ZERO_PAGE_FLOATS floats (the page masked DMA
-// lanes read).  group > 0 leaves one destination row free after every group rows (row l goes
-// to l + l/group).  Tin/Tout are float or uint16_t (bfloat16 bits).
+// lanes read).  Destination rows can be re-ordered: group > 0, interleave = 0 leaves one row
+// free after every group rows (row l goes to l + l/group); group > 0, interleave > 0 reads l
+// as (a, b) = (l / group, l % group) and writes row b*interleave + a.  Tin/Tout are float or
+// uint16_t (bfloat16 bits).
 template <typename Tin, typename Tout>
 __global__ __launch_bounds__(256) void transpose_in_kernel(
     const Tin* __restrict__ src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
     Tout* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch0, int batchValid,
-    float* __restrict__ zero_page, int group) {
+    float* __restrict__ zero_page, int group, int interleave) {
   __shared__ float tile[64][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
@@ -39,7 +41,7 @@ __global__ __launch_bounds__(256) void transpose_in_kernel(
   for (int i = 0; i < 16; ++i) {
     const int ll = ty + 4 * i;
     const int l = l0 + ll, n = n0 + tx;
-    const int lrow = group > 0 ? l + l / group : l;
+    const int lrow = group <= 0 ? l : interleave > 0 ? (l % group) * interleave + l / group : l + l / group;
     if (l < cols && n < rowsPad) store_from_f32<Tout>(dst + (int64_t)lrow * dstPitch + n, tile[tx][ll]);
   }
 }
