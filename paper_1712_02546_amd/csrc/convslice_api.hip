@@ -626,7 +626,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
       hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g1, partial, T, p.MB1,
                          p.CT1, p.nch, p.tail);
     probe.end(st);
-    const dim3 grid((g.C * g.HW + 63) / 64, (g.N + 63) / 64);
+    const dim3 grid((g.C * g.HW + cs::COL2IM_ROWS - 1) / cs::COL2IM_ROWS, (g.N + 63) / 64);
     const bool acc = desc->accumulate != 0;
     if (desc->dtype == CONV_F32) {
       if (acc) hipLaunchKernelGGL((cs::col2im_out_kernel<float, true>), grid, dim3(256), 0, st, g, T, (float*)dx);

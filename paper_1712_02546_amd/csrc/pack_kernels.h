@@ -81,48 +81,55 @@ __global__ __launch_bounds__(256) void transpose_out_kernel(
 // leaves T[(c,r,s)][p][q][n] = sum_k w[k,c,r,s] * dy[n,k,p,q]; every input pixel (h,v)
 // collects the (r,s,p,q) combinations whose window position lands on it:
 //   dx[n][c][h][v] (+)= sum_{r,s : p*sh-ph+r = h, q*sw-pw+s = v} T[(c,r,s)][p][q][n]
-// in increasing (r,s) order.  Same tiling as transpose_out_kernel: a wavefront reads
-// T rows along n (coalesced) and the tile is written out along (c,h,v).
-// grid = (ceil(C*H*W/64), ceil(N/64)).
+// in increasing (r,s) order.  A workgroup owns 16 consecutive (c,h,v) positions and 64 images:
+// a wavefront reads T rows along n (coalesced), the tile is turned in LDS and written out along
+// (c,h,v).  The tap loops are branch free (a miss reads a clamped element and adds a selected
+// zero), so that the loads of several taps are in flight together.
+// grid = (ceil(C*H*W/16), ceil(N/64)).
+constexpr int COL2IM_ROWS = 16;
 template <typename Tout, bool ACC>
 __global__ __launch_bounds__(256) void col2im_out_kernel(Geo g, const float* __restrict__ T,
                                                          Tout* __restrict__ dx) {
-  __shared__ float tile[64][65];
+  __shared__ float tile[COL2IM_ROWS][65];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  const int l0 = blockIdx.x * COL2IM_ROWS, n0 = blockIdx.y * 64;
   const int CHW = g.C * g.HW;
 #pragma unroll 1
-  for (int i = 0; i < 16; ++i) {
+  for (int i = 0; i < COL2IM_ROWS / 4; ++i) {
     const int ll = ty + 4 * i;
     const int l = l0 + ll, n = n0 + tx;
     float acc = 0.f;
     if (l < CHW && n < g.Np) {
       const int c = l / g.HW, hw = l - c * g.HW;
       const int h = hw / g.W, v = hw - h * g.W;
-      for (int r = 0; r < g.R; ++r) {
+      const float* Tc = T + (int64_t)c * g.RS * g.PQ * g.Np + n;
+      // only taps r = (h+ph) mod sh, +sh, ... can have h+ph-r divisible by the stride (same for s)
+      for (int r = (h + g.ph) % g.sh; r < g.R; r += g.sh) {
         const int hr = h + g.ph - r;
-        if (hr < 0) break;
         const int p = hr / g.sh;
-        if (p * g.sh != hr || p >= g.P) continue;
-        for (int s = 0; s < g.S; ++s) {
+        const bool rok = hr >= 0 && p < g.P;
+        const int pc = rok ? p : 0;
+#pragma unroll 5
+        for (int s = (v + g.pw) % g.sw; s < g.S; s += g.sw) {
           const int vs = v + g.pw - s;
-          if (vs < 0) break;
           const int q = vs / g.sw;
-          if (q * g.sw != vs || q >= g.Q) continue;
-          acc += T[((int64_t)(c * g.RS + r * g.S + s) * g.PQ + p * g.Q + q) * g.Np + n];
+          const bool ok = rok && vs >= 0 && q < g.Q;
+          const float t = Tc[((int64_t)(r * g.S + s) * g.PQ + pc * g.Q + (ok ? q : 0)) * g.Np];
+          acc += ok ? t : 0.f;
         }
       }
     }
     tile[ll][tx] = acc;
   }
   __syncthreads();
+  const int wl = threadIdx.x & (COL2IM_ROWS - 1), wn = threadIdx.x / COL2IM_ROWS;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int nn = ty + 4 * i;
-    const int n = n0 + nn, l = l0 + tx;
+  for (int i = 0; i < 64 / (256 / COL2IM_ROWS); ++i) {
+    const int nn = wn + (256 / COL2IM_ROWS) * i;
+    const int n = n0 + nn, l = l0 + wl;
     if (n < g.N && l < CHW) {
       Tout* p = dx + (int64_t)n * CHW + l;
-      float v = tile[tx][nn];
+      float v = tile[wl][nn];
       if (ACC) v += load_as_f32<Tout>(p);
       store_from_f32<Tout>(p, v);
     }
@@ -241,6 +248,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
        i += (int64_t)gridDim.x * blockDim.x) {
     float acc = part[i];
+#pragma unroll 8
     for (int z = 1; z < splits; ++z) acc += part[(int64_t)z * stride + i];
     dw[i] = acc;
   }
