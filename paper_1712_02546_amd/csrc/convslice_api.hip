@@ -149,19 +149,22 @@ cs::RunPlan plan_runs(const Geo& g, int MB) {
   int64_t taps = 0;
   for (int a = 0; a <= g.R; ++a)
     for (int b = 0; b <= g.S; ++b) taps += rowh[a] * colh[b] * (a * b > 0 ? a * b : 1);
-  const int tilesPerPix = (g.NB / 4) * MB;
+  // The line holds the column tiles only; each run of the line is computed by MB workgroups, one per row tile,
+  // which therefore walk through the same pixels, taps and k-chunks at the same time and share the dy operand.
+  const int tilesPerPix = g.NB / 4;
   const int64_t total = taps * tilesPerPix * nkc;
   const int S = chip_slots();
-  if (total >= (int64_t)1 << 30 || total < (int64_t)16 * S) return rp;   // too long for int, or too little work
+  const int nRuns = S / MB;
+  if (nRuns < 1 || total >= (int64_t)1 << 30 || total * MB < (int64_t)16 * S) return rp;   // too long for int, or too little work
   rp.enabled = 1;
   rp.tilesPerPix = tilesPerPix;
   rp.total = (int)total;
-  rp.nWg = S & ~7;
+  rp.nWg = nRuns * MB;
   // Runs are whole numbers of taps (nkc chunks each), so that every workgroup starts a tap at the same time and
-  // all of them sweep the kernel range together: what one compute die needs at any moment is then one k-chunk
-  // of every tap's filters and of every output pixel, which its L2 holds.
+  // all of them sweep the kernel range together; with runs of equal length only a few tap phases exist at any
+  // moment, and workgroups in the same phase share the filter operand.
   const int64_t pieces = total / nkc;
-  rp.units = (int)((pieces + rp.nWg - 1) / rp.nWg) * nkc;
+  rp.units = (int)((pieces + nRuns - 1) / nRuns) * nkc;
   return rp;
 }
 
@@ -661,7 +664,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(p.run.enabled ? p.run.nWg : cs::grid_dealt(MB, CT)), dim3(cs::NT),
+  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT)), dim3(cs::NT),
                      lds, st, g, wt, p.Ksp, dyt, perm, cls, dxt, MB, CT, p.run, partial);
   if (p.run.enabled)
     hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, cls, partial, dxt,

@@ -314,13 +314,15 @@ struct BwdDataLoadB {
 };
 
 // Even sharing of the input-gradient pass (tiles of unequal cost).  With every column tile
-// holding one pixel (Np a multiple of 128) the tiles form a line: pixels by decreasing tap
-// count (perm / cls from the ordering kernel), per pixel its Np/128 column tiles, per column
-// tile its MB row tiles.  A tile with t taps is max(t,1)*nkc chunks long.  The line is cut
-// into nWg equal runs of `units` chunks; a workgroup computes the tiles inside its run
-// whole and the (at most two) tiles that stick out at either end partially, into scratch
-// slot 2*run (the tile its run starts in) or 2*run+1; a fix-up kernel adds the slots of a
-// cut tile in run order.  enabled = 0: one workgroup per tile, heaviest first (tile_dealt).
+// holding one pixel (Np a multiple of 128) the column tiles form a line: pixels by decreasing
+// tap count (perm / cls from the ordering kernel), per pixel its tilesPerPix = Np/128 column
+// tiles.  A tile with t taps is max(t,1)*nkc chunks long; `total` is the length of the line.
+// The line is cut into equal runs of `units` chunks, and each run is computed by MB
+// workgroups, one per row tile (nWg = runs * MB): workgroup run*MB+mb computes row tile mb of
+// the column tiles inside its run whole and of the (at most two) tiles that stick out at either
+// end partially, into scratch slot 2*wg (the tile its run starts in) or 2*wg+1; a fix-up kernel
+// adds the slots of a cut tile in run order.  enabled = 0: one workgroup per tile, heaviest
+// first (tile_dealt).
 struct RunPlan {
   int enabled, units, nWg, tilesPerPix, total;
 };
@@ -433,14 +435,16 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
     return;
   }
 
-  // run mode: runs are dealt to the XCDs in contiguous blocks (run = xcd * nWg/8 + sequence)
-  const int run = (blockIdx.x & 7) * (rp.nWg >> 3) + (blockIdx.x >> 3);
+  // run mode: workgroups are dealt to the XCDs in contiguous blocks; workgroup w = run * MB + row tile
+  const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  if (wg >= rp.nWg) return;
+  const int run = wg / MB, mb = wg - run * MB;
   int pos = run * rp.units;
   const int end = min(pos + rp.units, rp.total);
   if (pos >= end) return;
   for (int i = threadIdx.x; i < 2 * (g.RS + 1); i += NT) s_cls[i] = cls[i];
   __syncthreads();
-  // locate pos: tap-count class wc (descending), tile index t inside the class, chunk c inside the tile
+  // locate pos: tap-count class wc (descending), column tile t inside the class, chunk c inside the tile
   int wc = g.RS, t = 0, c = 0;
   {
     int rest = pos;
@@ -456,15 +460,13 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
       rest -= span;
     }
   }
-  const int NBq = g.NB >> 2;
   bool first = true;
   while (pos < end) {
     const int len = max(wc, 1) * nkc;
     const int ce = min(len, c + (end - pos));
-    const int pi = t / rp.tilesPerPix, sub = t - pi * rp.tilesPerPix;
-    const int nbq = sub / MB, mb = sub - nbq * MB;
-    const int ct = (s_cls[2 * wc] + pi) * NBq + nbq;
-    segment(mb, ct, c, ce, c == 0 && ce == len, run * 2 + (first ? 0 : 1));
+    const int pi = t / rp.tilesPerPix, nbq = t - pi * rp.tilesPerPix;
+    const int ct = (s_cls[2 * wc] + pi) * rp.tilesPerPix + nbq;
+    segment(mb, ct, c, ce, c == 0 && ce == len, wg * 2 + (first ? 0 : 1));
     pos += ce - c;
     c = 0;
     first = false;
@@ -482,19 +484,19 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
                                                             const float* __restrict__ partial,
                                                             float* __restrict__ dxt, int MB, RunPlan rp) {
   const int nkc = (g.Ks + BK - 1) / BK;
-  const int NBq = g.NB >> 2;
+  const int NBq = rp.tilesPerPix;
   const int ct = blockIdx.x / MB, mb = blockIdx.x - ct * MB;
   const int sp = ct / NBq, nbq = ct - sp * NBq;
-  // position of the tile in the line
+  // position of the column tile in the line
   int a = 0, len = 0;
   for (int wc = g.RS; wc >= 0; --wc) {
     const int start = cls[2 * wc], cnt = cls[2 * wc + 1];
     len = max(wc, 1) * nkc;
     if (sp >= start && sp < start + cnt) {
-      a += ((sp - start) * rp.tilesPerPix + nbq * MB + mb) * len;
+      a += ((sp - start) * NBq + nbq) * len;
       break;
     }
-    a += cnt * rp.tilesPerPix * len;
+    a += cnt * NBq * len;
   }
   const int b = a + len;
   const int r0 = a / rp.units, r1 = (b - 1) / rp.units;
@@ -505,7 +507,7 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   for (int r = r0; r <= r1; ++r) {
     const int slot = r * rp.units >= a ? 0 : 1;   // a run that starts inside the tile used its first slot
-    const float* p = partial + (int64_t)(r * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
+    const float* p = partial + (int64_t)((r * MB + mb) * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];
   }
