@@ -21,7 +21,9 @@ EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_bwd_dat
            "conv_partition", "conv_partition_estimate", "conv_calibrate_workspace_bytes",
            "conv_calibrate", "conv_layer_workspace_bytes", "conv_layer_fwd",
            "conv_layer_bwd_data", "conv_layer_bwd_weight", "conv_comm_elements",
-           "conv_comm_elements_partition", "conv_scaling_estimate")
+           "conv_comm_elements_partition", "conv_scaling_estimate",
+           "net_norm_fwd", "net_norm_bwd", "net_pool_fwd", "net_pool_bwd", "net_fc_fwd", "net_fc_bwd",
+           "net_softmax_loss_fwd", "net_softmax_loss_bwd", "net_sgd_update")
 MAX_DEVICES = 64
 
 
@@ -115,6 +117,19 @@ def load() -> ctypes.CDLL:
         lib.conv_comm_elements_partition.restype = ctypes.c_int
         lib.conv_scaling_estimate.argtypes = [pd, pd, ctypes.c_int32, ctypes.c_int32] + [ctypes.c_double] * 4 + [pd] * 3
         lib.conv_scaling_estimate.restype = ctypes.c_int
+        i32, f32 = ctypes.c_int32, ctypes.c_float
+        lib.net_norm_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.net_norm_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.net_pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        lib.net_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        lib.net_fc_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+        lib.net_fc_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp]
+        lib.net_softmax_loss_fwd.argtypes = [vp, vp, vp, i32, i32, vp]
+        lib.net_softmax_loss_bwd.argtypes = [vp, vp, vp, i32, i32, vp]
+        lib.net_sgd_update.argtypes = [vp, vp, f32, ctypes.c_int64, vp]
+        for name in EXPORTS:
+            if name.startswith("net_"):
+                getattr(lib, name).restype = ctypes.c_int
         for name in ("conv_layer_fwd", "conv_layer_bwd_data", "conv_layer_bwd_weight"):
             f = getattr(lib, name)
             f.argtypes = [dp, pi, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -316,3 +331,54 @@ def conv_scaling_estimate(t_conv, shares, t_comp: float, elements: float, bytes_
     if rc != 0:
         raise ConvError(rc, "conv_scaling_estimate")
     return float(sec.value), float(sp.value), float(am.value)
+
+
+# ---- convnet.h: the network's other layers (fp32 device tensors) ------------------------------
+
+def _net(name, raw_status, *args):
+    rc = getattr(load(), name)(*args)
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, name)
+    return None
+
+
+def net_norm_fwd(x, y, scale, N, C, HW, size=5, kappa=1.0, alpha=1e-4, beta=0.75, stream=None, raw_status=False):
+    return _net("net_norm_fwd", raw_status, _ptr(x), _ptr(y), _ptr(scale), N, C, HW, size, kappa, alpha, beta,
+                _stream(stream))
+
+
+def net_norm_bwd(x, scale, dy, dx, N, C, HW, size=5, kappa=1.0, alpha=1e-4, beta=0.75, stream=None,
+                 raw_status=False):
+    return _net("net_norm_bwd", raw_status, _ptr(x), _ptr(scale), _ptr(dy), _ptr(dx), N, C, HW, size, kappa, alpha,
+                beta, _stream(stream))
+
+
+def net_pool_fwd(x, y, NC, H, W, win=2, stride=2, stream=None, raw_status=False):
+    return _net("net_pool_fwd", raw_status, _ptr(x), _ptr(y), NC, H, W, win, stride, _stream(stream))
+
+
+def net_pool_bwd(x, dy, dx, NC, H, W, win=2, stride=2, stream=None, raw_status=False):
+    return _net("net_pool_bwd", raw_status, _ptr(x), _ptr(dy), _ptr(dx), NC, H, W, win, stride, _stream(stream))
+
+
+def net_fc_fwd(x, W, b, y, N, I, O, stream=None, raw_status=False):
+    return _net("net_fc_fwd", raw_status, _ptr(x), _ptr(W), _ptr(b), _ptr(y), N, I, O, _stream(stream))
+
+
+def net_fc_bwd(x, W, dy, dx, dW, db, N, I, O, stream=None, raw_status=False):
+    return _net("net_fc_bwd", raw_status, _ptr(x), _ptr(W), _ptr(dy), _ptr(dx), _ptr(dW), _ptr(db), N, I, O,
+                _stream(stream))
+
+
+def net_softmax_loss_fwd(z, labels, loss, N, O, stream=None, raw_status=False):
+    return _net("net_softmax_loss_fwd", raw_status, _ptr(z), _ptr(labels), _ptr(loss), N, O, _stream(stream))
+
+
+def net_softmax_loss_bwd(z, labels, dz, N, O, stream=None, raw_status=False):
+    return _net("net_softmax_loss_bwd", raw_status, _ptr(z), _ptr(labels), _ptr(dz), N, O, _stream(stream))
+
+
+def net_sgd_update(w, dw, lr, count, stream=None, raw_status=False):
+    return _net("net_sgd_update", raw_status, _ptr(w), _ptr(dw), lr, count, _stream(stream))

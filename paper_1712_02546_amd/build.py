@@ -1,4 +1,4 @@
-"""Builds libconvslice.so (the C-ABI library of include/convslice.h and include/convlayer.h) for gfx950 with hipcc."""
+"""Builds libconvslice.so (the C-ABI library of include/*.h) for gfx950 with hipcc."""
 from __future__ import annotations
 
 import os
@@ -8,9 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconvslice.so")
-SOURCES = [os.path.join(CSRC, "convslice_api.hip"), os.path.join(CSRC, "convlayer_api.hip")]
+SOURCES = [os.path.join(CSRC, n) for n in ("convslice_api.hip", "convlayer_api.hip", "netlayers.hip")]
 HEADERS = [os.path.join(CSRC, n) for n in ("conv_common.h", "gemm_kernels.h", "pack_kernels.h")] + [
-    os.path.join(os.path.dirname(HERE), "include", n) for n in ("convslice.h", "convlayer.h")]
+    os.path.join(os.path.dirname(HERE), "include", n) for n in ("convslice.h", "convlayer.h", "convnet.h")]
 
 # packed-fp32 VALU forms are switched off for all device code on purpose.
 HIPCC_FLAGS = [

@@ -1,0 +1,342 @@
+// netlayers.hip -- the network's layers other than the convolutions (Section 4.1): channel
+// normalisation, max pooling, fully connected layer, softmax loss, gradient step.  All of them
+// are bound by memory traffic; the kernels are plain, coalesced along the innermost index,
+// free of atomics (fixed summation orders) and launched over the whole tensor.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+
+#include "../../include/convnet.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int64_t kMaxCount = ((int64_t)1 << 31) - 1;
+
+inline int blocks_for(int64_t count) { return (int)std::min<int64_t>((count + kThreads - 1) / kThreads, 65536); }
+inline int launch_status() { return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH; }
+
+// ---- normalisation ---------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                            float* __restrict__ scale, int C, int HW, int half,
+                                                            float kappa, float alpha, float beta, int64_t count) {
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
+    const int i = (int)(e % HW);
+    const int c = (int)((e / HW) % C);
+    const int64_t n = e / ((int64_t)HW * C);
+    const float* xn = x + n * C * HW + i;
+    const int lo = max(0, c - half), hi = min(C, c + half + 1);
+    float ss = 0.f;
+    for (int cc = lo; cc < hi; ++cc) {
+      const float v = xn[(int64_t)cc * HW];
+      ss += v * v;
+    }
+    const float s = kappa + alpha * ss;
+    scale[e] = s;
+    y[e] = x[e] * powf(s, -beta);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(const float* __restrict__ x, const float* __restrict__ scale,
+                                                            const float* __restrict__ dy, float* __restrict__ dx, int C,
+                                                            int HW, int half, float alpha, float beta, int64_t count) {
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
+    const int i = (int)(e % HW);
+    const int c = (int)((e / HW) % C);
+    const int64_t n = e / ((int64_t)HW * C);
+    const int64_t base = n * C * HW + i;
+    const int lo = max(0, c - half), hi = min(C, c + half + 1);
+    float t = 0.f;
+    for (int cc = lo; cc < hi; ++cc) {
+      const int64_t j = base + (int64_t)cc * HW;
+      t += dy[j] * x[j] * powf(scale[j], -beta - 1.f);
+    }
+    dx[e] = dy[e] * powf(scale[e], -beta) - 2.f * alpha * beta * x[e] * t;
+  }
+}
+
+// ---- max pooling -----------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void pool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int H,
+                                                            int W, int P, int Q, int win, int stride, int64_t count) {
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
+    const int q = (int)(e % Q);
+    const int p = (int)((e / Q) % P);
+    const int64_t m = e / ((int64_t)P * Q);
+    const float* xm = x + m * H * W + (int64_t)(p * stride) * W + q * stride;
+    float best = xm[0];
+    for (int i = 0; i < win; ++i)
+      for (int j = 0; j < win; ++j) best = fmaxf(best, xm[i * W + j]);
+    y[e] = best;
+  }
+}
+
+// Gather form: every input element looks at the windows that contain it and takes dy from those
+// whose first maximum it is.
+__global__ __launch_bounds__(kThreads) void pool_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                            float* __restrict__ dx, int H, int W, int P, int Q, int win,
+                                                            int stride, int64_t count) {
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
+    const int w = (int)(e % W);
+    const int h = (int)((e / W) % H);
+    const int64_t m = e / ((int64_t)H * W);
+    const float* xm = x + m * H * W;
+    const float mine = xm[h * W + w];
+    // windows p with p*stride <= h < p*stride + win
+    const int p0 = max(0, (h - win + stride) / stride), p1 = min(P - 1, h / stride);
+    const int q0 = max(0, (w - win + stride) / stride), q1 = min(Q - 1, w / stride);
+    float acc = 0.f;
+    for (int p = p0; p <= p1; ++p)
+      for (int q = q0; q <= q1; ++q) {
+        // is (h,w) the first maximum of window (p,q)?
+        bool first = true;
+        for (int i = 0; i < win && first; ++i)
+          for (int j = 0; j < win; ++j) {
+            const int hh = p * stride + i, ww = q * stride + j;
+            const float v = xm[hh * W + ww];
+            const bool before = hh < h || (hh == h && ww < w);
+            if (v > mine || (before && v == mine)) {
+              first = false;
+              break;
+            }
+          }
+        if (first) acc += dy[m * P * Q + (int64_t)p * Q + q];
+      }
+    dx[e] = acc;
+  }
+}
+
+// ---- fully connected -------------------------------------------------------------------
+constexpr int kOB = 8;   // outputs per workgroup / thread block of outputs
+
+// grid (N, ceil(O/kOB)): a workgroup forms kOB dot products of length I for one image.
+__global__ __launch_bounds__(kThreads) void fc_fwd_kernel(const float* __restrict__ x, const float* __restrict__ W,
+                                                          const float* __restrict__ b, float* __restrict__ y, int I,
+                                                          int O) {
+  __shared__ float red[kOB][kThreads];
+  const int n = blockIdx.x, o0 = blockIdx.y * kOB;
+  const float* xn = x + (int64_t)n * I;
+  float acc[kOB];
+#pragma unroll
+  for (int k = 0; k < kOB; ++k) acc[k] = 0.f;
+  for (int i = threadIdx.x; i < I; i += kThreads) {
+    const float v = xn[i];
+#pragma unroll
+    for (int k = 0; k < kOB; ++k)
+      if (o0 + k < O) acc[k] += v * W[(int64_t)(o0 + k) * I + i];
+  }
+#pragma unroll
+  for (int k = 0; k < kOB; ++k) red[k][threadIdx.x] = acc[k];
+  __syncthreads();
+  for (int s = kThreads / 2; s > 0; s >>= 1) {   // fixed tree: the same order on every run
+    if (threadIdx.x < s)
+#pragma unroll
+      for (int k = 0; k < kOB; ++k) red[k][threadIdx.x] += red[k][threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x < kOB && o0 + threadIdx.x < O)
+    y[(int64_t)n * O + o0 + threadIdx.x] = red[threadIdx.x][0] + (b ? b[o0 + threadIdx.x] : 0.f);
+}
+
+__global__ __launch_bounds__(kThreads) void fc_bwd_data_kernel(const float* __restrict__ W, const float* __restrict__ dy,
+                                                               float* __restrict__ dx, int I, int O, int64_t count) {
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
+    const int i = (int)(e % I);
+    const int64_t n = e / I;
+    float acc = 0.f;
+    for (int o = 0; o < O; ++o) acc += dy[n * O + o] * W[(int64_t)o * I + i];
+    dx[e] = acc;
+  }
+}
+
+// grid (ceil(I/kThreads), ceil(O/kOB)): a thread owns input i and kOB outputs, sums over the batch in order.
+__global__ __launch_bounds__(kThreads) void fc_bwd_weight_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                                 float* __restrict__ dW, int N, int I, int O) {
+  const int i = blockIdx.x * kThreads + threadIdx.x, o0 = blockIdx.y * kOB;
+  if (i >= I) return;
+  float acc[kOB];
+#pragma unroll
+  for (int k = 0; k < kOB; ++k) acc[k] = 0.f;
+  for (int n = 0; n < N; ++n) {
+    const float v = x[(int64_t)n * I + i];
+#pragma unroll
+    for (int k = 0; k < kOB; ++k)
+      if (o0 + k < O) acc[k] += dy[(int64_t)n * O + o0 + k] * v;
+  }
+#pragma unroll
+  for (int k = 0; k < kOB; ++k)
+    if (o0 + k < O) dW[(int64_t)(o0 + k) * I + i] = acc[k];
+}
+
+__global__ __launch_bounds__(kThreads) void fc_bwd_bias_kernel(const float* __restrict__ dy, float* __restrict__ db, int N,
+                                                               int O) {
+  const int o = blockIdx.x * kThreads + threadIdx.x;
+  if (o >= O) return;
+  float acc = 0.f;
+  for (int n = 0; n < N; ++n) acc += dy[(int64_t)n * O + o];
+  db[o] = acc;
+}
+
+// ---- softmax loss ----------------------------------------------------------------------
+__device__ __forceinline__ void row_max_and_sum(const float* zr, int O, float& mx, float& sum) {
+  mx = zr[0];
+  for (int o = 1; o < O; ++o) mx = fmaxf(mx, zr[o]);
+  sum = 0.f;
+  for (int o = 0; o < O; ++o) sum += expf(zr[o] - mx);
+}
+
+// One workgroup: per-image losses by its threads, then a fixed tree over the threads' partial sums.
+__global__ __launch_bounds__(kThreads) void softmax_loss_fwd_kernel(const float* __restrict__ z,
+                                                                    const int32_t* __restrict__ labels,
+                                                                    float* __restrict__ loss, int N, int O) {
+  __shared__ float red[kThreads];
+  float acc = 0.f;
+  for (int n = threadIdx.x; n < N; n += kThreads) {
+    const float* zr = z + (int64_t)n * O;
+    float mx, sum;
+    row_max_and_sum(zr, O, mx, sum);
+    acc += logf(sum) + mx - zr[labels[n]];
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = kThreads / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = red[0] / (float)N;
+}
+
+__global__ __launch_bounds__(kThreads) void softmax_loss_bwd_kernel(const float* __restrict__ z,
+                                                                    const int32_t* __restrict__ labels,
+                                                                    float* __restrict__ dz, int N, int O) {
+  const int n = blockIdx.x * kThreads + threadIdx.x;
+  if (n >= N) return;
+  const float* zr = z + (int64_t)n * O;
+  float mx, sum;
+  row_max_and_sum(zr, O, mx, sum);
+  const float inv = 1.f / (float)N;
+  const int lab = labels[n];
+  // softmax - 1 at the label is minus the other classes' share; formed from their sum, it keeps
+  // its relative accuracy when the label's probability is close to one
+  float others = 0.f;
+  for (int o = 0; o < O; ++o)
+    if (o != lab) others += expf(zr[o] - mx);
+  for (int o = 0; o < O; ++o)
+    dz[(int64_t)n * O + o] = (o == lab ? -others / sum : expf(zr[o] - mx) / sum) * inv;
+}
+
+__global__ __launch_bounds__(kThreads) void sgd_kernel(float* __restrict__ w, const float* __restrict__ dw, float lr,
+                                                       int64_t count) {
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads)
+    w[e] -= lr * dw[e];
+}
+
+}  // namespace
+
+extern "C" {
+
+int net_norm_fwd(const float* x, float* y, float* scale, int32_t N, int32_t C, int32_t HW, int32_t size, float kappa,
+                 float alpha, float beta, void* hip_stream) {
+  if (!x || !y || !scale) return CONV_ERR_NULL;
+  if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0) return CONV_ERR_SHAPE;
+  const int64_t count = (int64_t)N * C * HW;
+  if (count > kMaxCount) return CONV_ERR_SHAPE;
+  hipLaunchKernelGGL(norm_fwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, y, scale,
+                     C, HW, size / 2, kappa, alpha, beta, count);
+  return launch_status();
+}
+
+int net_norm_bwd(const float* x, const float* scale, const float* dy, float* dx, int32_t N, int32_t C, int32_t HW,
+                 int32_t size, float kappa, float alpha, float beta, void* hip_stream) {
+  (void)kappa;   // already inside scale
+  if (!x || !scale || !dy || !dx) return CONV_ERR_NULL;
+  if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0) return CONV_ERR_SHAPE;
+  const int64_t count = (int64_t)N * C * HW;
+  if (count > kMaxCount) return CONV_ERR_SHAPE;
+  hipLaunchKernelGGL(norm_bwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, scale, dy,
+                     dx, C, HW, size / 2, alpha, beta, count);
+  return launch_status();
+}
+
+static int pool_dims(int32_t NC, int32_t H, int32_t W, int32_t win, int32_t stride, int& P, int& Q) {
+  if (NC < 1 || H < 1 || W < 1 || win < 1 || stride < 1 || win > H || win > W) return CONV_ERR_SHAPE;
+  P = (H - win) / stride + 1;
+  Q = (W - win) / stride + 1;
+  if ((int64_t)NC * H * W > kMaxCount) return CONV_ERR_SHAPE;
+  return CONV_OK;
+}
+
+int net_pool_fwd(const float* x, float* y, int32_t NC, int32_t H, int32_t W, int32_t win, int32_t stride,
+                 void* hip_stream) {
+  if (!x || !y) return CONV_ERR_NULL;
+  int P, Q;
+  const int rc = pool_dims(NC, H, W, win, stride, P, Q);
+  if (rc != CONV_OK) return rc;
+  const int64_t count = (int64_t)NC * P * Q;
+  hipLaunchKernelGGL(pool_fwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, y, H, W,
+                     P, Q, win, stride, count);
+  return launch_status();
+}
+
+int net_pool_bwd(const float* x, const float* dy, float* dx, int32_t NC, int32_t H, int32_t W, int32_t win,
+                 int32_t stride, void* hip_stream) {
+  if (!x || !dy || !dx) return CONV_ERR_NULL;
+  int P, Q;
+  const int rc = pool_dims(NC, H, W, win, stride, P, Q);
+  if (rc != CONV_OK) return rc;
+  const int64_t count = (int64_t)NC * H * W;
+  hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, dy, dx, H,
+                     W, P, Q, win, stride, count);
+  return launch_status();
+}
+
+int net_fc_fwd(const float* x, const float* W, const float* b, float* y, int32_t N, int32_t I, int32_t O,
+               void* hip_stream) {
+  if (!x || !W || !y) return CONV_ERR_NULL;
+  if (N < 1 || I < 1 || O < 1 || N > 65535 || (int64_t)N * I > kMaxCount || (int64_t)O * I > kMaxCount)
+    return CONV_ERR_SHAPE;
+  hipLaunchKernelGGL(fc_fwd_kernel, dim3(N, (O + kOB - 1) / kOB), dim3(kThreads), 0, (hipStream_t)hip_stream, x, W, b, y,
+                     I, O);
+  return launch_status();
+}
+
+int net_fc_bwd(const float* x, const float* W, const float* dy, float* dx, float* dW, float* db, int32_t N, int32_t I,
+               int32_t O, void* hip_stream) {
+  if (!dy || (dx && !W) || (dW && !x)) return CONV_ERR_NULL;
+  if (N < 1 || I < 1 || O < 1 || (int64_t)N * I > kMaxCount || (int64_t)O * I > kMaxCount) return CONV_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dx) {
+    const int64_t count = (int64_t)N * I;
+    hipLaunchKernelGGL(fc_bwd_data_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, st, W, dy, dx, I, O, count);
+  }
+  if (dW)
+    hipLaunchKernelGGL(fc_bwd_weight_kernel, dim3((I + kThreads - 1) / kThreads, (O + kOB - 1) / kOB), dim3(kThreads), 0,
+                       st, x, dy, dW, N, I, O);
+  if (db) hipLaunchKernelGGL(fc_bwd_bias_kernel, dim3((O + kThreads - 1) / kThreads), dim3(kThreads), 0, st, dy, db, N, O);
+  return launch_status();
+}
+
+int net_softmax_loss_fwd(const float* z, const int32_t* labels, float* loss, int32_t N, int32_t O, void* hip_stream) {
+  if (!z || !labels || !loss) return CONV_ERR_NULL;
+  if (N < 1 || O < 1 || (int64_t)N * O > kMaxCount) return CONV_ERR_SHAPE;
+  hipLaunchKernelGGL(softmax_loss_fwd_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)hip_stream, z, labels, loss, N, O);
+  return launch_status();
+}
+
+int net_softmax_loss_bwd(const float* z, const int32_t* labels, float* dz, int32_t N, int32_t O, void* hip_stream) {
+  if (!z || !labels || !dz) return CONV_ERR_NULL;
+  if (N < 1 || O < 1 || (int64_t)N * O > kMaxCount) return CONV_ERR_SHAPE;
+  hipLaunchKernelGGL(softmax_loss_bwd_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                     (hipStream_t)hip_stream, z, labels, dz, N, O);
+  return launch_status();
+}
+
+int net_sgd_update(float* w, const float* dw, float lr, int64_t count, void* hip_stream) {
+  if (!w || !dw) return CONV_ERR_NULL;
+  if (count < 0) return CONV_ERR_SHAPE;
+  if (count == 0) return CONV_OK;
+  hipLaunchKernelGGL(sgd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, w, dw, lr, count);
+  return launch_status();
+}
+
+}  // extern "C"

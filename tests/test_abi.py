@@ -20,7 +20,7 @@ def declared_functions():
             continue
         text = open(os.path.join(inc, header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(conv_[a-z_]+)\s*\(", text))
+        names |= set(re.findall(r"\b((?:conv|net)_[a-z_]+)\s*\(", text))
     return sorted(names)
 
 
@@ -124,3 +124,18 @@ def test_loading_the_library_brings_in_torch_first():
             "libs = {l.split()[-1] for l in maps.splitlines() if 'libamdhip64' in l}; "
             "assert len(libs) == 1, libs")
     subprocess.check_call([sys.executable, "-c", code], cwd=ROOT)
+
+
+def test_net_layer_calls_reject_bad_arguments():
+    B = FakeBuf(0x30000)
+    assert cs.net_norm_fwd(B, B, B, 2, 4, 9, size=4, stream=0, raw_status=True) == -2        # even window
+    assert cs.net_norm_fwd(None, B, B, 2, 4, 9, stream=0, raw_status=True) == -1
+    assert cs.net_norm_bwd(B, B, B, B, 0, 4, 9, stream=0, raw_status=True) == -2
+    assert cs.net_pool_fwd(B, B, 6, 4, 4, win=5, stride=2, stream=0, raw_status=True) == -2   # window larger than the map
+    assert cs.net_pool_bwd(B, B, None, 6, 4, 4, stream=0, raw_status=True) == -1
+    assert cs.net_fc_fwd(B, B, None, B, 0, 5, 3, stream=0, raw_status=True) == -2
+    assert cs.net_fc_bwd(B, None, B, B, None, None, 2, 5, 3, stream=0, raw_status=True) == -1  # dx wanted but no W
+    assert cs.net_softmax_loss_fwd(B, B, None, 4, 10, stream=0, raw_status=True) == -1
+    assert cs.net_softmax_loss_bwd(B, B, B, 4, 0, stream=0, raw_status=True) == -2
+    assert cs.net_sgd_update(B, B, 0.1, -1, stream=0, raw_status=True) == -2
+    assert cs.net_sgd_update(B, B, 0.1, 0, stream=0, raw_status=True) == 0
