@@ -293,6 +293,41 @@ def scaling_study(cfg_name, dtype_name, max_devices, link_gbytes, comp_fraction,
             "link_GB_per_s": link_gbytes, "rows": rows}
 
 
+def net_study(steps, warmup, batches, sizes):
+    """Training step of the paper's network (Section 4.1) for its four sizes: time in the
+    convolutions against time in the other layers ("Comp. time", Section 4.2)."""
+    import torch
+
+    from paper_1712_02546_amd import net as pnet
+
+    rows = []
+    for k1, k2 in sizes:
+        for batch in batches:
+            net = pnet.PaperNet(batch, k1, k2, seed=1)
+            x = torch.rand((batch, 3, 32, 32), device="cuda:0")
+            labels = torch.randint(0, 10, (batch,), device="cuda:0", dtype=torch.int32)
+            for _ in range(warmup):
+                net.step(x, labels)
+            conv = other = 0.0
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                net.step(x, labels)
+                c, o = net.times_ms()
+                conv += c
+                other += o
+            wall = (time.perf_counter() - t0) * 1e3 / steps
+            conv /= steps
+            other /= steps
+            rows.append({"kernels": f"{k1}:{k2}", "batch": batch, "conv_ms": conv, "other_ms": other,
+                         "other_share": other / (conv + other), "amdahl_bound": (conv + other) / other,
+                         "wall_ms_per_step": wall, "images_per_s": batch / ((conv + other) * 1e-3)})
+            del net, x, labels
+            torch.cuda.empty_cache()
+    return {"what": "training step of the paper's network, convolutions against the other layers", "steps": steps,
+            "warmup": warmup, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -314,6 +349,10 @@ def main():
     ap.add_argument("--link-gbytes", type=float, default=153.0, help="bandwidth of the master's link, GB/s")
     ap.add_argument("--comp-fraction", type=float, default=0.13,
                     help="share of the other layers in the single-device time (the paper measured 13-25 %%)")
+    ap.add_argument("--net", action="store_true",
+                    help="time training steps of the paper's four network sizes: convolutions against the other "
+                         "layers (not the contract line)")
+    ap.add_argument("--net-batches", default="64,128,1024")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
@@ -335,6 +374,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.net:
+        sizes = [(50, 500), (150, 800), (300, 1000), (500, 1500)]
+        print(json.dumps(net_study(args.steps, args.warmup, [int(b) for b in args.net_batches.split(",")], sizes)))
+        return
 
     if args.scaling > 0:
         print(json.dumps(scaling_study(args.config, args.dtype, args.scaling, args.link_gbytes, args.comp_fraction,
