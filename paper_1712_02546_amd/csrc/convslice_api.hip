@@ -280,7 +280,7 @@ bool bf16_mfma_bwd_weight_ok(const Geo& g, int dtype) {
 struct Fwd16Plan {
   int Cp, nch, MB, CT;
   cs::TailPlan tail;
-  size_t off_x, off_w, off_yt, off_tail, total;
+  size_t off_x, off_w, off_yt, off_zero, off_tail, total;
 };
 Fwd16Plan plan_fwd16(const Geo& g) {
   Fwd16Plan p;
@@ -293,6 +293,7 @@ Fwd16Plan plan_fwd16(const Geo& g) {
   p.off_x = o;    o += seg16((int64_t)g.HW * g.Np * p.Cp);
   p.off_w = o;    o += seg16((int64_t)g.Ks * g.RS * p.Cp);
   p.off_yt = o;   o += seg((int64_t)g.Ks * g.PQ * g.Np);
+  p.off_zero = o; o += seg16((int64_t)32 * p.Cp + 64);   // a column block of zeros: 32 images x Cp channels
   p.off_tail = o; o += tail_bytes(p.tail);
   p.total = o;
   return p;
@@ -300,7 +301,7 @@ Fwd16Plan plan_fwd16(const Geo& g) {
 
 struct BwdData16Plan {
   int Ksp;
-  size_t off_dy, off_w, off_dxt, off_perm, off_cls, off_scratch, total;
+  size_t off_dy, off_w, off_dxt, off_perm, off_cls, off_scratch, off_zero, total;
 };
 BwdData16Plan plan_bwd_data16(const Geo& g) {
   BwdData16Plan p;
@@ -312,6 +313,7 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   p.off_perm = o; o += seg(g.HW);
   p.off_cls = o;  o += seg(2 * (g.RS + 1));
   p.off_scratch = o; o += seg((int64_t)g.H + g.W);
+  p.off_zero = o; o += seg16((int64_t)32 * p.Ksp + 64);   // a column block of zeros: 32 images x Ksp kernels
   p.total = o;
   return p;
 }
@@ -485,10 +487,12 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
     // per kernel: w[k] as a C x RS matrix -> w_krsc[k][rs][Cp]
     launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.CRS, g.RS, g.C, g.RS, wp,
                         (int64_t)g.RS * p.Cp, p.Cp, p.Cp, g.Ks, nullptr, st, true);
+    cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
+    hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Cp + 64);
     if ((rc = allow_big_lds(cs::fwd16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
     probe.begin(st);
     hipLaunchKernelGGL(cs::fwd16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg), dim3(cs::NT),
-                       cs::SMEM_BYTES, st, g, wp, p.Cp, xp, yt, p.MB, p.CT, p.nch, p.tail, partial);
+                       cs::SMEM_BYTES, st, g, wp, p.Cp, xp, zero, yt, p.MB, p.CT, p.nch, p.tail, partial);
     if (p.tail.nTail > 0)
       hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
                          p.CT, p.nch, p.tail);
@@ -584,13 +588,15 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
                         (int64_t)g.C * p.Ksp, p.Ksp, g.C, nullptr, st, true);
     hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm,
                        (int*)(base + p.off_cls), (int*)(base + p.off_scratch));
+    cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
+    hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Ksp + 64);
     const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
     if ((rc = allow_big_lds(cs::bwd_data16_gemm_kernel, lds)) != CONV_OK) return rc;
     const int MB = (g.C + cs::BM - 1) / cs::BM;
     const int CT = (g.HW * g.NB + 3) / 4;
     probe.begin(st);
     hipLaunchKernelGGL(cs::bwd_data16_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st, g, wp, p.Ksp,
-                       dyp, perm, dxt, MB, CT);
+                       dyp, zero, perm, dxt, MB, CT);
     probe.end(st);
     launch_transpose_out(CONV_BF16, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
     return check_launch();
@@ -696,12 +702,16 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
                         (float*)(base + p.off_xt - kZeroBytes), st, true);
     launch_transpose_in(CONV_BF16, (const char*)dy + (size_t)g.k0 * g.PQ * 2, 0, (int64_t)g.K * g.PQ, g.N,
                         g.Ks * g.PQ, dyt, 0, p.Np64, p.Np64, 1, nullptr, st, true);
-    if ((rc = allow_big_lds(cs::bwd_weight16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    const bool pad16 = needs_pad_checks(g);
+    if ((rc = allow_big_lds(pad16 ? cs::bwd_weight16_gemm_kernel<true> : cs::bwd_weight16_gemm_kernel<false>,
+                            cs::SMEM_BYTES)) != CONV_OK)
+      return rc;
     const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
     float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
     float* partial = (float*)(base + p.off_tail);
     probe.begin(st);
-    hipLaunchKernelGGL(cs::bwd_weight16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg, p.splits),
+    hipLaunchKernelGGL(pad16 ? cs::bwd_weight16_gemm_kernel<true> : cs::bwd_weight16_gemm_kernel<false>,
+                       dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg, p.splits),
                        dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt, p.Np64, out, sliceElems, p.MB, p.CT, p.nch,
                        p.chPerSplit, p.tail, partial);
     if (p.tail.nTail > 0)

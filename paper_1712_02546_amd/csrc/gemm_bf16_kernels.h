@@ -24,9 +24,8 @@ typedef uint16_t bf16_t;                  // storage type of a bfloat16 element
 constexpr int BK16 = 64;                  // reduction elements per chunk
 constexpr int ZERO_PAGE_BF16 = ZERO_PAGE_FLOATS * 2;   // the zero page counted in bf16 elements
 
-__device__ __forceinline__ void dma16h(const bf16_t* g, float* lds_uniform) {
-  __builtin_amdgcn_global_load_lds(CS_GPTR(g), CS_LPTR(lds_uniform), 16, 0, 0);
-}
+// 16-byte slot of a lane inside a chunk row of the col image, in bf16 elements (load i, lane l).
+__device__ __forceinline__ int slot8(int l, int i) { return 8 * ((l & 7) ^ col_key(8 * i + (l >> 3))); }
 
 struct Frag16 {
   f32x4 v[2];   // one MFMA operand (8 bf16) for each of the wavefront's two 32-wide blocks
@@ -34,7 +33,7 @@ struct Frag16 {
 
 // Operands of MFMA step j (0..3) of a chunk from a col image: logical slot 2*j + lane/32.
 __device__ __forceinline__ void read_frag16(Frag16& f, const float* tile, int wbase, int lane, int j) {
-  const int u = lane & 7, h = lane >> 5;
+  const int u = col_key(lane & 31), h = lane >> 5;
   const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
   f.v[0] = *(const f32x4*)(tile + slot * 4);
   f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
@@ -49,7 +48,7 @@ __device__ __forceinline__ void mfma16_group(const Frag16& a, const Frag16& b, f
   acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
 }
 
-// Main loop: same driving protocol as the fp32 loops (begin / addr(0..3) / end, dummy
+// Main loop: same driving protocol as the fp32 loops (begin / issue(0..3) / end, dummy
 // loads past the last chunk), one barrier per chunk, all four operand reads of a chunk
 // issued up front, DMA loads of the next chunk issued right after the barrier.
 template <class LA, class LB>
@@ -65,8 +64,8 @@ __device__ __forceinline__ void gemm16_mainloop(LA& la, LB& lb, int ch_begin, in
     lb.begin(ch, live);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      dma16h(la.addr(i), ta + (wv * 4 + i) * 256);
-      dma16h(lb.addr(i), tb + (wv * 4 + i) * 256);
+      la.issue(i, ta + (wv * 4 + i) * 256);
+      lb.issue(i, tb + (wv * 4 + i) * 256);
     }
     la.end();
     lb.end();
@@ -92,47 +91,52 @@ __device__ __forceinline__ void gemm16_mainloop(LA& la, LB& lb, int ch_begin, in
 }
 
 // ------------------------------------------------------------------ forward ----
-// A[m][kk] = w_krsc[m0+m][kk]: dense rows of R*S*Cp elements.
+// A[m][kk] = w_krsc[m0+m][kk]: dense rows of R*S*Cp elements.  As in the fp32 kernels every
+// load is "wave-uniform base + fixed per-lane byte offset", so the loop spends no vector
+// instructions on addresses.
 struct Fwd16LoadA {
-  const bf16_t* p[4];
-  int64_t adv;
-  __device__ Fwd16LoadA(const bf16_t* w, int64_t ldw, int m0, int Ks) {
+  const char* tile;   // uniform: row m0
+  const char* ub;
+  unsigned off[4];
+  __device__ Fwd16LoadA(const bf16_t* w, int64_t ldw, int m0, int Ks) : tile((const char*)(w + (int64_t)m0 * ldw)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int m = min(m0 + 32 * wv + 8 * i + (l >> 3), Ks - 1);  // rows past the slice repeat the last one
-      p[i] = w + (int64_t)m * ldw + kq8;
+      const int m = min(32 * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
+      off[i] = (unsigned)(m * ldw + slot8(l, i)) * 2u;
     }
   }
-  __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK16; }
-  __device__ __forceinline__ const bf16_t* addr(int i) const { return p[i] + adv; }
+  __device__ __forceinline__ void begin(int ch, bool live) { ub = tile + (int64_t)(live ? ch : 0) * (BK16 * 2); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {}
 };
 
 // B^T[(block,n)][kk] = x_hwnc[h0+r][w0+s][n][c]: chunk = (r, s, 64 channels); the pixel of
-// a column block is uniform per wavefront (wavefront wv stages block wv of the tile).
+// a column block is uniform per wavefront (wavefront wv stages block wv of the tile), so a
+// tap that falls into the padding switches the uniform base to a block of zeros.
 struct Fwd16LoadB {
-  const bf16_t* x;      // a zero page sits ZERO_PAGE_BF16 in front of it
-  int lane_off[4];
-  int h0, w0, H, W, S, R, NpCp, ncc;
+  const char* x;        // uniform: x_hwnc at the block's images
+  const char* zero;     // uniform: 32 rows of Cp zeros
+  const char* ub;
+  unsigned off[4];
+  int h0, w0, H, W, S, R, ncc;
+  int64_t pixBytes;     // one pixel: Np * Cp elements
   int r, s, cc;         // uniform walk over the next chunk to issue
-  int uoff;
-  bool ok;
-  __device__ Fwd16LoadB(const Geo& g, const bf16_t* x_, int Cp, int ct, int ch0) : x(x_) {
+  __device__ Fwd16LoadB(const Geo& g, const bf16_t* x_, const bf16_t* zero_, int Cp, int ct, int ch0)
+      : zero((const char*)zero_) {
     const int l = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
     const int gcb = ct * 4 + wv < g.PQ * g.NB ? ct * 4 + wv : 0;   // blocks past the end: computed, never stored
     const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
     const int p = pix / g.Q, q = pix - p * g.Q;
     h0 = p * g.sh - g.ph;
     w0 = q * g.sw - g.pw;
     H = g.H; W = g.W; S = g.S; R = g.R;
-    NpCp = g.Np * Cp;
+    pixBytes = (int64_t)g.Np * Cp * 2;
+    x = (const char*)(x_ + (int64_t)nb * 32 * Cp);
     ncc = Cp / BK16;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) lane_off[i] = (nb * 32 + 8 * i + (l >> 3)) * Cp + kq8;
+    for (int i = 0; i < 4; ++i) off[i] = (unsigned)((8 * i + (l >> 3)) * Cp + slot8(l, i)) * 2u;
     const int tap = ch0 / ncc;
     cc = ch0 - tap * ncc;
     r = tap / S;
@@ -140,10 +144,10 @@ struct Fwd16LoadB {
   }
   __device__ __forceinline__ void begin(int, bool live) {
     const int hh = h0 + r, vv = w0 + s;
-    ok = live & ((unsigned)hh < (unsigned)H) & ((unsigned)vv < (unsigned)W);
-    uoff = (hh * W + vv) * NpCp + cc * BK16;
+    const bool ok = live & ((unsigned)hh < (unsigned)H) & ((unsigned)vv < (unsigned)W);
+    ub = ok ? x + (hh * W + vv) * pixBytes + cc * (BK16 * 2) : zero;
   }
-  __device__ __forceinline__ const bf16_t* addr(int i) const { return x + (ok ? uoff + lane_off[i] : -ZERO_PAGE_BF16); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {   // branch-free carry over (cc, s, r)
     ++cc;
     const int c1 = cc == ncc;
@@ -156,7 +160,8 @@ struct Fwd16LoadB {
 };
 
 __global__ __launch_bounds__(NT) void fwd16_gemm_kernel(Geo g, const bf16_t* __restrict__ w, int Cp,
-                                                        const bf16_t* __restrict__ x, float* __restrict__ yt,
+                                                        const bf16_t* __restrict__ x,
+                                                        const bf16_t* __restrict__ zero, float* __restrict__ yt,
                                                         int MB, int CT, int nch, TailPlan tp,
                                                         float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(NT) void fwd16_gemm_kernel(Geo g, const bf16_t* __r
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     Fwd16LoadA la(w, (int64_t)g.RS * Cp, mb * BM, g.Ks);
-    Fwd16LoadB lb(g, x, Cp, ct, cb);
+    Fwd16LoadB lb(g, x, zero, Cp, ct, cb);
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) fwd_store_tile(g, yt, mb, ct, acc);
     else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
@@ -181,25 +186,30 @@ __global__ __launch_bounds__(NT) void fwd16_gemm_kernel(Geo g, const bf16_t* __r
 // ----------------------------------------------------------- input gradient ----
 // A[c][kk] = w_rsck[tap][c][k]: chunk = (tap, 64 kernels).
 struct BwdData16LoadA {
-  const bf16_t* wt;
+  const char* wt;     // uniform: channel m0 of tap 0
+  const char* ub;
   const int* taps;
-  int S, CKsp, tap, lane_off[4];
-  int uoff;
+  unsigned off[4];
+  unsigned tapBytes;
+  int S, tap;         // tap of walk.ti, fetched one call ahead (uniform, held in a vector register)
   TapWalk walk;
   __device__ BwdData16LoadA(const Geo& g, const bf16_t* wt_, int Ksp, int m0, const int* taps_, int nkc_)
-      : wt(wt_), taps(taps_), S(g.S), CKsp(g.C * Ksp), walk(nkc_, 0) {
+      : wt((const char*)(wt_ + (int64_t)m0 * Ksp)), taps(taps_), tapBytes((unsigned)g.C * (unsigned)Ksp * 2u), S(g.S),
+        walk(nkc_, 0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int c = min(m0 + 32 * wv + 8 * i + (l >> 3), g.C - 1);   // rows past C repeat the last one
-      lane_off[i] = c * Ksp + kq8;
+      const int c = min(32 * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // rows past C repeat the last one
+      off[i] = (unsigned)(c * Ksp + slot8(l, i)) * 2u;
     }
     const int e = taps[0];
     tap = (e >> 16) * S + (e & 0xffff);
   }
-  __device__ __forceinline__ void begin(int, bool live) { uoff = live ? tap * CKsp + walk.kc * BK16 : 0; }
-  __device__ __forceinline__ const bf16_t* addr(int i) const { return wt + (uoff + lane_off[i]); }
+  __device__ __forceinline__ void begin(int, bool live) {
+    const unsigned t = (unsigned)__builtin_amdgcn_readfirstlane(tap);
+    ub = wt + (live ? t * tapBytes + (unsigned)walk.kc * (BK16 * 2u) : 0u);
+  }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {
     walk.next();
     const int e = taps[walk.ti];
@@ -208,28 +218,29 @@ struct BwdData16LoadA {
 };
 
 // B^T[(block,n)][kk] = dy_pqnk[p][q][n][k] with (p,q) the output pixel the current tap maps
-// the block's input pixel to (from the per-tile LDS table), zero if there is none.
+// the block's input pixel to (from the per-tile LDS table; uniform per wavefront), or a block
+// of zeros if there is none.
 struct BwdData16LoadB {
-  const bf16_t* dy;     // a zero page sits ZERO_PAGE_BF16 in front of it
+  const char* dy;     // uniform
+  const char* zero;   // uniform: 32 rows of Ksp zeros
+  const char* ub;
   const int* tapoff;
-  int lane_off[4], toff, wvb;
-  int uoff;
-  bool ok;
+  unsigned off[4];
+  int toff, wvb;      // toff: element offset of the block's 32 images at the tap's output pixel, or -1
   TapWalk walk;
-  __device__ BwdData16LoadB(const bf16_t* dy_, int Ksp, const int* tapoff_, int nkc_)
-      : dy(dy_), tapoff(tapoff_), walk(nkc_, 0) {
+  __device__ BwdData16LoadB(const bf16_t* dy_, const bf16_t* zero_, int Ksp, const int* tapoff_, int nkc_)
+      : dy((const char*)dy_), zero((const char*)zero_), tapoff(tapoff_), walk(nkc_, 0) {
     const int l = threadIdx.x & 63;
     wvb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) lane_off[i] = (8 * i + (l >> 3)) * Ksp + kq8;
+    for (int i = 0; i < 4; ++i) off[i] = (unsigned)((8 * i + (l >> 3)) * Ksp + slot8(l, i)) * 2u;
     toff = tapoff[wvb];
   }
   __device__ __forceinline__ void begin(int, bool live) {
-    ok = live & (toff >= 0);
-    uoff = toff + walk.kc * BK16;
+    const int t = __builtin_amdgcn_readfirstlane(toff);
+    ub = (live & (t >= 0)) ? dy + ((unsigned)t * 2u + (unsigned)walk.kc * (BK16 * 2u)) : zero;
   }
-  __device__ __forceinline__ const bf16_t* addr(int i) const { return dy + (ok ? uoff + lane_off[i] : -ZERO_PAGE_BF16); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {
     walk.next();
     toff = tapoff[walk.ti * 4 + wvb];
@@ -238,6 +249,7 @@ struct BwdData16LoadB {
 
 __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t* __restrict__ wt, int Ksp,
                                                              const bf16_t* __restrict__ dy,
+                                                             const bf16_t* __restrict__ zero,
                                                              const int* __restrict__ perm,
                                                              float* __restrict__ dxt, int MB, int CT) {
   extern __shared__ __align__(16) float smem[];
@@ -299,7 +311,7 @@ __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   BwdData16LoadA la(g, wt, Ksp, mb * BM, s_taps, nkc);
-  BwdData16LoadB lb(dy, Ksp, s_tapoff, nkc);
+  BwdData16LoadB lb(dy, zero, Ksp, s_tapoff, nkc);
   gemm16_mainloop(la, lb, 0, ntaps * nkc, smem, acc);
 
   const int wm = wave >> 1, wn = wave & 1;
@@ -323,33 +335,38 @@ __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t
 // ---------------------------------------------------------- weight gradient ----
 // A[k][kk] = dy_t[k][pix][n]: dense rows of P*Q*Np64 elements; chunk = 64 images of one pixel.
 struct BwdWeight16LoadA {
-  const bf16_t* p[4];
-  int64_t adv;
-  __device__ BwdWeight16LoadA(const bf16_t* dyt, int64_t ld, int m0, int Ks) {
+  const char* tile;
+  const char* ub;
+  unsigned off[4];
+  __device__ BwdWeight16LoadA(const bf16_t* dyt, int64_t ld, int m0, int Ks) : tile((const char*)(dyt + (int64_t)m0 * ld)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int m = min(m0 + 32 * wv + 8 * i + (l >> 3), Ks - 1);
-      p[i] = dyt + (int64_t)m * ld + kq8;
+      const int m = min(32 * wv + 8 * i + (l >> 3), Ks - 1 - m0);
+      off[i] = (unsigned)(m * ld + slot8(l, i)) * 2u;
     }
   }
-  __device__ __forceinline__ void begin(int ch, bool live) { adv = (int64_t)(live ? ch : 0) * BK16; }
-  __device__ __forceinline__ const bf16_t* addr(int i) const { return p[i] + adv; }
+  __device__ __forceinline__ void begin(int ch, bool live) { ub = tile + (int64_t)(live ? ch : 0) * (BK16 * 2); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {}
 };
 
-// B^T[(c,r,s)][kk] = x_t[c][p*sh-ph+r][q*sw-pw+s][n]; zero where the tap is in the padding.
+// B^T[(c,r,s)][kk] = x_t[c][p*sh-ph+r][q*sw-pw+s][n]; zero where the tap is in the padding
+// (PAD: the base is the zero page in front of x_t and a lane whose tap is outside reads it).
+template <bool PAD>
 struct BwdWeight16LoadB {
-  const bf16_t* xt;     // a zero page sits ZERO_PAGE_BF16 in front of it
-  int coff[4], rj[4], sj[4];
+  const char* xt;       // uniform; PAD: the zero page ZERO_PAGE_BF16 elements in front of x_t
+  const char* ub;
+  unsigned coff[4];
+  int rj[4], sj[4];
   int NB64, Q, sh, sw, ph, pw, H, W, Np64;
   int p, q, nb;
-  int h0, v0, uoff;
-  __device__ BwdWeight16LoadB(const Geo& g, const bf16_t* xt_, int Np64_, int j0, int ch0) : xt(xt_) {
+  int h0, v0;
+  unsigned uoff;
+  __device__ BwdWeight16LoadB(const Geo& g, const bf16_t* xt_, int Np64_, int j0, int ch0)
+      : xt(PAD ? opaque_uniform(xt_ - ZERO_PAGE_BF16) : (const char*)xt_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     Np64 = Np64_; NB64 = Np64_ / BK16; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W;
-    const int kq8 = 8 * ((l & 7) ^ (l >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = j0 + 32 * wv + 8 * i + (l >> 3);
@@ -357,7 +374,7 @@ struct BwdWeight16LoadB {
       const int c = jj / g.RS, rs = jj - c * g.RS;
       rj[i] = rs / g.S;
       sj[i] = rs - rj[i] * g.S;
-      coff[i] = c * g.HW * Np64 + (rj[i] * g.W + sj[i]) * Np64 + kq8;
+      coff[i] = (unsigned)(c * g.HW * Np64 + (rj[i] * g.W + sj[i]) * Np64 + slot8(l, i) + (PAD ? ZERO_PAGE_BF16 : 0)) * 2u;
     }
     const int pix = ch0 / NB64;
     nb = ch0 - pix * NB64;
@@ -367,11 +384,18 @@ struct BwdWeight16LoadB {
   __device__ __forceinline__ void begin(int, bool live) {
     h0 = live ? p * sh - ph : 0;
     v0 = live ? q * sw - pw : 0;
-    uoff = (h0 * W + v0) * Np64 + (live ? nb * BK16 : 0);
+    const int u = (h0 * W + v0) * Np64 + (live ? nb * BK16 : 0);
+    if (PAD) uoff = (unsigned)u * 2u;
+    else ub = xt + (int64_t)u * 2;
   }
-  __device__ __forceinline__ const bf16_t* addr(int i) const {
-    const bool ok = ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
-    return xt + (ok ? coff[i] + uoff : -ZERO_PAGE_BF16);
+  __device__ __forceinline__ void issue(int i, float* dst) {
+    if (PAD) {
+      const bool ok = ((unsigned)(h0 + rj[i]) < (unsigned)H) & ((unsigned)(v0 + sj[i]) < (unsigned)W);
+      unsigned o = ok ? coff[i] + uoff : 0u;
+      dma16_uv(xt, o, dst);
+    } else {
+      dma16_uv(ub, coff[i], dst);
+    }
   }
   __device__ __forceinline__ void end() {
     ++nb;
@@ -384,6 +408,7 @@ struct BwdWeight16LoadB {
   }
 };
 
+template <bool PAD>
 __global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16_t* __restrict__ dyt,
                                                                const bf16_t* __restrict__ xt, int Np64,
                                                                float* __restrict__ out, int64_t splitStride,
@@ -409,7 +434,7 @@ __global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     BwdWeight16LoadA la(dyt, (int64_t)g.PQ * Np64, mb * BM, g.Ks);
-    BwdWeight16LoadB lb(g, xt, Np64, ct * BN, cb);
+    BwdWeight16LoadB<PAD> lb(g, xt, Np64, ct * BN, cb);
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
     else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
