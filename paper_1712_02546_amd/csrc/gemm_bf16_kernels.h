@@ -48,9 +48,11 @@ __device__ __forceinline__ void mfma16_group(const Frag16& a, const Frag16& b, f
   acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
 }
 
-// Main loop: same driving protocol as the fp32 loops (begin / issue(0..3) / end, dummy
-// loads past the last chunk), one barrier per chunk, all four operand reads of a chunk
-// issued up front, DMA loads of the next chunk issued right after the barrier.
+// Main loop: same driving protocol as the fp32 loop (begin / issue(0..3) / end, dummy loads
+// past the last chunk) and the same rotation across the one barrier per chunk: after the
+// barrier that publishes chunk ch a wavefront issues the DMA loads of chunk ch+1, runs steps
+// 2,3 of chunk ch-1 from registers while the operand reads of steps 0,1 of chunk ch are in
+// flight, then steps 0,1 of chunk ch while steps 2,3 are being read.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm16_mainloop(LA& la, LB& lb, int ch_begin, int ch_end, float* smem,
                                                 f32x16 (&acc)[2][2]) {
@@ -70,24 +72,55 @@ __device__ __forceinline__ void gemm16_mainloop(LA& la, LB& lb, int ch_begin, in
     la.end();
     lb.end();
   };
+  Frag16 a0, b0, a1, b1;
   issue(ch_begin, smem, smem + 2 * TILE_F, true);
   __syncthreads();
-  int cur = 0;
-  for (int ch = ch_begin; ch < ch_end; ++ch) {
+  read_frag16(a0, smem, wa, lane, 0);
+  read_frag16(b0, smem + 2 * TILE_F, wb, lane, 0);
+  read_frag16(a1, smem, wa, lane, 1);
+  read_frag16(b1, smem + 2 * TILE_F, wb, lane, 1);
+  issue(ch_begin + 1, smem + TILE_F, smem + 3 * TILE_F, ch_begin + 1 < ch_end);
+  CS_FENCE();
+  mfma16_group(a0, b0, acc);
+  CS_FENCE();
+  read_frag16(a0, smem, wa, lane, 2);
+  read_frag16(b0, smem + 2 * TILE_F, wb, lane, 2);
+  CS_FENCE();
+  mfma16_group(a1, b1, acc);
+  CS_FENCE();
+  read_frag16(a1, smem, wa, lane, 3);
+  read_frag16(b1, smem + 2 * TILE_F, wb, lane, 3);
+  __syncthreads();
+  int cur = TILE_F;
+  for (int ch = ch_begin + 1; ch < ch_end; ++ch) {
     const float* As = smem + cur;
     const float* Bs = smem + 2 * TILE_F + cur;
     issue(ch + 1, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F), ch + 1 < ch_end);
-    Frag16 a[4], b[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      read_frag16(a[j], As, wa, lane, j);
-      read_frag16(b[j], Bs, wb, lane, j);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) mfma16_group(a[j], b[j], acc);
+    CS_FENCE();
+    mfma16_group(a0, b0, acc);  // step 2 of chunk ch-1
+    CS_FENCE();
+    read_frag16(a0, As, wa, lane, 0);
+    read_frag16(b0, Bs, wb, lane, 0);
+    CS_FENCE();
+    mfma16_group(a1, b1, acc);  // step 3 of chunk ch-1
+    CS_FENCE();
+    read_frag16(a1, As, wa, lane, 1);
+    read_frag16(b1, Bs, wb, lane, 1);
+    CS_FENCE();
+    mfma16_group(a0, b0, acc);  // step 0 of chunk ch
+    CS_FENCE();
+    read_frag16(a0, As, wa, lane, 2);
+    read_frag16(b0, Bs, wb, lane, 2);
+    CS_FENCE();
+    mfma16_group(a1, b1, acc);  // step 1 of chunk ch
+    CS_FENCE();
+    read_frag16(a1, As, wa, lane, 3);
+    read_frag16(b1, Bs, wb, lane, 3);
     __syncthreads();
     cur ^= TILE_F;
   }
+  mfma16_group(a0, b0, acc);  // steps 2, 3 of the last chunk
+  mfma16_group(a1, b1, acc);
 }
 
 // ------------------------------------------------------------------ forward ----
