@@ -27,13 +27,13 @@ extern "C" {
  * Local response normalisation across channels (maps [N][C][HW]):
  *   scale[n,c,i] = kappa + alpha * sum_{c' in W(c)} x[n,c',i]^2,   y = x * scale^(-beta),
  * W(c) = the `size` channels centred on c (size odd), clipped at 0 and C.  scale is written for
- * the backward pass (same shape as x).  Backward:
+ * the backward pass (same shape as x), which also takes y.  N at most 65535.  Backward:
  *   dx[c] = dy[c]*scale[c]^(-beta) - 2*alpha*beta*x[c] * sum_{c' in W(c)} dy[c']*x[c']*scale[c']^(-beta-1).
  */
 int net_norm_fwd(const float *x, float *y, float *scale, int32_t N, int32_t C, int32_t HW, int32_t size,
                  float kappa, float alpha, float beta, void *hip_stream);
-int net_norm_bwd(const float *x, const float *scale, const float *dy, float *dx, int32_t N, int32_t C,
-                 int32_t HW, int32_t size, float kappa, float alpha, float beta, void *hip_stream);
+int net_norm_bwd(const float *x, const float *y, const float *scale, const float *dy, float *dx, int32_t N,
+                 int32_t C, int32_t HW, int32_t size, float kappa, float alpha, float beta, void *hip_stream);
 
 /*
  * Max pooling of NC maps of H x W over win x win windows with the given stride, no padding:

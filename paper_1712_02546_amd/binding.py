@@ -119,7 +119,7 @@ def load() -> ctypes.CDLL:
         lib.conv_scaling_estimate.restype = ctypes.c_int
         i32, f32 = ctypes.c_int32, ctypes.c_float
         lib.net_norm_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
-        lib.net_norm_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.net_norm_bwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
         lib.net_pool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
         lib.net_pool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
         lib.net_fc_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
@@ -349,10 +349,10 @@ def net_norm_fwd(x, y, scale, N, C, HW, size=5, kappa=1.0, alpha=1e-4, beta=0.75
                 _stream(stream))
 
 
-def net_norm_bwd(x, scale, dy, dx, N, C, HW, size=5, kappa=1.0, alpha=1e-4, beta=0.75, stream=None,
+def net_norm_bwd(x, y, scale, dy, dx, N, C, HW, size=5, kappa=1.0, alpha=1e-4, beta=0.75, stream=None,
                  raw_status=False):
-    return _net("net_norm_bwd", raw_status, _ptr(x), _ptr(scale), _ptr(dy), _ptr(dx), N, C, HW, size, kappa, alpha,
-                beta, _stream(stream))
+    return _net("net_norm_bwd", raw_status, _ptr(x), _ptr(y), _ptr(scale), _ptr(dy), _ptr(dx), N, C, HW, size, kappa,
+                alpha, beta, _stream(stream))
 
 
 def net_pool_fwd(x, y, NC, H, W, win=2, stride=2, stream=None, raw_status=False):

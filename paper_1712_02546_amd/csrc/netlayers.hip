@@ -18,56 +18,62 @@ inline int blocks_for(int64_t count) { return (int)std::min<int64_t>((count + kT
 inline int launch_status() { return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ERR_LAUNCH; }
 
 // ---- normalisation ---------------------------------------------------------------------
+// s^p for s > 0 through the hardware's base-2 logarithm and exponential (relative error about
+// 1e-6 for the exponents and scales that occur here, far inside the layer's tolerance).
+__device__ __forceinline__ float pow_pos(float s, float p) { return __builtin_amdgcn_exp2f(p * __builtin_amdgcn_logf(s)); }
+
+// grid = (ceil(C*HW/kThreads), N): one 32-bit division per thread.
 __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                             float* __restrict__ scale, int C, int HW, int half,
-                                                            float kappa, float alpha, float beta, int64_t count) {
-  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
-    const int i = (int)(e % HW);
-    const int c = (int)((e / HW) % C);
-    const int64_t n = e / ((int64_t)HW * C);
-    const float* xn = x + n * C * HW + i;
-    const int lo = max(0, c - half), hi = min(C, c + half + 1);
-    float ss = 0.f;
-    for (int cc = lo; cc < hi; ++cc) {
-      const float v = xn[(int64_t)cc * HW];
-      ss += v * v;
-    }
-    const float s = kappa + alpha * ss;
-    scale[e] = s;
-    y[e] = x[e] * powf(s, -beta);
+                                                            float kappa, float alpha, float beta) {
+  const unsigned ci = blockIdx.x * kThreads + threadIdx.x;
+  if (ci >= (unsigned)(C * HW)) return;
+  const int c = (int)(ci / (unsigned)HW), i = (int)(ci - (unsigned)c * (unsigned)HW);
+  const float* xn = x + (int64_t)blockIdx.y * C * HW + i;
+  const int lo = max(0, c - half), hi = min(C, c + half + 1);
+  float ss = 0.f;
+  for (int cc = lo; cc < hi; ++cc) {
+    const float v = xn[(int64_t)cc * HW];
+    ss += v * v;
   }
+  const float s = kappa + alpha * ss;
+  const int64_t e = (int64_t)blockIdx.y * C * HW + ci;
+  scale[e] = s;
+  y[e] = x[e] * pow_pos(s, -beta);
 }
 
-__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(const float* __restrict__ x, const float* __restrict__ scale,
-                                                            const float* __restrict__ dy, float* __restrict__ dx, int C,
-                                                            int HW, int half, float alpha, float beta, int64_t count) {
-  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
-    const int i = (int)(e % HW);
-    const int c = (int)((e / HW) % C);
-    const int64_t n = e / ((int64_t)HW * C);
-    const int64_t base = n * C * HW + i;
-    const int lo = max(0, c - half), hi = min(C, c + half + 1);
-    float t = 0.f;
-    for (int cc = lo; cc < hi; ++cc) {
-      const int64_t j = base + (int64_t)cc * HW;
-      t += dy[j] * x[j] * powf(scale[j], -beta - 1.f);
-    }
-    dx[e] = dy[e] * powf(scale[e], -beta) - 2.f * alpha * beta * x[e] * t;
+// dy[c']*x[c']*scale[c']^(-beta-1) = dy[c']*y[c']/scale[c'], so the window sum needs no power function.
+__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(const float* __restrict__ x, const float* __restrict__ y,
+                                                            const float* __restrict__ scale, const float* __restrict__ dy,
+                                                            float* __restrict__ dx, int C, int HW, int half, float alpha,
+                                                            float beta) {
+  const unsigned ci = blockIdx.x * kThreads + threadIdx.x;
+  if (ci >= (unsigned)(C * HW)) return;
+  const int c = (int)(ci / (unsigned)HW), i = (int)(ci - (unsigned)c * (unsigned)HW);
+  const int64_t base = (int64_t)blockIdx.y * C * HW + i;
+  const int lo = max(0, c - half), hi = min(C, c + half + 1);
+  float t = 0.f;
+  for (int cc = lo; cc < hi; ++cc) {
+    const int64_t j = base + (int64_t)cc * HW;
+    t += dy[j] * y[j] / scale[j];
   }
+  const int64_t e = base + (int64_t)c * HW;
+  dx[e] = dy[e] * pow_pos(scale[e], -beta) - 2.f * alpha * beta * x[e] * t;
 }
 
 // ---- max pooling -----------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int H,
                                                             int W, int P, int Q, int win, int stride, int64_t count) {
-  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
-    const int q = (int)(e % Q);
-    const int p = (int)((e / Q) % P);
-    const int64_t m = e / ((int64_t)P * Q);
-    const float* xm = x + m * H * W + (int64_t)(p * stride) * W + q * stride;
+  // counts are below 2^31: unsigned 32-bit divisions
+  for (int64_t e64 = (int64_t)blockIdx.x * kThreads + threadIdx.x; e64 < count; e64 += (int64_t)gridDim.x * kThreads) {
+    const unsigned e = (unsigned)e64;
+    const unsigned m = e / (unsigned)(P * Q), pq = e - m * (unsigned)(P * Q);
+    const int p = (int)(pq / (unsigned)Q), q = (int)(pq - (unsigned)p * (unsigned)Q);
+    const float* xm = x + (int64_t)m * H * W + (int64_t)(p * stride) * W + q * stride;
     float best = xm[0];
     for (int i = 0; i < win; ++i)
       for (int j = 0; j < win; ++j) best = fmaxf(best, xm[i * W + j]);
-    y[e] = best;
+    y[e64] = best;
   }
 }
 
@@ -76,10 +82,11 @@ __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(const float* __restr
 __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy,
                                                             float* __restrict__ dx, int H, int W, int P, int Q, int win,
                                                             int stride, int64_t count) {
-  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < count; e += (int64_t)gridDim.x * kThreads) {
-    const int w = (int)(e % W);
-    const int h = (int)((e / W) % H);
-    const int64_t m = e / ((int64_t)H * W);
+  for (int64_t e64 = (int64_t)blockIdx.x * kThreads + threadIdx.x; e64 < count; e64 += (int64_t)gridDim.x * kThreads) {
+    const unsigned e = (unsigned)e64;
+    const unsigned mm = e / (unsigned)(H * W), hw = e - mm * (unsigned)(H * W);
+    const int h = (int)(hw / (unsigned)W), w = (int)(hw - (unsigned)h * (unsigned)W);
+    const int64_t m = mm;
     const float* xm = x + m * H * W;
     const float mine = xm[h * W + w];
     // windows p with p*stride <= h < p*stride + win
@@ -102,7 +109,7 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(const float* __restr
           }
         if (first) acc += dy[m * P * Q + (int64_t)p * Q + q];
       }
-    dx[e] = acc;
+    dx[e64] = acc;
   }
 }
 
@@ -110,16 +117,18 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(const float* __restr
 constexpr int kOB = 8;   // outputs per workgroup / thread block of outputs
 
 // grid (N, ceil(O/kOB)): a workgroup forms kOB dot products of length I for one image.
-__global__ __launch_bounds__(kThreads) void fc_fwd_kernel(const float* __restrict__ x, const float* __restrict__ W,
-                                                          const float* __restrict__ b, float* __restrict__ y, int I,
-                                                          int O) {
-  __shared__ float red[kOB][kThreads];
+constexpr int kFcThreads = 1024;   // many loads in flight per compute unit: the dot products are latency bound
+__global__ __launch_bounds__(kFcThreads) void fc_fwd_kernel(const float* __restrict__ x, const float* __restrict__ W,
+                                                            const float* __restrict__ b, float* __restrict__ y, int I,
+                                                            int O) {
+  __shared__ float red[kOB][kFcThreads];
   const int n = blockIdx.x, o0 = blockIdx.y * kOB;
   const float* xn = x + (int64_t)n * I;
   float acc[kOB];
 #pragma unroll
   for (int k = 0; k < kOB; ++k) acc[k] = 0.f;
-  for (int i = threadIdx.x; i < I; i += kThreads) {
+#pragma unroll 2
+  for (int i = threadIdx.x; i < I; i += kFcThreads) {
     const float v = xn[i];
 #pragma unroll
     for (int k = 0; k < kOB; ++k)
@@ -128,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void fc_fwd_kernel(const float* __restric
 #pragma unroll
   for (int k = 0; k < kOB; ++k) red[k][threadIdx.x] = acc[k];
   __syncthreads();
-  for (int s = kThreads / 2; s > 0; s >>= 1) {   // fixed tree: the same order on every run
+  for (int s = kFcThreads / 2; s > 0; s >>= 1) {   // fixed tree: the same order on every run
     if (threadIdx.x < s)
 #pragma unroll
       for (int k = 0; k < kOB; ++k) red[k][threadIdx.x] += red[k][threadIdx.x + s];
@@ -238,23 +247,23 @@ extern "C" {
 int net_norm_fwd(const float* x, float* y, float* scale, int32_t N, int32_t C, int32_t HW, int32_t size, float kappa,
                  float alpha, float beta, void* hip_stream) {
   if (!x || !y || !scale) return CONV_ERR_NULL;
-  if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0) return CONV_ERR_SHAPE;
+  if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0 || N > 65535) return CONV_ERR_SHAPE;
   const int64_t count = (int64_t)N * C * HW;
   if (count > kMaxCount) return CONV_ERR_SHAPE;
-  hipLaunchKernelGGL(norm_fwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, y, scale,
-                     C, HW, size / 2, kappa, alpha, beta, count);
+  hipLaunchKernelGGL(norm_fwd_kernel, dim3((unsigned)(((int64_t)C * HW + kThreads - 1) / kThreads), N), dim3(kThreads), 0,
+                     (hipStream_t)hip_stream, x, y, scale, C, HW, size / 2, kappa, alpha, beta);
   return launch_status();
 }
 
-int net_norm_bwd(const float* x, const float* scale, const float* dy, float* dx, int32_t N, int32_t C, int32_t HW,
-                 int32_t size, float kappa, float alpha, float beta, void* hip_stream) {
+int net_norm_bwd(const float* x, const float* y, const float* scale, const float* dy, float* dx, int32_t N, int32_t C,
+                 int32_t HW, int32_t size, float kappa, float alpha, float beta, void* hip_stream) {
   (void)kappa;   // already inside scale
-  if (!x || !scale || !dy || !dx) return CONV_ERR_NULL;
-  if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0) return CONV_ERR_SHAPE;
+  if (!x || !y || !scale || !dy || !dx) return CONV_ERR_NULL;
+  if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0 || N > 65535) return CONV_ERR_SHAPE;
   const int64_t count = (int64_t)N * C * HW;
   if (count > kMaxCount) return CONV_ERR_SHAPE;
-  hipLaunchKernelGGL(norm_bwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, scale, dy,
-                     dx, C, HW, size / 2, alpha, beta, count);
+  hipLaunchKernelGGL(norm_bwd_kernel, dim3((unsigned)(((int64_t)C * HW + kThreads - 1) / kThreads), N), dim3(kThreads), 0,
+                     (hipStream_t)hip_stream, x, y, scale, dy, dx, C, HW, size / 2, alpha, beta);
   return launch_status();
 }
 
@@ -295,7 +304,7 @@ int net_fc_fwd(const float* x, const float* W, const float* b, float* y, int32_t
   if (!x || !W || !y) return CONV_ERR_NULL;
   if (N < 1 || I < 1 || O < 1 || N > 65535 || (int64_t)N * I > kMaxCount || (int64_t)O * I > kMaxCount)
     return CONV_ERR_SHAPE;
-  hipLaunchKernelGGL(fc_fwd_kernel, dim3(N, (O + kOB - 1) / kOB), dim3(kThreads), 0, (hipStream_t)hip_stream, x, W, b, y,
+  hipLaunchKernelGGL(fc_fwd_kernel, dim3(N, (O + kOB - 1) / kOB), dim3(kFcThreads), 0, (hipStream_t)hip_stream, x, W, b, y,
                      I, O);
   return launch_status();
 }

@@ -75,11 +75,11 @@ class PaperNet:
         T("other", cs.net_softmax_loss_bwd, self.z, labels, self.gz, N, CLASSES)
         T("other", cs.net_fc_bwd, self.p2, self.wf, self.gz, self.gp2, self.gwf, self.gbf, N, self.I, CLASSES)
         T("other", cs.net_pool_bwd, self.n2, self.gp2, self.gn2, N * K2, 10, 10)
-        T("other", cs.net_norm_bwd, self.a2, self.s2, self.gn2, self.ga2, N, K2, 10 * 10, **NORM)
+        T("other", cs.net_norm_bwd, self.a2, self.n2, self.s2, self.gn2, self.ga2, N, K2, 10 * 10, **NORM)
         T("conv", cs.conv_bwd_weight, self.d2, self.p1, self.ga2, self.gw2, self.ws)
         T("conv", cs.conv_bwd_data, self.d2, self.ga2, self.w2, self.gp1, self.ws)
         T("other", cs.net_pool_bwd, self.n1, self.gp1, self.gn1, N * K1, 28, 28)
-        T("other", cs.net_norm_bwd, self.a1, self.s1, self.gn1, self.ga1, N, K1, 28 * 28, **NORM)
+        T("other", cs.net_norm_bwd, self.a1, self.n1, self.s1, self.gn1, self.ga1, N, K1, 28 * 28, **NORM)
         T("conv", cs.conv_bwd_weight, self.d1, x, self.ga1, self.gw1, self.ws)   # the first layer needs no input gradient
         if update:
             for w, g in ((self.w1, self.gw1), (self.w2, self.gw2), (self.wf, self.gwf), (self.bf, self.gbf)):

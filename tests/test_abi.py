@@ -130,7 +130,7 @@ def test_net_layer_calls_reject_bad_arguments():
     B = FakeBuf(0x30000)
     assert cs.net_norm_fwd(B, B, B, 2, 4, 9, size=4, stream=0, raw_status=True) == -2        # even window
     assert cs.net_norm_fwd(None, B, B, 2, 4, 9, stream=0, raw_status=True) == -1
-    assert cs.net_norm_bwd(B, B, B, B, 0, 4, 9, stream=0, raw_status=True) == -2
+    assert cs.net_norm_bwd(B, B, B, B, B, 0, 4, 9, stream=0, raw_status=True) == -2
     assert cs.net_pool_fwd(B, B, 6, 4, 4, win=5, stride=2, stream=0, raw_status=True) == -2   # window larger than the map
     assert cs.net_pool_bwd(B, B, None, 6, 4, 4, stream=0, raw_status=True) == -1
     assert cs.net_fc_fwd(B, B, None, B, 0, 5, 3, stream=0, raw_status=True) == -2

@@ -50,7 +50,7 @@ def test_normalisation(N, C, H, W, size, kappa, alpha, beta):
     xd, dyd = dev(x), dev(dy)
     y, scale, dx = empty(x.shape), empty(x.shape), empty(x.shape)
     cs.net_norm_fwd(xd, y, scale, N, C, H * W, size, kappa, alpha, beta)
-    cs.net_norm_bwd(xd, scale, dyd, dx, N, C, H * W, size, kappa, alpha, beta)
+    cs.net_norm_bwd(xd, y, scale, dyd, dx, N, C, H * W, size, kappa, alpha, beta)
     assert rel_err(host(y), on.norm_fwd(x, size, kappa, alpha, beta)) <= TOL
     assert rel_err(host(scale), on.norm_scale(x, size, kappa, alpha)) <= TOL
     assert rel_err(host(dx), on.norm_bwd(x, dy, size, kappa, alpha, beta)) <= TOL
