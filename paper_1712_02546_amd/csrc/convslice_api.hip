@@ -47,7 +47,9 @@ int make_geo(const conv_desc_t* d, Geo& g) {
   if ((int64_t)d->C * HW * Np >= kMaxElems) return CONV_ERR_SHAPE;       // x, x_t, dx_t
   if (((int64_t)d->K + 32) * (PQ + 1) * Np >= kMaxElems) return CONV_ERR_SHAPE;   // y, dy and work copies (padded)
   if (((int64_t)PQ + 1) * Np >= ((int64_t)1 << 29)) return CONV_ERR_SHAPE;          // two rows of a work copy in 32 bits
-  if ((int64_t)d->K * Cp * RS + 4 * (int64_t)d->K >= kMaxElems) return CONV_ERR_SHAPE;  // w, w_t
+  // w and its work copies: rows re-pitched to a multiple of 32 (fwd), kernels padded to a multiple of 32 (bwd_data)
+  if ((int64_t)d->K * (round_up(Cp * RS, 32) + 32) >= kMaxElems) return CONV_ERR_SHAPE;
+  if (((int64_t)d->K + 32) * Cp * RS >= kMaxElems) return CONV_ERR_SHAPE;
   g.N = d->N; g.Np = (int)Np; g.NB = (int)(Np / 32);
   g.C = d->C; g.H = d->H; g.W = d->W; g.K = d->K; g.R = d->R; g.S = d->S; g.P = P; g.Q = Q;
   g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;

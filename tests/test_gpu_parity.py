@@ -196,3 +196,12 @@ def test_device_share_equals_slice_of_full_layer():
     y_part = d_part.fwd(fill=0.0)
     check(y_part[:, 500:1000], y_full[:, 500:1000], SAME_MATH_TOL, "share vs full layer")
     assert not y_part[:, :500].any() and not y_part[:, 1000:].any()
+
+
+def test_work_copies_beyond_two_gibibytes_fp32():
+    """A layer whose transposed input (and input gradient) is 2 GiB: byte offsets inside the
+    work copies pass 2^31, which the 32-bit lane offsets and 64-bit bases of the DMA loads
+    must handle.  Sampled against the oracle (the oracle's sampled routines work element by element)."""
+    cfg = synth.random_layer(40, N=256, C=512, H=64, W=64, K=8, R=3, S=3, k0=1, k1=8)
+    assert cfg.N * cfg.C * cfg.H * cfg.W * 4 == 1 << 31
+    _sampled(cfg, cs.CONV_F32, FP32_TOL, n=400)
