@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # scaled by a copy kernel of known size (profiles/cfg3_f32_pmc_counters.md).  None where not measured.
 TRAFFIC_BYTES = {
     ("cfg3", "f32", "fwd_gemm_kernel"): 3415000000,
-    ("cfg3", "f32", "bwd_data_gemm_kernel"): 9500000000,
+    ("cfg3", "f32", "bwd_data_gemm_kernel"): 8576000000,
     ("cfg3", "f32", "bwd_weight_gemm_kernel"): 2800000000,
 }
 
