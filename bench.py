@@ -395,7 +395,7 @@ def main():
         return
 
     runs = [("cfg1", "f32"), ("cfg2", "f32"), ("cfg3", "f32"), ("cfg4", "f32"), ("cfg5a", "f32"), ("cfg5b", "f32"),
-            ("cfg5a", "bf16"), ("cfg5b", "bf16")]
+            ("cfg5a", "bf16"), ("cfg5b", "bf16"), ("cfg3", "bf16")]
     rows = []
     for name, dt in runs:
         r = measure(name, dt, args.steps, args.warmup, 0, per_pass=True)
