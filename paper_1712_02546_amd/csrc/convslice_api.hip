@@ -167,6 +167,8 @@ cs::RunPlan plan_runs(const Geo& g, int MB) {
   // moment, and workgroups in the same phase share the filter operand.
   const int64_t pieces = total / nkc;
   rp.units = (int)((pieces + nRuns - 1) / nRuns) * nkc;
+  // ... unless whole taps are too coarse a unit (few, long taps): then the runs are cut at any chunk.
+  if ((double)total < 0.97 * (double)nRuns * rp.units) rp.units = (int)((total + nRuns - 1) / nRuns);
   return rp;
 }
 
