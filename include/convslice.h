@@ -30,6 +30,8 @@
  * Inputs are never written.  ws is scratch the caller provides: at least
  * conv_workspace_bytes(desc, pass) bytes, 256-byte aligned, contents
  * undefined before and after.  Calls that overlap in time must not share ws.
+ * The size never grows when the slice shrinks: a workspace sized for
+ * [k0,k1) serves every call of the same layer and pass on a part of it.
  *
  * Execution.  Work is enqueued on hip_stream (a hipStream_t passed as void*,
  * NULL = default stream) and the call returns without synchronising.  The

@@ -123,52 +123,19 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   return p;
 }
 
-// Even sharing of the input-gradient pass: possible when every column tile holds one pixel
-// (Np a multiple of 128).  The length of the tile line is computed here exactly as the
-// ordering kernel counts it: sum over pixels of max(taps,1) chunks-of-Ks, times the tiles per pixel.
-cs::RunPlan plan_runs(const Geo& g, int MB) {
+// Even sharing of the input-gradient pass: the line of column tiles is measured and cut on the device (by the
+// ordering kernel); the host only fixes the number of runs.  Each run of the line is computed by MB workgroups,
+// one per row tile, which therefore walk through the same pixels, taps and k-chunks at the same time and share
+// the dy operand.
+cs::RunPlan plan_runs(const Geo& g, int MB, int CT) {
   cs::RunPlan rp;
-  rp.enabled = 0; rp.units = 1; rp.nWg = 0; rp.tilesPerPix = 1; rp.total = 0;
-  if (g.NB % 4 != 0) return rp;
-  const int nkc = (g.Ks + cs::BK - 1) / cs::BK;
-  std::vector<int64_t> rowh(g.R + 1, 0), colh(g.S + 1, 0);
-  for (int h = 0; h < g.H; ++h) {
-    int n = 0;
-    for (int r = 0; r < g.R; ++r) {
-      const int hr = h + g.ph - r;
-      if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) ++n;
-    }
-    ++rowh[n];
-  }
-  for (int v = 0; v < g.W; ++v) {
-    int n = 0;
-    for (int s = 0; s < g.S; ++s) {
-      const int vs = v + g.pw - s;
-      if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) ++n;
-    }
-    ++colh[n];
-  }
-  int64_t taps = 0;
-  for (int a = 0; a <= g.R; ++a)
-    for (int b = 0; b <= g.S; ++b) taps += rowh[a] * colh[b] * (a * b > 0 ? a * b : 1);
-  // The line holds the column tiles only; each run of the line is computed by MB workgroups, one per row tile,
-  // which therefore walk through the same pixels, taps and k-chunks at the same time and share the dy operand.
-  const int tilesPerPix = g.NB / 4;
-  const int64_t total = taps * tilesPerPix * nkc;
+  rp.enabled = 0; rp.nRuns = 1; rp.nWg = 0;
+  const int64_t nkc = (g.Ks + cs::BK - 1) / cs::BK;
   const int S = chip_slots();
-  const int nRuns = S / MB;
-  if (nRuns < 1 || total >= (int64_t)1 << 30 || total * MB < (int64_t)16 * S) return rp;   // too long for int, or too little work
+  if (S / MB < 1 || (int64_t)CT * g.RS * nkc >= (int64_t)1 << 30) return rp;   // the line would be too long for an int
   rp.enabled = 1;
-  rp.tilesPerPix = tilesPerPix;
-  rp.total = (int)total;
-  rp.nWg = nRuns * MB;
-  // Runs are whole numbers of taps (nkc chunks each), so that every workgroup starts a tap at the same time and
-  // all of them sweep the kernel range together; with runs of equal length only a few tap phases exist at any
-  // moment, and workgroups in the same phase share the filter operand.
-  const int64_t pieces = total / nkc;
-  rp.units = (int)((pieces + nRuns - 1) / nRuns) * nkc;
-  // ... unless whole taps are too coarse a unit (few, long taps): then the runs are cut at any chunk.
-  if ((double)total < 0.97 * (double)nRuns * rp.units) rp.units = (int)((total + nRuns - 1) / nRuns);
+  rp.nRuns = S / MB;
+  rp.nWg = rp.nRuns * MB;
   return rp;
 }
 
@@ -177,7 +144,7 @@ struct BwdDataPlan {
   int Cp, Ksp, nch, MB1, CT1;   // Ksp: pitch of w' in the scatter form, a multiple of BK
   cs::TailPlan tail;
   cs::RunPlan run;
-  size_t off_dyt, off_wt, off_dxt, off_perm, off_cls, off_scratch, off_tab, off_T, off_tail, total;
+  size_t off_dyt, off_wt, off_dxt, off_perm, off_pre, off_scratch, off_tab, off_T, off_tail, total;
 };
 
 BwdDataPlan plan_bwd_data(const Geo& g) {
@@ -187,7 +154,18 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.nch = (g.Ks + cs::BK - 1) / cs::BK;
   // With C input channels the per-pixel form fills C of a tile's 128 rows; the scatter form
   // fills C*R*S of them and pays one round trip of T through memory instead.
-  p.scatter = g.C <= 32 && (int64_t)g.CRS * g.PQ * g.Np < kMaxElems;
+  // Cost model (seconds up to a common factor): matrix-core time is the nominal work divided by the share of
+  // tile rows that hold data; the scatter form adds one write and one read of T at HBM-side speed.  The choice
+  // is made for the whole layer (K, not the slice), so that every slice of a layer takes the same form and a
+  // workspace sized for a slice is large enough for any part of it.
+  {
+    const double F = 2.0 * g.Np * g.K * (double)g.CRS * g.PQ;
+    const double rows_pixel = (double)g.C / (double)(round_up(g.C, cs::BM));
+    const double rows_scatter = (double)g.CRS / (double)(round_up(g.CRS, cs::BM));
+    const double t_pixel = F / (130e12 * rows_pixel);
+    const double t_scatter = F / (130e12 * rows_scatter) + 2.0 * 4.0 * g.CRS * (double)g.PQ * g.Np / 3e12;
+    p.scatter = t_scatter < 0.9 * t_pixel && (int64_t)g.CRS * g.PQ * g.Np < kMaxElems;
+  }
   size_t o = 0;
   if (p.scatter) {
     o += kZeroBytes;
@@ -209,9 +187,10 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_wt = o;   o += seg((int64_t)g.RS * g.C * p.Ksp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
-  p.off_cls = o;  o += seg(2 * (g.RS + 1));
+  const int CT = (g.HW * g.NB + 3) / 4;
+  p.off_pre = o;  o += seg((int64_t)CT + 2);
   p.off_scratch = o; o += seg((int64_t)g.H + g.W);
-  p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM);
+  p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM, CT);
   p.off_tail = o; o += p.run.enabled ? (size_t)p.run.nWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
   p.total = o;
   return p;
@@ -591,7 +570,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.RS, g.CRS, g.Ks, g.RS, wp, p.Ksp,
                         (int64_t)g.C * p.Ksp, p.Ksp, g.C, nullptr, st, true);
     hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm,
-                       (int*)(base + p.off_cls), (int*)(base + p.off_scratch));
+                       (int*)(base + p.off_scratch), 0, 1, 1, (int*)nullptr);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Ksp + 64);
     const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
@@ -664,21 +643,22 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   // zero past Ks.  A tap's C rows are then a dense C x Ksp matrix, contiguous along the reduction.
   launch_transpose_in(desc->dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0, p.Ksp,
                       p.Ksp, 1, nullptr, st, false, -1, g.RS, g.C);
-  int* cls = (int*)(base + p.off_cls);
+  int* pre = (int*)(base + p.off_pre);
   int* scratch = (int*)(base + p.off_scratch);
   float* partial = (float*)(base + p.off_tail);
-  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm, cls, scratch);
-  // tiles + tap list + per-block tap offsets + copy of the class table
-  const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20 + (g.RS + 1) * 8;
-  if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel, lds)) != CONV_OK) return rc;
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
+  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm, scratch, CT, p.nch,
+                     p.run.nRuns, p.run.enabled ? pre : (int*)nullptr);
+  // tiles + tap list + per-block tap offsets
+  const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
+  if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel, lds)) != CONV_OK) return rc;
   probe.begin(st);
   hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT)), dim3(cs::NT),
-                     lds, st, g, wt, p.Ksp, dyt, perm, cls, dxt, MB, CT, p.run, partial);
+                     lds, st, g, wt, p.Ksp, dyt, perm, pre, dxt, MB, CT, p.run, partial);
   if (p.run.enabled)
-    hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, cls, partial, dxt,
-                       MB, p.run);
+    hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
+                       MB, CT);
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);

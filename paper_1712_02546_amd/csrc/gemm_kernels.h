@@ -313,18 +313,17 @@ struct BwdDataLoadB {
   }
 };
 
-// Even sharing of the input-gradient pass (tiles of unequal cost).  With every column tile
-// holding one pixel (Np a multiple of 128) the column tiles form a line: pixels by decreasing
-// tap count (perm / cls from the ordering kernel), per pixel its tilesPerPix = Np/128 column
-// tiles.  A tile with t taps is max(t,1)*nkc chunks long; `total` is the length of the line.
-// The line is cut into equal runs of `units` chunks, and each run is computed by MB
-// workgroups, one per row tile (nWg = runs * MB): workgroup run*MB+mb computes row tile mb of
+// Even sharing of the input-gradient pass (tiles of unequal cost).  The column tiles, pixels
+// by decreasing tap count, form a line on which tile ct covers chunks pre[ct] .. pre[ct+1]
+// (its taps times the k-chunks; the ordering kernel writes pre, the line's length pre[CT] and
+// the run length pre[CT+1]).  The line is cut into equal runs, and each run is computed by MB
+// workgroups, one per row tile (nWg = nRuns * MB): workgroup run*MB+mb computes row tile mb of
 // the column tiles inside its run whole and of the (at most two) tiles that stick out at either
 // end partially, into scratch slot 2*wg (the tile its run starts in) or 2*wg+1; a fix-up kernel
 // adds the slots of a cut tile in run order.  enabled = 0: one workgroup per tile, heaviest
 // first (tile_dealt).
 struct RunPlan {
-  int enabled, units, nWg, tilesPerPix, total;
+  int enabled, nRuns, nWg;
 };
 
 __device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __restrict__ dxt,
@@ -348,13 +347,12 @@ __device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __rest
 __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* __restrict__ wt, int Ksp,
                                                            const float* __restrict__ dyt,
                                                            const int* __restrict__ perm,
-                                                           const int* __restrict__ cls,
+                                                           const int* __restrict__ pre,
                                                            float* __restrict__ dxt, int MB, int CT, RunPlan rp,
                                                            float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
   int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 3]: the loaders run up to three entries past the list
   int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][4]
-  int* s_cls = s_tapoff + 4 * (g.RS + 3);      // [RS + 1][2], run mode only
   __shared__ int s_ntaps;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nkc = (g.Ks + BK - 1) / BK;
@@ -439,74 +437,44 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
   const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   if (wg >= rp.nWg) return;
   const int run = wg / MB, mb = wg - run * MB;
-  int pos = run * rp.units;
-  const int end = min(pos + rp.units, rp.total);
-  if (pos >= end) return;
-  for (int i = threadIdx.x; i < 2 * (g.RS + 1); i += NT) s_cls[i] = cls[i];
-  __syncthreads();
-  // locate pos: tap-count class wc (descending), column tile t inside the class, chunk c inside the tile
-  int wc = g.RS, t = 0, c = 0;
-  {
-    int rest = pos;
-    for (;; --wc) {
-      const int len = max(wc, 1) * nkc;
-      const int span = s_cls[2 * wc + 1] * rp.tilesPerPix * len;
-      if (rest < span) {
-        t = rest / len;
-        c = rest - t * len;
-        break;
-      }
-      if (wc == 0) return;   // cannot happen when the host's total matches the class table
-      rest -= span;
-    }
+  const int total = pre[CT], units = pre[CT + 1];
+  if ((int64_t)run * units >= total) return;
+  int pos = run * units;
+  const int end = min(pos + units, total);
+  // the tile that holds pos: pre[ct] <= pos < pre[ct+1]
+  int ct = 0;
+  for (int hi = CT; hi - ct > 1;) {
+    const int mid = (ct + hi) >> 1;
+    if (pre[mid] <= pos) ct = mid; else hi = mid;
   }
+  int c = pos - pre[ct];
   bool first = true;
-  while (pos < end) {
-    const int len = max(wc, 1) * nkc;
+  for (; pos < end && ct < CT; ++ct) {
+    const int len = pre[ct + 1] - pre[ct];
     const int ce = min(len, c + (end - pos));
-    const int pi = t / rp.tilesPerPix, nbq = t - pi * rp.tilesPerPix;
-    const int ct = (s_cls[2 * wc] + pi) * rp.tilesPerPix + nbq;
     segment(mb, ct, c, ce, c == 0 && ce == len, wg * 2 + (first ? 0 : 1));
     pos += ce - c;
     c = 0;
     first = false;
-    if (++t == s_cls[2 * wc + 1] * rp.tilesPerPix) {
-      t = 0;
-      do --wc; while (wc > 0 && s_cls[2 * wc + 1] == 0);
-      if (wc < 0 || s_cls[2 * wc + 1] == 0) break;   // end of the line
-    }
   }
 }
 
 // Adds up the scratch slots of every tile that was cut by a run boundary.  grid = (CT*MB, 4).
 __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __restrict__ perm,
-                                                            const int* __restrict__ cls,
+                                                            const int* __restrict__ pre,
                                                             const float* __restrict__ partial,
-                                                            float* __restrict__ dxt, int MB, RunPlan rp) {
-  const int nkc = (g.Ks + BK - 1) / BK;
-  const int NBq = rp.tilesPerPix;
+                                                            float* __restrict__ dxt, int MB, int CT) {
   const int ct = blockIdx.x / MB, mb = blockIdx.x - ct * MB;
-  const int sp = ct / NBq, nbq = ct - sp * NBq;
-  // position of the column tile in the line
-  int a = 0, len = 0;
-  for (int wc = g.RS; wc >= 0; --wc) {
-    const int start = cls[2 * wc], cnt = cls[2 * wc + 1];
-    len = max(wc, 1) * nkc;
-    if (sp >= start && sp < start + cnt) {
-      a += ((sp - start) * NBq + nbq) * len;
-      break;
-    }
-    a += cnt * NBq * len;
-  }
-  const int b = a + len;
-  const int r0 = a / rp.units, r1 = (b - 1) / rp.units;
+  const int units = pre[CT + 1];
+  const int a = pre[ct], b = pre[ct + 1];   // the tile's stretch of the line
+  const int r0 = a / units, r1 = (b - 1) / units;
   if (r0 == r1) return;   // inside one run: stored directly
   const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   for (int r = r0; r <= r1; ++r) {
-    const int slot = r * rp.units >= a ? 0 : 1;   // a run that starts inside the tile used its first slot
+    const int slot = r * units >= a ? 0 : 1;   // a run that starts inside the tile used its first slot
     const float* p = partial + (int64_t)((r * MB + mb) * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];

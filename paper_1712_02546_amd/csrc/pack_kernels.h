@@ -166,15 +166,22 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
 
 // Orders the H*W input pixels by decreasing tap count, ties in row-major order (a stable
 // counting sort by one workgroup, no atomics in the placement, so the order is the same
-// on every run).  perm[position] = pixel.  cls[2*w] = first position of tap count w,
-// cls[2*w+1] = number of pixels with tap count w, for w = 0..R*S.  scratch holds H + W ints.
+// on every run).  perm[position] = pixel.  scratch holds H + W ints.
 // A pixel's tap count is rows(h) * cols(v), so its rank among equal counts is a sum over the
 // earlier image rows of "columns with the matching factor" plus a scan of its own row.
+//
+// With `pre` given it also lays the CT column tiles (four blocks of 32 images each, blocks
+// numbered position-major in the new order) on a line: a tile is as many chunks long as
+// nkc times the number of taps that reach any of its pixels (at least one), pre[ct] is
+// where tile ct starts, pre[CT] the length of the line, and pre[CT+1] the length of the
+// equal runs it is cut into for nRuns workgroup groups: whole taps (nkc chunks) when that
+// leaves less than 3 % of the slots idle, any number of chunks otherwise, at least 8.
 __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
-                                                                    int* __restrict__ cls,
-                                                                    int* __restrict__ scratch) {
+                                                                    int* __restrict__ scratch, int CT, int nkc,
+                                                                    int nRuns, int* __restrict__ pre) {
   __shared__ int bins[1026];    // pixels per tap count, then first position per tap count
   __shared__ int ncolhist[1026];  // image columns per column-tap count
+  __shared__ int part[1024];    // scan of the tile lengths
   int* nrow = scratch;
   int* ncol = scratch + g.H;
   for (int i = threadIdx.x; i <= g.RS + 1; i += blockDim.x) bins[i] = 0;
@@ -205,8 +212,6 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
     for (int wgt = g.RS; wgt >= 0; --wgt) {
       const int cnt = bins[wgt];
       bins[wgt] = run;
-      cls[2 * wgt] = run;
-      cls[2 * wgt + 1] = cnt;
       run += cnt;
     }
   }
@@ -223,6 +228,59 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
     }
     for (int vv = 0; vv < v; ++vv) rank += nr * ncol[vv] == wgt;
     perm[bins[wgt] + rank] = px;
+  }
+  if (pre == nullptr) return;
+  __threadfence_block();
+  __syncthreads();
+  // Every thread takes a contiguous stretch of tiles: lengths first, then their running sum.
+  const int per = (CT + (int)blockDim.x - 1) / (int)blockDim.x;
+  const int t0 = min((int)threadIdx.x * per, CT), t1 = min(t0 + per, CT);
+  int sum = 0;
+  for (int ct = t0; ct < t1; ++ct) {
+    int hp[4], vp[4], np = 0;   // the tile's distinct pixels
+    for (int j = 0; j < 4; ++j) {
+      const int gcb = ct * 4 + j;
+      if (gcb >= g.HW * g.NB) break;
+      const int sp = gcb / g.NB;
+      if (j > 0 && sp == (gcb - 1) / g.NB) continue;
+      const int px = perm[sp];
+      hp[np] = px / g.W + g.ph;
+      vp[np] = px % g.W + g.pw;
+      ++np;
+    }
+    int taps = 0;
+    for (int r = 0; r < g.R; ++r)
+      for (int s2 = 0; s2 < g.S; ++s2) {
+        bool any = false;
+        for (int j = 0; j < np; ++j) {
+          const int hr = hp[j] - r, vs = vp[j] - s2;
+          any |= hr >= 0 && vs >= 0 && hr % g.sh == 0 && vs % g.sw == 0 && hr / g.sh < g.P && vs / g.sw < g.Q;
+        }
+        taps += any;
+      }
+    const int len = max(taps, 1) * nkc;
+    pre[ct + 1] = len;
+    sum += len;
+  }
+  part[threadIdx.x] = sum;
+  __syncthreads();
+  for (int d = 1; d < (int)blockDim.x; d <<= 1) {
+    const int v = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+    __syncthreads();
+    part[threadIdx.x] += v;
+    __syncthreads();
+  }
+  int run = part[threadIdx.x] - sum;
+  for (int ct = t0; ct < t1; ++ct) {
+    run += pre[ct + 1];
+    pre[ct + 1] = run;
+  }
+  if (threadIdx.x == 0) {
+    pre[0] = 0;
+    const int total = part[blockDim.x - 1];
+    int units = ((total / nkc + nRuns - 1) / nRuns) * nkc;
+    if ((double)total < 0.97 * (double)nRuns * units) units = (total + nRuns - 1) / nRuns;
+    pre[CT + 1] = max(units, 8);
   }
 }
 

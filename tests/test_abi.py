@@ -52,6 +52,27 @@ def test_output_dims_and_workspace_query():
     assert cs.conv_workspace_bytes(cs.ConvDesc(**GOOD), 7) == 0
 
 
+@pytest.mark.parametrize("dtype", [cs.CONV_F32, cs.CONV_BF16])
+@pytest.mark.parametrize("layer", [
+    dict(N=36, C=48, H=12, W=12, K=200, R=5, S=5, pad_h=1, pad_w=1),
+    dict(N=128, C=500, H=14, W=14, K=1500, R=5, S=5),
+    dict(N=64, C=3, H=32, W=32, K=150, R=5, S=5),
+    dict(N=1024, C=50, H=14, W=14, K=500, R=5, S=5),
+    dict(N=64, C=96, H=27, W=27, K=256, R=5, S=5, pad_h=2, pad_w=2),
+])
+def test_workspace_never_grows_when_the_slice_shrinks(layer, dtype):
+    K = layer["K"]
+    for p in (cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT):
+        full = cs.conv_workspace_bytes(cs.ConvDesc(**layer, dtype=dtype), p)
+        last = 0
+        for k1 in (1, 7, 31, 32, 33, K // 3, K // 2, K - 1, K):
+            need = cs.conv_workspace_bytes(cs.ConvDesc(**layer, dtype=dtype, k0=0, k1=k1), p)
+            assert last <= need <= full, (p, k1, need, full)
+            last = need
+            shifted = cs.conv_workspace_bytes(cs.ConvDesc(**layer, dtype=dtype, k0=K - k1, k1=K), p)
+            assert shifted == need, (p, k1)
+
+
 class FakeBuf:
     """Stands in for a device tensor: the calls below must fail before using it."""
 

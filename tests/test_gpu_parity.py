@@ -32,6 +32,8 @@ ADHOC = [
     synth.random_layer(14, N=128, C=130, H=12, W=12, K=100, R=3, S=3, pad=1, k0=2, k1=100),
     # the same with pixels no tap reaches (1x1, stride 2)
     synth.random_layer(15, N=100, C=130, H=24, W=24, K=260, R=1, S=1, stride=2),
+    # column tiles that span pixels with different tap sets (three image blocks per pixel, stride 2)
+    synth.random_layer(16, N=70, C=100, H=9, W=11, K=40, R=3, S=3, stride=2, pad=1, k0=0, k1=37),
 ]
 
 
