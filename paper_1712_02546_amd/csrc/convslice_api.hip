@@ -127,10 +127,9 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
 // ordering kernel); the host only fixes the number of runs.  Each run of the line is computed by MB workgroups,
 // one per row tile, which therefore walk through the same pixels, taps and k-chunks at the same time and share
 // the dy operand.
-cs::RunPlan plan_runs(const Geo& g, int MB, int CT) {
+cs::RunPlan plan_runs(const Geo& g, int MB, int CT, int64_t nkc) {
   cs::RunPlan rp;
   rp.enabled = 0; rp.nRuns = 1; rp.nWg = 0;
-  const int64_t nkc = (g.Ks + cs::BK - 1) / cs::BK;
   const int S = chip_slots();
   if (S / MB < 1 || (int64_t)CT * g.RS * nkc >= (int64_t)1 << 30) return rp;   // the line would be too long for an int
   rp.enabled = 1;
@@ -190,7 +189,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
   p.off_scratch = o; o += seg((int64_t)g.H + g.W);
-  p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM, CT);
+  p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM, CT, p.nch);
   p.off_tail = o; o += p.run.enabled ? (size_t)p.run.nWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
   p.total = o;
   return p;
@@ -284,7 +283,8 @@ Fwd16Plan plan_fwd16(const Geo& g) {
 
 struct BwdData16Plan {
   int Ksp;
-  size_t off_dy, off_w, off_dxt, off_perm, off_cls, off_scratch, off_zero, total;
+  cs::RunPlan run;
+  size_t off_dy, off_w, off_dxt, off_perm, off_pre, off_scratch, off_zero, off_tail, total;
 };
 BwdData16Plan plan_bwd_data16(const Geo& g) {
   BwdData16Plan p;
@@ -294,9 +294,16 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   p.off_w = o;    o += seg16((int64_t)g.RS * g.C * p.Ksp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
-  p.off_cls = o;  o += seg(2 * (g.RS + 1));
+  const int CT = (g.HW * g.NB + 3) / 4;
+  p.off_pre = o;  o += seg((int64_t)CT + 2);
   p.off_scratch = o; o += seg((int64_t)g.H + g.W);
   p.off_zero = o; o += seg16((int64_t)32 * p.Ksp + 64);   // a column block of zeros: 32 images x Ksp kernels
+  // With chunks this short the scratch round trip of the cut tiles costs about as much as uneven tiles do, so
+  // the runs are used only where one workgroup per tile would leave slots empty.
+  const int MB = (g.C + cs::BM - 1) / cs::BM;
+  p.run = plan_runs(g, MB, CT, p.Ksp / cs::BK16);
+  if ((int64_t)MB * CT >= chip_slots()) p.run.enabled = 0;
+  p.off_tail = o; o += p.run.enabled ? (size_t)p.run.nWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
   p.total = o;
   return p;
 }
@@ -569,17 +576,24 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     // per channel c: w[k0..k1)[c] as a Ks x RS matrix -> w_rsck[rs][c][Ksp]
     launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.RS, g.CRS, g.Ks, g.RS, wp, p.Ksp,
                         (int64_t)g.C * p.Ksp, p.Ksp, g.C, nullptr, st, true);
+    const int MB = (g.C + cs::BM - 1) / cs::BM;
+    const int CT = (g.HW * g.NB + 3) / 4;
+    int* pre = (int*)(base + p.off_pre);
+    float* partial = (float*)(base + p.off_tail);
     hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm,
-                       (int*)(base + p.off_scratch), 0, 1, 1, (int*)nullptr);
+                       (int*)(base + p.off_scratch), CT, p.Ksp / cs::BK16, p.run.nRuns,
+                       p.run.enabled ? pre : (int*)nullptr);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Ksp + 64);
     const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
     if ((rc = allow_big_lds(cs::bwd_data16_gemm_kernel, lds)) != CONV_OK) return rc;
-    const int MB = (g.C + cs::BM - 1) / cs::BM;
-    const int CT = (g.HW * g.NB + 3) / 4;
     probe.begin(st);
-    hipLaunchKernelGGL(cs::bwd_data16_gemm_kernel, dim3(cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st, g, wp, p.Ksp,
-                       dyp, zero, perm, dxt, MB, CT);
+    hipLaunchKernelGGL(cs::bwd_data16_gemm_kernel,
+                       dim3(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st, g,
+                       wp, p.Ksp, dyp, zero, perm, pre, dxt, MB, CT, p.run, partial);
+    if (p.run.enabled)
+      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
+                         MB, CT);
     probe.end(st);
     launch_transpose_out(CONV_BF16, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
     return check_launch();

@@ -226,16 +226,16 @@ struct BwdData16LoadA {
   unsigned tapBytes;
   int S, tap;         // tap of walk.ti, fetched one call ahead (uniform, held in a vector register)
   TapWalk walk;
-  __device__ BwdData16LoadA(const Geo& g, const bf16_t* wt_, int Ksp, int m0, const int* taps_, int nkc_)
+  __device__ BwdData16LoadA(const Geo& g, const bf16_t* wt_, int Ksp, int m0, const int* taps_, int nkc_, int ch0)
       : wt((const char*)(wt_ + (int64_t)m0 * Ksp)), taps(taps_), tapBytes((unsigned)g.C * (unsigned)Ksp * 2u), S(g.S),
-        walk(nkc_, 0) {
+        walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = min(32 * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // rows past C repeat the last one
       off[i] = (unsigned)(c * Ksp + slot8(l, i)) * 2u;
     }
-    const int e = taps[0];
+    const int e = taps[walk.ti];
     tap = (e >> 16) * S + (e & 0xffff);
   }
   __device__ __forceinline__ void begin(int, bool live) {
@@ -261,13 +261,13 @@ struct BwdData16LoadB {
   unsigned off[4];
   int toff, wvb;      // toff: element offset of the block's 32 images at the tap's output pixel, or -1
   TapWalk walk;
-  __device__ BwdData16LoadB(const bf16_t* dy_, const bf16_t* zero_, int Ksp, const int* tapoff_, int nkc_)
-      : dy((const char*)dy_), zero((const char*)zero_), tapoff(tapoff_), walk(nkc_, 0) {
+  __device__ BwdData16LoadB(const bf16_t* dy_, const bf16_t* zero_, int Ksp, const int* tapoff_, int nkc_, int ch0)
+      : dy((const char*)dy_), zero((const char*)zero_), tapoff(tapoff_), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63;
     wvb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
     for (int i = 0; i < 4; ++i) off[i] = (unsigned)((8 * i + (l >> 3)) * Ksp + slot8(l, i)) * 2u;
-    toff = tapoff[wvb];
+    toff = tapoff[walk.ti * 4 + wvb];
   }
   __device__ __forceinline__ void begin(int, bool live) {
     const int t = __builtin_amdgcn_readfirstlane(toff);
@@ -280,88 +280,114 @@ struct BwdData16LoadB {
   }
 };
 
+// Tiles, runs and scratch slots as in the fp32 kernel (RunPlan); the fp32 fix-up kernel serves both.
 __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t* __restrict__ wt, int Ksp,
                                                              const bf16_t* __restrict__ dy,
                                                              const bf16_t* __restrict__ zero,
                                                              const int* __restrict__ perm,
-                                                             float* __restrict__ dxt, int MB, int CT) {
+                                                             const int* __restrict__ pre,
+                                                             float* __restrict__ dxt, int MB, int CT, RunPlan rp,
+                                                             float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
   int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 3]
   int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][4]
   __shared__ int s_ntaps;
-  int mb, ct;
-  if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (wave == 0) {   // tap list of the tile, as in the fp32 kernel; offsets are into dy_pqnk
-    int hp[4], vp[4], nbo[4];
-    bool ok[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int gcb = ct * 4 + j;
-      ok[j] = gcb < g.HW * g.NB;
-      const int sp = ok[j] ? gcb / g.NB : 0;
-      const int px = perm[sp];
-      nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 * Ksp : 0;
-      hp[j] = px / g.W + g.ph;
-      vp[j] = px % g.W + g.pw;
-    }
-    int cnt = 0;
-    for (int b = 0; b < g.RS; b += 64) {
-      const int tp = b + lane;
-      const int rr = tp / g.S, ss = tp - rr * g.S;
-      bool any = false;
-      int offs[4];
+  const int nkc = Ksp / BK16;
+
+  auto segment = [&](int mb, int ct, int c0, int c1, bool direct, int slot) {
+    if (wave == 0) {   // tap list of the tile, as in the fp32 kernel; offsets are into dy_pqnk
+      int hp[4], vp[4], nbo[4];
+      bool ok[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int hr = hp[j] - rr, vs = vp[j] - ss;
-        const int p = hr / g.sh, q = vs / g.sw;
-        const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
-                         p < g.P && q < g.Q;
-        offs[j] = hit ? (p * g.Q + q) * g.Np * Ksp + nbo[j] : -1;
-        any |= hit;
+        const int gcb = ct * 4 + j;
+        ok[j] = gcb < g.HW * g.NB;
+        const int sp = ok[j] ? gcb / g.NB : 0;
+        const int px = perm[sp];
+        nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 * Ksp : 0;
+        hp[j] = px / g.W + g.ph;
+        vp[j] = px % g.W + g.pw;
       }
-      const unsigned long long mask = __ballot(any);
-      if (any) {
-        const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-        s_taps[pos] = (rr << 16) | ss;
+      int cnt = 0;
+      for (int b = 0; b < g.RS; b += 64) {
+        const int tp = b + lane;
+        const int rr = tp / g.S, ss = tp - rr * g.S;
+        bool any = false;
+        int offs[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
+        for (int j = 0; j < 4; ++j) {
+          const int hr = hp[j] - rr, vs = vp[j] - ss;
+          const int p = hr / g.sh, q = vs / g.sw;
+          const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
+                           p < g.P && q < g.Q;
+          offs[j] = hit ? (p * g.Q + q) * g.Np * Ksp + nbo[j] : -1;
+          any |= hit;
+        }
+        const unsigned long long mask = __ballot(any);
+        if (any) {
+          const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+          s_taps[pos] = (rr << 16) | ss;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) s_tapoff[pos * 4 + j] = offs[j];
+        }
+        cnt += __popcll(mask);
       }
-      cnt += __popcll(mask);
+      if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;
+      if (lane < 3) s_taps[cnt + lane] = 0;
+      if (lane == 0) s_ntaps = cnt;
     }
-    if (lane < 12) s_tapoff[cnt * 4 + lane] = -1;
-    if (lane < 3) s_taps[cnt + lane] = 0;
-    if (lane == 0) s_ntaps = cnt;
-  }
-  __syncthreads();
-  const int ntaps = s_ntaps;
-  const int nkc = Ksp / BK16;
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  BwdData16LoadA la(g, wt, Ksp, mb * BM, s_taps, nkc);
-  BwdData16LoadB lb(dy, zero, Ksp, s_tapoff, nkc);
-  gemm16_mainloop(la, lb, 0, ntaps * nkc, smem, acc);
-
-  const int wm = wave >> 1, wn = wave & 1;
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int gcb = ct * 4 + wn * 2 + j;
-    if (gcb >= g.HW * g.NB) continue;
-    const int sp = gcb / g.NB, nb = gcb - sp * g.NB;
-    const int px = perm[sp];
-    const int n = nb * 32 + (lane & 31);
+    __syncthreads();
+    const int nchunks = s_ntaps * nkc;
+    const int cb = min(c0, nchunks), ce = min(c1, nchunks);
+    f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int c = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
-        if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[i][j][v];
-      }
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    BwdData16LoadA la(g, wt, Ksp, mb * BM, s_taps, nkc, cb);
+    BwdData16LoadB lb(dy, zero, Ksp, s_tapoff, nkc, cb);
+    gemm16_mainloop(la, lb, cb, ce, smem, acc);
+    if (direct) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) bwd_data_store_block(g, dxt, perm, mb, ct, i, j, acc[i][j]);
+    } else {
+      store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+    }
+    __syncthreads();   // the next segment rewrites the tap list
+  };
+
+  if (!rp.enabled) {
+    int mb, ct;
+    if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
+    segment(mb, ct, 0, 0x7fffffff, true, 0);
+    return;
+  }
+  const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  if (wg >= rp.nWg) return;
+  const int run = wg / MB, mb = wg - run * MB;
+  const int total = pre[CT], units = pre[CT + 1];
+  if ((int64_t)run * units >= total) return;
+  int pos = run * units;
+  const int end = min(pos + units, total);
+  int ct = 0;   // the tile that holds pos: pre[ct] <= pos < pre[ct+1]
+  for (int hi = CT; hi - ct > 1;) {
+    const int mid = (ct + hi) >> 1;
+    if (pre[mid] <= pos) ct = mid; else hi = mid;
+  }
+  int c = pos - pre[ct];
+  bool first = true;
+  for (; pos < end && ct < CT; ++ct) {
+    const int len = pre[ct + 1] - pre[ct];
+    const int ce = min(len, c + (end - pos));
+    segment(mb, ct, c, ce, c == 0 && ce == len, wg * 2 + (first ? 0 : 1));
+    pos += ce - c;
+    c = 0;
+    first = false;
   }
 }
 
