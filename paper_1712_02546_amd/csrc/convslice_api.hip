@@ -92,8 +92,10 @@ cs::TailPlan plan_tail(int T, int nch) {
   tp.nTailWg = (int)((work + tp.units - 1) / tp.units);
   return tp;
 }
-inline size_t tail_bytes(const cs::TailPlan& tp) {
-  return tp.nTailWg > 0 ? (size_t)tp.nTailWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
+// Scratch slots for a shared tail: the most any slice of the layer can need (two per workgroup slot), so that the
+// workspace size does not depend on how the tile count of a slice happens to divide.
+inline size_t tail_bytes(int nch) {
+  return nch >= 16 ? (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
 }
 
 struct FwdPlan {
@@ -118,7 +120,7 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.off_yt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
   p.off_tab = o; o += seg((int64_t)(p.nch + 4) * cs::BK * 2);
-  p.off_tail = o; o += tail_bytes(p.tail);
+  p.off_tail = o; o += tail_bytes(p.nch);
   p.total = o;
   return p;
 }
@@ -175,7 +177,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     p.MB1 = (g.CRS + cs::BM - 1) / cs::BM;
     p.CT1 = (g.PQ * g.NB + 3) / 4;
     p.tail = plan_tail(p.MB1 * p.CT1, p.nch);
-    p.off_tail = o; o += tail_bytes(p.tail);
+    p.off_tail = o; o += tail_bytes(p.nch);
     p.off_dxt = p.off_perm = 0;
     p.total = o;
     return p;
@@ -190,9 +192,54 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_pre = o;  o += seg((int64_t)CT + 2);
   p.off_scratch = o; o += seg((int64_t)g.H + g.W);
   p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM, CT, p.nch);
-  p.off_tail = o; o += p.run.enabled ? (size_t)p.run.nWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
+  p.off_tail = o; o += (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4;   // two slots per workgroup, whatever the slice
   p.total = o;
   return p;
+}
+
+// Number of pieces the weight gradient's reduction (nch chunks) is cut into when the output has `tiles` tiles.
+// fp32 (the matrix pipe is the limit): cost model in chunk times.  A launch takes as long as its fullest compute
+// unit, a compute unit works through its workgroups' chunks one after the other (its two resident workgroups
+// share the pipe), and every workgroup adds about six chunk times of prologue and epilogue.  One piece means whole
+// tiles with the tail shared out evenly (plan_tail); it stays unless splitting is at least 3 % cheaper, but not
+// below 32 tiles, where the fix-up kernel would add up too many slots per tile.  Splits are tried from four
+// workgroups per compute unit (enough requests in flight when the layer is bound by memory) up to 4096
+// workgroups, with at least four chunks each.
+// bf16 (chunks so short that latency is the limit): measured best with about 1024 workgroups, whatever the tiles.
+int choose_splits(int64_t tiles, int64_t nch, bool pipe_bound) {
+  const int64_t S = chip_slots(), cus = S / 2;
+  const double c0 = 6.0;
+  if (tiles < 1) tiles = 1;
+  const int64_t cap = nch / 4 > 0 ? nch / 4 : 1;
+  const int64_t lo = std::min(cap, (2 * S + tiles - 1) / tiles), hi = std::min(cap, std::max<int64_t>(1, 4096 / tiles));
+  if (!pipe_bound) return (int)std::max<int64_t>(1, lo);
+  double best = tiles >= 32 ? 0.97 * (double)tiles / (double)cus * ((double)nch + c0) : 1e300;
+  int64_t bestS = 1;
+  for (int64_t sp = std::max<int64_t>(2, lo); sp <= hi; ++sp) {
+    const int64_t rounds = (tiles * sp + cus - 1) / cus, per = (nch + sp - 1) / sp;
+    const double c = (double)rounds * ((double)per + c0) + 0.02 * (double)sp;
+    if (c < best) { best = c; bestS = sp; }
+  }
+  return (int)bestS;
+}
+
+// Floats of split partials a weight-gradient call on Ks kernels may need, and never fewer than any call on fewer
+// kernels of the same layer needs (the split count grows as the slice shrinks).
+int64_t split_partial_elems(const Geo& g, int CT, int64_t nch, bool pipe_bound) {
+  int64_t need = 0;
+  for (int mb = 1; mb <= (g.Ks + cs::BM - 1) / cs::BM; ++mb) {
+    const int64_t ks = std::min<int64_t>(g.Ks, (int64_t)mb * cs::BM);
+    const int sp = choose_splits((int64_t)mb * CT, nch, pipe_bound);
+    if (sp > 1) need = std::max(need, (int64_t)sp * ks * g.CRS);
+  }
+  return need;
+}
+
+// Workgroups of a weight-gradient launch: one per (tile, split) when the reduction is split, else the whole tiles
+// plus the workgroups that share the tail.
+unsigned split_grid(int tiles, int splits, const cs::TailPlan& tail) {
+  if (splits > 1) return (unsigned)cs::grid_contiguous(tiles * splits);
+  return (unsigned)(cs::grid_contiguous(tail.nFull) + cs::grid_contiguous(tail.nTailWg));
 }
 
 struct BwdWeightPlan {
@@ -206,25 +253,20 @@ BwdWeightPlan plan_bwd_weight(const Geo& g) {
   p.MB = (g.Ks + cs::BM - 1) / cs::BM;
   p.CT = (g.CRS + cs::BN - 1) / cs::BN;
   p.nch = g.PQ * g.NB;
-  // Split the reduction until about four workgroups per compute unit exist, but keep
-  // at least four chunks per split so the pipeline prologue stays small.
   const int64_t tiles = (int64_t)(p.MB > 0 ? p.MB : 1) * p.CT;
-  int64_t want = (1024 + tiles - 1) / tiles;
-  const int64_t cap = p.nch / 4 > 0 ? p.nch / 4 : 1;
-  if (want > cap) want = cap;
-  if (want < 1) want = 1;
-  p.chPerSplit = (int)((p.nch + want - 1) / want);
-  p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;
+  p.splits = choose_splits(tiles, p.nch, true);
+  p.chPerSplit = (p.nch + p.splits - 1) / p.splits;
   size_t o = kZeroBytes;
   p.off_xt = o;   o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
-  p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
-  if (p.splits > 1) {   // already split over gridDim.y: whole tiles only
+  if (p.splits > 1) {   // the reduction is split: whole tiles only
     p.tail.nFull = (int)tiles; p.tail.nTail = 0; p.tail.units = 1; p.tail.nTailWg = 0;
   } else {
     p.tail = plan_tail((int)tiles, p.nch);
   }
-  p.off_tail = o; o += tail_bytes(p.tail);
+  // split partials or tail slots: a call uses one of them, in the same place
+  p.off_part = p.off_tail = o;
+  o += std::max(seg(split_partial_elems(g, p.CT, p.nch, true)), tail_bytes(p.nch));
   p.total = o;
   return p;
 }
@@ -276,7 +318,7 @@ Fwd16Plan plan_fwd16(const Geo& g) {
   p.off_w = o;    o += seg16((int64_t)g.Ks * g.RS * p.Cp);
   p.off_yt = o;   o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_zero = o; o += seg16((int64_t)32 * p.Cp + 64);   // a column block of zeros: 32 images x Cp channels
-  p.off_tail = o; o += tail_bytes(p.tail);
+  p.off_tail = o; o += tail_bytes(p.nch);
   p.total = o;
   return p;
 }
@@ -302,8 +344,9 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   // the runs are used only where one workgroup per tile would leave slots empty.
   const int MB = (g.C + cs::BM - 1) / cs::BM;
   p.run = plan_runs(g, MB, CT, p.Ksp / cs::BK16);
-  if ((int64_t)MB * CT >= chip_slots()) p.run.enabled = 0;
-  p.off_tail = o; o += p.run.enabled ? (size_t)p.run.nWg * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
+  const bool few = (int64_t)MB * CT < chip_slots();
+  if (!few) p.run.enabled = 0;
+  p.off_tail = o; o += few ? (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
   p.total = o;
   return p;
 }
@@ -320,12 +363,9 @@ BwdWeight16Plan plan_bwd_weight16(const Geo& g) {
   p.CT = (g.CRS + cs::BN - 1) / cs::BN;
   p.nch = g.PQ * (p.Np64 / cs::BK16);
   const int64_t tiles = (int64_t)p.MB * p.CT;
-  int64_t want = (1024 + tiles - 1) / tiles;
-  const int64_t cap = p.nch / 4 > 0 ? p.nch / 4 : 1;
-  if (want > cap) want = cap;
-  if (want < 1) want = 1;
-  p.chPerSplit = (int)((p.nch + want - 1) / want);
-  p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;
+  p.splits = choose_splits(tiles, p.nch, false);
+  p.chPerSplit = (p.nch + p.splits - 1) / p.splits;
+  p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;   // whole blocks of chPerSplit chunks: no empty split
   if (p.splits > 1) {
     p.tail.nFull = (int)tiles; p.tail.nTail = 0; p.tail.units = 1; p.tail.nTailWg = 0;
   } else {
@@ -334,8 +374,8 @@ BwdWeight16Plan plan_bwd_weight16(const Geo& g) {
   size_t o = kZeroBytes;
   p.off_xt = o;   o += seg16((int64_t)g.C * g.HW * p.Np64);
   p.off_dyt = o;  o += seg16((int64_t)g.Ks * g.PQ * p.Np64);
-  p.off_part = o; o += p.splits > 1 ? seg((int64_t)p.splits * g.Ks * g.CRS) : 0;
-  p.off_tail = o; o += tail_bytes(p.tail);
+  p.off_part = p.off_tail = o;   // split partials or tail slots: a call uses one of them
+  o += std::max(seg(split_partial_elems(g, p.CT, p.nch, false)), tail_bytes(p.nch));
   p.total = o;
   return p;
 }
@@ -481,7 +521,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Cp + 64);
     if ((rc = allow_big_lds(cs::fwd16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
     probe.begin(st);
-    hipLaunchKernelGGL(cs::fwd16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg), dim3(cs::NT),
+    hipLaunchKernelGGL(cs::fwd16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)), dim3(cs::NT),
                        cs::SMEM_BYTES, st, g, wp, p.Cp, xp, zero, yt, p.MB, p.CT, p.nch, p.tail, partial);
     if (p.tail.nTail > 0)
       hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
@@ -527,7 +567,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   float* partial = (float*)(base + p.off_tail);
   probe.begin(st);
   hipLaunchKernelGGL(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>,
-                     dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg), dim3(cs::NT), cs::SMEM_BYTES, st, g,
+                     dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
                      wmat, p.ldw, xt, tab, entries, yt, p.MB, p.CT, p.nch, p.tail, partial);
   if (p.tail.nTail > 0)
     hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
@@ -625,7 +665,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
     float* partial = (float*)(base + p.off_tail);
     probe.begin(st);
-    hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg),
+    hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)),
                        dim3(cs::NT), cs::SMEM_BYTES, st, g1, wt, p.Ksp, dyt, tab, entries, T, p.MB1, p.CT1, p.nch,
                        p.tail, partial);
     if (p.tail.nTail > 0)
@@ -709,9 +749,9 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
     float* partial = (float*)(base + p.off_tail);
     probe.begin(st);
     hipLaunchKernelGGL(pad16 ? cs::bwd_weight16_gemm_kernel<true> : cs::bwd_weight16_gemm_kernel<false>,
-                       dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg, p.splits),
+                       dim3(split_grid(p.MB * p.CT, p.splits, p.tail)),
                        dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt, p.Np64, out, sliceElems, p.MB, p.CT, p.nch,
-                       p.chPerSplit, p.tail, partial);
+                       p.chPerSplit, p.splits, p.tail, partial);
     if (p.tail.nTail > 0)
       hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
                          p.MB, p.CT, p.nch, p.tail);
@@ -745,8 +785,8 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   probe.begin(st);
   float* partial = (float*)(base + p.off_tail);
   hipLaunchKernelGGL(pad ? cs::bwd_weight_gemm_kernel<true> : cs::bwd_weight_gemm_kernel<false>,
-                     dim3(cs::grid_contiguous(p.tail.nFull) + p.tail.nTailWg, p.splits), dim3(cs::NT),
-                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.chPerSplit, p.tail, partial);
+                     dim3(split_grid(p.MB * p.CT, p.splits, p.tail)), dim3(cs::NT),
+                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.splits, p.tail, partial);
   if (p.tail.nTail > 0)
     hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
                        p.MB, p.CT, p.nch, p.tail);

@@ -472,19 +472,23 @@ __global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16
                                                                const bf16_t* __restrict__ xt, int Np64,
                                                                float* __restrict__ out, int64_t splitStride,
                                                                int MB, int CT, int nch, int chPerSplit,
-                                                               TailPlan tp, float* __restrict__ partial) {
+                                                               int splits, TailPlan tp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
-  const int z = blockIdx.y;
+  // split mode: workgroup -> (tile, split) as in the fp32 kernel; a split is a block of chPerSplit chunks
+  int z = 0, Lsplit = 0;
+  if (splits > 1) {
+    const int tiles = MB * CT;
+    int item;
+    if (!line_contiguous(blockIdx.x, tiles * splits, item)) return;
+    z = item / tiles;
+    Lsplit = item - z * tiles;
+  }
   const int ch0 = z * chPerSplit;
   const int ch1 = min(nch, ch0 + chPerSplit);
   float* o = out + (int64_t)z * splitStride;
-  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+  auto compute = [&](int L, int cb, int ce, bool direct, int slot) __attribute__((always_inline)) {
     int mb, ct;
     tile_from_line(L, MB, CT, mb, ct);
-    if (direct) {
-      cb = ch0;
-      ce = ch1;
-    }
     f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -497,7 +501,12 @@ __global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
     else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
-  });
+  };
+  if (splits > 1) {
+    compute(Lsplit, ch0, ch1, true, 0);
+    return;
+  }
+  for_each_segment(tp, nch, compute);
 }
 
 }  // namespace cs

@@ -150,7 +150,8 @@ __device__ __forceinline__ void for_each_segment(const TailPlan& tp, int nch, Bo
     if (line_contiguous(gid, tp.nFull, L)) body(L, 0, nch, true, 0);
     return;
   }
-  const int w = gid - gfull;
+  int w;   // the runs of the tail are dealt to the XCDs in contiguous blocks too: neighbours share operand panels
+  if (!line_contiguous(gid - gfull, tp.nTailWg, w)) return;
   int u0 = w * tp.units;
   const int u1 = min(u0 + tp.units, tp.nTail * nch);
   int tl = u0 / nch;
@@ -492,8 +493,9 @@ struct BwdWeightLoadA {
   const char* tile;   // uniform: row m0 of dy_t
   const char* ub;     // uniform: tile + the chunk being issued
   unsigned off[4];
-  __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0)
-      : tile((const char*)(dyt + (int64_t)m0 * g.PQ * g.Np)) {
+  int first, stride;  // step i of the walk is chunk first + i*stride
+  __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0, int first_, int stride_)
+      : tile((const char*)(dyt + (int64_t)m0 * g.PQ * g.Np)), first(first_), stride(stride_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -502,7 +504,7 @@ struct BwdWeightLoadA {
       off[i] = ((unsigned)m * (unsigned)(g.PQ * g.Np) + kq4) * 4u;
     }
   }
-  __device__ __forceinline__ void begin(int ch, bool live) { ub = tile + (int64_t)(live ? ch : 0) * (BK * 4); }  // dummy: chunk 0
+  __device__ __forceinline__ void begin(int i, bool live) { ub = tile + (int64_t)(live ? first + i * stride : 0) * (BK * 4); }  // dummy: chunk 0
   __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {}
 };
@@ -521,9 +523,10 @@ struct BwdWeightLoadB {
   int rj[4], sj[4];
   int NB, Q, sh, sw, ph, pw, H, W, Np;
   int p, q, nb;          // uniform position of the next chunk to issue
+  int dp, dq, dnb;       // one step of the walk (stride chunks) as a (p, q, nb) increment
   int h0, v0;            // uniform, of the chunk being issued
   unsigned uoff;
-  __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, int ch0)
+  __device__ BwdWeightLoadB(const Geo& g, const float* xt_, int j0, int ch0, int stride)
       : xt(PAD ? opaque_uniform(xt_ - ZERO_PAGE_FLOATS) : (const char*)xt_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     NB = g.NB; Q = g.Q; sh = g.sh; sw = g.sw; ph = g.ph; pw = g.pw; H = g.H; W = g.W; Np = g.Np;
@@ -541,6 +544,10 @@ struct BwdWeightLoadB {
     nb = ch0 - pix * NB;
     p = pix / Q;
     q = pix - p * Q;
+    const int dpix = stride / NB;
+    dnb = stride - dpix * NB;
+    dp = dpix / Q;
+    dq = dpix - dp * Q;
   }
   __device__ __forceinline__ void begin(int, bool live) {
     h0 = live ? p * sh - ph : 0;       // the dummy issue re-reads the first pixel
@@ -558,14 +565,14 @@ struct BwdWeightLoadB {
       dma16_uv(ub, coff[i], dst);
     }
   }
-  __device__ __forceinline__ void end() {   // branch-free carry: (nb, q, p) += 1 chunk
-    ++nb;
-    const int cq = nb == NB;
-    nb = cq ? 0 : nb;
-    q += cq;
-    const int cp = q == Q;
-    q = cp ? 0 : q;
-    p += cp;
+  __device__ __forceinline__ void end() {   // branch-free carry: (nb, q, p) += one step
+    nb += dnb;
+    const int cq = nb >= NB;
+    nb -= cq ? NB : 0;
+    q += dq + cq;
+    const int cp = q >= Q;
+    q -= cp ? Q : 0;
+    p += dp + cp;
   }
 };
 
@@ -591,25 +598,34 @@ __device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __res
 }
 
 // out[z][m][j]: partial (or final when one split) weight gradients of the slice.  Either
-// the reduction is split evenly over gridDim.y (small outputs; tp then has no tail) or
-// gridDim.y is 1 and tp shares out the tail tiles.
+// splits = 1 and tp shares out the tail tiles, or (small outputs) the reduction is split:
+// the tiles * splits work items (split-major) are dealt to the XCDs in contiguous blocks, so
+// that every XCD has work whatever the tile count and the tiles of one split, which share
+// operand rows, follow each other on one XCD.  grid = grid_contiguous(tiles * splits).  Split z
+// takes chunks z, z + splits, z + 2*splits, ...: the workgroups of all splits run side by
+// side, so together they read a contiguous stretch of every operand row at any moment.
 template <bool PAD>
 __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float* __restrict__ dyt,
                                                              const float* __restrict__ xt,
                                                              float* __restrict__ out, int64_t splitStride,
-                                                             int MB, int CT, int nch, int chPerSplit,
+                                                             int MB, int CT, int nch, int splits,
                                                              TailPlan tp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
-  const int z = blockIdx.y;
-  const int ch0 = z * chPerSplit;
-  const int ch1 = min(nch, ch0 + chPerSplit);
+  int z = 0, Lsplit = 0;
+  if (splits > 1) {
+    const int tiles = MB * CT;
+    int item;
+    if (!line_contiguous(blockIdx.x, tiles * splits, item)) return;
+    z = item / tiles;
+    Lsplit = item - z * tiles;
+  }
   float* o = out + (int64_t)z * splitStride;
-  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+  auto body = [&](int L, int cb, int ce, bool direct, int slot) {
     int mb, ct;
     tile_from_line(L, MB, CT, mb, ct);
-    if (direct) {   // whole tile: this split's chunk range
-      cb = ch0;
-      ce = ch1;
+    if (direct) {   // a whole tile: every chunk of this split
+      cb = 0;
+      ce = (nch - z + splits - 1) / splits;
     }
     f32x16 acc[2][2];
 #pragma unroll
@@ -618,12 +634,17 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    BwdWeightLoadA la(g, dyt, mb * BM);
-    BwdWeightLoadB<PAD> lb(g, xt, ct * BN, cb);
+    BwdWeightLoadA la(g, dyt, mb * BM, z, splits);
+    BwdWeightLoadB<PAD> lb(g, xt, ct * BN, z + cb * splits, splits);
     gemm_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
     else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
-  });
+  };
+  if (splits > 1) {
+    body(Lsplit, 0, 0, true, 0);
+    return;
+  }
+  for_each_segment(tp, nch, body);
 }
 
 __global__ __launch_bounds__(NT) void bwd_weight_tail_fixup_kernel(Geo g, const float* __restrict__ partial,

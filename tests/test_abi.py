@@ -73,6 +73,15 @@ def test_workspace_never_grows_when_the_slice_shrinks(layer, dtype):
             assert shifted == need, (p, k1)
 
 
+def test_workspace_is_monotone_over_every_slice_size():
+    layer = dict(N=64, C=128, H=56, W=56, K=300, R=3, S=3, pad_h=1, pad_w=1)
+    for dtype in (cs.CONV_F32, cs.CONV_BF16):
+        for p in (cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT):
+            sizes = [cs.conv_workspace_bytes(cs.ConvDesc(**layer, dtype=dtype, k0=0, k1=k1), p)
+                     for k1 in range(1, layer["K"] + 1)]
+            assert all(a <= b for a, b in zip(sizes, sizes[1:])), (dtype, p)
+
+
 class FakeBuf:
     """Stands in for a device tensor: the calls below must fail before using it."""
 
