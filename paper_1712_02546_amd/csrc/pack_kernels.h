@@ -164,11 +164,14 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
   tab[entries + i] = (r << 16) | s;
 }
 
-// Orders the H*W input pixels by decreasing tap count, ties in row-major order (a stable
-// counting sort by one workgroup, no atomics in the placement, so the order is the same
-// on every run).  perm[position] = pixel.  scratch holds H + W ints.
-// A pixel's tap count is rows(h) * cols(v), so its rank among equal counts is a sum over the
-// earlier image rows of "columns with the matching factor" plus a scan of its own row.
+// Orders the H*W input pixels by decreasing tap count (a counting sort by one workgroup; no
+// atomics in the placement, so the order is the same on every run).  perm[position] = pixel.
+// A pixel's tap count is a*b with a = rows(h) and b = cols(v) the taps that reach it along
+// each axis.  Pixels with the same count are ordered by a, then by the rank of their row among
+// the rows with that a, then by the rank of their column among the columns with that b, so a
+// pixel's position is a closed form of per-row and per-column ranks: no loop over the image.
+// Pixels no tap reaches (a*b = 0) come last: whole rows with a = 0 first, then the columns with
+// b = 0 of the other rows.  scratch holds 3*H + 2*W ints (used when they do not fit in LDS).
 //
 // With `pre` given it also lays the CT column tiles (four blocks of 32 images each, blocks
 // numbered position-major in the new order) on a line: a tile is as many chunks long as
@@ -179,13 +182,18 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
 __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
                                                                     int* __restrict__ scratch, int CT, int nkc,
                                                                     int nRuns, int* __restrict__ pre) {
-  __shared__ int bins[1026];    // pixels per tap count, then first position per tap count
-  __shared__ int ncolhist[1026];  // image columns per column-tap count
-  __shared__ int part[1024];    // scan of the tile lengths
-  int* nrow = scratch;
-  int* ncol = scratch + g.H;
+  __shared__ int bins[1026];     // pixels per tap count, then first position per tap count
+  __shared__ int rowCnt[34], colCnt[34];   // rows per a (0..R), columns per b (0..S)
+  __shared__ int part[1024];     // scan of the tile lengths
+  __shared__ int s_axes[4096];
+  const bool in_lds = 3 * g.H + 2 * g.W <= 4096;
+  int* nrow = in_lds ? s_axes : scratch;   // a of every row
+  int* rowRank = nrow + g.H;               // rank among the rows with the same a
+  int* nzRank = rowRank + g.H;             // rank among the rows with a > 0
+  int* ncol = nzRank + g.H;                // b of every column
+  int* colRank = ncol + g.W;               // rank among the columns with the same b
   for (int i = threadIdx.x; i <= g.RS + 1; i += blockDim.x) bins[i] = 0;
-  for (int i = threadIdx.x; i <= g.S + 1; i += blockDim.x) ncolhist[i] = 0;
+  if (threadIdx.x < 34) rowCnt[threadIdx.x] = colCnt[threadIdx.x] = 0;
   for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
     int n = 0;
     for (int r = 0; r < g.R; ++r) {
@@ -204,8 +212,31 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
   }
   __threadfence_block();
   __syncthreads();
-  for (int v = threadIdx.x; v < g.W; v += blockDim.x) atomicAdd(&ncolhist[ncol[v]], 1);   // counts only
-  for (int px = threadIdx.x; px < g.HW; px += blockDim.x) atomicAdd(&bins[nrow[px / g.W] * ncol[px % g.W]], 1);
+  for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
+    const int a = nrow[h];
+    int same = 0, nz = 0;
+    for (int hh = 0; hh < h; ++hh) {
+      const int o = nrow[hh];
+      same += o == a;
+      nz += o > 0;
+    }
+    rowRank[h] = same;
+    nzRank[h] = nz;
+    atomicAdd(&rowCnt[a], 1);   // counts only
+  }
+  for (int v = threadIdx.x; v < g.W; v += blockDim.x) {
+    const int b2 = ncol[v];
+    int same = 0;
+    for (int vv = 0; vv < v; ++vv) same += ncol[vv] == b2;
+    colRank[v] = same;
+    atomicAdd(&colCnt[b2], 1);
+  }
+  __threadfence_block();
+  __syncthreads();
+  for (int i = threadIdx.x; i < (g.R + 1) * (g.S + 1); i += blockDim.x) {
+    const int a = i / (g.S + 1), b2 = i - a * (g.S + 1);
+    atomicAdd(&bins[a * b2], rowCnt[a] * colCnt[b2]);   // counts only
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0;
@@ -218,16 +249,22 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
   __syncthreads();
   for (int px = threadIdx.x; px < g.HW; px += blockDim.x) {
     const int h = px / g.W, v = px - h * g.W;
-    const int nr = nrow[h];
-    const int wgt = nr * ncol[v];
-    int rank = 0;
-    for (int hh = 0; hh < h; ++hh) {   // pixels of earlier rows with the same tap count
-      const int a = nrow[hh];
-      if (a == 0) rank += wgt == 0 ? g.W : 0;
-      else if (wgt % a == 0 && wgt / a <= g.S) rank += ncolhist[wgt / a];
+    const int a = nrow[h], b2 = ncol[v];
+    const int wgt = a * b2;
+    int pos;
+    if (wgt > 0) {
+      int before = 0;   // pixels with the same count and a smaller a
+      for (int a2 = 1; a2 < a; ++a2) {
+        const int q = wgt / a2;
+        if (q * a2 == wgt && q <= g.S) before += rowCnt[a2] * colCnt[q];
+      }
+      pos = bins[wgt] + before + rowRank[h] * colCnt[b2] + colRank[v];
+    } else if (a == 0) {
+      pos = bins[0] + rowRank[h] * g.W + v;
+    } else {
+      pos = bins[0] + rowCnt[0] * g.W + nzRank[h] * colCnt[0] + colRank[v];
     }
-    for (int vv = 0; vv < v; ++vv) rank += nr * ncol[vv] == wgt;
-    perm[bins[wgt] + rank] = px;
+    perm[pos] = px;
   }
   if (pre == nullptr) return;
   __threadfence_block();
@@ -236,7 +273,15 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
   const int per = (CT + (int)blockDim.x - 1) / (int)blockDim.x;
   const int t0 = min((int)threadIdx.x * per, CT), t1 = min(t0 + per, CT);
   int sum = 0;
+  const bool one_pixel = g.NB % 4 == 0;   // every tile lies inside one pixel: its taps are a*b
   for (int ct = t0; ct < t1; ++ct) {
+    if (one_pixel) {
+      const int px = perm[ct / (g.NB >> 2)];
+      const int len = max(nrow[px / g.W] * ncol[px % g.W], 1) * nkc;
+      pre[ct + 1] = len;
+      sum += len;
+      continue;
+    }
     int hp[4], vp[4], np = 0;   // the tile's distinct pixels
     for (int j = 0; j < 4; ++j) {
       const int gcb = ct * 4 + j;
