@@ -166,18 +166,21 @@ __device__ __forceinline__ void dma16_uv(const char* base_uniform, unsigned& lan
 // wavefront's 16-byte LDS reads run at 256 bytes per clock, with m & 7 at half of that.
 __device__ __forceinline__ int col_key(int row) { return (row >> 1) & 7; }
 
-struct Frag {          // operands of four MFMA steps (one j) for the wavefront's two 32-wide blocks
-  f32x4 v[2];          // v[blk][t]
+template <int NBLK>
+struct FragN {         // operands of four MFMA steps (one j) for NBLK of the wavefront's 32-wide blocks
+  f32x4 v[NBLK];       // v[blk][t]
 };
+using Frag = FragN<2>;
 
-template <bool COL>
-__device__ __forceinline__ void read_frag(Frag& f, const float* tile, int wbase, int lane, int j, int blk1) {
+template <bool COL, int NBLK>
+__device__ __forceinline__ void read_frag(FragN<NBLK>& f, const float* tile, int wbase, int lane, int j, int blk1) {
   if constexpr (COL) {
     const int u = col_key(lane & 31), h = lane >> 5;
     const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
     f.v[0] = *(const f32x4*)(tile + slot * 4);
-    f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
+    if constexpr (NBLK == 2) f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
   } else {
+    static_assert(NBLK == 2, "row images always feed two blocks");
     // The second block lies blk1 = 32 floats to the right.  blk1 is an opaque register (see
     // opaque_block_offset), so the two blocks keep separate base registers and the reads of
     // rows t, t+1 of one block (512 bytes apart) pair up into LDS reads with 256-byte offset
@@ -197,14 +200,16 @@ __device__ __forceinline__ int opaque_block_offset() {
   return o;
 }
 
-// Sixteen MFMAs: four reduction steps on the wavefront's 2x2 accumulator blocks.
-__device__ __forceinline__ void mfma_group(const Frag& a, const Frag& b, f32x16 (&acc)[2][2]) {
+// Four reduction steps on the wavefront's MI x 2 accumulator blocks (sixteen MFMAs for MI = 2).
+template <int MI>
+__device__ __forceinline__ void mfma_group(const FragN<MI>& a, const Frag& b, f32x16 (&acc)[MI][2]) {
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[0][t], acc[0][0], 0, 0, 0);
-    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][t], b.v[1][t], acc[0][1], 0, 0, 0);
-    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[0][t], acc[1][0], 0, 0, 0);
-    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[1][t], b.v[1][t], acc[1][1], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[0][t], acc[i][0], 0, 0, 0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[1][t], acc[i][1], 0, 0, 0);
+    }
   }
 }
 
@@ -219,13 +224,16 @@ __device__ __forceinline__ void mfma_group(const Frag& a, const Frag& b, f32x16 
 // (chunks are requested in increasing order, once each; live = false marks chunks past the
 // last one, whose loads must stay harmless so that the loop body needs no branch).  LDS
 // holds [A stage0][A stage1][B stage0][B stage1].
+// The A operand has 64*MI rows (LA::MI = 2: the 128-row tile, 1: the half tile for a short
+// last row tile), i.e. 2*MI loads per wavefront and chunk.
 template <class LA, class LB>
 __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, float* tb, int wv, bool live) {
+  constexpr int MI = LA::MI;
   la.begin(ch, live);
   lb.begin(ch, live);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    la.issue(i, ta + (wv * 4 + i) * 256);
+    if (i < 2 * MI) la.issue(i, ta + (wv * 2 * MI + i) * 256);
     lb.issue(i, tb + (wv * 4 + i) * 256);
   }
   la.end();
@@ -239,15 +247,18 @@ __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, flo
 // chunk ch while G2,G3 are being read.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch_begin, int ch_end,
-                                              float* smem, f32x16 (&acc)[2][2]) {
+                                              float* smem, f32x16 (&acc)[LA::MI][2]) {
   constexpr bool AC = LA::COL, BC = LB::COL;
+  constexpr int MI = LA::MI;
+  static_assert(MI == 2 || AC, "the half tile needs a col-image A operand");
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wa = (wv >> 1) * 64, wb = (wv & 1) * 64;
+  const int wa = (wv >> 1) * (32 * MI), wb = (wv & 1) * 64;
   if (ch_begin >= ch_end) return;
   const int blk1 = opaque_block_offset();
-  Frag a0, b0, a1, b1;
+  FragN<MI> a0, a1;
+  Frag b0, b1;
   // prologue: chunk ch_begin into stage 0
   issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
   __syncthreads();  // includes the wait for this wavefront's own DMA loads
@@ -301,7 +312,7 @@ __device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch
 
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
-                                              float* smem, f32x16 (&acc)[2][2]) {
+                                              float* smem, f32x16 (&acc)[LA::MI][2]) {
   gemm_mainloop_one_barrier(la, lb, ch_begin, ch_end, smem, acc);
 }
 

@@ -98,6 +98,20 @@ inline size_t tail_bytes(int nch) {
   return nch >= 16 ? (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
 }
 
+// Row tiles of a matrix-core pass with M rows: `full` tiles of 128 rows and, when the rest is at most 64 rows, one
+// half tile (64 rows) for it, computed by a second launch; a rest above 64 rows takes a full tile.
+struct RowSplit {
+  int full, half;   // half = 1 if a half tile follows the full ones
+};
+RowSplit split_rows(int M) {
+  RowSplit r;
+  r.full = M / cs::BM;
+  const int rest = M - r.full * cs::BM;
+  r.half = rest > 0 && rest <= cs::BM / 2;
+  if (rest > cs::BM / 2) ++r.full;
+  return r;
+}
+
 struct FwdPlan {
   bool repitch;      // filters copied to zero-padded fp32 rows of pitch ldw (bf16 input, or C*R*S not a multiple of BK)
   int ldw, nch;
@@ -125,15 +139,15 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   return p;
 }
 
-// Even sharing of the input-gradient pass: the line of column tiles is measured and cut on the device (by the
-// ordering kernel); the host only fixes the number of runs.  Each run of the line is computed by MB workgroups,
-// one per row tile, which therefore walk through the same pixels, taps and k-chunks at the same time and share
-// the dy operand.
-cs::RunPlan plan_runs(const Geo& g, int MB, int CT, int64_t nkc) {
+// Even sharing of the input-gradient pass: the line of column tiles is measured on the device (by the ordering
+// kernel) and cut by the kernels themselves; the host only fixes the number of runs.  Each run of the line is
+// computed by MB workgroups, one per row tile, which therefore walk through the same pixels, taps and k-chunks at
+// the same time and share the dy operand.
+cs::RunPlan plan_runs(int MB, bool possible) {
   cs::RunPlan rp;
   rp.enabled = 0; rp.nRuns = 1; rp.nWg = 0;
   const int S = chip_slots();
-  if (S / MB < 1 || (int64_t)CT * g.RS * nkc >= (int64_t)1 << 30) return rp;   // the line would be too long for an int
+  if (!possible || S / MB < 1) return rp;
   rp.enabled = 1;
   rp.nRuns = S / MB;
   rp.nWg = rp.nRuns * MB;
@@ -144,7 +158,6 @@ struct BwdDataPlan {
   bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
   int Cp, Ksp, nch, MB1, CT1;   // Ksp: pitch of w' in the scatter form, a multiple of BK
   cs::TailPlan tail;
-  cs::RunPlan run;
   size_t off_dyt, off_wt, off_dxt, off_perm, off_pre, off_scratch, off_tab, off_T, off_tail, total;
 };
 
@@ -191,7 +204,6 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
   p.off_scratch = o; o += seg((int64_t)3 * g.H + 2 * g.W);
-  p.run = plan_runs(g, (g.C + cs::BM - 1) / cs::BM, CT, p.nch);
   p.off_tail = o; o += (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4;   // two slots per workgroup, whatever the slice
   p.total = o;
   return p;
@@ -224,13 +236,18 @@ int choose_splits(int64_t tiles, int64_t nch, bool pipe_bound) {
 }
 
 // Floats of split partials a weight-gradient call on Ks kernels may need, and never fewer than any call on fewer
-// kernels of the same layer needs (the split count grows as the slice shrinks).
+// kernels of the same layer needs (the split count grows as the slice shrinks).  A call makes one launch for its
+// full row tiles and one for a half tile; the launches follow each other and use the same place.
 int64_t split_partial_elems(const Geo& g, int CT, int64_t nch, bool pipe_bound) {
   int64_t need = 0;
-  for (int mb = 1; mb <= (g.Ks + cs::BM - 1) / cs::BM; ++mb) {
-    const int64_t ks = std::min<int64_t>(g.Ks, (int64_t)mb * cs::BM);
-    const int sp = choose_splits((int64_t)mb * CT, nch, pipe_bound);
-    if (sp > 1) need = std::max(need, (int64_t)sp * ks * g.CRS);
+  for (int t = 1; t <= (g.Ks + cs::BM - 1) / cs::BM; ++t) {
+    const int64_t rows = std::min<int64_t>(g.Ks, (int64_t)t * cs::BM);
+    const int sp = choose_splits((int64_t)t * CT, nch, pipe_bound);
+    if (sp > 1) need = std::max(need, (int64_t)sp * rows * g.CRS);
+  }
+  if (pipe_bound && g.Ks > 0) {   // the half tile (fp32 kernels only)
+    const int sp = choose_splits(CT, nch, pipe_bound);
+    if (sp > 1) need = std::max(need, (int64_t)sp * std::min(g.Ks, cs::BM / 2) * g.CRS);
   }
   return need;
 }
@@ -243,8 +260,7 @@ unsigned split_grid(int tiles, int splits, const cs::TailPlan& tail) {
 }
 
 struct BwdWeightPlan {
-  int MB, CT, nch, splits, chPerSplit;
-  cs::TailPlan tail;
+  int MB, CT, nch;
   size_t off_xt, off_dyt, off_part, off_tail, total;
 };
 
@@ -253,18 +269,10 @@ BwdWeightPlan plan_bwd_weight(const Geo& g) {
   p.MB = (g.Ks + cs::BM - 1) / cs::BM;
   p.CT = (g.CRS + cs::BN - 1) / cs::BN;
   p.nch = g.PQ * g.NB;
-  const int64_t tiles = (int64_t)(p.MB > 0 ? p.MB : 1) * p.CT;
-  p.splits = choose_splits(tiles, p.nch, true);
-  p.chPerSplit = (p.nch + p.splits - 1) / p.splits;
   size_t o = kZeroBytes;
   p.off_xt = o;   o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_dyt = o;  o += seg((int64_t)g.Ks * g.PQ * g.Np);
-  if (p.splits > 1) {   // the reduction is split: whole tiles only
-    p.tail.nFull = (int)tiles; p.tail.nTail = 0; p.tail.units = 1; p.tail.nTailWg = 0;
-  } else {
-    p.tail = plan_tail((int)tiles, p.nch);
-  }
-  // split partials or tail slots: a call uses one of them, in the same place
+  // split partials or tail slots: a launch uses one of them, in the same place
   p.off_part = p.off_tail = o;
   o += std::max(seg(split_partial_elems(g, p.CT, p.nch, true)), tail_bytes(p.nch));
   p.total = o;
@@ -343,9 +351,8 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   // With chunks this short the scratch round trip of the cut tiles costs about as much as uneven tiles do, so
   // the runs are used only where one workgroup per tile would leave slots empty.
   const int MB = (g.C + cs::BM - 1) / cs::BM;
-  p.run = plan_runs(g, MB, CT, p.Ksp / cs::BK16);
   const bool few = (int64_t)MB * CT < chip_slots();
-  if (!few) p.run.enabled = 0;
+  p.run = plan_runs(MB, few && (int64_t)CT * g.RS * (p.Ksp / cs::BK16) < (int64_t)1 << 30);
   p.off_tail = o; o += few ? (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
   p.total = o;
   return p;
@@ -493,6 +500,38 @@ size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
   }
 }
 
+// The forward kernel over all rows of g (g.Ks of them): full row tiles first, then the half tile, each with its
+// own tail plan; the two launches share the scratch slots (stream order keeps them apart).
+int launch_fwd_gemm(const Geo& g, bool pad, const float* wmat, int ldw, const float* xt, const int* tab, int entries,
+                    float* out, int CT, int nch, float* partial, hipStream_t st) {
+  int rc;
+  const RowSplit rs = split_rows(g.Ks);
+  if (rs.full > 0) {
+    auto kern = pad ? cs::fwd_gemm_kernel<true, 2> : cs::fwd_gemm_kernel<false, 2>;
+    if ((rc = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    const cs::TailPlan tp = plan_tail(rs.full * CT, nch);
+    hipLaunchKernelGGL(kern,
+                       dim3(cs::grid_contiguous(tp.nFull) + cs::grid_contiguous(tp.nTailWg)), dim3(cs::NT),
+                       cs::SMEM_BYTES, st, g, wmat, ldw, xt, tab, entries, out, 0, rs.full, CT, nch, tp, partial);
+    if (tp.nTail > 0)
+      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<2>, dim3(tp.nTail, 4), dim3(cs::NT), 0, st, g, partial, out, 0,
+                         rs.full, CT, nch, tp);
+  }
+  if (rs.half) {
+    auto kern = pad ? cs::fwd_gemm_kernel<true, 1> : cs::fwd_gemm_kernel<false, 1>;
+    if ((rc = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    const cs::TailPlan tp = plan_tail(CT, nch);
+    const int m0 = rs.full * cs::BM;
+    hipLaunchKernelGGL(kern,
+                       dim3(cs::grid_contiguous(tp.nFull) + cs::grid_contiguous(tp.nTailWg)), dim3(cs::NT),
+                       cs::SMEM_BYTES, st, g, wmat, ldw, xt, tab, entries, out, m0, 1, CT, nch, tp, partial);
+    if (tp.nTail > 0)
+      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<1>, dim3(tp.nTail, 2), dim3(cs::NT), 0, st, g, partial, out, m0, 1,
+                         CT, nch, tp);
+  }
+  return CONV_OK;
+}
+
 int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
              void* hip_stream) {
   const Probe probe;
@@ -524,7 +563,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
     hipLaunchKernelGGL(cs::fwd16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)), dim3(cs::NT),
                        cs::SMEM_BYTES, st, g, wp, p.Cp, xp, zero, yt, p.MB, p.CT, p.nch, p.tail, partial);
     if (p.tail.nTail > 0)
-      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
+      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<2>, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, 0, p.MB,
                          p.CT, p.nch, p.tail);
     probe.end(st);
     launch_transpose_out(CONV_BF16, false, yt, g.Np, g.N, g.Ks * g.PQ, (char*)y + (size_t)g.k0 * g.PQ * 2,
@@ -561,18 +600,11 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   int* tab = (int*)(base + p.off_tab);
   const int entries = (p.nch + 4) * cs::BK;
   hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, entries, tab);
-  const bool pad = needs_pad_checks(g);
-  if ((rc = allow_big_lds(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK)
-    return rc;
   float* partial = (float*)(base + p.off_tail);
   probe.begin(st);
-  hipLaunchKernelGGL(pad ? cs::fwd_gemm_kernel<true> : cs::fwd_gemm_kernel<false>,
-                     dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
-                     wmat, p.ldw, xt, tab, entries, yt, p.MB, p.CT, p.nch, p.tail, partial);
-  if (p.tail.nTail > 0)
-    hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, p.MB,
-                       p.CT, p.nch, p.tail);
+  rc = launch_fwd_gemm(g, needs_pad_checks(g), wmat, p.ldw, xt, tab, entries, yt, p.CT, p.nch, partial, st);
   probe.end(st);
+  if (rc != CONV_OK) return rc;
   // y_t[Ks*P*Q][Np] -> y[n][k0*P*Q + ...]
   launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
                        (char*)y + (size_t)g.k0 * g.PQ * es, (int64_t)g.K * g.PQ, st);
@@ -621,8 +653,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     int* pre = (int*)(base + p.off_pre);
     float* partial = (float*)(base + p.off_tail);
     hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm,
-                       (int*)(base + p.off_scratch), CT, p.Ksp / cs::BK16, p.run.nRuns,
-                       p.run.enabled ? pre : (int*)nullptr);
+                       (int*)(base + p.off_scratch), CT, p.Ksp / cs::BK16, p.run.enabled ? pre : (int*)nullptr);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Ksp + 64);
     const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
@@ -632,8 +663,8 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
                        dim3(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st, g,
                        wp, p.Ksp, dyp, zero, perm, pre, dxt, MB, CT, p.run, partial);
     if (p.run.enabled)
-      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
-                         MB, CT);
+      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<2>, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
+                         0, MB, CT, p.Ksp / cs::BK16, p.run.nRuns);
     probe.end(st);
     launch_transpose_out(CONV_BF16, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
     return check_launch();
@@ -662,16 +693,11 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
                         p.Ksp, p.Ksp, 1, nullptr, st);
     const int entries = (p.nch + 4) * cs::BK;
     hipLaunchKernelGGL(cs::fwd_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g1, entries, tab);
-    if ((rc = allow_big_lds(cs::fwd_gemm_kernel<false>, cs::SMEM_BYTES)) != CONV_OK) return rc;
     float* partial = (float*)(base + p.off_tail);
     probe.begin(st);
-    hipLaunchKernelGGL(cs::fwd_gemm_kernel<false>, dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)),
-                       dim3(cs::NT), cs::SMEM_BYTES, st, g1, wt, p.Ksp, dyt, tab, entries, T, p.MB1, p.CT1, p.nch,
-                       p.tail, partial);
-    if (p.tail.nTail > 0)
-      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g1, partial, T, p.MB1,
-                         p.CT1, p.nch, p.tail);
+    rc = launch_fwd_gemm(g1, false, wt, p.Ksp, dyt, tab, entries, T, p.CT1, p.nch, partial, st);
     probe.end(st);
+    if (rc != CONV_OK) return rc;
     const dim3 grid((g.C * g.HW + cs::COL2IM_ROWS - 1) / cs::COL2IM_ROWS, (g.N + 63) / 64);
     const bool acc = desc->accumulate != 0;
     if (desc->dtype == CONV_F32) {
@@ -700,19 +726,35 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   int* pre = (int*)(base + p.off_pre);
   int* scratch = (int*)(base + p.off_scratch);
   float* partial = (float*)(base + p.off_tail);
-  const int MB = (g.C + cs::BM - 1) / cs::BM;
   const int CT = (g.HW * g.NB + 3) / 4;
+  const bool runs = (int64_t)CT * g.RS * p.nch < (int64_t)1 << 30;   // else the line would be too long for an int
   hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm, scratch, CT, p.nch,
-                     p.run.nRuns, p.run.enabled ? pre : (int*)nullptr);
+                     runs ? pre : (int*)nullptr);
   // tiles + tap list + per-block tap offsets
   const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
-  if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel, lds)) != CONV_OK) return rc;
+  // Channels in full row tiles first, then the half tile for a rest of at most 64 channels; both launches walk the
+  // same line of column tiles and share the scratch slots (stream order keeps them apart).
+  const RowSplit rs = split_rows(g.C);
   probe.begin(st);
-  hipLaunchKernelGGL(cs::bwd_data_gemm_kernel, dim3(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT)), dim3(cs::NT),
-                     lds, st, g, wt, p.Ksp, dyt, perm, pre, dxt, MB, CT, p.run, partial);
-  if (p.run.enabled)
-    hipLaunchKernelGGL(cs::bwd_data_fixup_kernel, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
-                       MB, CT);
+  if (rs.full > 0) {
+    if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel<2>, lds)) != CONV_OK) return rc;
+    const cs::RunPlan rp = plan_runs(rs.full, runs);
+    hipLaunchKernelGGL(cs::bwd_data_gemm_kernel<2>, dim3(rp.enabled ? (rp.nWg + 7) / 8 * 8 : cs::grid_dealt(rs.full, CT)),
+                       dim3(cs::NT), lds, st, g, wt, p.Ksp, dyt, perm, pre, dxt, 0, rs.full, CT, rp, partial);
+    if (rp.enabled)
+      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<2>, dim3(CT * rs.full, 4), dim3(cs::NT), 0, st, g, perm, pre, partial,
+                         dxt, 0, rs.full, CT, p.nch, rp.nRuns);
+  }
+  if (rs.half) {
+    if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel<1>, lds)) != CONV_OK) return rc;
+    const cs::RunPlan rp = plan_runs(1, runs);
+    const int c0 = rs.full * cs::BM;
+    hipLaunchKernelGGL(cs::bwd_data_gemm_kernel<1>, dim3(rp.enabled ? (rp.nWg + 7) / 8 * 8 : cs::grid_dealt(1, CT)),
+                       dim3(cs::NT), lds, st, g, wt, p.Ksp, dyt, perm, pre, dxt, c0, 1, CT, rp, partial);
+    if (rp.enabled)
+      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<1>, dim3(CT, 2), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt, c0,
+                         1, CT, p.nch, rp.nRuns);
+  }
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
@@ -753,8 +795,8 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
                        dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt, p.Np64, out, sliceElems, p.MB, p.CT, p.nch,
                        p.chPerSplit, p.splits, p.tail, partial);
     if (p.tail.nTail > 0)
-      hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
-                         p.MB, p.CT, p.nch, p.tail);
+      hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel<2>, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
+                         0, 0, p.MB, p.CT, p.nch, p.tail);
     probe.end(st);
     if (p.splits > 1) {
       const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);
@@ -777,25 +819,42 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
                       g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, nullptr, st);
   const bool pad = needs_pad_checks(g);
-  if ((rc = allow_big_lds(pad ? cs::bwd_weight_gemm_kernel<true> : cs::bwd_weight_gemm_kernel<false>,
-                          cs::SMEM_BYTES)) != CONV_OK)
-    return rc;
-  const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
-  float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
+  float* scratch = (float*)(base + p.off_part);   // split partials or tail slots
+  // One launch over `tiles` row tiles of 64*mi rows from row m0: the reduction split (partials, then a sum in
+  // split order) or whole tiles with a shared tail.
+  auto launch = [&](auto kern, auto fixup, int mi, int m0, int tiles) -> int {
+    int rc2;
+    if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
+    const int rows = std::min(g.Ks - m0, tiles * 64 * mi);
+    const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true);
+    cs::TailPlan tp;
+    if (splits > 1) { tp.nFull = tiles * p.CT; tp.nTail = 0; tp.units = 1; tp.nTailWg = 0; }
+    else tp = plan_tail(tiles * p.CT, p.nch);
+    const int64_t stride = (int64_t)rows * g.CRS;
+    float* out = splits > 1 ? scratch : dwslice;
+    const int rowBase = splits > 1 ? m0 : 0;
+    hipLaunchKernelGGL(kern, dim3(split_grid(tiles * p.CT, splits, tp)), dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt,
+                       out, stride, m0, rowBase, tiles, p.CT, p.nch, splits, tp, scratch);
+    if (tp.nTail > 0)
+      hipLaunchKernelGGL(fixup, dim3(tp.nTail, 2 * mi), dim3(cs::NT), 0, st, g, scratch, out, m0, rowBase, tiles, p.CT,
+                         p.nch, tp);
+    if (splits > 1) {
+      const int blocks = (int)((stride + 255) / 256 < 8192 ? (stride + 255) / 256 : 8192);
+      hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, scratch, stride, splits,
+                         dwslice + (int64_t)m0 * g.CRS, stride);
+    }
+    return CONV_OK;
+  };
+  const RowSplit rs = split_rows(g.Ks);
   probe.begin(st);
-  float* partial = (float*)(base + p.off_tail);
-  hipLaunchKernelGGL(pad ? cs::bwd_weight_gemm_kernel<true> : cs::bwd_weight_gemm_kernel<false>,
-                     dim3(split_grid(p.MB * p.CT, p.splits, p.tail)), dim3(cs::NT),
-                     cs::SMEM_BYTES, st, g, dyt, xt, out, sliceElems, p.MB, p.CT, p.nch, p.splits, p.tail, partial);
-  if (p.tail.nTail > 0)
-    hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
-                       p.MB, p.CT, p.nch, p.tail);
+  if (rs.full > 0)
+    rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 2>, cs::bwd_weight_tail_fixup_kernel<2>, 2, 0, rs.full)
+             : launch(cs::bwd_weight_gemm_kernel<false, 2>, cs::bwd_weight_tail_fixup_kernel<2>, 2, 0, rs.full);
+  if (rc == CONV_OK && rs.half)
+    rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 1>, cs::bwd_weight_tail_fixup_kernel<1>, 1, rs.full * cs::BM, 1)
+             : launch(cs::bwd_weight_gemm_kernel<false, 1>, cs::bwd_weight_tail_fixup_kernel<1>, 1, rs.full * cs::BM, 1);
   probe.end(st);
-  if (p.splits > 1) {
-    const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);
-    hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, out, sliceElems, p.splits,
-                       dwslice, sliceElems);
-  }
+  if (rc != CONV_OK) return rc;
   return check_launch();
 }
 

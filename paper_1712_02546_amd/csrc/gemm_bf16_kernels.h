@@ -211,8 +211,8 @@ __global__ __launch_bounds__(NT) void fwd16_gemm_kernel(Geo g, const bf16_t* __r
     Fwd16LoadA la(w, (int64_t)g.RS * Cp, mb * BM, g.Ks);
     Fwd16LoadB lb(g, x, zero, Cp, ct, cb);
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
-    if (direct) fwd_store_tile(g, yt, mb, ct, acc);
-    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+    if (direct) fwd_store_tile<2>(g, yt, mb * BM, ct, acc);
+    else store_partial<2>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
   });
 }
 
@@ -354,9 +354,9 @@ __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) bwd_data_store_block(g, dxt, perm, mb, ct, i, j, acc[i][j]);
+        for (int i = 0; i < 2; ++i) bwd_data_store_block<2>(g, dxt, perm, mb * BM, ct, i, j, acc[i][j]);
     } else {
-      store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+      store_partial<2>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
     }
     __syncthreads();   // the next segment rewrites the tap list
   };
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t
   const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   if (wg >= rp.nWg) return;
   const int run = wg / MB, mb = wg - run * MB;
-  const int total = pre[CT], units = pre[CT + 1];
+  const int total = pre[CT], units = run_units(total, nkc, rp.nRuns);
   if ((int64_t)run * units >= total) return;
   int pos = run * units;
   const int end = min(pos + units, total);
@@ -499,8 +499,8 @@ __global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16
     BwdWeight16LoadA la(dyt, (int64_t)g.PQ * Np64, mb * BM, g.Ks);
     BwdWeight16LoadB<PAD> lb(g, xt, Np64, ct * BN, cb);
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
-    if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
-    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+    if (direct) bwd_weight_store_tile<2>(g, o, mb * BM, 0, ct, acc);
+    else store_partial<2>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
   };
   if (splits > 1) {
     compute(Lsplit, ch0, ch1, true, 0);

@@ -16,17 +16,19 @@ __device__ __forceinline__ float* dma_dst(float* tile, int wv, int i) { return t
 // A[m][kk] = w[k0+m0+m][kk]: rows of the filter matrix, col image.  The row pitch ldw is a
 // multiple of BK and rows are zero past C*R*S, so no lane ever needs a mask: a lane's byte
 // offset from the tile's first row is fixed and only the uniform base moves along the rows.
+template <int MI_>
 struct FwdLoadA {
   static constexpr bool COL = true;
+  static constexpr int MI = MI_;   // tile rows / 64
   const char* tile;   // uniform: row m0 of the filter matrix
   const char* ub;     // uniform: tile + the chunk being issued
-  unsigned off[4];
+  unsigned off[2 * MI];
   __device__ FwdLoadA(const float* w, int ldw, int m0, int Ks) : tile((const char*)(w + (int64_t)m0 * ldw)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2 * MI; ++i) {
       const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-      const int m = min(32 * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
+      const int m = min(16 * MI * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
       off[i] = ((unsigned)m * (unsigned)ldw + kq4) * 4u;
     }
   }
@@ -114,9 +116,10 @@ struct FwdLoadB {
 };
 
 // Accumulator images in wavefront layout: element e = (i*2+j)*16+v of thread t at [e*NT + t].
-__device__ __forceinline__ void store_partial(float* slot, const f32x16 (&acc)[2][2]) {
+template <int MI>
+__device__ __forceinline__ void store_partial(float* slot, const f32x16 (&acc)[MI][2]) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -166,7 +169,9 @@ __device__ __forceinline__ void for_each_segment(const TailPlan& tp, int nch, Bo
 }
 
 // Stores accumulator block (i,j) of this wavefront: 32 kernels x 32 images of one pixel.
-__device__ __forceinline__ void fwd_store_block(const Geo& g, float* __restrict__ yt, int mb, int ct, int i, int j,
+// m0 = first row of the tile, MI = tile rows / 64.
+template <int MI>
+__device__ __forceinline__ void fwd_store_block(const Geo& g, float* __restrict__ yt, int m0, int ct, int i, int j,
                                                 const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -176,56 +181,60 @@ __device__ __forceinline__ void fwd_store_block(const Geo& g, float* __restrict_
   const int n = nb * 32 + (lane & 31);
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int m = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
+    const int m = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
     if (m < g.Ks) yt[((int64_t)m * g.PQ + pix) * g.Np + n] = acc[v];
   }
 }
 
-__device__ __forceinline__ void fwd_store_tile(const Geo& g, float* __restrict__ yt, int mb, int ct,
-                                               const f32x16 (&acc)[2][2]) {
+template <int MI>
+__device__ __forceinline__ void fwd_store_tile(const Geo& g, float* __restrict__ yt, int m0, int ct,
+                                               const f32x16 (&acc)[MI][2]) {
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fwd_store_block(g, yt, mb, ct, i, j, acc[i][j]);
+    for (int i = 0; i < MI; ++i) fwd_store_block<MI>(g, yt, m0, ct, i, j, acc[i][j]);
 }
 
-// y_t[k][pix][n] for the slice; a tile is 128 kernels x 4 column blocks.
-template <bool PAD>
+// y_t[k][pix][n] for rows mOrigin .. of the slice; a tile is 64*MI kernels x 4 column blocks
+// and MB counts the row tiles of this launch.
+template <bool PAD, int MI>
 __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __restrict__ w, int ldw,
                                                       const float* __restrict__ xt,
                                                       const int* __restrict__ tab, int entries,
-                                                      float* __restrict__ yt, int MB, int CT, int nch,
+                                                      float* __restrict__ yt, int mOrigin, int MB, int CT, int nch,
                                                       TailPlan tp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
   for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
     int mb, ct;
     tile_from_line(L, MB, CT, mb, ct);
-    f32x16 acc[2][2];
+    const int m0 = mOrigin + mb * (64 * MI);
+    f32x16 acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    FwdLoadA la(w, ldw, mb * BM, g.Ks);
+    FwdLoadA<MI> la(w, ldw, m0, g.Ks);
     FwdLoadB<PAD> lb(g, xt, tab, entries, ct, cb);
     gemm_mainloop(la, lb, cb, ce, smem, acc);
-    if (direct) fwd_store_tile(g, yt, mb, ct, acc);
-    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+    if (direct) fwd_store_tile<MI>(g, yt, m0, ct, acc);
+    else store_partial<MI>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
   });
 }
 
-// Adds up the scratch slots of each tail tile and stores the tile.  grid = (nTail, 4): one
+// Adds up the scratch slots of each tail tile and stores the tile.  grid = (nTail, 2*MI): one
 // workgroup per tile and accumulator block.
+template <int MI>
 __global__ __launch_bounds__(NT) void fwd_tail_fixup_kernel(Geo g, const float* __restrict__ partial,
-                                                            float* __restrict__ yt, int MB, int CT, int nch,
-                                                            TailPlan tp) {
+                                                            float* __restrict__ yt, int mOrigin, int MB, int CT,
+                                                            int nch, TailPlan tp) {
   const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
   f32x16 acc;
   gather_partials(partial, tp, nch, blockIdx.x, bi, bj, acc);
   int mb, ct;
   tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
-  fwd_store_block(g, yt, mb, ct, bi, bj, acc);
+  fwd_store_block<MI>(g, yt, mOrigin + mb * (64 * MI), ct, bi, bj, acc);
 }
 
 // --------------------------------------------------------- input gradient ----
@@ -247,12 +256,14 @@ struct TapWalk {
 // A[c][k] = w_t[tap][c][k] (filters re-laid tap-major with k innermost, pitch Ksp = 32*nkc,
 // zero past Ks), col image, like the forward pass's filter operand: the uniform base is the
 // chunk's (tap, k) position in the tile's first channel row, a lane's offset never changes.
+template <int MI_>
 struct BwdDataLoadA {
   static constexpr bool COL = true;
+  static constexpr int MI = MI_;   // tile rows / 64
   const char* wt;     // uniform: w_t at channel m0 of tap 0
   const char* ub;     // uniform base of the chunk being issued
   const int* taps;
-  unsigned off[4];
+  unsigned off[2 * MI];
   unsigned tapBytes;  // one tap: C rows (a whole work copy is below 4 GiB)
   int tap;            // flat tap r*S+s of walk.ti, fetched one call ahead (uniform, held in a vector register)
   TapWalk walk;
@@ -260,9 +271,9 @@ struct BwdDataLoadA {
       : wt((const char*)(wt_ + (int64_t)m0 * Ksp)), taps(taps_), tapBytes((unsigned)g.C * (unsigned)Ksp * 4u), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2 * MI; ++i) {
       const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-      const int c = min(32 * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // channels past the end repeat the last one (never stored)
+      const int c = min(16 * MI * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // channels past the end repeat the last one (never stored)
       off[i] = ((unsigned)c * (unsigned)Ksp + kq4) * 4u;
     }
     tap = taps[walk.ti];
@@ -316,8 +327,8 @@ struct BwdDataLoadB {
 
 // Even sharing of the input-gradient pass (tiles of unequal cost).  The column tiles, pixels
 // by decreasing tap count, form a line on which tile ct covers chunks pre[ct] .. pre[ct+1]
-// (its taps times the k-chunks; the ordering kernel writes pre, the line's length pre[CT] and
-// the run length pre[CT+1]).  The line is cut into equal runs, and each run is computed by MB
+// (its taps times the k-chunks; the ordering kernel writes pre and the line's length pre[CT]).
+// The line is cut into nRuns equal runs (run_units), and each run is computed by MB
 // workgroups, one per row tile (nWg = nRuns * MB): workgroup run*MB+mb computes row tile mb of
 // the column tiles inside its run whole and of the (at most two) tiles that stick out at either
 // end partially, into scratch slot 2*wg (the tile its run starts in) or 2*wg+1; a fix-up kernel
@@ -327,8 +338,19 @@ struct RunPlan {
   int enabled, nRuns, nWg;
 };
 
+// Length of the equal runs a line of `total` chunks is cut into for nRuns groups: whole taps
+// (nkc chunks) when that leaves less than 3 % of the slots idle, any number of chunks
+// otherwise (few, long taps); at least 8.
+__device__ __forceinline__ int run_units(int total, int nkc, int nRuns) {
+  int units = ((total / nkc + nRuns - 1) / nRuns) * nkc;
+  if ((float)total < 0.97f * (float)nRuns * (float)units) units = (total + nRuns - 1) / nRuns;
+  return max(units, 8);
+}
+
+// m0 = first channel of the tile, MI = tile rows / 64.
+template <int MI>
 __device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __restrict__ dxt,
-                                                     const int* __restrict__ perm, int mb, int ct, int i, int j,
+                                                     const int* __restrict__ perm, int m0, int ct, int i, int j,
                                                      const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -339,18 +361,20 @@ __device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __rest
   const int n = nb * 32 + (lane & 31);
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int c = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
+    const int c = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
     if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[v];
   }
 }
 
-// dx_t[c][pixel][n]; column tiles follow the pixel order in perm.
+// dx_t[c][pixel][n] for channels mOrigin .. in MB row tiles of 64*MI channels; column tiles
+// follow the pixel order in perm.
+template <int MI>
 __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* __restrict__ wt, int Ksp,
                                                            const float* __restrict__ dyt,
                                                            const int* __restrict__ perm,
                                                            const int* __restrict__ pre,
-                                                           float* __restrict__ dxt, int MB, int CT, RunPlan rp,
-                                                           float* __restrict__ partial) {
+                                                           float* __restrict__ dxt, int mOrigin, int MB, int CT,
+                                                           RunPlan rp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
   int* s_taps = (int*)(smem + 4 * TILE_F);     // [RS + 3]: the loaders run up to three entries past the list
   int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][4]
@@ -406,23 +430,24 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
     __syncthreads();
     const int nchunks = s_ntaps * nkc;
     const int cb = min(c0, nchunks), ce = min(c1, nchunks);
-    f32x16 acc[2][2];
+    const int m0 = mOrigin + mb * (64 * MI);
+    f32x16 acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    BwdDataLoadA la(g, wt, Ksp, mb * BM, s_taps, nkc, cb);
+    BwdDataLoadA<MI> la(g, wt, Ksp, m0, s_taps, nkc, cb);
     BwdDataLoadB lb(g, dyt, s_tapoff, nkc, cb);
     gemm_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) {
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) bwd_data_store_block(g, dxt, perm, mb, ct, i, j, acc[i][j]);
+        for (int i = 0; i < MI; ++i) bwd_data_store_block<MI>(g, dxt, perm, m0, ct, i, j, acc[i][j]);
     } else {
-      store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+      store_partial<MI>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
     }
     __syncthreads();   // the next segment rewrites the tap list
   };
@@ -438,7 +463,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
   const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   if (wg >= rp.nWg) return;
   const int run = wg / MB, mb = wg - run * MB;
-  const int total = pre[CT], units = pre[CT + 1];
+  const int total = pre[CT], units = run_units(total, nkc, rp.nRuns);
   if ((int64_t)run * units >= total) return;
   int pos = run * units;
   const int end = min(pos + units, total);
@@ -460,13 +485,16 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
   }
 }
 
-// Adds up the scratch slots of every tile that was cut by a run boundary.  grid = (CT*MB, 4).
+// Adds up the scratch slots of every tile that was cut by a run boundary.  grid = (CT*MB, 2*MI);
+// nkc and nRuns as in the kernel that wrote the slots.
+template <int MI>
 __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __restrict__ perm,
                                                             const int* __restrict__ pre,
                                                             const float* __restrict__ partial,
-                                                            float* __restrict__ dxt, int MB, int CT) {
+                                                            float* __restrict__ dxt, int mOrigin, int MB, int CT,
+                                                            int nkc, int nRuns) {
   const int ct = blockIdx.x / MB, mb = blockIdx.x - ct * MB;
-  const int units = pre[CT + 1];
+  const int units = run_units(pre[CT], nkc, nRuns);
   const int a = pre[ct], b = pre[ct + 1];   // the tile's stretch of the line
   const int r0 = a / units, r1 = (b - 1) / units;
   if (r0 == r1) return;   // inside one run: stored directly
@@ -480,7 +508,7 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];
   }
-  bwd_data_store_block(g, dxt, perm, mb, ct, bi, bj, acc);
+  bwd_data_store_block<MI>(g, dxt, perm, mOrigin + mb * (64 * MI), ct, bi, bj, acc);
 }
 
 // ---------------------------------------------------------- weight gradient ----
@@ -488,19 +516,21 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
 // ch / NB, images nb*32 .. nb*32+31 with nb = ch % NB.
 // A[m][kk] = dy_t[m0+m][ch*32 + kk]: rows of dy_t, col image.  A lane's offset from the
 // tile's first row never changes; the uniform base advances by one chunk.
+template <int MI_>
 struct BwdWeightLoadA {
   static constexpr bool COL = true;
+  static constexpr int MI = MI_;   // tile rows / 64
   const char* tile;   // uniform: row m0 of dy_t
   const char* ub;     // uniform: tile + the chunk being issued
-  unsigned off[4];
+  unsigned off[2 * MI];
   int first, stride;  // step i of the walk is chunk first + i*stride
   __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0, int first_, int stride_)
       : tile((const char*)(dyt + (int64_t)m0 * g.PQ * g.Np)), first(first_), stride(stride_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2 * MI; ++i) {
       const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-      const int m = min(32 * wv + 8 * i + (l >> 3), g.Ks - 1 - m0);  // rows past the slice repeat the last one
+      const int m = min(16 * MI * wv + 8 * i + (l >> 3), g.Ks - 1 - m0);  // rows past the slice repeat the last one
       off[i] = ((unsigned)m * (unsigned)(g.PQ * g.Np) + kq4) * 4u;
     }
   }
@@ -576,25 +606,28 @@ struct BwdWeightLoadB {
   }
 };
 
-__device__ __forceinline__ void bwd_weight_store_block(const Geo& g, float* __restrict__ o, int mb, int ct, int i,
-                                                       int j, const f32x16& acc) {
+// m0 = first row of the tile, MI = tile rows / 64; row m goes to row m - rowBase of `o`.
+template <int MI>
+__device__ __forceinline__ void bwd_weight_store_block(const Geo& g, float* __restrict__ o, int m0, int rowBase,
+                                                       int ct, int i, int j, const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
   if (col >= g.CRS) return;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int m = mb * BM + wm * 64 + i * 32 + acc_row(v, lane);
-    if (m < g.Ks) o[(int64_t)m * g.CRS + col] = acc[v];
+    const int m = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
+    if (m < g.Ks) o[(int64_t)(m - rowBase) * g.CRS + col] = acc[v];
   }
 }
 
-__device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __restrict__ o, int mb, int ct,
-                                                      const f32x16 (&acc)[2][2]) {
+template <int MI>
+__device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __restrict__ o, int m0, int rowBase, int ct,
+                                                      const f32x16 (&acc)[MI][2]) {
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) bwd_weight_store_block(g, o, mb, ct, i, j, acc[i][j]);
+    for (int i = 0; i < MI; ++i) bwd_weight_store_block<MI>(g, o, m0, rowBase, ct, i, j, acc[i][j]);
 }
 
 // out[z][m][j]: partial (or final when one split) weight gradients of the slice.  Either
@@ -604,12 +637,12 @@ __device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __res
 // operand rows, follow each other on one XCD.  grid = grid_contiguous(tiles * splits).  Split z
 // takes chunks z, z + splits, z + 2*splits, ...: the workgroups of all splits run side by
 // side, so together they read a contiguous stretch of every operand row at any moment.
-template <bool PAD>
+template <bool PAD, int MI>
 __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float* __restrict__ dyt,
                                                              const float* __restrict__ xt,
                                                              float* __restrict__ out, int64_t splitStride,
-                                                             int MB, int CT, int nch, int splits,
-                                                             TailPlan tp, float* __restrict__ partial) {
+                                                             int mOrigin, int rowBase, int MB, int CT, int nch,
+                                                             int splits, TailPlan tp, float* __restrict__ partial) {
   extern __shared__ __align__(16) float smem[];
   int z = 0, Lsplit = 0;
   if (splits > 1) {
@@ -623,22 +656,23 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
   auto body = [&](int L, int cb, int ce, bool direct, int slot) {
     int mb, ct;
     tile_from_line(L, MB, CT, mb, ct);
+    const int m0 = mOrigin + mb * (64 * MI);
     if (direct) {   // a whole tile: every chunk of this split
       cb = 0;
       ce = (nch - z + splits - 1) / splits;
     }
-    f32x16 acc[2][2];
+    f32x16 acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    BwdWeightLoadA la(g, dyt, mb * BM, z, splits);
+    BwdWeightLoadA<MI> la(g, dyt, m0, z, splits);
     BwdWeightLoadB<PAD> lb(g, xt, ct * BN, z + cb * splits, splits);
     gemm_mainloop(la, lb, cb, ce, smem, acc);
-    if (direct) bwd_weight_store_tile(g, o, mb, ct, acc);
-    else store_partial(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
+    if (direct) bwd_weight_store_tile<MI>(g, o, m0, rowBase, ct, acc);
+    else store_partial<MI>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
   };
   if (splits > 1) {
     body(Lsplit, 0, 0, true, 0);
@@ -647,15 +681,17 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
   for_each_segment(tp, nch, body);
 }
 
+// grid = (nTail, 2*MI)
+template <int MI>
 __global__ __launch_bounds__(NT) void bwd_weight_tail_fixup_kernel(Geo g, const float* __restrict__ partial,
-                                                                   float* __restrict__ out, int MB, int CT,
-                                                                   int nch, TailPlan tp) {
+                                                                   float* __restrict__ out, int mOrigin, int rowBase,
+                                                                   int MB, int CT, int nch, TailPlan tp) {
   const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
   f32x16 acc;
   gather_partials(partial, tp, nch, blockIdx.x, bi, bj, acc);
   int mb, ct;
   tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
-  bwd_weight_store_block(g, out, mb, ct, bi, bj, acc);
+  bwd_weight_store_block<MI>(g, out, mOrigin + mb * (64 * MI), rowBase, ct, bi, bj, acc);
 }
 
 }  // namespace cs

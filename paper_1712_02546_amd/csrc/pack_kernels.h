@@ -176,12 +176,10 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
 // With `pre` given it also lays the CT column tiles (four blocks of 32 images each, blocks
 // numbered position-major in the new order) on a line: a tile is as many chunks long as
 // nkc times the number of taps that reach any of its pixels (at least one), pre[ct] is
-// where tile ct starts, pre[CT] the length of the line, and pre[CT+1] the length of the
-// equal runs it is cut into for nRuns workgroup groups: whole taps (nkc chunks) when that
-// leaves less than 3 % of the slots idle, any number of chunks otherwise, at least 8.
+// where tile ct starts and pre[CT] the length of the line.
 __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
                                                                     int* __restrict__ scratch, int CT, int nkc,
-                                                                    int nRuns, int* __restrict__ pre) {
+                                                                    int* __restrict__ pre) {
   __shared__ int bins[1026];     // pixels per tap count, then first position per tap count
   __shared__ int rowCnt[34], colCnt[34];   // rows per a (0..R), columns per b (0..S)
   __shared__ int part[1024];     // scan of the tile lengths
@@ -320,13 +318,7 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
     run += pre[ct + 1];
     pre[ct + 1] = run;
   }
-  if (threadIdx.x == 0) {
-    pre[0] = 0;
-    const int total = part[blockDim.x - 1];
-    int units = ((total / nkc + nRuns - 1) / nRuns) * nkc;
-    if ((double)total < 0.97 * (double)nRuns * units) units = (total + nRuns - 1) / nRuns;
-    pre[CT + 1] = max(units, 8);
-  }
+  if (threadIdx.x == 0) pre[0] = 0;
 }
 
 template <typename T>
