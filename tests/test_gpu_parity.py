@@ -181,9 +181,17 @@ def test_benchmark_configs_sampled_fp32(name):
     _sampled(synth.CONFIGS[name], cs.CONV_F32, FP32_TOL)
 
 
-@pytest.mark.parametrize("name", ["cfg5a", "cfg5b"])
+@pytest.mark.parametrize("name", ["cfg5a", "cfg5b", "cfg3"])
 def test_benchmark_configs_sampled_bf16(name):
     _sampled(synth.CONFIGS[name], cs.CONV_BF16, BF16_TOL)
+
+
+@pytest.mark.parametrize("k0,k1", [(188, 376), (1313, 1500), (0, 64)])
+def test_eighth_of_the_large_layer_sampled_fp32(k0, k1):
+    """One of eight equal shares of the 1500-kernel layer (Eq. (1) with equal devices): a full
+    row tile plus a half row tile in the forward and weight-gradient passes; and a share that
+    is a half tile only."""
+    _sampled(synth.CONFIGS["cfg3"].with_slice(k0, k1), cs.CONV_F32, FP32_TOL)
 
 
 def test_device_share_equals_slice_of_full_layer():
