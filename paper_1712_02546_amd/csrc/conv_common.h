@@ -135,10 +135,6 @@ static inline int grid_dealt(int MB, int CT) { return 8 * ((CT + 7) / 8) * MB; }
 // to the constant address space are scalar loads.
 #define CS_CONST __attribute__((address_space(4)))
 
-__device__ __forceinline__ void dma16(const float* g, float* lds_uniform) {
-  __builtin_amdgcn_global_load_lds(CS_GPTR(g), CS_LPTR(lds_uniform), 16, 0, 0);
-}
-
 // A pointer the compiler must treat as an opaque wave-uniform value (no folding of the
 // arithmetic that produced it into later address computations).
 __device__ __forceinline__ const char* opaque_uniform(const void* p) {
@@ -246,8 +242,8 @@ __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, flo
 // from registers while the LDS reads of G0,G1 of chunk ch are in flight, then G0,G1 of
 // chunk ch while G2,G3 are being read.
 template <class LA, class LB>
-__device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch_begin, int ch_end,
-                                              float* smem, f32x16 (&acc)[LA::MI][2]) {
+__device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end, float* smem,
+                                              f32x16 (&acc)[LA::MI][2]) {
   constexpr bool AC = LA::COL, BC = LB::COL;
   constexpr int MI = LA::MI;
   static_assert(MI == 2 || AC, "the half tile needs a col-image A operand");
@@ -308,12 +304,6 @@ __device__ __forceinline__ void gemm_mainloop_one_barrier(LA& la, LB& lb, int ch
   }
   mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
   mfma_group(a1, b1, acc);
-}
-
-template <class LA, class LB>
-__device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end,
-                                              float* smem, f32x16 (&acc)[LA::MI][2]) {
-  gemm_mainloop_one_barrier(la, lb, ch_begin, ch_end, smem, acc);
 }
 
 // Position of accumulator register v of a 32x32 MFMA block inside the block.

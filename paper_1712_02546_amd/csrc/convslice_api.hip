@@ -115,8 +115,7 @@ RowSplit split_rows(int M) {
 struct FwdPlan {
   bool repitch;      // filters copied to zero-padded fp32 rows of pitch ldw (bf16 input, or C*R*S not a multiple of BK)
   int ldw, nch;
-  int MB, CT;
-  cs::TailPlan tail;
+  int CT;            // column tiles; the row tiles and tail plans are fixed per launch (launch_fwd_gemm)
   size_t off_xt, off_yt, off_w, off_tab, off_tail, total;
 };
 
@@ -125,9 +124,7 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
   p.repitch = dtype != CONV_F32 || (g.CRS % cs::BK) != 0;
   p.ldw = p.repitch ? (int)round_up(g.CRS, cs::BK) : g.CRS;
   p.nch = (g.CRS + cs::BK - 1) / cs::BK;
-  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
   p.CT = (g.PQ * g.NB + 3) / 4;
-  p.tail = plan_tail(p.MB * p.CT, p.nch);
   size_t o = 0;
   o += kZeroBytes;
   p.off_xt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
@@ -156,8 +153,7 @@ cs::RunPlan plan_runs(int MB, bool possible) {
 
 struct BwdDataPlan {
   bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
-  int Cp, Ksp, nch, MB1, CT1;   // Ksp: pitch of w' in the scatter form, a multiple of BK
-  cs::TailPlan tail;
+  int Cp, Ksp, nch, CT1;   // Ksp: pitch of w' in the scatter form, a multiple of BK; CT1: its column tiles
   size_t off_dyt, off_wt, off_dxt, off_perm, off_pre, off_scratch, off_tab, off_T, off_tail, total;
 };
 
@@ -187,9 +183,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
     p.off_wt = o;   o += seg((int64_t)g.CRS * p.Ksp);          // w'[(c,r,s)][k], zero past Ks
     p.off_tab = o;  o += seg((int64_t)(p.nch + 4) * cs::BK * 2);
     p.off_T = o;    o += seg((int64_t)g.CRS * g.PQ * g.Np);
-    p.MB1 = (g.CRS + cs::BM - 1) / cs::BM;
     p.CT1 = (g.PQ * g.NB + 3) / 4;
-    p.tail = plan_tail(p.MB1 * p.CT1, p.nch);
     p.off_tail = o; o += tail_bytes(p.nch);
     p.off_dxt = p.off_perm = 0;
     p.total = o;

@@ -1,16 +1,15 @@
-// The three matrix-core passes.  Each is an implicit GEMM on 128x128 tiles whose
-// 32-lane column blocks are "32 images at one pixel" (fwd, bwd_data) or 32 filter
-// taps (bwd_weight); the operand loaders below are the only pass-specific code.
+// The three matrix-core passes.  Each is an implicit GEMM on 128x128 tiles (MI = 2; a
+// last row tile of at most 64 rows is computed on 64x128 tiles, MI = 1, by a launch of
+// its own) whose 32-lane column blocks are "32 images at one pixel" (fwd, bwd_data) or
+// 32 filter taps (bwd_weight); the operand loaders below are the only pass-specific code.
 // A loader computes, per lane, the global address of the 16 bytes that lane moves
-// into LDS for each of its wavefront's four DMA loads per chunk (see the staging
-// notes in conv_common.h for the row and col tile images).
+// into LDS for each of its wavefront's DMA loads per chunk (four for a 128-row or
+// 128-column operand, two for the 64 rows of a half tile; see the staging notes in
+// conv_common.h for the row and col tile images).
 #pragma once
 #include "conv_common.h"
 
 namespace cs {
-
-// Wave-uniform LDS destination of DMA load number i of wavefront wv.
-__device__ __forceinline__ float* dma_dst(float* tile, int wv, int i) { return tile + (wv * 4 + i) * 256; }
 
 // ---------------------------------------------------------------- forward ----
 // A[m][kk] = w[k0+m0+m][kk]: rows of the filter matrix, col image.  The row pitch ldw is a
