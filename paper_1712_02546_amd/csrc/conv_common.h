@@ -54,6 +54,27 @@ template <typename T> __device__ __forceinline__ void store_from_f32(T* p, float
 template <> __device__ __forceinline__ void store_from_f32<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
 
+// Four consecutive elements at once (the address must be a multiple of four elements).
+template <typename T> __device__ __forceinline__ f32x4 load4_as_f32(const T* p);
+template <> __device__ __forceinline__ f32x4 load4_as_f32<float>(const float* p) { return *(const f32x4*)p; }
+template <> __device__ __forceinline__ f32x4 load4_as_f32<uint16_t>(const uint16_t* p) {
+  const uint2 u = *(const uint2*)p;
+  f32x4 v;
+  v[0] = __uint_as_float(u.x << 16);
+  v[1] = __uint_as_float(u.x & 0xffff0000u);
+  v[2] = __uint_as_float(u.y << 16);
+  v[3] = __uint_as_float(u.y & 0xffff0000u);
+  return v;
+}
+template <typename T> __device__ __forceinline__ void store4_from_f32(T* p, const f32x4& v);
+template <> __device__ __forceinline__ void store4_from_f32<float>(float* p, const f32x4& v) { *(f32x4*)p = v; }
+template <> __device__ __forceinline__ void store4_from_f32<uint16_t>(uint16_t* p, const f32x4& v) {
+  uint2 u;
+  u.x = (unsigned)f32_to_bf16(v[0]) | ((unsigned)f32_to_bf16(v[1]) << 16);
+  u.y = (unsigned)f32_to_bf16(v[2]) | ((unsigned)f32_to_bf16(v[3]) << 16);
+  *(uint2*)p = u;
+}
+
 // Workgroup id -> (row tile mb, column tile ct).  Workgroups are dealt round-robin
 // to the 8 XCDs, each with its own L2, so id g runs on XCD g%8 as that XCD's
 // (g/8)-th workgroup.

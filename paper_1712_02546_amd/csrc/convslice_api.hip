@@ -420,19 +420,26 @@ void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t s
     const int nb = batch - b0 < 32768 ? batch - b0 : 32768;
     const dim3 grid((cols + 63) / 64, (rowsPad + 63) / 64, nb);
     float* zp = b0 == 0 ? zero_page : nullptr;
-    if (dtype == CONV_F32 && !out16)
-      hipLaunchKernelGGL((cs::transpose_in_kernel<float, float>), grid, dim3(256), 0, st, (const float*)src,
-                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave);
-    else if (dtype == CONV_F32)
-      hipLaunchKernelGGL((cs::transpose_in_kernel<float, uint16_t>), grid, dim3(256), 0, st, (const float*)src,
-                         srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave);
-    else if (!out16)
-      hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, float>), grid, dim3(256), 0, st, (const uint16_t*)src,
-                         srcBatch, srcPitch, rows, cols, (float*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave);
-    else
-      hipLaunchKernelGGL((cs::transpose_in_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st,
-                         (const uint16_t*)src, srcBatch, srcPitch, rows, cols, (uint16_t*)dst, dstBatch, dstPitch,
-                         rowsPad, b0, batchValid, zp, group, interleave);
+    const size_t ain = dtype == CONV_F32 ? 16 : 8, aout = out16 ? 8 : 16;   // four elements
+    const bool vec4 = (uintptr_t)src % ain == 0 && (uintptr_t)dst % aout == 0 && cols % 4 == 0 && rowsPad % 4 == 0 &&
+                      (srcPitch | srcBatch | dstPitch | dstBatch) % 4 == 0;
+#define CS_LAUNCH_TRANSPOSE_IN(KERNEL, TIN, TOUT)                                                                  \
+  hipLaunchKernelGGL((KERNEL<TIN, TOUT>), grid, dim3(256), 0, st, (const TIN*)src, srcBatch, srcPitch, rows, cols, \
+                     (TOUT*)dst, dstBatch, dstPitch, rowsPad, b0, batchValid, zp, group, interleave)
+    if (dtype == CONV_F32 && !out16) {
+      if (vec4) CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_v4_kernel, float, float);
+      else CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_kernel, float, float);
+    } else if (dtype == CONV_F32) {
+      if (vec4) CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_v4_kernel, float, uint16_t);
+      else CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_kernel, float, uint16_t);
+    } else if (!out16) {
+      if (vec4) CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_v4_kernel, uint16_t, float);
+      else CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_kernel, uint16_t, float);
+    } else {
+      if (vec4) CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_v4_kernel, uint16_t, uint16_t);
+      else CS_LAUNCH_TRANSPOSE_IN(cs::transpose_in_kernel, uint16_t, uint16_t);
+    }
+#undef CS_LAUNCH_TRANSPOSE_IN
   }
 }
 
@@ -440,21 +447,23 @@ void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t s
 void launch_transpose_out(int dtype, bool acc, const float* src, int64_t srcPitch, int rows, int cols,
                           void* dst, int64_t dstPitch, hipStream_t st) {
   const dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  const size_t aout = dtype == CONV_F32 ? 16 : 8;   // four elements
+  const bool vec4 = (uintptr_t)src % 16 == 0 && (uintptr_t)dst % aout == 0 && cols % 4 == 0 &&
+                    (srcPitch | dstPitch) % 4 == 0;
+#define CS_LAUNCH_TRANSPOSE_OUT(KERNEL, TOUT, ACC) \
+  hipLaunchKernelGGL((KERNEL<TOUT, ACC>), grid, dim3(256), 0, st, src, srcPitch, rows, cols, (TOUT*)dst, dstPitch)
   if (dtype == CONV_F32) {
-    if (acc)
-      hipLaunchKernelGGL((cs::transpose_out_kernel<float, true>), grid, dim3(256), 0, st, src, srcPitch, rows,
-                         cols, (float*)dst, dstPitch);
-    else
-      hipLaunchKernelGGL((cs::transpose_out_kernel<float, false>), grid, dim3(256), 0, st, src, srcPitch, rows,
-                         cols, (float*)dst, dstPitch);
+    if (vec4 && acc) CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_v4_kernel, float, true);
+    else if (vec4) CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_v4_kernel, float, false);
+    else if (acc) CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_kernel, float, true);
+    else CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_kernel, float, false);
   } else {
-    if (acc)
-      hipLaunchKernelGGL((cs::transpose_out_kernel<uint16_t, true>), grid, dim3(256), 0, st, src, srcPitch,
-                         rows, cols, (uint16_t*)dst, dstPitch);
-    else
-      hipLaunchKernelGGL((cs::transpose_out_kernel<uint16_t, false>), grid, dim3(256), 0, st, src, srcPitch,
-                         rows, cols, (uint16_t*)dst, dstPitch);
+    if (vec4 && acc) CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_v4_kernel, uint16_t, true);
+    else if (vec4) CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_v4_kernel, uint16_t, false);
+    else if (acc) CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_kernel, uint16_t, true);
+    else CS_LAUNCH_TRANSPOSE_OUT(cs::transpose_out_kernel, uint16_t, false);
   }
+#undef CS_LAUNCH_TRANSPOSE_OUT
 }
 
 inline size_t elem_size(int dtype) { return dtype == CONV_F32 ? 4 : 2; }

@@ -46,6 +46,49 @@ __global__ __launch_bounds__(256) void transpose_in_kernel(
   }
 }
 
+// The same when every address involved is a multiple of four elements (16 bytes for fp32, 8 for
+// bfloat16) and cols, rowsPad and all pitches are multiples of four: four elements per global
+// load and store, a quarter of the memory instructions.  Thread (tx, ty) = (t % 16, t / 16)
+// loads columns 4*tx..+3 of rows ty, ty+16, .. and stores images 4*tx..+3 of destination rows
+// ty, ty+16, ..
+template <typename Tin, typename Tout>
+__global__ __launch_bounds__(256) void transpose_in_v4_kernel(
+    const Tin* __restrict__ src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
+    Tout* __restrict__ dst, int64_t dstBatch, int64_t dstPitch, int rowsPad, int batch0, int batchValid,
+    float* __restrict__ zero_page, int group, int interleave) {
+  __shared__ float tile[64][65];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  if (zero_page && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+    for (int i = threadIdx.x; i < ZERO_PAGE_FLOATS; i += 256) zero_page[i] = 0.f;
+  const int b = batch0 + blockIdx.z;
+  const bool bok = b < batchValid;
+  src += (int64_t)(bok ? b : 0) * srcBatch;
+  dst += (int64_t)b * dstBatch;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int nn = ty + 16 * i;
+    const int n = n0 + nn, l = l0 + 4 * tx;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (bok && n < rows && l < cols) v = load4_as_f32<Tin>(src + (int64_t)n * srcPitch + l);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) tile[nn][4 * tx + k] = v[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ll = ty + 16 * i;
+    const int l = l0 + ll, n = n0 + 4 * tx;
+    const int lrow = group <= 0 ? l : interleave > 0 ? (l % group) * interleave + l / group : l + l / group;
+    if (l < cols && n < rowsPad) {
+      f32x4 v;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = tile[4 * tx + k][ll];
+      store4_from_f32<Tout>(dst + (int64_t)lrow * dstPitch + n, v);
+    }
+  }
+}
+
 // dst[n*dstPitch + l] (+)= src[l*srcPitch + n] for 0 <= l < cols, 0 <= n < rows.
 // grid = (ceil(cols/64), ceil(rows/64)).
 template <typename Tout, bool ACC>
@@ -73,6 +116,44 @@ __global__ __launch_bounds__(256) void transpose_out_kernel(
       float v = tile[tx][nn];
       if (ACC) v += load_as_f32<Tout>(p);
       store_from_f32<Tout>(p, v);
+    }
+  }
+}
+
+// The same when every address is a multiple of four elements and cols and both pitches are
+// multiples of four (rows may be ragged: the source rows are padded).
+template <typename Tout, bool ACC>
+__global__ __launch_bounds__(256) void transpose_out_v4_kernel(
+    const float* __restrict__ src, int64_t srcPitch, int rows, int cols,
+    Tout* __restrict__ dst, int64_t dstPitch) {
+  __shared__ float tile[64][65];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int l0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ll = ty + 16 * i;
+    const int l = l0 + ll, n = n0 + 4 * tx;   // srcPitch covers the padded batch: a whole vector is readable
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (l < cols && n < srcPitch) v = *(const f32x4*)(src + (int64_t)l * srcPitch + n);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) tile[ll][4 * tx + k] = v[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int nn = ty + 16 * i;
+    const int n = n0 + nn, l = l0 + 4 * tx;
+    if (n < rows && l < cols) {
+      Tout* p = dst + (int64_t)n * dstPitch + l;
+      f32x4 v;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = tile[4 * tx + k][nn];
+      if (ACC) {
+        const f32x4 o = load4_as_f32<Tout>(p);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] += o[k];
+      }
+      store4_from_f32<Tout>(p, v);
     }
   }
 }
