@@ -197,7 +197,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_perm = o; o += seg(g.HW);
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
-  p.off_scratch = o; o += seg((int64_t)3 * g.H + 2 * g.W);
+  p.off_scratch = o; o += seg((int64_t)4 * g.H + 3 * g.W);
   p.off_tail = o; o += (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4;   // two slots per workgroup, whatever the slice
   p.total = o;
   return p;
@@ -340,7 +340,7 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   p.off_perm = o; o += seg(g.HW);
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
-  p.off_scratch = o; o += seg((int64_t)3 * g.H + 2 * g.W);
+  p.off_scratch = o; o += seg((int64_t)4 * g.H + 3 * g.W);
   p.off_zero = o; o += seg16((int64_t)32 * p.Ksp + 64);   // a column block of zeros: 32 images x Ksp kernels
   // With chunks this short the scratch round trip of the cut tiles costs about as much as uneven tiles do, so
   // the runs are used only where one workgroup per tile would leave slots empty.

@@ -247,12 +247,16 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
 
 // Orders the H*W input pixels by decreasing tap count (a counting sort by one workgroup; no
 // atomics in the placement, so the order is the same on every run).  perm[position] = pixel.
-// A pixel's tap count is a*b with a = rows(h) and b = cols(v) the taps that reach it along
-// each axis.  Pixels with the same count are ordered by a, then by the rank of their row among
-// the rows with that a, then by the rank of their column among the columns with that b, so a
-// pixel's position is a closed form of per-row and per-column ranks: no loop over the image.
-// Pixels no tap reaches (a*b = 0) come last: whole rows with a = 0 first, then the columns with
-// b = 0 of the other rows.  scratch holds 3*H + 2*W ints (used when they do not fit in LDS).
+// The taps that reach a pixel are (rows of taps reaching h) x (columns of taps reaching v);
+// along an axis they form an arithmetic progression with the stride as step, named by its
+// length (a for rows, b for columns) and its first tap.  The tap count is a*b.  Pixels with
+// the same count are ordered by a, then by the first row tap, then by the first column tap,
+// so that pixels with the same set of taps are neighbours (column tiles that hold several
+// pixels then walk no tap in vain), and inside such a group by the rank of the row and of
+// the column in their classes: a pixel's position is a closed form of per-row and per-column
+// ranks and class sizes, no loop over the image.  Pixels no tap reaches (a*b = 0) come last:
+// whole rows with a = 0 first, then the columns with b = 0 of the other rows.
+// scratch holds 4*H + 3*W ints (used when they do not fit in LDS).
 //
 // With `pre` given it also lays the CT column tiles (four blocks of 32 images each, blocks
 // numbered position-major in the new order) on a line: a tile is as many chunks long as
@@ -262,53 +266,66 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
                                                                     int* __restrict__ scratch, int CT, int nkc,
                                                                     int* __restrict__ pre) {
   __shared__ int bins[1026];     // pixels per tap count, then first position per tap count
-  __shared__ int rowCnt[34], colCnt[34];   // rows per a (0..R), columns per b (0..S)
+  __shared__ int rowCnt[34], colCnt[34];       // rows per a (0..R), columns per b (0..S)
+  __shared__ int rowCls[1056], colCls[1056];   // rows per class a*R + first tap, columns per class b*S + first tap
   __shared__ int part[1024];     // scan of the tile lengths
   __shared__ int s_axes[4096];
-  const bool in_lds = 3 * g.H + 2 * g.W <= 4096;
+  const bool in_lds = 4 * g.H + 3 * g.W <= 4096;
   int* nrow = in_lds ? s_axes : scratch;   // a of every row
-  int* rowRank = nrow + g.H;               // rank among the rows with the same a
+  int* rowKey = nrow + g.H;                // class of every row
+  int* rowRank = rowKey + g.H;             // rank among the rows of the same class
   int* nzRank = rowRank + g.H;             // rank among the rows with a > 0
   int* ncol = nzRank + g.H;                // b of every column
-  int* colRank = ncol + g.W;               // rank among the columns with the same b
+  int* colKey = ncol + g.W;                // class of every column
+  int* colRank = colKey + g.W;             // rank among the columns of the same class
   for (int i = threadIdx.x; i <= g.RS + 1; i += blockDim.x) bins[i] = 0;
+  for (int i = threadIdx.x; i < 1056; i += blockDim.x) rowCls[i] = colCls[i] = 0;
   if (threadIdx.x < 34) rowCnt[threadIdx.x] = colCnt[threadIdx.x] = 0;
   for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
-    int n = 0;
-    for (int r = 0; r < g.R; ++r) {
+    int n = 0, first = 0;
+    for (int r = g.R - 1; r >= 0; --r) {
       const int hr = h + g.ph - r;
-      if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) ++n;
+      if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) {
+        ++n;
+        first = r;
+      }
     }
     nrow[h] = n;
+    rowKey[h] = n * g.R + first;
   }
   for (int v = threadIdx.x; v < g.W; v += blockDim.x) {
-    int n = 0;
-    for (int s = 0; s < g.S; ++s) {
-      const int vs = v + g.pw - s;
-      if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) ++n;
+    int n = 0, first = 0;
+    for (int s2 = g.S - 1; s2 >= 0; --s2) {
+      const int vs = v + g.pw - s2;
+      if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) {
+        ++n;
+        first = s2;
+      }
     }
     ncol[v] = n;
+    colKey[v] = n * g.S + first;
   }
   __threadfence_block();
   __syncthreads();
   for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
-    const int a = nrow[h];
+    const int key = rowKey[h];
     int same = 0, nz = 0;
     for (int hh = 0; hh < h; ++hh) {
-      const int o = nrow[hh];
-      same += o == a;
-      nz += o > 0;
+      same += rowKey[hh] == key;
+      nz += nrow[hh] > 0;
     }
     rowRank[h] = same;
     nzRank[h] = nz;
-    atomicAdd(&rowCnt[a], 1);   // counts only
+    atomicAdd(&rowCnt[nrow[h]], 1);   // counts only
+    atomicAdd(&rowCls[key], 1);
   }
   for (int v = threadIdx.x; v < g.W; v += blockDim.x) {
-    const int b2 = ncol[v];
+    const int key = colKey[v];
     int same = 0;
-    for (int vv = 0; vv < v; ++vv) same += ncol[vv] == b2;
+    for (int vv = 0; vv < v; ++vv) same += colKey[vv] == key;
     colRank[v] = same;
-    atomicAdd(&colCnt[b2], 1);
+    atomicAdd(&colCnt[ncol[v]], 1);
+    atomicAdd(&colCls[key], 1);
   }
   __threadfence_block();
   __syncthreads();
@@ -332,12 +349,15 @@ __global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* 
     const int wgt = a * b2;
     int pos;
     if (wgt > 0) {
-      int before = 0;   // pixels with the same count and a smaller a
-      for (int a2 = 1; a2 < a; ++a2) {
+      const int rkey = rowKey[h], ckey = colKey[v];
+      int before = 0;
+      for (int a2 = 1; a2 < a; ++a2) {   // groups with a smaller a
         const int q = wgt / a2;
         if (q * a2 == wgt && q <= g.S) before += rowCnt[a2] * colCnt[q];
       }
-      pos = bins[wgt] + before + rowRank[h] * colCnt[b2] + colRank[v];
+      for (int k = a * g.R; k < rkey; ++k) before += rowCls[k] * colCnt[b2];      // same a, earlier first row tap
+      for (int k = b2 * g.S; k < ckey; ++k) before += rowCls[rkey] * colCls[k];   // same rows, earlier first column tap
+      pos = bins[wgt] + before + rowRank[h] * colCls[ckey] + colRank[v];
     } else if (a == 0) {
       pos = bins[0] + rowRank[h] * g.W + v;
     } else {
