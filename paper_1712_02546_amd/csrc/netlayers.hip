@@ -42,6 +42,57 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const float* __restr
   y[e] = x[e] * pow_pos(s, -beta);
 }
 
+// Four neighbouring pixels per thread (HW a multiple of four, 16-byte aligned tensors): 16-byte loads and stores.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(kThreads) void norm_fwd_v4_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                               float* __restrict__ scale, int C, int HW, int half,
+                                                               float kappa, float alpha, float beta) {
+  const unsigned ci = (blockIdx.x * kThreads + threadIdx.x) * 4u;
+  if (ci >= (unsigned)(C * HW)) return;
+  const int c = (int)(ci / (unsigned)HW), i = (int)(ci - (unsigned)c * (unsigned)HW);
+  const float* xn = x + (int64_t)blockIdx.y * C * HW + i;
+  const int lo = max(0, c - half), hi = min(C, c + half + 1);
+  f32x4 ss = {0.f, 0.f, 0.f, 0.f};
+  for (int cc = lo; cc < hi; ++cc) {
+    const f32x4 v = *(const f32x4*)(xn + (int64_t)cc * HW);
+    ss += v * v;
+  }
+  const int64_t e = (int64_t)blockIdx.y * C * HW + ci;
+  const f32x4 xe = *(const f32x4*)(x + e);
+  f32x4 s, o;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    s[k] = kappa + alpha * ss[k];
+    o[k] = xe[k] * pow_pos(s[k], -beta);
+  }
+  *(f32x4*)(scale + e) = s;
+  *(f32x4*)(y + e) = o;
+}
+
+__global__ __launch_bounds__(kThreads) void norm_bwd_v4_kernel(const float* __restrict__ x, const float* __restrict__ y,
+                                                               const float* __restrict__ scale,
+                                                               const float* __restrict__ dy, float* __restrict__ dx, int C,
+                                                               int HW, int half, float alpha, float beta) {
+  const unsigned ci = (blockIdx.x * kThreads + threadIdx.x) * 4u;
+  if (ci >= (unsigned)(C * HW)) return;
+  const int c = (int)(ci / (unsigned)HW), i = (int)(ci - (unsigned)c * (unsigned)HW);
+  const int64_t base = (int64_t)blockIdx.y * C * HW + i;
+  const int lo = max(0, c - half), hi = min(C, c + half + 1);
+  f32x4 t = {0.f, 0.f, 0.f, 0.f};
+  for (int cc = lo; cc < hi; ++cc) {
+    const int64_t j = base + (int64_t)cc * HW;
+    const f32x4 a = *(const f32x4*)(dy + j), b = *(const f32x4*)(y + j), d = *(const f32x4*)(scale + j);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) t[k] += a[k] * b[k] / d[k];
+  }
+  const int64_t e = base + (int64_t)c * HW;
+  const f32x4 de = *(const f32x4*)(dy + e), se = *(const f32x4*)(scale + e), xe = *(const f32x4*)(x + e);
+  f32x4 o;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) o[k] = de[k] * pow_pos(se[k], -beta) - 2.f * alpha * beta * xe[k] * t[k];
+  *(f32x4*)(dx + e) = o;
+}
+
 // dy[c']*x[c']*scale[c']^(-beta-1) = dy[c']*y[c']/scale[c'], so the window sum needs no power function.
 __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(const float* __restrict__ x, const float* __restrict__ y,
                                                             const float* __restrict__ scale, const float* __restrict__ dy,
@@ -113,6 +164,27 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(const float* __restr
   }
 }
 
+// Windows that tile the image exactly (win = stride = 2, H = 2P, W = 2Q): a thread owns one window, finds its first
+// maximum and writes the window's four gradients.
+__global__ __launch_bounds__(kThreads) void pool_bwd_2x2_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                                float* __restrict__ dx, int W, int P, int Q, int64_t count) {
+  for (int64_t e64 = (int64_t)blockIdx.x * kThreads + threadIdx.x; e64 < count; e64 += (int64_t)gridDim.x * kThreads) {
+    const unsigned e = (unsigned)e64;
+    const unsigned m = e / (unsigned)(P * Q), pq = e - m * (unsigned)(P * Q);
+    const int p = (int)(pq / (unsigned)Q), q = (int)(pq - (unsigned)p * (unsigned)Q);
+    const int64_t o = (int64_t)m * (4 * P * Q) + (int64_t)(2 * p) * W + 2 * q;
+    const float2 top = *(const float2*)(x + o), bot = *(const float2*)(x + o + W);
+    int arg = 0;
+    float best = top.x;
+    if (top.y > best) { best = top.y; arg = 1; }
+    if (bot.x > best) { best = bot.x; arg = 2; }
+    if (bot.y > best) { best = bot.y; arg = 3; }
+    const float g = dy[e64];
+    *(float2*)(dx + o) = make_float2(arg == 0 ? g : 0.f, arg == 1 ? g : 0.f);
+    *(float2*)(dx + o + W) = make_float2(arg == 2 ? g : 0.f, arg == 3 ? g : 0.f);
+  }
+}
+
 // ---- fully connected -------------------------------------------------------------------
 constexpr int kOB = 8;   // outputs per workgroup / thread block of outputs
 
@@ -158,14 +230,18 @@ __global__ __launch_bounds__(kThreads) void fc_bwd_data_kernel(const float* __re
   }
 }
 
-// grid (ceil(I/kThreads), ceil(O/kOB)): a thread owns input i and kOB outputs, sums over the batch in order.
-__global__ __launch_bounds__(kThreads) void fc_bwd_weight_kernel(const float* __restrict__ x, const float* __restrict__ dy,
-                                                                 float* __restrict__ dW, int N, int I, int O) {
-  const int i = blockIdx.x * kThreads + threadIdx.x, o0 = blockIdx.y * kOB;
+// grid (ceil(I/kFcWThreads), ceil(O/kOB)): a thread owns input i and kOB outputs, sums over the batch in order.
+// Small workgroups so that a few thousand inputs already fill the chip; the batch loop is unrolled to keep
+// several loads in flight per thread.
+constexpr int kFcWThreads = 64;
+__global__ __launch_bounds__(kFcWThreads) void fc_bwd_weight_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                                    float* __restrict__ dW, int N, int I, int O) {
+  const int i = blockIdx.x * kFcWThreads + threadIdx.x, o0 = blockIdx.y * kOB;
   if (i >= I) return;
   float acc[kOB];
 #pragma unroll
   for (int k = 0; k < kOB; ++k) acc[k] = 0.f;
+#pragma unroll 8
   for (int n = 0; n < N; ++n) {
     const float v = x[(int64_t)n * I + i];
 #pragma unroll
@@ -250,8 +326,12 @@ int net_norm_fwd(const float* x, float* y, float* scale, int32_t N, int32_t C, i
   if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0 || N > 65535) return CONV_ERR_SHAPE;
   const int64_t count = (int64_t)N * C * HW;
   if (count > kMaxCount) return CONV_ERR_SHAPE;
-  hipLaunchKernelGGL(norm_fwd_kernel, dim3((unsigned)(((int64_t)C * HW + kThreads - 1) / kThreads), N), dim3(kThreads), 0,
-                     (hipStream_t)hip_stream, x, y, scale, C, HW, size / 2, kappa, alpha, beta);
+  if (HW % 4 == 0 && ((uintptr_t)x | (uintptr_t)y | (uintptr_t)scale) % 16 == 0)
+    hipLaunchKernelGGL(norm_fwd_v4_kernel, dim3((unsigned)(((int64_t)C * HW / 4 + kThreads - 1) / kThreads), N),
+                       dim3(kThreads), 0, (hipStream_t)hip_stream, x, y, scale, C, HW, size / 2, kappa, alpha, beta);
+  else
+    hipLaunchKernelGGL(norm_fwd_kernel, dim3((unsigned)(((int64_t)C * HW + kThreads - 1) / kThreads), N), dim3(kThreads),
+                       0, (hipStream_t)hip_stream, x, y, scale, C, HW, size / 2, kappa, alpha, beta);
   return launch_status();
 }
 
@@ -262,8 +342,12 @@ int net_norm_bwd(const float* x, const float* y, const float* scale, const float
   if (N < 1 || C < 1 || HW < 1 || size < 1 || size % 2 == 0 || N > 65535) return CONV_ERR_SHAPE;
   const int64_t count = (int64_t)N * C * HW;
   if (count > kMaxCount) return CONV_ERR_SHAPE;
-  hipLaunchKernelGGL(norm_bwd_kernel, dim3((unsigned)(((int64_t)C * HW + kThreads - 1) / kThreads), N), dim3(kThreads), 0,
-                     (hipStream_t)hip_stream, x, y, scale, dy, dx, C, HW, size / 2, alpha, beta);
+  if (HW % 4 == 0 && ((uintptr_t)x | (uintptr_t)y | (uintptr_t)scale | (uintptr_t)dy | (uintptr_t)dx) % 16 == 0)
+    hipLaunchKernelGGL(norm_bwd_v4_kernel, dim3((unsigned)(((int64_t)C * HW / 4 + kThreads - 1) / kThreads), N),
+                       dim3(kThreads), 0, (hipStream_t)hip_stream, x, y, scale, dy, dx, C, HW, size / 2, alpha, beta);
+  else
+    hipLaunchKernelGGL(norm_bwd_kernel, dim3((unsigned)(((int64_t)C * HW + kThreads - 1) / kThreads), N), dim3(kThreads),
+                       0, (hipStream_t)hip_stream, x, y, scale, dy, dx, C, HW, size / 2, alpha, beta);
   return launch_status();
 }
 
@@ -293,6 +377,12 @@ int net_pool_bwd(const float* x, const float* dy, float* dx, int32_t NC, int32_t
   int P, Q;
   const int rc = pool_dims(NC, H, W, win, stride, P, Q);
   if (rc != CONV_OK) return rc;
+  if (win == 2 && stride == 2 && H == 2 * P && W == 2 * Q && ((uintptr_t)x | (uintptr_t)dx) % 8 == 0) {
+    const int64_t windows = (int64_t)NC * P * Q;
+    hipLaunchKernelGGL(pool_bwd_2x2_kernel, dim3(blocks_for(windows)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, dy,
+                       dx, W, P, Q, windows);
+    return launch_status();
+  }
   const int64_t count = (int64_t)NC * H * W;
   hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, (hipStream_t)hip_stream, x, dy, dx, H,
                      W, P, Q, win, stride, count);
@@ -319,7 +409,7 @@ int net_fc_bwd(const float* x, const float* W, const float* dy, float* dx, float
     hipLaunchKernelGGL(fc_bwd_data_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, st, W, dy, dx, I, O, count);
   }
   if (dW)
-    hipLaunchKernelGGL(fc_bwd_weight_kernel, dim3((I + kThreads - 1) / kThreads, (O + kOB - 1) / kOB), dim3(kThreads), 0,
+    hipLaunchKernelGGL(fc_bwd_weight_kernel, dim3((I + kFcWThreads - 1) / kFcWThreads, (O + kOB - 1) / kOB), dim3(kFcWThreads), 0,
                        st, x, dy, dW, N, I, O);
   if (db) hipLaunchKernelGGL(fc_bwd_bias_kernel, dim3((O + kThreads - 1) / kThreads), dim3(kThreads), 0, st, dy, db, N, O);
   return launch_status();

@@ -41,6 +41,7 @@ def f32(a):
     (2, 33, 3, 3, 3, 2.0, 0.3, 0.5),
     (5, 4, 6, 5, 9, 1.0, 0.05, 0.75),       # window wider than the channel count
     (2, 5, 2, 2, 1, 1.5, 0.2, 1.0),         # window of one channel
+    (4, 6, 4, 6, 9, 1.0, 0.05, 0.75),       # four pixels per thread, window wider than the channel count
     (16, 500, 28, 28, 5, 1.0, 1e-4, 0.75),  # after C1 of the largest network (batch reduced)
 ])
 def test_normalisation(N, C, H, W, size, kappa, alpha, beta):
