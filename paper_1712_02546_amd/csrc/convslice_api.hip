@@ -88,7 +88,9 @@ cs::TailPlan plan_tail(int T, int nch) {
   tp.nFull = T - rem;
   tp.nTail = rem;
   const int64_t work = (int64_t)rem * nch;
-  tp.units = (int)((work + S - 1) / S);
+  // Equal runs over all slots, but no tile in more than 16 pieces: the fix-up kernel adds a tile's slots one after
+  // the other, and a handful of tail tiles cut 500 ways would cost more there than they save here.
+  tp.units = (int)std::max<int64_t>((work + S - 1) / S, (nch + 15) / 16);
   tp.nTailWg = (int)((work + tp.units - 1) / tp.units);
   return tp;
 }
