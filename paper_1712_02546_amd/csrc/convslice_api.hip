@@ -558,9 +558,9 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
     // per image: x[n] as a C x HW matrix -> x_hwnc[hw][n][Cp]; images N..Np-1 are zero
     launch_transpose_in(CONV_BF16, x, (int64_t)g.C * g.HW, g.HW, g.C, g.HW, xp, p.Cp, (int64_t)g.Np * p.Cp, p.Cp,
                         g.Np, (float*)(base + p.off_x - kZeroBytes), st, true, g.N);
-    // per kernel: w[k] as a C x RS matrix -> w_krsc[k][rs][Cp]
-    launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.CRS, g.RS, g.C, g.RS, wp,
-                        (int64_t)g.RS * p.Cp, p.Cp, p.Cp, g.Ks, nullptr, st, true);
+    // w[k][c][rs] -> w_krsc[k][rs][Cp]
+    hipLaunchKernelGGL(cs::filters_to_krsc_kernel, dim3((p.Cp + 63) / 64, g.Ks), dim3(256), 0, st,
+                       (const uint16_t*)w + (size_t)g.k0 * g.CRS, g.C, g.RS, p.Cp, (uint16_t*)wp);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Cp + 64);
     if ((rc = allow_big_lds(cs::fwd16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
@@ -650,9 +650,9 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     launch_transpose_in(CONV_BF16, (const char*)dy + (size_t)g.k0 * g.PQ * 2, (int64_t)g.K * g.PQ, g.PQ, g.Ks, g.PQ,
                         dyp, p.Ksp, (int64_t)g.Np * p.Ksp, p.Ksp, g.Np, (float*)(base + p.off_dy - kZeroBytes), st,
                         true, g.N);
-    // per channel c: w[k0..k1)[c] as a Ks x RS matrix -> w_rsck[rs][c][Ksp]
-    launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, g.RS, g.CRS, g.Ks, g.RS, wp, p.Ksp,
-                        (int64_t)g.C * p.Ksp, p.Ksp, g.C, nullptr, st, true);
+    // w[k][(c,rs)] -> w_rsck[rs][c][Ksp]: the slice's filter matrix transposed, rows re-ordered tap-major, zero past Ks
+    launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, 0, g.CRS, g.Ks, g.CRS, wp, 0, p.Ksp,
+                        p.Ksp, 1, nullptr, st, true, -1, g.RS, g.C);
     const int MB = (g.C + cs::BM - 1) / cs::BM;
     const int CT = (g.HW * g.NB + 3) / 4;
     int* pre = (int*)(base + p.off_pre);

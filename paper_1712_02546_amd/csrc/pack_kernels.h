@@ -231,6 +231,33 @@ __global__ __launch_bounds__(256) void repitch_rows_kernel(
   }
 }
 
+// bf16 filters w[k][c][rs] -> w_krsc[k][rs][Cp] (channels innermost, zero for C <= c < Cp).
+// A workgroup takes 64 channels of one kernel: their 64*RS elements are contiguous in w, and
+// each tap's 64 channels are contiguous in the result.  grid = (ceil(Cp/64), Ks); taps in
+// rounds of 64 so that the LDS tile stays at 16 KB.
+__global__ __launch_bounds__(256) void filters_to_krsc_kernel(const uint16_t* __restrict__ w, int C, int RS, int Cp,
+                                                              uint16_t* __restrict__ out) {
+  __shared__ uint16_t tile[64 * 65];   // [channel][tap of the round], pitch 65
+  const int c0 = blockIdx.x * 64, k = blockIdx.y;
+  const uint16_t* wk = w + (int64_t)k * C * RS;
+  uint16_t* ok = out + (int64_t)k * RS * Cp;
+  for (int t0 = 0; t0 < RS; t0 += 64) {
+    const int nt = min(64, RS - t0);
+    // read: thread -> (channel, tap) with taps fastest, as they lie in memory
+    for (int e = threadIdx.x; e < 64 * nt; e += 256) {
+      const int c = e / nt, t = e - c * nt;
+      tile[c * 65 + t] = c0 + c < C ? wk[(int64_t)(c0 + c) * RS + t0 + t] : (uint16_t)0;
+    }
+    __syncthreads();
+    // write: thread -> (tap, channel) with channels fastest
+    for (int e = threadIdx.x; e < 64 * nt; e += 256) {
+      const int t = e >> 6, c = e & 63;
+      if (c0 + c < Cp) ok[(int64_t)(t0 + t) * Cp + c0 + c] = tile[c * 65 + t];
+    }
+    __syncthreads();
+  }
+}
+
 // Forward pass: for reduction index kk = (c,r,s), tab[kk] = byte offset of that tap inside
 // x_t relative to a pixel's window origin, counted from the zero page in front of x_t, and
 // tab[entries + kk] = (r<<16)|s.  Entries past C*R*S repeat entry 0: the filter operand is
