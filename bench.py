@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of a matrix-core kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # scaled by a copy kernel of known size (profiles/cfg3_f32_pmc_counters.md).  None where not measured.
 TRAFFIC_BYTES = {
-    ("cfg3", "f32", "fwd_gemm_kernel"): 4969000000,
-    ("cfg3", "f32", "bwd_data_gemm_kernel"): 8310000000,
-    ("cfg3", "f32", "bwd_weight_gemm_kernel"): 2743000000,
+    ("cfg3", "f32", "fwd_gemm_kernel"): 5022000000,
+    ("cfg3", "f32", "bwd_data_gemm_kernel"): 8473000000,
+    ("cfg3", "f32", "bwd_weight_gemm_kernel"): 2746000000,
 }
 
 METRIC = "conv fwd+bwd TFLOP/s and % of MFMA peak, 1500-kernel 5x5 layer, batch 128"
