@@ -181,7 +181,7 @@ def test_benchmark_configs_sampled_fp32(name):
     _sampled(synth.CONFIGS[name], cs.CONV_F32, FP32_TOL)
 
 
-@pytest.mark.parametrize("name", ["cfg5a", "cfg5b", "cfg3"])
+@pytest.mark.parametrize("name", SAMPLED)
 def test_benchmark_configs_sampled_bf16(name):
     _sampled(synth.CONFIGS[name], cs.CONV_BF16, BF16_TOL)
 
