@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconvslice.so")
 SOURCES = [os.path.join(CSRC, n) for n in ("convslice_api.hip", "convlayer_api.hip", "netlayers.hip")]
-HEADERS = [os.path.join(CSRC, n) for n in ("conv_common.h", "gemm_kernels.h", "gemm_bf16_kernels.h", "pack_kernels.h")] + [
+HEADERS = sorted(os.path.join(CSRC, n) for n in os.listdir(CSRC) if n.endswith(".h")) + [
     os.path.join(os.path.dirname(HERE), "include", n) for n in ("convslice.h", "convlayer.h", "convnet.h")]
 
 # packed-fp32 VALU forms are switched off for all device code on purpose.

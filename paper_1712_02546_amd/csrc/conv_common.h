@@ -12,6 +12,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "geo.h"
+
 namespace cs {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -25,14 +27,6 @@ constexpr int BK = 32;              // reduction elements per staged chunk
 constexpr int TILE_F = BM * BK;     // floats of one operand tile in LDS (16 KB)
 constexpr int SMEM_BYTES = 4 * TILE_F * 4;  // A and B, two stages each: 64 KB
 constexpr int ZERO_PAGE_FLOATS = 256;       // zero-filled scratch that masked lanes load from
-
-struct Geo {
-  int N, Np, NB;                    // batch, padded batch, Np/32
-  int C, H, W, K, R, S, P, Q;
-  int sh, sw, ph, pw;
-  int k0, Ks;
-  int HW, PQ, RS, CRS;
-};
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);

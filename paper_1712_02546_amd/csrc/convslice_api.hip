@@ -39,7 +39,7 @@ int make_geo(const conv_desc_t* d, Geo& g) {
   const int P = out_extent(d->H, d->pad_h, d->R, d->stride_h);
   const int Q = out_extent(d->W, d->pad_w, d->S, d->stride_w);
   if (P < 1 || Q < 1) return CONV_ERR_SHAPE;
-  if ((int64_t)d->R * d->S > 1024) return CONV_ERR_SHAPE;
+  if ((int64_t)d->R * d->S > cs::po::MAX_RS) return CONV_ERR_SHAPE;
   if (d->pad_h > (1 << 20) || d->pad_w > (1 << 20)) return CONV_ERR_SHAPE;
   const int64_t Np = round_up(d->N, 32);
   const int64_t HW = (int64_t)d->H * d->W, PQ = (int64_t)P * Q, RS = (int64_t)d->R * d->S;
@@ -199,7 +199,7 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   p.off_perm = o; o += seg(g.HW);
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
-  p.off_scratch = o; o += seg((int64_t)4 * g.H + 3 * g.W);
+  p.off_scratch = o; o += seg(cs::po::axes_ints(g.H, g.W));
   p.off_tail = o; o += (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4;   // two slots per workgroup, whatever the slice
   p.total = o;
   return p;
@@ -342,7 +342,7 @@ BwdData16Plan plan_bwd_data16(const Geo& g) {
   p.off_perm = o; o += seg(g.HW);
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
-  p.off_scratch = o; o += seg((int64_t)4 * g.H + 3 * g.W);
+  p.off_scratch = o; o += seg(cs::po::axes_ints(g.H, g.W));
   p.off_zero = o; o += seg16((int64_t)32 * p.Ksp + 64);   // a column block of zeros: 32 images x Ksp kernels
   // With chunks this short the scratch round trip of the cut tiles costs about as much as uneven tiles do, so
   // the runs are used only where one workgroup per tile would leave slots empty.
@@ -657,7 +657,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     const int CT = (g.HW * g.NB + 3) / 4;
     int* pre = (int*)(base + p.off_pre);
     float* partial = (float*)(base + p.off_tail);
-    hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm,
+    hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(cs::po::THREADS), 0, st, g, perm,
                        (int*)(base + p.off_scratch), CT, p.Ksp / cs::BK16, p.run.enabled ? pre : (int*)nullptr);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Ksp + 64);
@@ -733,7 +733,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   float* partial = (float*)(base + p.off_tail);
   const int CT = (g.HW * g.NB + 3) / 4;
   const bool runs = (int64_t)CT * g.RS * p.nch < (int64_t)1 << 30;   // else the line would be too long for an int
-  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(1024), 0, st, g, perm, scratch, CT, p.nch,
+  hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(cs::po::THREADS), 0, st, g, perm, scratch, CT, p.nch,
                      runs ? pre : (int*)nullptr);
   // tiles + tap list + per-block tap offsets
   const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;

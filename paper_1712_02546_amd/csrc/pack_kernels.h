@@ -3,6 +3,7 @@
 // small set-up kernels (pixel ordering, fills, reductions).
 #pragma once
 #include "conv_common.h"
+#include "pixel_order.h"
 
 namespace cs {
 
@@ -272,181 +273,42 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
   tab[entries + i] = (r << 16) | s;
 }
 
-// Orders the H*W input pixels by decreasing tap count (a counting sort by one workgroup; no
-// atomics in the placement, so the order is the same on every run).  perm[position] = pixel.
-// The taps that reach a pixel are (rows of taps reaching h) x (columns of taps reaching v);
-// along an axis they form an arithmetic progression with the stride as step, named by its
-// length (a for rows, b for columns) and its first tap.  The tap count is a*b.  Pixels with
-// the same count are ordered by a, then by the first row tap, then by the first column tap,
-// so that pixels with the same set of taps are neighbours (column tiles that hold several
-// pixels then walk no tap in vain), and inside such a group by the rank of the row and of
-// the column in their classes: a pixel's position is a closed form of per-row and per-column
-// ranks and class sizes, no loop over the image.  Pixels no tap reaches (a*b = 0) come last:
-// whole rows with a = 0 first, then the columns with b = 0 of the other rows.
-// scratch holds 4*H + 3*W ints (used when they do not fit in LDS).
-//
-// With `pre` given it also lays the CT column tiles (four blocks of 32 images each, blocks
-// numbered position-major in the new order) on a line: a tile is as many chunks long as
-// nkc times the number of taps that reach any of its pixels (at least one), pre[ct] is
-// where tile ct starts and pre[CT] the length of the line.
-__global__ __launch_bounds__(1024) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
-                                                                    int* __restrict__ scratch, int CT, int nkc,
-                                                                    int* __restrict__ pre) {
-  __shared__ int bins[1026];     // pixels per tap count, then first position per tap count
-  __shared__ int rowCnt[34], colCnt[34];       // rows per a (0..R), columns per b (0..S)
-  __shared__ int rowCls[1056], colCls[1056];   // rows per class a*R + first tap, columns per class b*S + first tap
-  __shared__ int part[1024];     // scan of the tile lengths
-  __shared__ int s_axes[4096];
-  const bool in_lds = 4 * g.H + 3 * g.W <= 4096;
-  int* nrow = in_lds ? s_axes : scratch;   // a of every row
-  int* rowKey = nrow + g.H;                // class of every row
-  int* rowRank = rowKey + g.H;             // rank among the rows of the same class
-  int* nzRank = rowRank + g.H;             // rank among the rows with a > 0
-  int* ncol = nzRank + g.H;                // b of every column
-  int* colKey = ncol + g.W;                // class of every column
-  int* colRank = colKey + g.W;             // rank among the columns of the same class
-  for (int i = threadIdx.x; i <= g.RS + 1; i += blockDim.x) bins[i] = 0;
-  for (int i = threadIdx.x; i < 1056; i += blockDim.x) rowCls[i] = colCls[i] = 0;
-  if (threadIdx.x < 34) rowCnt[threadIdx.x] = colCnt[threadIdx.x] = 0;
-  for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
-    int n = 0, first = 0;
-    for (int r = g.R - 1; r >= 0; --r) {
-      const int hr = h + g.ph - r;
-      if (hr >= 0 && hr % g.sh == 0 && hr / g.sh < g.P) {
-        ++n;
-        first = r;
-      }
-    }
-    nrow[h] = n;
-    rowKey[h] = n * g.R + first;
-  }
-  for (int v = threadIdx.x; v < g.W; v += blockDim.x) {
-    int n = 0, first = 0;
-    for (int s2 = g.S - 1; s2 >= 0; --s2) {
-      const int vs = v + g.pw - s2;
-      if (vs >= 0 && vs % g.sw == 0 && vs / g.sw < g.Q) {
-        ++n;
-        first = s2;
-      }
-    }
-    ncol[v] = n;
-    colKey[v] = n * g.S + first;
-  }
+// One workgroup runs the phases of pixel_order.h: perm[position] = pixel, pixels by decreasing
+// tap count, and (with `pre`) the line of column tiles.  scratch holds po::axes_ints(H, W)
+// ints, used when the per-axis tables do not fit in LDS.  Launch with po::THREADS threads.
+__global__ __launch_bounds__(po::THREADS) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
+                                                                           int* __restrict__ scratch, int CT, int nkc,
+                                                                           int* __restrict__ pre) {
+  __shared__ int bins[po::BINS], rowCnt[po::AXIS_CNT], colCnt[po::AXIS_CNT], part[po::THREADS];
+  __shared__ int s_axes[po::AXES_LDS];
+  po::Tables<int*> t;
+  t.bins = bins; t.rowCnt = rowCnt; t.colCnt = colCnt; t.part = part;
+  t.axes = po::axes_ints(g.H, g.W) <= po::AXES_LDS ? s_axes : scratch;
+  t.perm = perm; t.pre = pre;
+  const int tid = threadIdx.x, T = po::THREADS;
+  po::phase_axes(g, t, tid, T);
   __threadfence_block();
   __syncthreads();
-  for (int h = threadIdx.x; h < g.H; h += blockDim.x) {
-    const int key = rowKey[h];
-    int same = 0, nz = 0;
-    for (int hh = 0; hh < h; ++hh) {
-      same += rowKey[hh] == key;
-      nz += nrow[hh] > 0;
-    }
-    rowRank[h] = same;
-    nzRank[h] = nz;
-    atomicAdd(&rowCnt[nrow[h]], 1);   // counts only
-    atomicAdd(&rowCls[key], 1);
-  }
-  for (int v = threadIdx.x; v < g.W; v += blockDim.x) {
-    const int key = colKey[v];
-    int same = 0;
-    for (int vv = 0; vv < v; ++vv) same += colKey[vv] == key;
-    colRank[v] = same;
-    atomicAdd(&colCnt[ncol[v]], 1);
-    atomicAdd(&colCls[key], 1);
-  }
+  po::phase_ranks(g, t, tid, T);
   __threadfence_block();
   __syncthreads();
-  for (int i = threadIdx.x; i < (g.R + 1) * (g.S + 1); i += blockDim.x) {
-    const int a = i / (g.S + 1), b2 = i - a * (g.S + 1);
-    atomicAdd(&bins[a * b2], rowCnt[a] * colCnt[b2]);   // counts only
-  }
+  po::phase_bins(g, t, tid, T);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int wgt = g.RS; wgt >= 0; --wgt) {
-      const int cnt = bins[wgt];
-      bins[wgt] = run;
-      run += cnt;
-    }
-  }
+  po::phase_scan_bins(g, t, tid, T);
   __syncthreads();
-  for (int px = threadIdx.x; px < g.HW; px += blockDim.x) {
-    const int h = px / g.W, v = px - h * g.W;
-    const int a = nrow[h], b2 = ncol[v];
-    const int wgt = a * b2;
-    int pos;
-    if (wgt > 0) {
-      const int rkey = rowKey[h], ckey = colKey[v];
-      int before = 0;
-      for (int a2 = 1; a2 < a; ++a2) {   // groups with a smaller a
-        const int q = wgt / a2;
-        if (q * a2 == wgt && q <= g.S) before += rowCnt[a2] * colCnt[q];
-      }
-      for (int k = a * g.R; k < rkey; ++k) before += rowCls[k] * colCnt[b2];      // same a, earlier first row tap
-      for (int k = b2 * g.S; k < ckey; ++k) before += rowCls[rkey] * colCls[k];   // same rows, earlier first column tap
-      pos = bins[wgt] + before + rowRank[h] * colCls[ckey] + colRank[v];
-    } else if (a == 0) {
-      pos = bins[0] + rowRank[h] * g.W + v;
-    } else {
-      pos = bins[0] + rowCnt[0] * g.W + nzRank[h] * colCnt[0] + colRank[v];
-    }
-    perm[pos] = px;
-  }
+  po::phase_place(g, t, tid, T);
   if (pre == nullptr) return;
   __threadfence_block();
   __syncthreads();
-  // Every thread takes a contiguous stretch of tiles: lengths first, then their running sum.
-  const int per = (CT + (int)blockDim.x - 1) / (int)blockDim.x;
-  const int t0 = min((int)threadIdx.x * per, CT), t1 = min(t0 + per, CT);
-  int sum = 0;
-  const bool one_pixel = g.NB % 4 == 0;   // every tile lies inside one pixel: its taps are a*b
-  for (int ct = t0; ct < t1; ++ct) {
-    if (one_pixel) {
-      const int px = perm[ct / (g.NB >> 2)];
-      const int len = max(nrow[px / g.W] * ncol[px % g.W], 1) * nkc;
-      pre[ct + 1] = len;
-      sum += len;
-      continue;
-    }
-    int hp[4], vp[4], np = 0;   // the tile's distinct pixels
-    for (int j = 0; j < 4; ++j) {
-      const int gcb = ct * 4 + j;
-      if (gcb >= g.HW * g.NB) break;
-      const int sp = gcb / g.NB;
-      if (j > 0 && sp == (gcb - 1) / g.NB) continue;
-      const int px = perm[sp];
-      hp[np] = px / g.W + g.ph;
-      vp[np] = px % g.W + g.pw;
-      ++np;
-    }
-    int taps = 0;
-    for (int r = 0; r < g.R; ++r)
-      for (int s2 = 0; s2 < g.S; ++s2) {
-        bool any = false;
-        for (int j = 0; j < np; ++j) {
-          const int hr = hp[j] - r, vs = vp[j] - s2;
-          any |= hr >= 0 && vs >= 0 && hr % g.sh == 0 && vs % g.sw == 0 && hr / g.sh < g.P && vs / g.sw < g.Q;
-        }
-        taps += any;
-      }
-    const int len = max(taps, 1) * nkc;
-    pre[ct + 1] = len;
-    sum += len;
-  }
-  part[threadIdx.x] = sum;
+  po::phase_lengths(g, t, CT, nkc, tid, T);
   __syncthreads();
-  for (int d = 1; d < (int)blockDim.x; d <<= 1) {
-    const int v = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+  for (int d = 1; d < T; d <<= 1) {   // part[] becomes its inclusive running sum
+    const int v = tid >= d ? part[tid - d] : 0;
     __syncthreads();
-    part[threadIdx.x] += v;
+    part[tid] += v;
     __syncthreads();
   }
-  int run = part[threadIdx.x] - sum;
-  for (int ct = t0; ct < t1; ++ct) {
-    run += pre[ct + 1];
-    pre[ct + 1] = run;
-  }
-  if (threadIdx.x == 0) pre[0] = 0;
+  po::phase_prefix(t, CT, tid, T);
 }
 
 template <typename T>

@@ -127,6 +127,19 @@ def test_null_misaligned_and_workspace_errors(fn):
         fn(d, None, A, A, WS, stream=0)
 
 
+def test_filter_extent_limit_is_on_the_product_only():
+    """R*S <= 1024 is the documented limit: long thin filters are admitted, one tap more is not."""
+    for R, S in ((1024, 1), (1, 1024), (33, 31), (64, 16)):
+        d = cs.ConvDesc(N=2, C=64, H=R + 4, W=S + 4, K=4, R=R, S=S)
+        assert cs.conv_output_dims(d) == (5, 5)
+        for p in (cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT):
+            assert cs.conv_workspace_bytes(d, p) > 0
+    for R, S in ((1025, 1), (33, 32), (1, 1025)):
+        d = cs.ConvDesc(N=2, C=64, H=R + 4, W=S + 4, K=4, R=R, S=S)
+        assert cs.conv_fwd(d, A, A, A, WS, stream=0, raw_status=True) == -2
+        assert cs.conv_bwd_data(d, A, A, A, WS, stream=0, raw_status=True) == -2
+
+
 def test_null_descriptor():
     lib = cs.load()
     assert lib.conv_fwd(None, 1, 1, 1, 1, 0, None) == -1

@@ -34,6 +34,10 @@ ADHOC = [
     synth.random_layer(15, N=100, C=130, H=24, W=24, K=260, R=1, S=1, stride=2),
     # column tiles that span pixels with different tap sets (three image blocks per pixel, stride 2)
     synth.random_layer(16, N=70, C=100, H=9, W=11, K=40, R=3, S=3, stride=2, pad=1, k0=0, k1=37),
+    # filters longer than 32 taps along an axis, with enough channels for the per-pixel input-gradient form
+    synth.random_layer(17, N=2, C=64, H=40, W=10, K=8, R=33, S=3),
+    synth.random_layer(18, N=2, C=40, H=34, W=34, K=4, R=32, S=32),                  # R*S at the limit, per pixel
+    synth.random_layer(19, N=3, C=48, H=70, W=5, K=5, R=64, S=2, stride=2, pad=1),
 ]
 
 
@@ -64,17 +68,24 @@ def test_full_tensors_match_oracle_fp32(cfg):
     assert np.all(dw[:k0] == 7.0) and np.all(dw[k1:] == 7.0), "filters outside the slice were written"
 
 
-@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], synth.CONFIGS["cfg1"]],
+@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], ADHOC[16], synth.CONFIGS["cfg1"]],
                          ids=lambda c: c.name)
 def test_full_tensors_match_oracle_bf16(cfg):
-    x, w, dy = (synth.round_to_bf16(a) for a in synth.make_inputs(cfg))
+    xo, wo, dyo = synth.make_inputs(cfg)
+    x, w, dy = (synth.round_to_bf16(a) for a in (xo, wo, dyo))
     sh = oracle_shape(cfg)
     k0, k1 = cfg.slice
     dev = Device(cfg, x, w, dy, dtype=cs.CONV_BF16)
-    check(dev.fwd()[:, k0:k1], oracle.conv_fwd(sh, x, w)[:, k0:k1], BF16_TOL, "y")
-    check(dev.bwd_data(), oracle.conv_bwd_data(sh, dy, w), BF16_TOL, "dx")
+    y, dx, dw = dev.fwd(), dev.bwd_data(), dev.bwd_weight()
+    # against the oracle on the rounded inputs: accumulation and output rounding only
+    check(y[:, k0:k1], oracle.conv_fwd(sh, x, w)[:, k0:k1], BF16_TOL, "y")
+    check(dx, oracle.conv_bwd_data(sh, dy, w), BF16_TOL, "dx")
     # dw is stored in fp32, so it is held to the fp32 tolerance on the rounded inputs
-    check(dev.bwd_weight()[k0:k1], oracle.conv_bwd_weight(sh, x, dy)[k0:k1], FP32_TOL, "dw")
+    check(dw[k0:k1], oracle.conv_bwd_weight(sh, x, dy)[k0:k1], FP32_TOL, "dw")
+    # against the oracle on the inputs before rounding: input rounding included
+    check(y[:, k0:k1], oracle.conv_fwd(sh, xo, wo)[:, k0:k1], BF16_TOL, "y vs unrounded inputs")
+    check(dx, oracle.conv_bwd_data(sh, dyo, wo), BF16_TOL, "dx vs unrounded inputs")
+    check(dw[k0:k1], oracle.conv_bwd_weight(sh, xo, dyo)[k0:k1], BF16_TOL, "dw vs unrounded inputs")
 
 
 @pytest.mark.parametrize("C", [24, 48])
@@ -133,11 +144,100 @@ def test_results_are_bit_stable_run_to_run(which, dtype):
         assert np.array_equal(u, v)
 
 
-# ------------------------------------------------ full benchmark sizes, sampled outputs
-SAMPLED = ["cfg2", "cfg3", "cfg4", "cfg5a", "cfg5b"]
+# ------------------------------------------------ full benchmark sizes, every element
+# The oracle computes the whole layer of a seed family once (all K kernels); configurations
+# that are slices of it (the device share, the eighth shares) compare against its channels.
+# Two families are kept, so that consecutive tests on one family do not recompute it.
+_FULL = {}
+
+
+def _full_layer_oracle(cfg, rounded):
+    """(x, w, dy, y_ref, dw_ref) for all K kernels of cfg's layer; inputs rounded to bf16 first if asked."""
+    key = (cfg.index, cfg.N, cfg.C, cfg.H, cfg.W, cfg.K, cfg.R, cfg.S, cfg.stride, cfg.pad, rounded)
+    if key not in _FULL:
+        while len(_FULL) >= 2:
+            _FULL.pop(next(iter(_FULL)))
+        whole = cfg.with_slice(0, cfg.K)
+        x, w, dy = synth.make_inputs(whole)
+        if rounded:
+            x, w, dy = (synth.round_to_bf16(a) for a in (x, w, dy))
+        sh = oracle_shape(whole)
+        _FULL[key] = (x, w, dy, oracle.conv_fwd(sh, x, w), oracle.conv_bwd_weight(sh, x, dy))
+    else:
+        _FULL[key] = _FULL.pop(key)   # most recently used last
+    return _FULL[key]
+
+
+def _report(what, got, ref, tol):
+    """Gate on the declared metric (RMS-floored relative error); print the two plain figures beside it."""
+    got = np.asarray(got, dtype=np.float64)
+    e = rel_err(got, ref)
+    diff = np.abs(got - ref)
+    inf_ratio = float(diff.max() / np.abs(ref).max())
+    big = np.abs(ref) >= 1e-3 * np.abs(ref).max()          # plain relative error where the reference is not tiny
+    plain = float((diff[big] / np.abs(ref[big])).max())
+    print(f"  {what}: rms-floored max rel {e:.3e} (gate {tol:.0e}); |g-o|_inf/|o|_inf {inf_ratio:.3e}; "
+          f"plain max rel over |o| >= 1e-3 |o|_inf {plain:.3e}")
+    assert e <= tol, f"{what}: max rel err {e:.3e} > {tol:.1e}"
+
+
+def _full(cfg, dtype):
+    """All three passes at full size against the oracle, every element of the slice."""
+    k0, k1 = cfg.slice
+    bf16 = dtype == cs.CONV_BF16
+    x, w, dy, y_ref, dw_ref = _full_layer_oracle(cfg, rounded=bf16)
+    sh = oracle_shape(cfg)
+    dev = Device(cfg, x, w, dy, dtype=dtype)
+    tag = f"{cfg.name}[{k0},{k1}) {'bf16' if bf16 else 'f32'}"
+    tol = BF16_TOL if bf16 else FP32_TOL
+    y = dev.fwd(fill=5.0)
+    _report(f"{tag} y", y[:, k0:k1], y_ref[:, k0:k1], tol)
+    if k0 > 0 or k1 < cfg.K:
+        assert np.all(y[:, :k0] == 5.0) and np.all(y[:, k1:] == 5.0), "channels outside the slice were written"
+    dx = dev.bwd_data()
+    dx_ref = oracle.conv_bwd_data(sh, dy, w)
+    _report(f"{tag} dx", dx, dx_ref, tol)
+    dw = dev.bwd_weight(fill=5.0)
+    _report(f"{tag} dw", dw[k0:k1], dw_ref[k0:k1], FP32_TOL)   # dw is fp32 also on the bf16 path
+    if k0 > 0 or k1 < cfg.K:
+        assert np.all(dw[:k0] == 5.0) and np.all(dw[k1:] == 5.0), "filters outside the slice were written"
+    if not bf16:
+        return
+    # The same device results against the oracle on the inputs BEFORE rounding to bf16: input
+    # rounding, accumulation and output rounding together must stay inside the bf16 tolerance.
+    xo, wo, dyo, yo_ref, dwo_ref = _full_layer_oracle(cfg, rounded=False)
+    _report(f"{tag} y vs oracle on unrounded inputs", y[:, k0:k1], yo_ref[:, k0:k1], BF16_TOL)
+    _report(f"{tag} dx vs oracle on unrounded inputs", dx, oracle.conv_bwd_data(sh, dyo, wo), BF16_TOL)
+    _report(f"{tag} dw vs oracle on unrounded inputs", dw[k0:k1], dwo_ref[k0:k1], BF16_TOL)
+
+
+FULL_SIZE = [("cfg2", "f32"), ("cfg5a", "f32"), ("cfg5a", "bf16"), ("cfg5b", "f32"), ("cfg5b", "bf16"),
+             ("cfg3", "f32"), ("cfg4", "f32")]
+
+
+@pytest.mark.parametrize("name,dtype", FULL_SIZE)
+def test_benchmark_configs_every_element(name, dtype):
+    _full(synth.CONFIGS[name], cs.CONV_F32 if dtype == "f32" else cs.CONV_BF16)
+
+
+@pytest.mark.parametrize("k0,k1", [(188, 376), (1313, 1500), (0, 64)])
+def test_eighth_of_the_large_layer_every_element_fp32(k0, k1):
+    """One of eight equal shares of the 1500-kernel layer (Eq. (1) with equal devices): a full
+    row tile plus a half row tile in the forward and weight-gradient passes; and a share that
+    is a half tile only."""
+    _full(synth.CONFIGS["cfg3"].with_slice(k0, k1), cs.CONV_F32)
+
+
+def test_large_layer_every_element_bf16():
+    _full(synth.CONFIGS["cfg3"], cs.CONV_BF16)
+
+
+def test_full_size_oracle_cache_is_released():
+    _FULL.clear()
 
 
 def _sampled(cfg, dtype, tol, n=1500):
+    """Sampled comparison, for layers too large for the full oracle."""
     x, w, dy = synth.make_inputs(cfg)
     if dtype == cs.CONV_BF16:
         x, w, dy = (synth.round_to_bf16(a) for a in (x, w, dy))
@@ -174,24 +274,6 @@ def _sampled(cfg, dtype, tol, n=1500):
     assert err <= (tol if dtype == cs.CONV_F32 else FP32_TOL), f"dw sampled: {err:.3e}"
     if k0 > 0 or k1 < cfg.K:
         assert np.all(dw[:k0] == 5.0) and np.all(dw[k1:] == 5.0)
-
-
-@pytest.mark.parametrize("name", SAMPLED)
-def test_benchmark_configs_sampled_fp32(name):
-    _sampled(synth.CONFIGS[name], cs.CONV_F32, FP32_TOL)
-
-
-@pytest.mark.parametrize("name", SAMPLED)
-def test_benchmark_configs_sampled_bf16(name):
-    _sampled(synth.CONFIGS[name], cs.CONV_BF16, BF16_TOL)
-
-
-@pytest.mark.parametrize("k0,k1", [(188, 376), (1313, 1500), (0, 64)])
-def test_eighth_of_the_large_layer_sampled_fp32(k0, k1):
-    """One of eight equal shares of the 1500-kernel layer (Eq. (1) with equal devices): a full
-    row tile plus a half row tile in the forward and weight-gradient passes; and a share that
-    is a half tile only."""
-    _sampled(synth.CONFIGS["cfg3"].with_slice(k0, k1), cs.CONV_F32, FP32_TOL)
 
 
 def test_device_share_equals_slice_of_full_layer():
