@@ -75,8 +75,13 @@ class HipEvents:
 
 
 def cpu_baseline(cfg, x, w, dy, images):
-    """The oracle as it stands on the first `images` images of the batch, all kernels of the slice."""
+    """The oracle as it stands on the first `images` images of the batch (default: all of them), all
+    kernels of the slice, compiled -O3 -march=native on this host when a compiler is there."""
     import oracle
+    try:
+        flags = oracle.use_native_build()
+    except Exception as e:   # no compiler on this host: the portable in-tree build is timed instead
+        flags = f"-O2 -fopenmp (portable build; native build failed: {type(e).__name__})"
     k0, k1 = cfg.slice
     n = min(images, cfg.N)
     sh = oracle.Shape(n, cfg.C, cfg.H, cfg.W, cfg.K, cfg.R, cfg.S, cfg.stride, cfg.stride, cfg.pad, cfg.pad, k0, k1)
@@ -87,9 +92,10 @@ def cpu_baseline(cfg, x, w, dy, images):
     oracle.conv_bwd_weight(sh, xs, dys)
     dt = time.perf_counter() - t0
     flops = 3 * 2 * n * (k1 - k0) * cfg.P * cfg.Q * cfg.C * cfg.R * cfg.S
+    which = f"all {cfg.N} images" if n == cfg.N else f"first {n} of {cfg.N} images"
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"first {n} of {cfg.N} images of {cfg.name}, all {k1 - k0} kernels of the slice, "
-                      f"fwd+bwd_data+bwd_weight, fp64 direct loops, {dt:.1f} s"}
+            "sample": f"{which} of {cfg.name}, all {k1 - k0} kernels of the slice (the whole layer), "
+                      f"fwd+bwd_data+bwd_weight, fp64 direct loops, gcc {flags}, {dt:.1f} s"}
 
 
 KERNEL_OF = {"conv_fwd": "fwd_gemm_kernel", "conv_bwd_data": "bwd_data_gemm_kernel",
@@ -335,7 +341,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg3", help="cfg1..cfg5b (default: the 1500-kernel layer)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--cpu-images", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-images", type=int, default=1 << 30,
+                    help="images in the CPU-oracle sample (default: the whole batch; 0 = skip)")
     ap.add_argument("--table", action="store_true", help="measure all configurations (not the contract line)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="first run one plain device copy of this many MiB (a kernel of known HBM traffic "

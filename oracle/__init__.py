@@ -34,6 +34,21 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def use_native_build() -> str:
+    """For the timed baseline only: the same source compiled ``-O3 -march=native`` for the
+    host this process runs on, into a temporary directory, and used from then on in this
+    process.  Returns the compiler flags used.  (The in-tree build stays portable, because
+    it is built on one machine and may be loaded on another.)"""
+    global _lib
+    import tempfile
+    flags = ["-O3", "-march=native", "-fopenmp"]
+    out = os.path.join(tempfile.mkdtemp(prefix="conv_oracle_"), "libconv_oracle_native.so")
+    subprocess.check_call(["gcc"] + flags + ["-shared", "-fPIC", "-std=c11", "-o", out, _SRC])
+    _lib = None
+    _load(out)
+    return " ".join(flags)
+
+
 class _Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("N", "C", "H", "W", "K", "R", "S", "sh", "sw", "ph", "pw", "k0", "k1")]
@@ -69,10 +84,10 @@ class Shape:
 _lib = None
 
 
-def _load():
+def _load(path: str | None = None):
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        lib = ctypes.CDLL(path or build())
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int64)
         sp = ctypes.POINTER(_Shape)
