@@ -104,6 +104,25 @@ int conv_fwd(const conv_desc_t *desc, const void *x, const void *w, void *y,
              void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * conv_fwd for callers that cannot allocate device memory or hand over a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same kernels, with the workspace taken from a device
+ * array of CONV_NOALLOC_MAX_WORKSPACE bytes that is part of the library's code
+ * object (each GPU the library runs on holds its own copy until the process
+ * ends).  The call itself allocates nothing.  Arguments and errors as for
+ * conv_fwd; a layer whose conv_workspace_bytes(desc, CONV_PASS_FWD) exceeds
+ * CONV_NOALLOC_MAX_WORKSPACE is refused with CONV_ERR_WORKSPACE before any
+ * launch.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on one GPU (different streams or host threads) race and must be
+ * serialised by the caller; calls on one stream are safe.  The array keeps the
+ * last call's contents; the kernels write every part they read, so no call
+ * depends on them.
+ */
+#define CONV_NOALLOC_MAX_WORKSPACE (96u << 20)
+int conv_fwd_noalloc(const conv_desc_t *desc, const void *x, const void *w, void *y,
+                     void *hip_stream);
+
+/*
  * Input gradient of the slice (backward convolution, abstract):
  *   dx[n,c,h,v] (+)= sum_{k0<=k<k1} sum_{r,s} dy[n,k,p,q] * w[k,c,r,s]
  * over the (p,q) with p*stride_h-pad_h+r = h and q*stride_w-pad_w+s = v.

@@ -16,7 +16,9 @@ LIB_PATH = os.environ.get("CONVSLICE_LIB") or os.path.join(_HERE, "libconvslice.
 CONV_F32, CONV_BF16 = 0, 1
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 
-EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_bwd_data",
+NOALLOC_MAX_WORKSPACE = 96 << 20
+
+EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_fwd_noalloc", "conv_bwd_data",
            "conv_bwd_weight", "conv_status_string", "conv_probe_next_call",
            "conv_partition", "conv_partition_estimate", "conv_calibrate_workspace_bytes",
            "conv_calibrate", "conv_layer_workspace_bytes", "conv_layer_fwd",
@@ -95,6 +97,8 @@ def load() -> ctypes.CDLL:
             f = getattr(lib, name)
             f.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
             f.restype = ctypes.c_int
+        lib.conv_fwd_noalloc.argtypes = [dp, vp, vp, vp, vp]
+        lib.conv_fwd_noalloc.restype = ctypes.c_int
         lib.conv_probe_next_call.argtypes = [vp, vp]
         lib.conv_probe_next_call.restype = ctypes.c_int
         lib.conv_status_string.argtypes = [ctypes.c_int]
@@ -187,6 +191,17 @@ def _call(name: str, desc: ConvDesc, a, b, out, ws, stream, raw_status: bool):
 def conv_fwd(desc: ConvDesc, x, w, y, ws=None, stream=None, raw_status=False):
     """y[:, k0:k1] = conv(x, w[k0:k1]) enqueued on the stream; returns y."""
     return _call("conv_fwd", desc, x, w, y, ws, stream, raw_status)
+
+
+def conv_fwd_noalloc(desc: ConvDesc, x, w, y, stream=None, raw_status=False):
+    """conv_fwd on the library's own fixed scratch array (layers up to NOALLOC_MAX_WORKSPACE); returns y."""
+    cd = desc.c_struct()
+    rc = load().conv_fwd_noalloc(ctypes.byref(cd), _ptr(x), _ptr(w), _ptr(y), _stream(stream))
+    if raw_status:
+        return rc
+    if rc != 0:
+        raise ConvError(rc, "conv_fwd_noalloc")
+    return y
 
 
 def conv_bwd_data(desc: ConvDesc, dy, w, dx, ws=None, stream=None, raw_status=False):

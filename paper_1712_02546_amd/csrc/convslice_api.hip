@@ -616,6 +616,55 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   return check_launch();
 }
 
+// ---- forward pass for callers that cannot allocate: the workspace is a device array of the library ----
+}  // extern "C"
+
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)CONV_NOALLOC_MAX_WORKSPACE;
+// In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU (every GPU holds its own copy)
+std::mutex g_scratch_mu;
+
+// The device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CONV_ERR_LAUNCH;
+  const std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return CONV_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return CONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_fwd_noalloc(const conv_desc_t* desc, const void* x, const void* w, void* y, void* hip_stream) {
+  Geo g;
+  const int rc = make_geo(desc, g);
+  if (rc != CONV_OK) return rc;
+  if (!x || !w || !y) return CONV_ERR_NULL;
+  if (conv_workspace_bytes(desc, CONV_PASS_FWD) > kStaticScratchBytes) return CONV_ERR_WORKSPACE;
+  if (g.Ks == 0) return CONV_OK;
+  void* ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs != CONV_OK) return rs;
+  // Every part of the workspace a kernel reads is written earlier in the same call (work copies, zero pages,
+  // tap table, tail slots), so nothing has to be cleared between calls.
+  return conv_fwd(desc, x, w, y, ws, kStaticScratchBytes, hip_stream);
+}
+
 int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
                   void* hip_stream) {
   const Probe probe;

@@ -140,6 +140,18 @@ def test_filter_extent_limit_is_on_the_product_only():
         assert cs.conv_bwd_data(d, A, A, A, WS, stream=0, raw_status=True) == -2
 
 
+def test_noalloc_forward_rejects_before_any_launch():
+    """conv_fwd_noalloc: argument errors as conv_fwd, and a layer whose workspace exceeds the
+    library's fixed array is refused (none of these calls reaches the GPU)."""
+    assert cs.conv_fwd_noalloc(cs.ConvDesc(**{**GOOD, "N": 0}), A, A, A, stream=0, raw_status=True) == -2
+    assert cs.conv_fwd_noalloc(cs.ConvDesc(**GOOD), None, A, A, stream=0, raw_status=True) == -1
+    assert cs.conv_fwd_noalloc(cs.ConvDesc(**GOOD, k0=5, k1=4), A, A, A, stream=0, raw_status=True) == -3
+    big = cs.ConvDesc(N=128, C=500, H=14, W=14, K=1500, R=5, S=5)
+    assert cs.conv_workspace_bytes(big, cs.PASS_FWD) > cs.NOALLOC_MAX_WORKSPACE
+    assert cs.conv_fwd_noalloc(big, A, A, A, stream=0, raw_status=True) == -5
+    assert cs.conv_fwd_noalloc(cs.ConvDesc(**GOOD, k0=4, k1=4), A, A, A, stream=0, raw_status=True) == 0
+
+
 def test_null_descriptor():
     lib = cs.load()
     assert lib.conv_fwd(None, 1, 1, 1, 1, 0, None) == -1
