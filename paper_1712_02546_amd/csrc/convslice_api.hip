@@ -12,6 +12,7 @@
 #include "gemm_kernels.h"
 #include "gemm_bf16_kernels.h"
 #include "pack_kernels.h"
+#include "pm_kernels.h"
 
 namespace {
 
@@ -411,6 +412,78 @@ bool needs_pad_checks(const Geo& g) {
   return g.ph > 0 || g.pw > 0 || (g.P - 1) * g.sh - g.ph + g.R > g.H || (g.Q - 1) * g.sw - g.pw + g.S > g.W;
 }
 
+// ---- pixel-major path for layers with few input channels (pm_kernels.h) ----
+// Chosen for the whole layer (never by the slice), so that every slice of a layer takes the same path.
+struct PmPlan {
+  bool ok;        // forward and weight gradient can take the path
+  bool ok_data;   // the input gradient too (its T = w^T * dy matrix fits)
+  bool copy;      // taps are read from a zero-bordered fp32 copy of x (padding, or bf16 input) instead of x itself
+  cs::PmGeo pg;
+};
+PmPlan plan_pm(const Geo& g, int dtype) {
+  PmPlan p;
+  const bool pad = needs_pad_checks(g);
+  p.copy = pad || dtype != CONV_F32;
+  p.pg.Hp = pad ? (g.P - 1) * g.sh + g.R : g.H;
+  p.pg.Wp = pad ? (g.Q - 1) * g.sw + g.S : g.W;
+  p.pg.NPQ = (int)std::min<int64_t>((int64_t)g.N * g.PQ, INT32_MAX);
+  p.pg.CT = (p.pg.NPQ + cs::BN - 1) / cs::BN;
+  p.pg.NC = (g.PQ + 31) / 32;
+  p.ok = g.C <= 16 && g.CRS <= 480 && g.PQ >= 32 && (int64_t)g.N * g.C * p.pg.Hp * p.pg.Wp < kMaxElems;
+  p.ok_data = p.ok && (int64_t)g.N * g.CRS * g.PQ < kMaxElems;
+  return p;
+}
+
+struct PmFwdPlan {
+  bool repitch;
+  int ldw, nch;
+  size_t off_xb, off_w, off_tab, total;
+};
+PmFwdPlan plan_pm_fwd(const Geo& g, const PmPlan& pm, int dtype) {
+  PmFwdPlan p;
+  p.repitch = dtype != CONV_F32 || (g.CRS % cs::BK) != 0;
+  p.ldw = (int)round_up(g.CRS, cs::BK);
+  p.nch = p.ldw / cs::BK;
+  size_t o = 0;
+  p.off_xb = o;  o += pm.copy ? seg((int64_t)g.N * g.C * pm.pg.Hp * pm.pg.Wp) : 0;
+  p.off_w = o;   o += p.repitch ? seg((int64_t)g.Ks * p.ldw) : 0;
+  p.off_tab = o; o += seg((int64_t)(p.nch + 4) * cs::BK);
+  p.total = o;
+  return p;
+}
+
+struct PmBwdDataPlan {
+  int Ksp, nch;
+  size_t off_dy, off_wt, off_T, total;
+};
+PmBwdDataPlan plan_pm_bwd_data(const Geo& g, int dtype) {
+  PmBwdDataPlan p;
+  p.Ksp = (int)round_up(g.Ks, cs::BK);
+  p.nch = p.Ksp / cs::BK;
+  size_t o = 0;
+  p.off_dy = o; o += dtype != CONV_F32 ? seg((int64_t)g.N * g.Ks * g.PQ) : 0;   // fp32 copy of the slice's maps
+  p.off_wt = o; o += seg((int64_t)g.CRS * p.Ksp);
+  p.off_T = o;  o += seg((int64_t)g.N * g.CRS * g.PQ);
+  p.total = o;
+  return p;
+}
+
+struct PmBwdWeightPlan {
+  int CT, nch;
+  size_t off_xb, off_pix, off_part, total;
+};
+PmBwdWeightPlan plan_pm_bwd_weight(const Geo& g, const PmPlan& pm) {
+  PmBwdWeightPlan p;
+  p.CT = (g.CRS + cs::BN - 1) / cs::BN;
+  p.nch = g.N * pm.pg.NC;
+  size_t o = kZeroBytes;
+  p.off_xb = o;   o += pm.copy ? seg((int64_t)g.N * g.C * pm.pg.Hp * pm.pg.Wp) : 0;
+  p.off_pix = o;  o += seg((int64_t)pm.pg.NC * 32);
+  p.off_part = o; o += seg(split_partial_elems(g, p.CT, p.nch, true));
+  p.total = o;
+  return p;
+}
+
 // src[rows][cols] (pitch srcPitch, element type by dtype) -> dst[cols][rowsPad] (fp32, or bf16 when
 // out16), for batches 0..batch-1; batches at or past batchValid are written as zeros.
 void launch_transpose_in(int dtype, const void* src, int64_t srcBatch, int64_t srcPitch, int rows, int cols,
@@ -476,6 +549,175 @@ int check_ws(const void* ws, size_t ws_bytes, size_t need) {
   return CONV_OK;
 }
 
+// ---- pixel-major passes: host side ----
+inline int grid_for(int64_t count, int cap = 8192) { return (int)std::min<int64_t>((count + 255) / 256, cap); }
+
+// The image the taps are read from: x itself, or its zero-bordered fp32 copy (made here).
+const float* pm_input(const Geo& g, const PmPlan& pm, int dtype, const void* x, float* xb, hipStream_t st) {
+  if (!pm.copy) return (const float*)x;
+  const int64_t count = (int64_t)g.N * g.C * pm.pg.Hp * pm.pg.Wp;
+  if (dtype == CONV_F32)
+    hipLaunchKernelGGL(cs::pm_border_copy_kernel<float>, dim3(grid_for(count)), dim3(256), 0, st, g, pm.pg.Hp, pm.pg.Wp,
+                       (const float*)x, xb);
+  else
+    hipLaunchKernelGGL(cs::pm_border_copy_kernel<uint16_t>, dim3(grid_for(count)), dim3(256), 0, st, g, pm.pg.Hp,
+                       pm.pg.Wp, (const uint16_t*)x, xb);
+  return xb;
+}
+
+int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+           hipStream_t st, const Probe& probe) {
+  const PmFwdPlan p = plan_pm_fwd(g, pm, dtype);
+  int rc;
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  char* base = (char*)ws;
+  const size_t es = elem_size(dtype);
+  const float* xb = pm_input(g, pm, dtype, x, (float*)(base + p.off_xb), st);
+  const float* wmat;
+  if (p.repitch) {
+    float* wp = (float*)(base + p.off_w);
+    const char* wsrc = (const char*)w + (size_t)g.k0 * g.CRS * es;
+    const int blocks = grid_for((int64_t)g.Ks * p.ldw, 4096);
+    if (dtype == CONV_F32)
+      hipLaunchKernelGGL(cs::repitch_rows_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)wsrc,
+                         (int64_t)g.CRS, g.Ks, g.CRS, wp, p.ldw);
+    else
+      hipLaunchKernelGGL(cs::repitch_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)wsrc,
+                         (int64_t)g.CRS, g.Ks, g.CRS, wp, p.ldw);
+    wmat = wp;
+  } else {
+    wmat = (const float*)w + (size_t)g.k0 * g.CRS;
+  }
+  int* tab = (int*)(base + p.off_tab);
+  const int entries = (p.nch + 4) * cs::BK;
+  hipLaunchKernelGGL(cs::pm_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, pm.pg.Hp, pm.pg.Wp, entries,
+                     tab);
+  const RowSplit rs = split_rows(g.Ks);
+  probe.begin(st);
+  auto launch = [&](auto kern, auto* yout, int m0, int tiles) -> int {
+    int rc2;
+    if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
+    hipLaunchKernelGGL(kern, dim3(cs::grid_contiguous(tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wmat,
+                       p.ldw, xb, tab, yout, m0, tiles, p.nch);
+    return CONV_OK;
+  };
+  rc = CONV_OK;
+  if (dtype == CONV_F32) {
+    if (rs.full > 0) rc = launch(cs::fwd_pm_gemm_kernel<2, float>, (float*)y, 0, rs.full);
+    if (rc == CONV_OK && rs.half) rc = launch(cs::fwd_pm_gemm_kernel<1, float>, (float*)y, rs.full * cs::BM, 1);
+  } else {
+    if (rs.full > 0) rc = launch(cs::fwd_pm_gemm_kernel<2, uint16_t>, (uint16_t*)y, 0, rs.full);
+    if (rc == CONV_OK && rs.half) rc = launch(cs::fwd_pm_gemm_kernel<1, uint16_t>, (uint16_t*)y, rs.full * cs::BM, 1);
+  }
+  probe.end(st);
+  if (rc != CONV_OK) return rc;
+  return check_launch();
+}
+
+int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void* dy, const void* w, void* dx, void* ws,
+                size_t ws_bytes, hipStream_t st, const Probe& probe) {
+  const PmBwdDataPlan p = plan_pm_bwd_data(g, dtype);
+  int rc;
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  char* base = (char*)ws;
+  const size_t es = elem_size(dtype);
+  // the slice's maps in fp32: dy in place, or a compact copy of the slice's channels for bf16
+  const float* dy_k0;
+  int64_t imgPitch;
+  if (dtype == CONV_F32) {
+    dy_k0 = (const float*)dy + (size_t)g.k0 * g.PQ;
+    imgPitch = (int64_t)g.K * g.PQ;
+  } else {
+    float* d = (float*)(base + p.off_dy);
+    imgPitch = (int64_t)g.Ks * g.PQ;
+    hipLaunchKernelGGL(cs::pm_slice_to_f32_kernel, dim3(grid_for((int64_t)g.N * imgPitch)), dim3(256), 0, st,
+                       (const uint16_t*)dy + (size_t)g.k0 * g.PQ, (int64_t)g.K * g.PQ, imgPitch, g.N, d);
+    dy_k0 = d;
+  }
+  // w[k][(c,r,s)] -> wt[(c,r,s)][Ksp], zero past Ks
+  float* wt = (float*)(base + p.off_wt);
+  launch_transpose_in(dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0, p.Ksp, p.Ksp, 1,
+                      nullptr, st);
+  float* T = (float*)(base + p.off_T);
+  const bool vec4 = g.PQ % 4 == 0;
+  const RowSplit rs = split_rows(g.CRS);
+  probe.begin(st);
+  auto launch = [&](auto kern, int m0, int tiles) -> int {
+    int rc2;
+    if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
+    hipLaunchKernelGGL(kern, dim3(cs::grid_contiguous(tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wt,
+                       p.Ksp, dy_k0, imgPitch, T, m0, tiles, p.nch);
+    return CONV_OK;
+  };
+  rc = CONV_OK;
+  if (vec4) {
+    if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, true>, 0, rs.full);
+    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_data_pm_gemm_kernel<1, true>, rs.full * cs::BM, 1);
+  } else {
+    if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, false>, 0, rs.full);
+    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_data_pm_gemm_kernel<1, false>, rs.full * cs::BM, 1);
+  }
+  probe.end(st);
+  if (rc != CONV_OK) return rc;
+  const int blocks = grid_for((int64_t)g.N * g.C * g.HW, 1 << 20);
+  if (dtype == CONV_F32) {
+    if (acc) hipLaunchKernelGGL((cs::col2im_pm_kernel<float, true>), dim3(blocks), dim3(256), 0, st, g, T, (float*)dx);
+    else hipLaunchKernelGGL((cs::col2im_pm_kernel<float, false>), dim3(blocks), dim3(256), 0, st, g, T, (float*)dx);
+  } else {
+    if (acc) hipLaunchKernelGGL((cs::col2im_pm_kernel<uint16_t, true>), dim3(blocks), dim3(256), 0, st, g, T, (uint16_t*)dx);
+    else hipLaunchKernelGGL((cs::col2im_pm_kernel<uint16_t, false>), dim3(blocks), dim3(256), 0, st, g, T, (uint16_t*)dx);
+  }
+  return check_launch();
+}
+
+// fp32 only (bf16 layers take the bf16 matrix-core weight gradient).
+int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
+                  hipStream_t st, const Probe& probe) {
+  const PmBwdWeightPlan p = plan_pm_bwd_weight(g, pm);
+  int rc;
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  char* base = (char*)ws;
+  float* zero = (float*)base;
+  hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
+  const float* xb = pm_input(g, pm, CONV_F32, x, (float*)(base + p.off_xb), st);
+  int* pixtab = (int*)(base + p.off_pix);
+  hipLaunchKernelGGL(cs::pm_pixel_table_kernel, dim3((pm.pg.NC * 32 + 255) / 256), dim3(256), 0, st, g, pm.pg.Wp, pm.pg.NC,
+                     pixtab);
+  const float* dy_k0 = (const float*)dy + (size_t)g.k0 * g.PQ;
+  const int64_t imgPitch = (int64_t)g.K * g.PQ;
+  float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
+  float* scratch = (float*)(base + p.off_part);
+  auto launch = [&](auto kern, int mi, int m0, int tiles) -> int {
+    int rc2;
+    if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
+    const int rows = std::min(g.Ks - m0, tiles * 64 * mi);
+    const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true);
+    const int64_t stride = (int64_t)rows * g.CRS;
+    float* out = splits > 1 ? scratch : dwslice;
+    const int rowBase = splits > 1 ? m0 : 0;
+    hipLaunchKernelGGL(kern, dim3(cs::grid_contiguous(tiles * p.CT * splits)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg,
+                       dy_k0, imgPitch, xb, zero, pixtab, out, stride, m0, rowBase, tiles, p.CT, p.nch, splits);
+    if (splits > 1)
+      hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(grid_for(stride)), dim3(256), 0, st, scratch, stride, splits,
+                         dwslice + (int64_t)m0 * g.CRS, stride);
+    return CONV_OK;
+  };
+  const bool vec4 = g.PQ % 4 == 0;
+  const RowSplit rs = split_rows(g.Ks);
+  rc = CONV_OK;
+  probe.begin(st);
+  if (vec4) {
+    if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, true>, 2, 0, rs.full);
+    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, true>, 1, rs.full * cs::BM, 1);
+  } else {
+    if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, false>, 2, 0, rs.full);
+    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, false>, 1, rs.full * cs::BM, 1);
+  }
+  probe.end(st);
+  if (rc != CONV_OK) return rc;
+  return check_launch();
+}
+
 }  // namespace
 
 extern "C" {
@@ -494,13 +736,18 @@ size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
   Geo g;
   if (make_geo(desc, g) != CONV_OK) return 0;
   if (g.Ks == 0) return 0;
+  const PmPlan pm = plan_pm(g, desc->dtype);
   switch (pass) {
     case CONV_PASS_FWD:
+      if (pm.ok) return plan_pm_fwd(g, pm, desc->dtype).total;
       return bf16_mfma_fwd_ok(g, desc->dtype) ? plan_fwd16(g).total : plan_fwd(g, desc->dtype).total;
     case CONV_PASS_BWD_DATA:
+      if (pm.ok_data) return plan_pm_bwd_data(g, desc->dtype).total;
       return bf16_mfma_bwd_data_ok(g, desc->dtype) ? plan_bwd_data16(g).total : plan_bwd_data(g).total;
     case CONV_PASS_BWD_WEIGHT:
-      return bf16_mfma_bwd_weight_ok(g, desc->dtype) ? plan_bwd_weight16(g).total : plan_bwd_weight(g).total;
+      if (bf16_mfma_bwd_weight_ok(g, desc->dtype)) return plan_bwd_weight16(g).total;
+      if (pm.ok) return plan_pm_bwd_weight(g, pm).total;
+      return plan_bwd_weight(g).total;
     default: return 0;
   }
 }
@@ -546,6 +793,8 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   if (!x || !w || !y) return CONV_ERR_NULL;
   if (misaligned(x, 16) || misaligned(w, 16) || misaligned(y, 16)) return CONV_ERR_ALIGN;
   if (g.Ks == 0) return CONV_OK;
+  const PmPlan pm = plan_pm(g, desc->dtype);
+  if (pm.ok) return pm_fwd(g, pm, desc->dtype, x, w, y, ws, ws_bytes, (hipStream_t)hip_stream, probe);
   if (bf16_mfma_fwd_ok(g, desc->dtype)) {
     const Fwd16Plan p = plan_fwd16(g);
     if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
@@ -687,6 +936,8 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     }
     return CONV_OK;
   }
+  const PmPlan pm = plan_pm(g, desc->dtype);
+  if (pm.ok_data) return pm_bwd_data(g, pm, desc->dtype, desc->accumulate != 0, dy, w, dx, ws, ws_bytes, st, probe);
   if (bf16_mfma_bwd_data_ok(g, desc->dtype)) {
     const BwdData16Plan p = plan_bwd_data16(g);
     if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
@@ -858,6 +1109,10 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
                          dwslice, sliceElems);
     }
     return check_launch();
+  }
+  {
+    const PmPlan pm = plan_pm(g, desc->dtype);
+    if (pm.ok) return pm_bwd_weight(g, pm, x, dy, dw, ws, ws_bytes, (hipStream_t)hip_stream, probe);
   }
   const BwdWeightPlan p = plan_bwd_weight(g);
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;

@@ -1,0 +1,450 @@
+// Pixel-major passes for layers with few input channels (first layers: C = 3).
+//
+// There the input x is tiny next to y / dy (cfg2: 1.6 MB against 200 MB), so the layout of
+// the GEMM is chosen for y and dy: a 32-lane column block is 32 consecutive output pixels of
+// one image, i.e. 128 contiguous bytes of the caller's NCHW tensor.  y is written and dy is
+// read in place -- no batch-innermost work copy of either -- and the im2col side, which is
+// a gather in this mapping, is staged with 4-byte LDS-DMA loads whose lane offsets are
+// constants (a lane is one pixel, or one filter tap) while the tap (or pixel) moves in a
+// scalar base register.  Out-of-image taps never need a test: when the layer has padding,
+// x is first copied once into a zero-bordered fp32 image xb[N][C][Hp][Wp] (a few MB).
+//
+//   fwd         y_n[k][pix]   = sum_j  w[k][j]      * x_n[tap j at pix]      M = Ks, red = C*R*S
+//   bwd_data    T_n[j][pix]   = sum_k  w[k][j]      * dy_n[k][pix]           M = C*R*S, red = Ks
+//               dx_n[c][h][v] = sum of the T_n[(c,r,s)][pix] whose window tap lands on (h,v)
+//   bwd_weight  dw[k][j]      = sum_(n,pix) dy_n[k][pix] * x_n[tap j at pix] M = Ks, red = N*P*Q
+//
+// Columns are the flattened index n*P*Q + pix in tiles of 128; tiles, main loop, LDS images
+// and the weight-gradient split are those of gemm_kernels.h.
+#pragma once
+#include "conv_common.h"
+#include "gemm_kernels.h"
+
+namespace cs {
+
+struct PmGeo {
+  int Hp, Wp;   // extents of the image the taps are read from: x itself, or its zero-bordered copy
+  int NPQ;      // N*P*Q columns
+  int CT;       // column tiles of 128 (forward, input gradient)
+  int NC;       // reduction chunks of 32 pixels per image (weight gradient)
+};
+
+// 4-byte LDS-DMA load: lane l's dword lands at lds_uniform + 4*l; address = uniform base + lane offset.
+__device__ __forceinline__ void dma4_uv(const char* base_uniform, unsigned& lane_off, float* lds_uniform) {
+  asm volatile("" : "+v"(lane_off));
+  __builtin_amdgcn_global_load_lds(CS_GPTR(base_uniform + lane_off), CS_LPTR(lds_uniform), 4, 0, 0);
+}
+
+static __device__ __forceinline__ int pick8(const i32x4 (&v)[2], int r) { return v[r >> 2][r & 3]; }   // r: compile-time 0..7
+
+// xb[n][c][hp][wp] = x[n][c][hp-ph][wp-pw] inside the image, 0 outside; converted to fp32.
+template <typename Tin>
+__global__ __launch_bounds__(256) void pm_border_copy_kernel(Geo g, int Hp, int Wp, const Tin* __restrict__ x,
+                                                             float* __restrict__ xb) {
+  const int64_t total = (int64_t)g.N * g.C * Hp * Wp;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int wp = (int)(i % Wp);
+    const int64_t t = i / Wp;
+    const int hp = (int)(t % Hp);
+    const int64_t nc = t / Hp;
+    const int h = hp - g.ph, v = wp - g.pw;
+    float val = 0.f;
+    if (h >= 0 && h < g.H && v >= 0 && v < g.W) val = load_as_f32<Tin>(x + (nc * g.H + h) * g.W + v);
+    xb[i] = val;
+  }
+}
+
+// dst[n][k][pix] (fp32, Ks channels) = src[n][k0+k][pix] (bf16, K channels).
+__global__ __launch_bounds__(256) void pm_slice_to_f32_kernel(const uint16_t* __restrict__ src, int64_t srcImg,
+                                                              int64_t dstImg, int N, float* __restrict__ dst) {
+  const int64_t total = (int64_t)N * dstImg;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t n = i / dstImg;
+    dst[i] = bf16_to_f32(src[n * srcImg + (i - n * dstImg)]);
+  }
+}
+
+// tab[j] = byte offset of tap j = (c,r,s) from a window's origin inside one image of xb; entries
+// past C*R*S repeat tap 0 (the filter operand is zero there).
+__global__ void pm_tap_table_kernel(Geo g, int Hp, int Wp, int entries, int* __restrict__ tab) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= entries) return;
+  const int j = i < g.CRS ? i : 0;
+  const int c = j / g.RS, rs = j - c * g.RS;
+  const int r = rs / g.S, s = rs - r * g.S;
+  tab[i] = ((c * Hp + r) * Wp + s) * 4;
+}
+
+// Weight gradient: reduction chunk pc of an image covers 32 output pixels.  tab[pc*32 + kk] =
+// byte offset of the window origin of that chunk's pixel kk inside one image of xb, or -1 if the
+// pixel does not count.  The last chunk of an image is moved back so that it ends with the
+// image's last pixel (the dy rows are read in place and must not be over-read); the pixels it
+// shares with the chunk before are the ones that do not count.  Needs P*Q >= 32.
+__global__ void pm_pixel_table_kernel(Geo g, int Wp, int NC, int* __restrict__ tab) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= NC * 32) return;
+  const int pc = i >> 5, kk = i & 31;
+  const int start = pc == NC - 1 ? g.PQ - 32 : pc * 32;
+  const int pix = start + kk;
+  const int p = pix / g.Q, q = pix - p * g.Q;
+  tab[i] = pix >= pc * 32 ? (p * g.sh * Wp + q * g.sw) * 4 : -1;
+}
+
+// Stores this wavefront's accumulators: rows m0.. of `rows` valid rows, columns = flattened
+// (image, pixel) index; element (m, n, pix) goes to out[n*imgPitch + m*PQ + pix].
+template <int MI, typename TOUT>
+__device__ __forceinline__ void pm_store_tile(TOUT* __restrict__ out, int rows, int64_t imgPitch, int PQ, int NPQ,
+                                              int m0, int ct, const f32x16 (&acc)[MI][2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
+    if (col >= NPQ) continue;
+    const int n = col / PQ, pix = col - n * PQ;
+    TOUT* base = out + (int64_t)n * imgPitch + pix;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
+        if (m < rows) store_from_f32<TOUT>(base + (int64_t)m * PQ, acc[i][j][v]);
+      }
+  }
+}
+
+// ---------------------------------------------------------------- forward ----
+// B[kk][col] = xb[n][tap kk at the column's pixel] (row image).  A lane is a pixel: its byte
+// offset (image + window origin) never changes; the tap's offset is added to the uniform base.
+// The tap table is read with scalar loads one chunk ahead.
+struct PmFwdLoadB {
+  static constexpr bool COL = false;
+  const char* xb;
+  const CS_CONST int* tab;
+  i32x4 cur[2], nxt[2];   // tap offsets of rows 8*wv .. 8*wv+7 of the chunk being issued / the next one
+  unsigned laneoff[2];    // the lane's pixel in the tile's columns 0..63 and 64..127
+  __device__ PmFwdLoadB(const Geo& g, const PmGeo& pg, const float* xb_, const int* tab_, int ct, int ch0)
+      : xb((const char*)xb_), tab((const CS_CONST int*)tab_) {
+    const int l = threadIdx.x & 63;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int col = min(ct * BN + 64 * h + l, pg.NPQ - 1);   // columns past the end repeat the last one (never stored)
+      const int n = col / g.PQ, pix = col - n * g.PQ;
+      const int p = pix / g.Q, q = pix - p * g.Q;
+      laneoff[h] = (unsigned)(((n * g.C * pg.Hp) + p * g.sh) * pg.Wp + q * g.sw) * 4u;
+    }
+    fetch(ch0);
+  }
+  __device__ __forceinline__ void fetch(int ch) {
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const CS_CONST i32x4* po = (const CS_CONST i32x4*)(tab + ch * BK + 8 * wv);
+    nxt[0] = po[0];
+    nxt[1] = po[1];
+  }
+  // The table runs three chunks past the end and repeats tap 0 there, so dummy chunks need no test.
+  __device__ __forceinline__ void begin(int ch, bool) {
+    cur[0] = nxt[0];
+    cur[1] = nxt[1];
+    fetch(ch + 1);
+  }
+  __device__ __forceinline__ void issue(int i, float* dst) {   // rows 2i, 2i+1 of the wavefront's eight
+    const char* b0 = xb + (unsigned)pick8(cur, 2 * i);
+    const char* b1 = xb + (unsigned)pick8(cur, 2 * i + 1);
+    dma4_uv(b0, laneoff[0], dst);
+    dma4_uv(b0, laneoff[1], dst + 64);
+    dma4_uv(b1, laneoff[0], dst + 128);
+    dma4_uv(b1, laneoff[1], dst + 192);
+  }
+  __device__ __forceinline__ void end() {}
+};
+
+// y[n][k0+m][pix] for rows mOrigin.. of the slice; w rows have pitch ldw (a multiple of BK, zero past C*R*S).
+template <int MI, typename TOUT>
+__global__ __launch_bounds__(NT) void fwd_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ w, int ldw,
+                                                         const float* __restrict__ xb, const int* __restrict__ tab,
+                                                         TOUT* __restrict__ y, int mOrigin, int MB, int nch) {
+  extern __shared__ __align__(16) float smem[];
+  int L;
+  if (!line_contiguous(blockIdx.x, MB * pg.CT, L)) return;
+  int mb, ct;
+  tile_from_line(L, MB, pg.CT, mb, ct);
+  const int m0 = mOrigin + mb * (64 * MI);
+  f32x16 acc[MI][2];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  FwdLoadA<MI> la(w, ldw, m0, g.Ks);
+  PmFwdLoadB lb(g, pg, xb, tab, ct, 0);
+  gemm_mainloop(la, lb, 0, nch, smem, acc);
+  pm_store_tile<MI, TOUT>(y + (int64_t)g.k0 * g.PQ, g.Ks, (int64_t)g.K * g.PQ, g.PQ, pg.NPQ, m0, ct, acc);
+}
+
+// --------------------------------------------------------- input gradient ----
+// B[kk][col] = dy[n][k0 + kk][pix] (row image), read in place: a row is a kernel, a lane a
+// pixel (VEC4: four consecutive pixels with one 16-byte load, which needs P*Q % 4 == 0).
+// Reduction rows past the slice repeat its last kernel: the filter operand is zero there.
+template <bool VEC4>
+struct PmDyLoadB {
+  static constexpr bool COL = false;
+  const char* dy;        // uniform: channel k0 of image 0
+  unsigned rowBytes;     // one kernel's map
+  int lastRow;           // Ks - 1
+  unsigned laneoff[2];   // VEC4: [0] only
+  unsigned upmask;
+  int wv8, r0;
+  __device__ PmDyLoadB(const Geo& g, const PmGeo& pg, const float* dy_k0, int64_t imgPitch, int ct)
+      : dy((const char*)dy_k0), rowBytes((unsigned)g.PQ * 4u), lastRow(g.Ks - 1) {
+    const int l = threadIdx.x & 63;
+    wv8 = 8 * __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    upmask = l >= 32 ? ~0u : 0u;
+    asm volatile("" : "+v"(upmask));
+    if (VEC4) {
+      const int col = min(ct * BN + 4 * (l & 31), pg.NPQ - 4);
+      const int n = col / g.PQ, pix = col - n * g.PQ;
+      laneoff[0] = (unsigned)(n * imgPitch + pix) * 4u;
+      laneoff[1] = 0;
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int col = min(ct * BN + 64 * h + l, pg.NPQ - 1);
+        const int n = col / g.PQ, pix = col - n * g.PQ;
+        laneoff[h] = (unsigned)(n * imgPitch + pix) * 4u;
+      }
+    }
+  }
+  __device__ __forceinline__ void begin(int ch, bool live) { r0 = (live ? ch : 0) * BK + wv8; }
+  __device__ __forceinline__ void issue(int i, float* dst) {
+    const unsigned ra = (unsigned)min(r0 + 2 * i, lastRow) * rowBytes;
+    const unsigned rb = (unsigned)min(r0 + 2 * i + 1, lastRow) * rowBytes;
+    if (VEC4) {   // lower half-wave: row 2i, upper half-wave: row 2i+1
+      unsigned off = laneoff[0] + ra + ((rb - ra) & upmask);
+      dma16_uv(dy, off, dst);
+    } else {
+      dma4_uv(dy + ra, laneoff[0], dst);
+      dma4_uv(dy + ra, laneoff[1], dst + 64);
+      dma4_uv(dy + rb, laneoff[0], dst + 128);
+      dma4_uv(dy + rb, laneoff[1], dst + 192);
+    }
+  }
+  __device__ __forceinline__ void end() {}
+};
+
+// T[n][j][pix] = sum_k wt[j][k] * dy[n][k0+k][pix]; wt = the slice's filter matrix transposed, pitch Ksp.
+template <int MI, bool VEC4>
+__global__ __launch_bounds__(NT) void bwd_data_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ wt, int Ksp,
+                                                              const float* __restrict__ dy_k0, int64_t imgPitch,
+                                                              float* __restrict__ T, int mOrigin, int MB, int nch) {
+  extern __shared__ __align__(16) float smem[];
+  int L;
+  if (!line_contiguous(blockIdx.x, MB * pg.CT, L)) return;
+  int mb, ct;
+  tile_from_line(L, MB, pg.CT, mb, ct);
+  const int m0 = mOrigin + mb * (64 * MI);
+  f32x16 acc[MI][2];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  FwdLoadA<MI> la(wt, Ksp, m0, g.CRS);
+  PmDyLoadB<VEC4> lb(g, pg, dy_k0, imgPitch, ct);
+  gemm_mainloop(la, lb, 0, nch, smem, acc);
+  pm_store_tile<MI, float>(T, g.CRS, (int64_t)g.CRS * g.PQ, g.PQ, pg.NPQ, m0, ct, acc);
+}
+
+// dx[n][c][h][v] (+)= sum over the taps (r,s) whose window position (p,q) lands on (h,v) of
+// T[n][(c,r,s)][p*Q+q], in increasing (r,s) order.  One thread per input element, v fastest, so
+// a wavefront reads runs of q along each T row it touches.  Misses read a clamped element and
+// add a selected zero (branch-free: several taps' loads in flight).
+template <typename TOUT, bool ACC>
+__global__ __launch_bounds__(256) void col2im_pm_kernel(Geo g, const float* __restrict__ T, TOUT* __restrict__ dx) {
+  const int64_t total = (int64_t)g.N * g.C * g.HW;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int v = (int)(i % g.W);
+    const int64_t t = i / g.W;
+    const int h = (int)(t % g.H);
+    const int64_t nc = t / g.H;               // n*C + c
+    const float* Tc = T + nc * g.RS * g.PQ;   // T[n][(c,0,0)][0]
+    float acc = 0.f;
+    for (int r = (h + g.ph) % g.sh; r < g.R; r += g.sh) {
+      const int hr = h + g.ph - r;
+      const int p = hr / g.sh;
+      const bool rok = hr >= 0 && p < g.P;
+      const int pc = rok ? p : 0;
+#pragma unroll 5
+      for (int s = (v + g.pw) % g.sw; s < g.S; s += g.sw) {
+        const int vs = v + g.pw - s;
+        const int q = vs / g.sw;
+        const bool ok = rok && vs >= 0 && q < g.Q;
+        const float tv = Tc[(int64_t)(r * g.S + s) * g.PQ + pc * g.Q + (ok ? q : 0)];
+        acc += ok ? tv : 0.f;
+      }
+    }
+    TOUT* o = dx + i;
+    if (ACC) acc += load_as_f32<TOUT>(o);
+    store_from_f32<TOUT>(o, acc);
+  }
+}
+
+// ---------------------------------------------------------- weight gradient ----
+// Reduction chunk = 32 pixels of one image; the chunks (n, pc) of a split are walked with
+// uniform carry counters: step i of split z is chunk z + i*splits.
+struct PmChunkWalk {
+  int n, pc, NC, dn, dpc;
+  __device__ PmChunkWalk(int first, int stride, int NC_) : n(first / NC_), pc(first - (first / NC_) * NC_), NC(NC_),
+                                                           dn(stride / NC_), dpc(stride - (stride / NC_) * NC_) {}
+  __device__ __forceinline__ void next() {
+    pc += dpc;
+    const int c = pc >= NC;
+    pc -= c ? NC : 0;
+    n += dn + c;
+  }
+};
+
+// A[m][kk] = dy[n][k0+m0+m][start(pc) + kk] (col image), read in place.  VEC4 (P*Q % 4 == 0):
+// 16-byte loads as in the other passes' filter operand; otherwise 4-byte loads, each lane
+// fetching the element that the col image's swizzle puts at its LDS position.  Rows past the
+// slice repeat its last kernel (never stored).
+template <int MI_, bool VEC4>
+struct PmDyLoadA {
+  static constexpr bool COL = true;
+  static constexpr int MI = MI_;
+  const char* dy;        // uniform: channel k0 of image 0
+  const char* ub;
+  int64_t imgBytes;
+  int PQ, N;
+  unsigned off[VEC4 ? 2 * MI : 8 * MI];
+  PmChunkWalk walk;
+  __device__ PmDyLoadA(const Geo& g, const PmGeo& pg, const float* dy_k0, int64_t imgPitch, int m0, int first, int stride)
+      : dy((const char*)dy_k0), imgBytes(imgPitch * 4), PQ(g.PQ), N(g.N), walk(first, stride, pg.NC) {
+    const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (VEC4) {
+#pragma unroll
+      for (int i = 0; i < 2 * MI; ++i) {
+        const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
+        const int m = min(m0 + 16 * MI * wv + 8 * i + (l >> 3), g.Ks - 1);
+        off[i] = ((unsigned)m * (unsigned)g.PQ + kq4) * 4u;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2 * MI; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int row = 8 * i + 2 * jj + (l >> 5);                       // within the wavefront's rows
+          const int kk = ((((l & 31) >> 2) ^ col_key(row)) << 2) + (l & 3);   // element stored at this lane's LDS position
+          const int m = min(m0 + 16 * MI * wv + row, g.Ks - 1);
+          off[i * 4 + jj] = ((unsigned)m * (unsigned)g.PQ + kk) * 4u;
+        }
+    }
+  }
+  __device__ __forceinline__ void begin(int, bool live) {   // dummy chunks re-read the first chunk of image 0
+    const int n = live ? walk.n : 0, pc = live ? walk.pc : 0;
+    const int start = pc == walk.NC - 1 ? PQ - 32 : pc * 32;
+    ub = dy + ((int64_t)n * imgBytes + (int64_t)start * 4);
+  }
+  __device__ __forceinline__ void issue(int i, float* dst) {
+    if (VEC4) {
+      dma16_uv(ub, off[i], dst);
+    } else {
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) dma4_uv(ub, off[i * 4 + jj], dst + 64 * jj);
+    }
+  }
+  __device__ __forceinline__ void end() { walk.next(); }
+};
+
+// B[kk][j] = xb[n][tap j at pixel kk of the chunk] (row image): a row is a pixel (uniform base from
+// the pixel table, scalar loads one chunk ahead), a lane is a tap with a constant offset.  Pixels
+// that do not count (table entry -1) read the zero page.  Taps past C*R*S repeat tap 0 (never stored).
+struct PmTapLoadB {
+  static constexpr bool COL = false;
+  const char* xb;
+  const char* zero;
+  const char* img;       // uniform: image of the chunk being issued
+  const CS_CONST int* pixtab;
+  int64_t imgBytes;
+  int N;
+  i32x4 cur[2], nxt[2];
+  unsigned tapoff[2], zoff;
+  PmChunkWalk walk;
+  __device__ PmTapLoadB(const Geo& g, const PmGeo& pg, const float* xb_, const float* zero_, const int* pixtab_, int j0,
+                        int first, int stride)
+      : xb((const char*)xb_), zero((const char*)zero_), pixtab((const CS_CONST int*)pixtab_),
+        imgBytes((int64_t)g.C * pg.Hp * pg.Wp * 4), N(g.N), walk(first, stride, pg.NC) {
+    const int l = threadIdx.x & 63;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int j = j0 + 64 * h + l;
+      const int jj = j < g.CRS ? j : 0;
+      const int c = jj / g.RS, rs = jj - c * g.RS;
+      const int r = rs / g.S, s = rs - r * g.S;
+      tapoff[h] = (unsigned)((c * pg.Hp + r) * pg.Wp + s) * 4u;
+    }
+    zoff = (unsigned)l * 4u;
+    fetch(walk.pc);
+  }
+  __device__ __forceinline__ void fetch(int pc) {
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const CS_CONST i32x4* po = (const CS_CONST i32x4*)(pixtab + pc * 32 + 8 * wv);
+    nxt[0] = po[0];
+    nxt[1] = po[1];
+  }
+  __device__ __forceinline__ void begin(int, bool) {   // dummy chunks read real pixels of the last image
+    cur[0] = nxt[0];
+    cur[1] = nxt[1];
+    img = xb + (int64_t)min(walk.n, N - 1) * imgBytes;
+  }
+  __device__ __forceinline__ void issue(int i, float* dst) {
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      const int po = pick8(cur, 2 * i + rr);
+      const bool live = po >= 0;
+      const char* b = live ? img + (unsigned)po : zero;
+      unsigned o0 = live ? tapoff[0] : zoff, o1 = live ? tapoff[1] : zoff;
+      dma4_uv(b, o0, dst + 128 * rr);
+      dma4_uv(b, o1, dst + 128 * rr + 64);
+    }
+  }
+  __device__ __forceinline__ void end() {
+    walk.next();
+    fetch(walk.pc);
+  }
+};
+
+// out[z][m][j]: split z of the weight gradient (chunks z, z + splits, ...); tiles * splits work
+// items dealt to the XCDs in contiguous blocks, as in bwd_weight_gemm_kernel.
+template <int MI, bool VEC4>
+__global__ __launch_bounds__(NT) void bwd_weight_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ dy_k0,
+                                                                int64_t imgPitch, const float* __restrict__ xb,
+                                                                const float* __restrict__ zero,
+                                                                const int* __restrict__ pixtab,
+                                                                float* __restrict__ out, int64_t splitStride,
+                                                                int mOrigin, int rowBase, int MB, int CT, int nch,
+                                                                int splits) {
+  extern __shared__ __align__(16) float smem[];
+  const int tiles = MB * CT;
+  int item;
+  if (!line_contiguous(blockIdx.x, tiles * splits, item)) return;
+  const int z = item / tiles, L = item - z * tiles;
+  int mb, ct;
+  tile_from_line(L, MB, CT, mb, ct);
+  const int m0 = mOrigin + mb * (64 * MI);
+  const int count = (nch - z + splits - 1) / splits;
+  f32x16 acc[MI][2];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  PmDyLoadA<MI, VEC4> la(g, pg, dy_k0, imgPitch, m0, z, splits);
+  PmTapLoadB lb(g, pg, xb, zero, pixtab, ct * BN, z, splits);
+  gemm_mainloop(la, lb, 0, count, smem, acc);
+  bwd_weight_store_tile<MI>(g, out + (int64_t)z * splitStride, m0, rowBase, ct, acc);
+}
+
+}  // namespace cs

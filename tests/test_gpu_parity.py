@@ -38,6 +38,12 @@ ADHOC = [
     synth.random_layer(17, N=2, C=64, H=40, W=10, K=8, R=33, S=3),
     synth.random_layer(18, N=2, C=40, H=34, W=34, K=4, R=32, S=32),                  # R*S at the limit, per pixel
     synth.random_layer(19, N=3, C=48, H=70, W=5, K=5, R=64, S=2, stride=2, pad=1),
+    # few input channels (pixel-major path): odd P*Q, padding and stride, a full plus a half row tile
+    synth.random_layer(22, N=3, C=3, H=20, W=17, K=190, R=5, S=3, stride=2, pad=1),
+    # P*Q a multiple of 4, interior slice of 132 kernels, 36 taps (half row tile in the input gradient), ragged columns
+    synth.random_layer(23, N=6, C=4, H=16, W=16, K=140, R=3, S=3, k0=5, k1=137),
+    # C*R*S = 480, the most the pixel-major path takes; 8.75 reduction chunks per image in the weight gradient
+    synth.random_layer(24, N=2, C=16, H=12, W=40, K=33, R=5, S=6),
 ]
 
 
@@ -68,7 +74,8 @@ def test_full_tensors_match_oracle_fp32(cfg):
     assert np.all(dw[:k0] == 7.0) and np.all(dw[k1:] == 7.0), "filters outside the slice were written"
 
 
-@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], ADHOC[16], synth.CONFIGS["cfg1"]],
+@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], ADHOC[16], ADHOC[19], ADHOC[20], ADHOC[21],
+                          synth.CONFIGS["cfg1"]],
                          ids=lambda c: c.name)
 def test_full_tensors_match_oracle_bf16(cfg):
     xo, wo, dyo = synth.make_inputs(cfg)
