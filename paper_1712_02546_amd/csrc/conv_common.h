@@ -321,6 +321,136 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   mfma_group(a1, b1, acc);
 }
 
+// Four reduction steps that start a tile: the first step writes the accumulators (C operand zero) instead of
+// adding to them, so a new tile needs no clearing pass over the accumulator registers.
+template <int MI>
+__device__ __forceinline__ void mfma_group_first(const FragN<MI>& a, const Frag& b, f32x16 (&acc)[MI][2]) {
+  f32x16 zero;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][0], b.v[0][0], zero, 0, 0, 0);
+    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][0], b.v[1][0], zero, 0, 0, 0);
+  }
+#pragma unroll
+  for (int t = 1; t < 4; ++t) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[0][t], acc[i][0], 0, 0, 0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[1][t], acc[i][1], 0, 0, 0);
+    }
+  }
+}
+
+// The same loop over a stream of tiles that all have nch chunks: a workgroup computes its tiles one after the
+// other and the chunk pipeline runs on across tile boundaries -- the first loads of the next tile are issued
+// while the last chunk of the current one is multiplied, and a finished tile's accumulators are stored between
+// two MFMA groups of the next tile's first chunk.  For tiles with short reductions (a few chunks) this keeps
+// the per-tile prologue, epilogue and workgroup launch off the critical path.
+// `tiles` supplies the stream: advance() moves on to the next tile to load (false: none left), make_a() builds
+// the A loader of that tile; its B loader is built by make_b(), or, when same_b() says that the tile has the
+// column tile of the one before, the current B loader is only restarted (restart()); store(acc) stores the
+// oldest tile not yet stored (tiles are stored in the order they were loaded).
+template <class LA, class LB, class Tiles>
+__device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem) {
+  constexpr bool AC = LA::COL, BC = LB::COL;
+  constexpr int MI = LA::MI;
+  static_assert(MI == 2 || AC, "the half tile needs a col-image A operand");
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wa = (wv >> 1) * (32 * MI), wb = (wv & 1) * 64;
+  if (!tiles.advance()) return;
+  LA la = tiles.make_a();
+  LB lb = tiles.make_b();
+  const int blk1 = opaque_block_offset();
+  f32x16 acc[MI][2];
+  // Issues the loads of the chunk that follows chunk ch of the tile being loaded; false at the end of the stream.
+  auto issue_next = [&](int ch, float* ta, float* tb) -> bool {
+    if (ch + 1 < nch) {
+      issue_all(la, lb, ch + 1, ta, tb, wv, true);
+      return true;
+    }
+    if (!tiles.advance()) return false;
+    la = tiles.make_a();
+    if (tiles.same_b()) lb.restart();
+    else lb = tiles.make_b();
+    issue_all(la, lb, 0, ta, tb, wv, true);
+    return true;
+  };
+  FragN<MI> a0, a1;
+  Frag b0, b1;
+  issue_all(la, lb, 0, smem, smem + 2 * TILE_F, wv, true);
+  __syncthreads();
+  read_frag<AC>(a0, smem, wa, lane, 0, blk1);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 0, blk1);
+  read_frag<AC>(a1, smem, wa, lane, 1, blk1);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1, blk1);
+  int ch = 0;   // chunk, within its tile, whose fragments are in registers
+  bool more = issue_next(ch, smem + TILE_F, smem + 3 * TILE_F);
+  CS_FENCE();
+  mfma_group_first(a0, b0, acc);
+  CS_FENCE();
+  read_frag<AC>(a0, smem, wa, lane, 2, blk1);
+  read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 2, blk1);
+  CS_FENCE();
+  mfma_group(a1, b1, acc);
+  CS_FENCE();
+  read_frag<AC>(a1, smem, wa, lane, 3, blk1);
+  read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 3, blk1);
+  __syncthreads();
+  int cur = TILE_F;
+  while (more) {
+    ++ch;
+    const bool newtile = ch == nch;   // the chunk entered now is the first of the next tile
+    ch = newtile ? 0 : ch;
+    const float* As = smem + cur;
+    const float* Bs = smem + 2 * TILE_F + cur;
+    more = issue_next(ch, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F));
+    CS_FENCE();
+    mfma_group(a0, b0, acc);  // G2 of the chunk before
+    CS_FENCE();
+    read_frag<AC>(a0, As, wa, lane, 0, blk1);
+    read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
+    CS_FENCE();
+    mfma_group(a1, b1, acc);  // G3 of the chunk before
+    CS_FENCE();
+    read_frag<AC>(a1, As, wa, lane, 1, blk1);
+    read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
+    CS_FENCE();
+    if (newtile) {
+      tiles.store(acc);
+      mfma_group_first(a0, b0, acc);  // G0 of this chunk, starting a tile
+    } else {
+      mfma_group(a0, b0, acc);        // G0 of this chunk
+    }
+    CS_FENCE();
+    read_frag<AC>(a0, As, wa, lane, 2, blk1);
+    read_frag<BC>(b0, Bs, wb, lane, 2, blk1);
+    CS_FENCE();
+    mfma_group(a1, b1, acc);  // G1 of this chunk
+    CS_FENCE();
+    read_frag<AC>(a1, As, wa, lane, 3, blk1);
+    read_frag<BC>(b1, Bs, wb, lane, 3, blk1);
+    __syncthreads();
+    cur ^= TILE_F;
+  }
+  mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
+  mfma_group(a1, b1, acc);
+  tiles.store(acc);
+}
+
+// A workgroup's contiguous run [begin, end) of a line of T equal tiles, for a grid of W persistent workgroups
+// (W a multiple of 8).  Workgroups are dealt to the XCDs in contiguous blocks, so the runs resident together on
+// one XCD are neighbours in the line.
+__device__ __forceinline__ void stream_run(int T, int& begin, int& end) {
+  const int W = gridDim.x;
+  const int w = (blockIdx.x & 7) * (W >> 3) + (blockIdx.x >> 3);
+  begin = (int)((int64_t)T * w / W);
+  end = (int)((int64_t)T * (w + 1) / W);
+}
+
 // Position of accumulator register v of a 32x32 MFMA block inside the block.
 __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 

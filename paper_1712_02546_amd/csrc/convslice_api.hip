@@ -215,12 +215,13 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
 // workgroups per compute unit (enough requests in flight when the layer is bound by memory) up to 4096
 // workgroups, with at least four chunks each.
 // bf16 (chunks so short that latency is the limit): measured best with about 1024 workgroups, whatever the tiles.
-int choose_splits(int64_t tiles, int64_t nch, bool pipe_bound) {
+int choose_splits(int64_t tiles, int64_t nch, bool pipe_bound, int min_rounds = 2) {
   const int64_t S = chip_slots(), cus = S / 2;
   const double c0 = 6.0;
   if (tiles < 1) tiles = 1;
   const int64_t cap = nch / 4 > 0 ? nch / 4 : 1;
-  const int64_t lo = std::min(cap, (2 * S + tiles - 1) / tiles), hi = std::min(cap, std::max<int64_t>(1, 4096 / tiles));
+  // at least min_rounds workgroups per workgroup slot
+  const int64_t lo = std::min(cap, (min_rounds * S + tiles - 1) / tiles), hi = std::min(cap, std::max<int64_t>(1, 4096 / tiles));
   if (!pipe_bound) return (int)std::max<int64_t>(1, lo);
   double best = tiles >= 32 ? 0.97 * (double)tiles / (double)cus * ((double)nch + c0) : 1e300;
   int64_t bestS = 1;
@@ -235,15 +236,15 @@ int choose_splits(int64_t tiles, int64_t nch, bool pipe_bound) {
 // Floats of split partials a weight-gradient call on Ks kernels may need, and never fewer than any call on fewer
 // kernels of the same layer needs (the split count grows as the slice shrinks).  A call makes one launch for its
 // full row tiles and one for a half tile; the launches follow each other and use the same place.
-int64_t split_partial_elems(const Geo& g, int CT, int64_t nch, bool pipe_bound) {
+int64_t split_partial_elems(const Geo& g, int CT, int64_t nch, bool pipe_bound, int min_rounds = 2) {
   int64_t need = 0;
   for (int t = 1; t <= (g.Ks + cs::BM - 1) / cs::BM; ++t) {
     const int64_t rows = std::min<int64_t>(g.Ks, (int64_t)t * cs::BM);
-    const int sp = choose_splits((int64_t)t * CT, nch, pipe_bound);
+    const int sp = choose_splits((int64_t)t * CT, nch, pipe_bound, min_rounds);
     if (sp > 1) need = std::max(need, (int64_t)sp * rows * g.CRS);
   }
   if (pipe_bound && g.Ks > 0) {   // the half tile (fp32 kernels only)
-    const int sp = choose_splits(CT, nch, pipe_bound);
+    const int sp = choose_splits(CT, nch, pipe_bound, min_rounds);
     if (sp > 1) need = std::max(need, (int64_t)sp * std::min(g.Ks, cs::BM / 2) * g.CRS);
   }
   return need;
@@ -468,6 +469,9 @@ PmBwdDataPlan plan_pm_bwd_data(const Geo& g, int dtype) {
   return p;
 }
 
+// Workgroups per workgroup slot the pixel-major weight gradient is split into at least (its operands sit in
+// the caches, so one round of long pieces beats several rounds of short ones).
+constexpr int kPmSplitRounds = 1;
 struct PmBwdWeightPlan {
   int CT, nch;
   size_t off_xb, off_pix, off_part, total;
@@ -479,7 +483,7 @@ PmBwdWeightPlan plan_pm_bwd_weight(const Geo& g, const PmPlan& pm) {
   size_t o = kZeroBytes;
   p.off_xb = o;   o += pm.copy ? seg((int64_t)g.N * g.C * pm.pg.Hp * pm.pg.Wp) : 0;
   p.off_pix = o;  o += seg((int64_t)pm.pg.NC * 32);
-  p.off_part = o; o += seg(split_partial_elems(g, p.CT, p.nch, true));
+  p.off_part = o; o += seg(split_partial_elems(g, p.CT, p.nch, true, kPmSplitRounds));
   p.total = o;
   return p;
 }
@@ -551,6 +555,8 @@ int check_ws(const void* ws, size_t ws_bytes, size_t need) {
 
 // ---- pixel-major passes: host side ----
 inline int grid_for(int64_t count, int cap = 8192) { return (int)std::min<int64_t>((count + 255) / 256, cap); }
+// Persistent workgroups for a stream kernel over `tiles` tiles: one per workgroup slot, fewer when there are fewer tiles.
+inline unsigned stream_grid(int64_t tiles) { return (unsigned)cs::grid_contiguous((int)std::min<int64_t>(tiles, chip_slots())); }
 
 // The image the taps are read from: x itself, or its zero-bordered fp32 copy (made here).
 const float* pm_input(const Geo& g, const PmPlan& pm, int dtype, const void* x, float* xb, hipStream_t st) {
@@ -597,8 +603,8 @@ int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void*
   auto launch = [&](auto kern, auto* yout, int m0, int tiles) -> int {
     int rc2;
     if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
-    hipLaunchKernelGGL(kern, dim3(cs::grid_contiguous(tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wmat,
-                       p.ldw, xb, tab, yout, m0, tiles, p.nch);
+    hipLaunchKernelGGL(kern, dim3(stream_grid((int64_t)tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg,
+                       wmat, p.ldw, xb, tab, yout, m0, tiles, p.nch);
     return CONV_OK;
   };
   rc = CONV_OK;
@@ -645,7 +651,7 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
   auto launch = [&](auto kern, int m0, int tiles) -> int {
     int rc2;
     if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
-    hipLaunchKernelGGL(kern, dim3(cs::grid_contiguous(tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wt,
+    hipLaunchKernelGGL(kern, dim3(stream_grid((int64_t)tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wt,
                        p.Ksp, dy_k0, imgPitch, T, m0, tiles, p.nch);
     return CONV_OK;
   };
@@ -691,7 +697,7 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
     int rc2;
     if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
     const int rows = std::min(g.Ks - m0, tiles * 64 * mi);
-    const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true);
+    const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true, kPmSplitRounds);
     const int64_t stride = (int64_t)rows * g.CRS;
     float* out = splits > 1 ? scratch : dwslice;
     const int rowBase = splits > 1 ? m0 : 0;

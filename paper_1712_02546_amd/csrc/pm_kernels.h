@@ -156,30 +156,130 @@ struct PmFwdLoadB {
     dma4_uv(b1, laneoff[1], dst + 192);
   }
   __device__ __forceinline__ void end() {}
+  __device__ __forceinline__ void restart() { fetch(0); }   // the same pixels again, from the first tap
+};
+
+// A store whose address is a wave-uniform base plus a 32-bit per-lane byte offset: the row of the tile moves in
+// scalar registers and the lane's offset (its pixel) is reused by every store of the tile.
+template <typename T>
+__device__ __forceinline__ void store_uv(const char* base_uniform, unsigned& lane_off, float v) {
+  asm volatile("" : "+v"(lane_off));
+  store_from_f32<T>((T*)(base_uniform + lane_off), v);
+}
+
+// The stream of tiles of one persistent workgroup: a run of the line of CT x MB tiles, row tiles fastest, so
+// that consecutive tiles share their column tile (the B loader is only restarted and the lanes' output offsets
+// are kept).  A = rows of a dense matrix (FwdLoadA), B = MakeB(ct), output element (m, n, pix) at
+// out[n*imgPitch + m*PQ + pix].
+template <int MI, typename TOUT, class LB, class MakeB>
+struct PmTiles {
+  const Geo& g;
+  const PmGeo& pg;
+  const float* a;
+  int lda, rows;
+  MakeB makeB;
+  TOUT* out;
+  int64_t imgPitch;
+  int mOrigin, MB;
+  int ld, end;        // line position of the tile being loaded, end of the run
+  int ld_mb, ld_ct;   // its coordinates
+  int st_mb, st_ct;   // coordinates of the oldest tile not stored
+  bool sameb;
+  int cache_ct;       // column tile the lane offsets below belong to
+  unsigned soff[2];
+  bool sok[2];
+  __device__ __forceinline__ void start(int begin, int end_) {
+    ld = begin - 1;
+    end = end_;
+    ld_ct = st_ct = begin / MB;
+    st_mb = begin - ld_ct * MB;
+    ld_mb = st_mb - 1;
+    sameb = false;
+    cache_ct = -1;
+  }
+  __device__ __forceinline__ bool advance() {
+    if (ld + 1 >= end) return false;
+    ++ld;
+    ++ld_mb;
+    sameb = ld_mb < MB;
+    if (!sameb) {
+      ld_mb = 0;
+      ++ld_ct;
+    }
+    return true;
+  }
+  __device__ __forceinline__ bool same_b() const { return sameb; }
+  __device__ __forceinline__ FwdLoadA<MI> make_a() const { return FwdLoadA<MI>(a, lda, mOrigin + ld_mb * (64 * MI), rows); }
+  __device__ __forceinline__ LB make_b() const { return makeB(ld_ct); }
+  __device__ __forceinline__ void store(const f32x16 (&acc)[MI][2]) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = mOrigin + st_mb * (64 * MI);
+    const int ct = st_ct;
+    if (++st_mb == MB) {
+      st_mb = 0;
+      ++st_ct;
+    }
+    if (cache_ct != ct) {   // the lane's two pixels: their offset in `out`, half-wave row included
+      cache_ct = ct;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
+        sok[j] = col < pg.NPQ;
+        const int c = min(col, pg.NPQ - 1);
+        const int n = c / g.PQ, pix = c - n * g.PQ;
+        soff[j] = (unsigned)((n * imgPitch + pix + 4 * (lane >> 5) * g.PQ) * (int64_t)sizeof(TOUT));
+      }
+    }
+    const int64_t rowBytes = (int64_t)g.PQ * sizeof(TOUT);
+    const char* sb = (const char*)out + (int64_t)(m0 + wm * (32 * MI)) * rowBytes;
+    if (m0 + 64 * MI <= rows && (ct + 1) * BN <= pg.NPQ) {   // whole tile inside: no per-element tests
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            store_uv<TOUT>(sb + (i * 32 + 8 * (v >> 2) + (v & 3)) * rowBytes, soff[j], acc[i][j][v]);
+      return;
+    }
+    const int mlane = m0 + wm * (32 * MI) + 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (!sok[j]) continue;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = i * 32 + 8 * (v >> 2) + (v & 3);
+          if (mlane + r < rows) store_from_f32<TOUT>((TOUT*)(sb + r * rowBytes + soff[j]), acc[i][j][v]);
+        }
+    }
+  }
+};
+
+struct PmFwdMakeB {
+  const Geo* g;
+  const PmGeo* pg;
+  const float* xb;
+  const int* tab;
+  __device__ __forceinline__ PmFwdLoadB operator()(int ct) const { return PmFwdLoadB(*g, *pg, xb, tab, ct, 0); }
 };
 
 // y[n][k0+m][pix] for rows mOrigin.. of the slice; w rows have pitch ldw (a multiple of BK, zero past C*R*S).
+// Persistent workgroups (grid = a multiple of 8, at most the chip's workgroup slots), each with a run of tiles.
 template <int MI, typename TOUT>
-__global__ __launch_bounds__(NT) void fwd_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ w, int ldw,
-                                                         const float* __restrict__ xb, const int* __restrict__ tab,
-                                                         TOUT* __restrict__ y, int mOrigin, int MB, int nch) {
+__global__ __launch_bounds__(NT, 2) void fwd_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ w, int ldw,
+                                                            const float* __restrict__ xb, const int* __restrict__ tab,
+                                                            TOUT* __restrict__ y, int mOrigin, int MB, int nch) {
   extern __shared__ __align__(16) float smem[];
-  int L;
-  if (!line_contiguous(blockIdx.x, MB * pg.CT, L)) return;
-  int mb, ct;
-  tile_from_line(L, MB, pg.CT, mb, ct);
-  const int m0 = mOrigin + mb * (64 * MI);
-  f32x16 acc[MI][2];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  FwdLoadA<MI> la(w, ldw, m0, g.Ks);
-  PmFwdLoadB lb(g, pg, xb, tab, ct, 0);
-  gemm_mainloop(la, lb, 0, nch, smem, acc);
-  pm_store_tile<MI, TOUT>(y + (int64_t)g.k0 * g.PQ, g.Ks, (int64_t)g.K * g.PQ, g.PQ, pg.NPQ, m0, ct, acc);
+  PmTiles<MI, TOUT, PmFwdLoadB, PmFwdMakeB> tiles{g, pg, w, ldw, g.Ks, PmFwdMakeB{&g, &pg, xb, tab},
+                                                   y + (int64_t)g.k0 * g.PQ, (int64_t)g.K * g.PQ, mOrigin, MB};
+  int begin, end;
+  stream_run(MB * pg.CT, begin, end);
+  tiles.start(begin, end);
+  gemm_stream<FwdLoadA<MI>, PmFwdLoadB>(tiles, nch, smem);
 }
 
 // --------------------------------------------------------- input gradient ----
@@ -230,30 +330,31 @@ struct PmDyLoadB {
     }
   }
   __device__ __forceinline__ void end() {}
+  __device__ __forceinline__ void restart() {}
+};
+
+template <bool VEC4>
+struct PmDyMakeB {
+  const Geo* g;
+  const PmGeo* pg;
+  const float* dy_k0;
+  int64_t imgPitch;
+  __device__ __forceinline__ PmDyLoadB<VEC4> operator()(int ct) const { return PmDyLoadB<VEC4>(*g, *pg, dy_k0, imgPitch, ct); }
 };
 
 // T[n][j][pix] = sum_k wt[j][k] * dy[n][k0+k][pix]; wt = the slice's filter matrix transposed, pitch Ksp.
+// Persistent workgroups, each with a run of the line of tiles.
 template <int MI, bool VEC4>
-__global__ __launch_bounds__(NT) void bwd_data_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ wt, int Ksp,
-                                                              const float* __restrict__ dy_k0, int64_t imgPitch,
-                                                              float* __restrict__ T, int mOrigin, int MB, int nch) {
+__global__ __launch_bounds__(NT, 2) void bwd_data_pm_gemm_kernel(Geo g, PmGeo pg, const float* __restrict__ wt, int Ksp,
+                                                                 const float* __restrict__ dy_k0, int64_t imgPitch,
+                                                                 float* __restrict__ T, int mOrigin, int MB, int nch) {
   extern __shared__ __align__(16) float smem[];
-  int L;
-  if (!line_contiguous(blockIdx.x, MB * pg.CT, L)) return;
-  int mb, ct;
-  tile_from_line(L, MB, pg.CT, mb, ct);
-  const int m0 = mOrigin + mb * (64 * MI);
-  f32x16 acc[MI][2];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  FwdLoadA<MI> la(wt, Ksp, m0, g.CRS);
-  PmDyLoadB<VEC4> lb(g, pg, dy_k0, imgPitch, ct);
-  gemm_mainloop(la, lb, 0, nch, smem, acc);
-  pm_store_tile<MI, float>(T, g.CRS, (int64_t)g.CRS * g.PQ, g.PQ, pg.NPQ, m0, ct, acc);
+  PmTiles<MI, float, PmDyLoadB<VEC4>, PmDyMakeB<VEC4>> tiles{g, pg, wt, Ksp, g.CRS, PmDyMakeB<VEC4>{&g, &pg, dy_k0, imgPitch},
+                                                             T, (int64_t)g.CRS * g.PQ, mOrigin, MB};
+  int begin, end;
+  stream_run(MB * pg.CT, begin, end);
+  tiles.start(begin, end);
+  gemm_stream<FwdLoadA<MI>, PmDyLoadB<VEC4>>(tiles, nch, smem);
 }
 
 // dx[n][c][h][v] (+)= sum over the taps (r,s) whose window position (p,q) lands on (h,v) of
