@@ -27,13 +27,27 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of a matrix-core kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# scaled by a copy kernel of known size (profiles/cfg3_f32_pmc_counters.md).  None where not measured.
-TRAFFIC_BYTES = {
-    ("cfg3", "f32", "fwd_gemm_kernel"): 5022000000,
-    ("cfg3", "f32", "bwd_data_gemm_kernel"): 8473000000,
-    ("cfg3", "f32", "bwd_weight_gemm_kernel"): 2746000000,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def measured_traffic():
+    """HBM-side bytes per launch of the matrix-core kernels, read from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic.md: FETCH_SIZE and WRITE_SIZE runs scaled by a copy kernel of known size).
+    Returns {(config, dtype, kernel): bytes}; empty when the file is not there."""
+    table = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 6 and cells[0].startswith("cfg") and cells[1] in ("f32", "bf16"):
+                    try:
+                        table[(cells[0], cells[1], cells[2])] = int(float(cells[-2])) + int(float(cells[-1]))
+                    except ValueError:
+                        pass
+    except OSError:
+        pass
+    return table
+
 
 METRIC = "conv fwd+bwd TFLOP/s and % of MFMA peak, 1500-kernel 5x5 layer, batch 128"
 
@@ -98,8 +112,7 @@ def cpu_baseline(cfg, x, w, dy, images):
                       f"fwd+bwd_data+bwd_weight, fp64 direct loops, gcc {flags}, {dt:.1f} s"}
 
 
-KERNEL_OF = {"conv_fwd": "fwd_gemm_kernel", "conv_bwd_data": "bwd_data_gemm_kernel",
-             "conv_bwd_weight": "bwd_weight_gemm_kernel"}
+PASS_OF = {"conv_fwd": 0, "conv_bwd_data": 1, "conv_bwd_weight": 2}
 
 
 def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
@@ -157,11 +170,18 @@ def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
     F = cfg.flops_per_pass
     value = 3 * F / (ms_per_step * 1e-3) / 1e12
     kern = []
+    es = 4 if dtype == cs.CONV_F32 else 2
+    # bytes a pass must move at least: each of x, the slice of w and the slice of y once (dw is fp32)
+    nx, ny, nw = x.size, y.numel() * (k1 - k0) // cfg.K, w.size * (k1 - k0) // cfg.K
+    pass_bytes = {"conv_fwd": (nx + nw + ny) * es, "conv_bwd_data": (nx + nw + ny) * es,
+                  "conv_bwd_weight": (nx + ny) * es + nw * 4}
     for i, (name, _, _) in enumerate(passes):
         d = [events.elapsed_ms(6 * s + 2 * i, 6 * s + 2 * i + 1) for s in range(steps)]
         avg = sum(d) / len(d)
-        kern.append({"entry": name, "kernel": KERNEL_OF[name], "avg_ms": avg, "min_ms": min(d),
-                     "tflops": F / (avg * 1e-3) / 1e12})
+        path = cs.conv_pass_path(desc, PASS_OF[name])
+        kern.append({"entry": name, "kernel": path.split(":")[0], "path": path, "avg_ms": avg, "min_ms": min(d),
+                     "tflops": F / (avg * 1e-3) / 1e12, "algorithmic_bytes": pass_bytes[name],
+                     "gbs_on_algorithmic_bytes": pass_bytes[name] / (avg * 1e-3) / 1e9})
     events.destroy()
     if per_pass:  # whole entry point (layout kernels included), each pass timed on its own
         for k, (name, fn, (a, b, out)) in zip(kern, passes):
@@ -173,11 +193,22 @@ def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
             k["entry_ms"] = (time.perf_counter() - t0) * 1e3 / steps
     dom = max(kern, key=lambda k: k["avg_ms"])
     peak = PEAK_TFLOPS[dtype_name]
-    es = 4 if dtype == cs.CONV_F32 else 2
-    min_bytes = 3 * ((x.size + y.numel() * (k1 - k0) // cfg.K) * es + w.size * (k1 - k0) // cfg.K * es)
-    roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s",
-                "frac": dom["tflops"] / peak, "avg_ms": dom["avg_ms"],
-                "traffic": TRAFFIC_BYTES.get((cfg_name, dtype_name, dom["kernel"]))}
+    # A converted-operand path multiplies on the fp32 matrix cores whatever the tensor dtype is.
+    kpeak = PEAK_TFLOPS["f32"] if "fp32 MFMA" in dom["path"] else PEAK_TFLOPS["bf16"]
+    min_bytes = sum(pass_bytes.values())
+    f_mfma = dom["tflops"] / kpeak
+    f_hbm = dom["gbs_on_algorithmic_bytes"] / HBM_PEAK_GBS
+    traffic = measured_traffic().get((cfg_name, dtype_name, dom["kernel"]))
+    # The roofline that binds the dominant kernel is the one it is closer to; the other fraction is reported beside it.
+    if f_mfma >= f_hbm:
+        roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"], "peak": kpeak, "unit": "TFLOP/s",
+                    "frac": f_mfma, "avg_ms": dom["avg_ms"], "traffic": traffic,
+                    "hbm_side": {"achieved": dom["gbs_on_algorithmic_bytes"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                 "frac": f_hbm}}
+    else:
+        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs_on_algorithmic_bytes"],
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": f_hbm, "avg_ms": dom["avg_ms"], "traffic": traffic,
+                    "mfma_side": {"achieved": dom["tflops"], "peak": kpeak, "unit": "TFLOP/s", "frac": f_mfma}}
     out = {
         "metric": METRIC,
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,

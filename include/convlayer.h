@@ -3,8 +3,8 @@
  * partition of Section 3.1.1 (calibration probe, Eq. (1)) and a driver that runs
  * all slices of a partitioned layer through the per-device entry points of
  * convslice.h and assembles the layer's outputs in place (Algorithm 1 without
- * the sockets: "all devices receive the same inputs but different kernels",
- * the master puts the returned maps side by side).
+ * the sockets: inputs broadcast, kernels split, the returned maps put side by
+ * side).
  *
  * Same conventions as convslice.h: conv_status_t return codes, device pointers
  * for tensors and workspaces, host pointers for descriptors, times, shares and
@@ -82,9 +82,12 @@ int conv_calibrate(const conv_desc_t *desc, int pass_mask, int reps, void *ws, s
  *
  * ws must hold conv_layer_workspace_bytes(...) bytes: every slice gets a region
  * of its own (for bwd_data one region reused in turn).  Empty slices are skipped.
- * The calls return without synchronising.  Not re-entrant per device: two
- * conv_layer_* calls that overlap in time on one GPU share the internal streams
- * (correct, but serialised against each other).
+ * The calls return without synchronising.  Host threads may call concurrently:
+ * the fork / enqueue / join sequence on the device's internal streams is taken
+ * under a lock, so calls that use them are enqueued one after the other (and
+ * their slices serialise on those streams).  As for every entry point, calls
+ * that overlap in time must not share ws.  Workspace sizes are valid for the
+ * device that is current when they are queried.
  */
 size_t conv_layer_workspace_bytes(const conv_desc_t *desc, const int32_t *bounds, int32_t n_slices,
                                   int pass);

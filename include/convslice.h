@@ -46,6 +46,10 @@
  * Precision.  CONV_F32: fp32 tensors, fp32 matrix-core (MFMA) products and
  * accumulation.  CONV_BF16: x, w, y, dy, dx are bfloat16 (upper 16 bits of an
  * fp32, round-to-nearest-even on output), accumulation is fp32, dw is fp32.
+ * bf16 products run on the bf16 matrix-core instructions, except the forward
+ * pass and input gradient of layers with fewer than 32 input channels (first
+ * layers: C = 3), which convert their operands to fp32 copies and run the fp32
+ * kernels; their weight gradient is bf16 MFMA like every other layer's.
  *
  * Limits.  Each tensor (and each internal transposed copy, whose batch extent
  * is rounded up to a multiple of 32) must have fewer than 2^30 - 4096 elements
@@ -92,7 +96,10 @@ typedef struct {
 /* Output extents P and Q of the layer.  Returns CONV_OK or CONV_ERR_*. */
 int conv_output_dims(const conv_desc_t *desc, int32_t *P, int32_t *Q);
 
-/* Scratch bytes the given pass needs for this descriptor (0 on invalid input). */
+/* Scratch bytes the given pass needs for this descriptor (0 on invalid input).  Host arithmetic,
+ * except that the first call asks the HIP runtime for the compute-unit count of the current
+ * device (512 workgroup slots are assumed when no device is visible): sizes are valid for
+ * that device. */
 size_t conv_workspace_bytes(const conv_desc_t *desc, int pass);
 
 /*
@@ -151,6 +158,13 @@ int conv_bwd_weight(const conv_desc_t *desc, const void *x, const void *dy, void
  * Passing NULL for either event disarms it.  Always returns CONV_OK.
  */
 int conv_probe_next_call(void *start_event, void *stop_event);
+
+/*
+ * Measurement aid: which kernel family serves the given pass of this layer, as
+ * "<matrix-core kernel>: <arithmetic>, <layout>" (static string; host logic only, the
+ * same decision the pass itself takes).  "invalid descriptor" / "unknown pass" otherwise.
+ */
+const char *conv_pass_path(const conv_desc_t *desc, int pass);
 
 /* Static, never-NULL description of a status code. */
 const char *conv_status_string(int status);

@@ -19,7 +19,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 NOALLOC_MAX_WORKSPACE = 96 << 20
 
 EXPORTS = ("conv_output_dims", "conv_workspace_bytes", "conv_fwd", "conv_fwd_noalloc", "conv_bwd_data",
-           "conv_bwd_weight", "conv_status_string", "conv_probe_next_call",
+           "conv_bwd_weight", "conv_status_string", "conv_probe_next_call", "conv_pass_path",
            "conv_partition", "conv_partition_estimate", "conv_calibrate_workspace_bytes",
            "conv_calibrate", "conv_layer_workspace_bytes", "conv_layer_fwd",
            "conv_layer_bwd_data", "conv_layer_bwd_weight", "conv_comm_elements",
@@ -101,6 +101,8 @@ def load() -> ctypes.CDLL:
         lib.conv_fwd_noalloc.restype = ctypes.c_int
         lib.conv_probe_next_call.argtypes = [vp, vp]
         lib.conv_probe_next_call.restype = ctypes.c_int
+        lib.conv_pass_path.argtypes = [dp, ctypes.c_int]
+        lib.conv_pass_path.restype = ctypes.c_char_p
         lib.conv_status_string.argtypes = [ctypes.c_int]
         lib.conv_status_string.restype = ctypes.c_char_p
         pd, pi = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
@@ -144,6 +146,12 @@ def load() -> ctypes.CDLL:
 
 def status_string(status: int) -> str:
     return load().conv_status_string(int(status)).decode()
+
+
+def conv_pass_path(desc: "ConvDesc", which: int) -> str:
+    """Kernel family that serves the pass: "<matrix-core kernel>: <arithmetic>, <layout>"."""
+    cd = desc.c_struct()
+    return load().conv_pass_path(ctypes.byref(cd), int(which)).decode()
 
 
 def conv_probe_next_call(start_event, stop_event) -> int:

@@ -9,6 +9,7 @@
 #include <mutex>
 
 #include "../../include/convlayer.h"
+#include "conv_internal.h"
 
 namespace {
 
@@ -61,6 +62,7 @@ int check_layer(const conv_desc_t* desc) {
 // ---- internal streams of the layer driver, one set per device ----------------------------
 constexpr int kStreams = 4;
 constexpr double kFillsGpuFlop = 2e10;   // a slice pass of this size keeps 256 CUs busy for >0.1 ms
+constexpr int64_t kFillsGpuTiles = 512; // two workgroup slots on each of 256 CUs
 constexpr int kMaxGpus = 16;
 struct StreamSet {
   bool ready = false;
@@ -117,18 +119,35 @@ int run_disjoint(slice_fn fn, int pass, const conv_desc_t* desc, const int32_t* 
   const conv_desc_t whole = slice_of(*desc, 0, desc->K);
   (void)conv_output_dims(&whole, &P, &Q);
   const double flop_per_kernel = 2.0 * desc->N * P * Q * (double)desc->C * desc->R * desc->S;
+  // ... or with at least as many 128 x 128 output tiles as the chip has workgroup slots (layers with few input
+  // channels: little work per tile, but persistent workgroups on every slot)
+  const int64_t col_tiles = ((int64_t)desc->N * P * Q + 127) / 128;
   int big = 0;
-  for (int i = 0; i < n; ++i) big += (bounds[i + 1] - bounds[i]) * flop_per_kernel >= kFillsGpuFlop;
+  for (int i = 0; i < n; ++i) {
+    const int ks = bounds[i + 1] - bounds[i];
+    big += ks > 0 && (ks * flop_per_kernel >= kFillsGpuFlop || (int64_t)((ks + 127) / 128) * col_tiles >= kFillsGpuTiles);
+  }
   if (big == live) {
+    // One workspace, one stream: the work copy of the shared input x that the first slice makes serves the others.
+    int done = 0;
     for (int i = 0; i < n; ++i) {
       if (bounds[i + 1] == bounds[i]) continue;
       const conv_desc_t d = slice_of(*desc, bounds[i], bounds[i + 1]);
-      if ((rc = fn(&d, a, b, out, base, ws_bytes, hip_stream)) != CONV_OK) return rc;
+      if (pass == CONV_PASS_FWD) rc = cs_internal::conv_fwd_shared(&d, a, b, out, base, ws_bytes, hip_stream, done > 0);
+      else if (pass == CONV_PASS_BWD_WEIGHT)
+        rc = cs_internal::conv_bwd_weight_shared(&d, a, b, out, base, ws_bytes, hip_stream, done > 0);
+      else rc = fn(&d, a, b, out, base, ws_bytes, hip_stream);
+      if (rc != CONV_OK) return rc;
+      ++done;
     }
     return CONV_OK;
   }
   StreamSet* ss = stream_set();
   if (!ss) return CONV_ERR_LAUNCH;
+  // The device's stream set and its events are shared by all callers: one fork / enqueue / join sequence at a
+  // time, so that a second host thread cannot re-record an event between this call's record and its waits.
+  static std::mutex fork_join_mutex;
+  const std::lock_guard<std::mutex> fork_join_lock(fork_join_mutex);
   const int used = std::min(live, kStreams);
   if (hipEventRecord(ss->fork, user) != hipSuccess) return CONV_ERR_LAUNCH;
   for (int s = 0; s < used; ++s)

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "conv_common.h"
+#include "conv_internal.h"
 #include "gemm_kernels.h"
 #include "gemm_bf16_kernels.h"
 #include "pack_kernels.h"
@@ -559,8 +560,10 @@ inline int grid_for(int64_t count, int cap = 8192) { return (int)std::min<int64_
 inline unsigned stream_grid(int64_t tiles) { return (unsigned)cs::grid_contiguous((int)std::min<int64_t>(tiles, chip_slots())); }
 
 // The image the taps are read from: x itself, or its zero-bordered fp32 copy (made here).
-const float* pm_input(const Geo& g, const PmPlan& pm, int dtype, const void* x, float* xb, hipStream_t st) {
+const float* pm_input(const Geo& g, const PmPlan& pm, int dtype, const void* x, float* xb, hipStream_t st,
+                      bool ready = false) {
   if (!pm.copy) return (const float*)x;
+  if (ready) return xb;
   const int64_t count = (int64_t)g.N * g.C * pm.pg.Hp * pm.pg.Wp;
   if (dtype == CONV_F32)
     hipLaunchKernelGGL(cs::pm_border_copy_kernel<float>, dim3(grid_for(count)), dim3(256), 0, st, g, pm.pg.Hp, pm.pg.Wp,
@@ -572,13 +575,13 @@ const float* pm_input(const Geo& g, const PmPlan& pm, int dtype, const void* x, 
 }
 
 int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
-           hipStream_t st, const Probe& probe) {
+           hipStream_t st, const Probe& probe, bool input_ready) {
   const PmFwdPlan p = plan_pm_fwd(g, pm, dtype);
   int rc;
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
   char* base = (char*)ws;
   const size_t es = elem_size(dtype);
-  const float* xb = pm_input(g, pm, dtype, x, (float*)(base + p.off_xb), st);
+  const float* xb = pm_input(g, pm, dtype, x, (float*)(base + p.off_xb), st, input_ready);
   const float* wmat;
   if (p.repitch) {
     float* wp = (float*)(base + p.off_w);
@@ -678,14 +681,14 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
 
 // fp32 only (bf16 layers take the bf16 matrix-core weight gradient).
 int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
-                  hipStream_t st, const Probe& probe) {
+                  hipStream_t st, const Probe& probe, bool input_ready) {
   const PmBwdWeightPlan p = plan_pm_bwd_weight(g, pm);
   int rc;
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
   char* base = (char*)ws;
   float* zero = (float*)base;
   hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
-  const float* xb = pm_input(g, pm, CONV_F32, x, (float*)(base + p.off_xb), st);
+  const float* xb = pm_input(g, pm, CONV_F32, x, (float*)(base + p.off_xb), st, input_ready);
   int* pixtab = (int*)(base + p.off_pix);
   hipLaunchKernelGGL(cs::pm_pixel_table_kernel, dim3((pm.pg.NC * 32 + 255) / 256), dim3(256), 0, st, g, pm.pg.Wp, pm.pg.NC,
                      pixtab);
@@ -790,8 +793,12 @@ int launch_fwd_gemm(const Geo& g, bool pad, const float* wmat, int ldw, const fl
   return CONV_OK;
 }
 
-int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
-             void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+int fwd_impl(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+             void* hip_stream, bool input_ready) {
   const Probe probe;
   Geo g;
   int rc = make_geo(desc, g);
@@ -800,7 +807,7 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   if (misaligned(x, 16) || misaligned(w, 16) || misaligned(y, 16)) return CONV_ERR_ALIGN;
   if (g.Ks == 0) return CONV_OK;
   const PmPlan pm = plan_pm(g, desc->dtype);
-  if (pm.ok) return pm_fwd(g, pm, desc->dtype, x, w, y, ws, ws_bytes, (hipStream_t)hip_stream, probe);
+  if (pm.ok) return pm_fwd(g, pm, desc->dtype, x, w, y, ws, ws_bytes, (hipStream_t)hip_stream, probe, input_ready);
   if (bf16_mfma_fwd_ok(g, desc->dtype)) {
     const Fwd16Plan p = plan_fwd16(g);
     if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
@@ -811,8 +818,9 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
     float* yt = (float*)(base + p.off_yt);
     float* partial = (float*)(base + p.off_tail);
     // per image: x[n] as a C x HW matrix -> x_hwnc[hw][n][Cp]; images N..Np-1 are zero
-    launch_transpose_in(CONV_BF16, x, (int64_t)g.C * g.HW, g.HW, g.C, g.HW, xp, p.Cp, (int64_t)g.Np * p.Cp, p.Cp,
-                        g.Np, (float*)(base + p.off_x - kZeroBytes), st, true, g.N);
+    if (!input_ready)
+      launch_transpose_in(CONV_BF16, x, (int64_t)g.C * g.HW, g.HW, g.C, g.HW, xp, p.Cp, (int64_t)g.Np * p.Cp, p.Cp,
+                          g.Np, (float*)(base + p.off_x - kZeroBytes), st, true, g.N);
     // w[k][c][rs] -> w_krsc[k][rs][Cp]
     hipLaunchKernelGGL(cs::filters_to_krsc_kernel, dim3((p.Cp + 63) / 64, g.Ks), dim3(256), 0, st,
                        (const uint16_t*)w + (size_t)g.k0 * g.CRS, g.C, g.RS, p.Cp, (uint16_t*)wp);
@@ -839,8 +847,9 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   const size_t es = elem_size(desc->dtype);
 
   // x[N][C*H*W] -> x_t[C*H*W][Np]
-  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
-                      xt - cs::ZERO_PAGE_FLOATS, st);
+  if (!input_ready)
+    launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
+                        xt - cs::ZERO_PAGE_FLOATS, st);
   const float* wmat;
   if (p.repitch) {
     float* wp = (float*)(base + p.off_w);
@@ -869,6 +878,15 @@ int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   launch_transpose_out(desc->dtype, false, yt, g.Np, g.N, g.Ks * g.PQ,
                        (char*)y + (size_t)g.k0 * g.PQ * es, (int64_t)g.K * g.PQ, st);
   return check_launch();
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_fwd(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+             void* hip_stream) {
+  return fwd_impl(desc, x, w, y, ws, ws_bytes, hip_stream, false);
 }
 
 // ---- forward pass for callers that cannot allocate: the workspace is a device array of the library ----
@@ -1072,8 +1090,12 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   return check_launch();
 }
 
-int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
-                    void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+int bwd_weight_impl(const conv_desc_t* desc, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
+                    void* hip_stream, bool input_ready) {
   const Probe probe;
   Geo g;
   int rc = make_geo(desc, g);
@@ -1089,8 +1111,9 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
     cs::bf16_t* xt = (cs::bf16_t*)(base + p.off_xt);
     cs::bf16_t* dyt = (cs::bf16_t*)(base + p.off_dyt);
     float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
-    launch_transpose_in(CONV_BF16, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, p.Np64, p.Np64, 1,
-                        (float*)(base + p.off_xt - kZeroBytes), st, true);
+    if (!input_ready)
+      launch_transpose_in(CONV_BF16, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, p.Np64, p.Np64, 1,
+                          (float*)(base + p.off_xt - kZeroBytes), st, true);
     launch_transpose_in(CONV_BF16, (const char*)dy + (size_t)g.k0 * g.PQ * 2, 0, (int64_t)g.K * g.PQ, g.N,
                         g.Ks * g.PQ, dyt, 0, p.Np64, p.Np64, 1, nullptr, st, true);
     const bool pad16 = needs_pad_checks(g);
@@ -1118,7 +1141,7 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   }
   {
     const PmPlan pm = plan_pm(g, desc->dtype);
-    if (pm.ok) return pm_bwd_weight(g, pm, x, dy, dw, ws, ws_bytes, (hipStream_t)hip_stream, probe);
+    if (pm.ok) return pm_bwd_weight(g, pm, x, dy, dw, ws, ws_bytes, (hipStream_t)hip_stream, probe, input_ready);
   }
   const BwdWeightPlan p = plan_bwd_weight(g);
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
@@ -1129,8 +1152,9 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   float* dyt = (float*)(base + p.off_dyt);
   float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;
 
-  launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
-                      xt - cs::ZERO_PAGE_FLOATS, st);
+  if (!input_ready)
+    launch_transpose_in(desc->dtype, x, 0, (int64_t)g.C * g.HW, g.N, g.C * g.HW, xt, 0, g.Np, g.Np, 1,
+                        xt - cs::ZERO_PAGE_FLOATS, st);
   launch_transpose_in(desc->dtype, (const char*)dy + (size_t)g.k0 * g.PQ * es, 0, (int64_t)g.K * g.PQ, g.N,
                       g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, nullptr, st);
   const bool pad = needs_pad_checks(g);
@@ -1171,6 +1195,58 @@ int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void
   probe.end(st);
   if (rc != CONV_OK) return rc;
   return check_launch();
+}
+
+}  // namespace
+
+namespace cs_internal {
+int conv_fwd_shared(const conv_desc_t* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+                    void* hip_stream, int input_ready) {
+  return fwd_impl(desc, x, w, y, ws, ws_bytes, hip_stream, input_ready != 0);
+}
+int conv_bwd_weight_shared(const conv_desc_t* desc, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
+                           void* hip_stream, int input_ready) {
+  return bwd_weight_impl(desc, x, dy, dw, ws, ws_bytes, hip_stream, input_ready != 0);
+}
+}  // namespace cs_internal
+
+extern "C" {
+
+int conv_bwd_weight(const conv_desc_t* desc, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
+                    void* hip_stream) {
+  return bwd_weight_impl(desc, x, dy, dw, ws, ws_bytes, hip_stream, false);
+}
+
+const char* conv_pass_path(const conv_desc_t* desc, int pass) {
+  Geo g;
+  if (make_geo(desc, g) != CONV_OK) return "invalid descriptor";
+  const int dt = desc->dtype;
+  const bool bf = dt == CONV_BF16;
+  const PmPlan pm = plan_pm(g, dt);
+  switch (pass) {
+    case CONV_PASS_FWD:
+      if (pm.ok) return bf ? "fwd_pm_gemm_kernel: fp32 MFMA on operands converted from bf16, pixel-major, y stored in place"
+                           : "fwd_pm_gemm_kernel: fp32 MFMA, pixel-major, y stored in place";
+      if (bf16_mfma_fwd_ok(g, dt)) return "fwd16_gemm_kernel: bf16 MFMA, batch-innermost work copies";
+      return bf ? "fwd_gemm_kernel: fp32 MFMA on operands converted from bf16, batch-innermost work copies"
+                : "fwd_gemm_kernel: fp32 MFMA, batch-innermost work copies";
+    case CONV_PASS_BWD_DATA:
+      if (pm.ok_data)
+        return bf ? "bwd_data_pm_gemm_kernel: fp32 MFMA on operands converted from bf16, pixel-major T = w^T dy, then col2im_pm_kernel"
+                  : "bwd_data_pm_gemm_kernel: fp32 MFMA, pixel-major T = w^T dy read from dy in place, then col2im_pm_kernel";
+      if (bf16_mfma_bwd_data_ok(g, dt)) return "bwd_data16_gemm_kernel: bf16 MFMA, per-pixel taps, batch-innermost work copies";
+      if (plan_bwd_data(g).scatter)
+        return bf ? "fwd_gemm_kernel: fp32 MFMA on operands converted from bf16, T = w^T dy, then col2im_out_kernel"
+                  : "fwd_gemm_kernel: fp32 MFMA, T = w^T dy on batch-innermost work copies, then col2im_out_kernel";
+      return bf ? "bwd_data_gemm_kernel: fp32 MFMA on operands converted from bf16, per-pixel taps, batch-innermost work copies"
+                : "bwd_data_gemm_kernel: fp32 MFMA, per-pixel taps, batch-innermost work copies";
+    case CONV_PASS_BWD_WEIGHT:
+      if (bf16_mfma_bwd_weight_ok(g, dt)) return "bwd_weight16_gemm_kernel: bf16 MFMA, batch-innermost work copies";
+      if (pm.ok) return "bwd_weight_pm_gemm_kernel: fp32 MFMA, pixel-major, dy read in place";
+      return bf ? "bwd_weight_gemm_kernel: fp32 MFMA on operands converted from bf16, batch-innermost work copies"
+                : "bwd_weight_gemm_kernel: fp32 MFMA, batch-innermost work copies";
+    default: return "unknown pass";
+  }
 }
 
 int conv_probe_next_call(void* start_event, void* stop_event) {

@@ -152,6 +152,20 @@ def test_noalloc_forward_rejects_before_any_launch():
     assert cs.conv_fwd_noalloc(cs.ConvDesc(**GOOD, k0=4, k1=4), A, A, A, stream=0, raw_status=True) == 0
 
 
+def test_pass_path_names_the_kernel_family():
+    first = cs.ConvDesc(N=128, C=3, H=32, W=32, K=500, R=5, S=5)
+    second = cs.ConvDesc(N=128, C=500, H=14, W=14, K=1500, R=5, S=5)
+    assert cs.conv_pass_path(first, cs.PASS_FWD).startswith("fwd_pm_gemm_kernel: fp32 MFMA")
+    assert cs.conv_pass_path(first, cs.PASS_BWD_DATA).startswith("bwd_data_pm_gemm_kernel")
+    assert cs.conv_pass_path(second, cs.PASS_FWD).startswith("fwd_gemm_kernel: fp32 MFMA")
+    assert cs.conv_pass_path(second, cs.PASS_BWD_DATA).startswith("bwd_data_gemm_kernel")
+    bf = cs.ConvDesc(N=64, C=3, H=224, W=224, K=96, R=11, S=11, stride_h=4, stride_w=4, pad_h=2, pad_w=2, dtype=cs.CONV_BF16)
+    assert "converted from bf16" in cs.conv_pass_path(bf, cs.PASS_FWD)
+    assert cs.conv_pass_path(bf, cs.PASS_BWD_WEIGHT).startswith("bwd_weight16_gemm_kernel: bf16 MFMA")
+    assert cs.conv_pass_path(second, 9) == "unknown pass"
+    assert cs.conv_pass_path(cs.ConvDesc(N=0, C=3, H=32, W=32, K=5, R=5, S=5), 0) == "invalid descriptor"
+
+
 def test_null_descriptor():
     lib = cs.load()
     assert lib.conv_fwd(None, 1, 1, 1, 1, 0, None) == -1

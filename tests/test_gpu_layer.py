@@ -81,6 +81,34 @@ def test_partitioned_layer_matches_oracle_bf16():
     check(dw, oracle.conv_bwd_weight(sh, x, dy), FP32_TOL, "dw")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_slices_share_the_input_work_copy(dtype):
+    """Slices that each fill the GPU run one after the other on one workspace, and only the first
+    re-lays the shared input (Algorithm 1: every device receives the same inputs).  The 1500-kernel
+    layer split for four devices against the same layer in one call: the same sums, possibly in
+    another order.  (Every element of the one-call result is checked against the oracle elsewhere.)"""
+    cfg = synth.CONFIGS["cfg3"]
+    x, w, dy = synth.make_inputs(cfg)
+    dt = cs.CONV_F32 if dtype == "f32" else cs.CONV_BF16
+    if dt == cs.CONV_BF16:
+        x, w, dy = (synth.round_to_bf16(a) for a in (x, w, dy))
+    _, bounds = cs.conv_partition([0.8, 1.0, 1.7, 2.4], cfg.K)
+    dev = Device(cfg, x, w, dy, dtype=dt)
+    y, dx, dw = run_layer(dev, cfg, bounds, dt)
+    # bf16 tensors differ by at most one rounding of the stored value when the fp32 sums differ in their last bits.
+    # dx is the sum of four partial gradients of 9 000 to 14 000 terms each instead of one sum of 37 500 terms:
+    # both are fp32 evaluations within the fp32 tolerance of the exact sum, and so is their difference.
+    tol = SAME_MATH_TOL if dt == cs.CONV_F32 else 2.0 ** -7
+    # (in bf16 every slice's partial gradient is rounded into the bf16 dx as it is added: four roundings instead of one)
+    tol_dx = FP32_TOL if dt == cs.CONV_F32 else BF16_TOL
+    for got, one, name, t in ((y, dev.fwd(), "y", tol), (dx, dev.bwd_data(), "dx", tol_dx),
+                              (dw, dev.bwd_weight(), "dw", SAME_MATH_TOL)):
+        e = rel_err(got, one)
+        print(f"  {dtype} {name}: partitioned vs one call, rms-floored max rel {e:.3e}; "
+              f"{np.count_nonzero(got != one)} of {got.size} elements differ")
+        assert e <= t, f"{name}: {e:.3e}"
+
+
 def test_partitioned_layer_is_bit_stable_and_honours_accumulate():
     cfg, times = CASES[2]
     cfg = cfg.with_slice(0, cfg.K)
