@@ -79,9 +79,9 @@ int chip_slots() {
 }
 
 // Splits T equal tiles of nch chunks into whole-tile rounds and an evenly shared tail.
-cs::TailPlan plan_tail(int T, int nch) {
+cs::TailPlan plan_tail(int T, int nch, int S = 0) {
   cs::TailPlan tp;
-  const int S = chip_slots();
+  if (S <= 0) S = chip_slots();
   const int rem = T % S;
   if (rem == 0 || nch < 16) {   // nothing left over, or reductions too short to be worth splitting
     tp.nFull = T; tp.nTail = 0; tp.units = 1; tp.nTailWg = 0;
@@ -144,10 +144,10 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
 // kernel) and cut by the kernels themselves; the host only fixes the number of runs.  Each run of the line is
 // computed by MB workgroups, one per row tile, which therefore walk through the same pixels, taps and k-chunks at
 // the same time and share the dy operand.
-cs::RunPlan plan_runs(int MB, bool possible) {
+cs::RunPlan plan_runs(int MB, bool possible, int S = 0) {
   cs::RunPlan rp;
   rp.enabled = 0; rp.nRuns = 1; rp.nWg = 0;
-  const int S = chip_slots();
+  if (S <= 0) S = chip_slots();
   if (!possible || S / MB < 1) return rp;
   rp.enabled = 1;
   rp.nRuns = S / MB;
@@ -308,7 +308,17 @@ bool bf16_mfma_bwd_weight_ok(const Geo& g, int dtype) {
   return dtype == CONV_BF16 && (int64_t)g.C * g.HW * Np64 < kMaxElems && (int64_t)g.Ks * g.PQ * Np64 < kMaxElems;
 }
 
+// Workgroup slots and tail scratch of the wide (256 x 256, 128 KB of LDS) bf16 tiles: one workgroup per compute unit.
+inline int wide_slots() { return chip_slots() / 2; }
+inline size_t wide_tail_bytes(int nch) {
+  return nch >= 16 ? (size_t)wide_slots() * 2 * cs::TAIL2_SLOT_FLOATS * 4 : 0;
+}
+// A slice of more than 128 kernels needs two 128-row tiles anyway; one 256-row tile then computes the same rows
+// with half the staged bytes and three quarters of the LDS reads per MFMA.
+inline bool wide_rows(int rows) { return rows > cs::BM; }
+
 struct Fwd16Plan {
+  bool wide;
   int Cp, nch, MB, CT;
   cs::TailPlan tail;
   size_t off_x, off_w, off_yt, off_zero, off_tail, total;
@@ -317,71 +327,125 @@ Fwd16Plan plan_fwd16(const Geo& g) {
   Fwd16Plan p;
   p.Cp = (int)round_up(g.C, 64);
   p.nch = g.RS * (p.Cp / cs::BK16);
-  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
-  p.CT = (g.PQ * g.NB + 3) / 4;
-  p.tail = plan_tail(p.MB * p.CT, p.nch);
+  p.wide = wide_rows(g.Ks);
+  if (p.wide) {
+    p.MB = (g.Ks + cs::BM2 - 1) / cs::BM2;
+    p.CT = (g.PQ * g.NB + 7) / 8;
+    p.tail = plan_tail(p.MB * p.CT, p.nch, wide_slots());
+  } else {
+    p.MB = (g.Ks + cs::BM - 1) / cs::BM;
+    p.CT = (g.PQ * g.NB + 3) / 4;
+    p.tail = plan_tail(p.MB * p.CT, p.nch);
+  }
   size_t o = kZeroBytes;
   p.off_x = o;    o += seg16((int64_t)g.HW * g.Np * p.Cp);
   p.off_w = o;    o += seg16((int64_t)g.Ks * g.RS * p.Cp);
   p.off_yt = o;   o += seg((int64_t)g.Ks * g.PQ * g.Np);
   p.off_zero = o; o += seg16((int64_t)32 * p.Cp + 64);   // a column block of zeros: 32 images x Cp channels
-  p.off_tail = o; o += tail_bytes(p.nch);
+  p.off_tail = o; o += p.wide ? wide_tail_bytes(p.nch) : tail_bytes(p.nch);
   p.total = o;
   return p;
 }
 
 struct BwdData16Plan {
-  int Ksp;
+  bool wide;
+  int Ksp, MB, CT;
   cs::RunPlan run;
   size_t off_dy, off_w, off_dxt, off_perm, off_pre, off_scratch, off_zero, off_tail, total;
 };
 BwdData16Plan plan_bwd_data16(const Geo& g) {
   BwdData16Plan p;
   p.Ksp = (int)round_up(g.Ks, 64);
+  // Wide tiles when the channels need two 128-row tiles anyway and the tap tables (36 bytes per tap) fit behind
+  // the 128 KB of stages.  With fewer wide tiles than compute units the line of tiles is cut into equal runs, and
+  // nearly every workgroup then parks two 256 KB accumulator images for the fix-up kernel: that pays only when a
+  // run is long (measured: 235 chunks per run 7 % faster than the narrow tiles, 78 chunks 19 % slower).
+  p.wide = wide_rows(g.C) && g.RS <= 512;
+  if (p.wide) {
+    const int MB2 = (g.C + cs::BM2 - 1) / cs::BM2;
+    const int64_t CT2 = ((int64_t)g.HW * g.NB + 7) / 8;
+    if (MB2 * CT2 < wide_slots()) {
+      // taps that reach a pixel, summed over the pixels: (valid (p,r) pairs) x (valid (q,s) pairs)
+      int64_t rows = 0, cols = 0;
+      for (int pp = 0; pp < g.P; ++pp)
+        for (int r = 0; r < g.R; ++r) rows += (unsigned)(pp * g.sh - g.ph + r) < (unsigned)g.H;
+      for (int q = 0; q < g.Q; ++q)
+        for (int ss = 0; ss < g.S; ++ss) cols += (unsigned)(q * g.sw - g.pw + ss) < (unsigned)g.W;
+      const int64_t line = rows * cols * g.NB / 8 * (p.Ksp / cs::BK16);   // chunks on the line of wide tiles, about
+      p.wide = line / std::max(1, wide_slots() / MB2) >= 160;
+    }
+  }
+  const int bpt = p.wide ? 8 : 4;
+  p.MB = p.wide ? (g.C + cs::BM2 - 1) / cs::BM2 : (g.C + cs::BM - 1) / cs::BM;
+  p.CT = (g.HW * g.NB + bpt - 1) / bpt;
   size_t o = kZeroBytes;
   p.off_dy = o;   o += seg16((int64_t)g.PQ * g.Np * p.Ksp);
   p.off_w = o;    o += seg16((int64_t)g.RS * g.C * p.Ksp);
   p.off_dxt = o;  o += seg((int64_t)g.C * g.HW * g.Np);
   p.off_perm = o; o += seg(g.HW);
-  const int CT = (g.HW * g.NB + 3) / 4;
-  p.off_pre = o;  o += seg((int64_t)CT + 2);
+  p.off_pre = o;  o += seg((int64_t)(g.HW * g.NB + 3) / 4 + 2);   // room for the narrow tiles' line, whatever the choice
   p.off_scratch = o; o += seg(cs::po::axes_ints(g.H, g.W));
   p.off_zero = o; o += seg16((int64_t)32 * p.Ksp + 64);   // a column block of zeros: 32 images x Ksp kernels
   // With chunks this short the scratch round trip of the cut tiles costs about as much as uneven tiles do, so
   // the runs are used only where one workgroup per tile would leave slots empty.
-  const int MB = (g.C + cs::BM - 1) / cs::BM;
-  const bool few = (int64_t)MB * CT < chip_slots();
-  p.run = plan_runs(MB, few && (int64_t)CT * g.RS * (p.Ksp / cs::BK16) < (int64_t)1 << 30);
-  p.off_tail = o; o += few ? (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4 : 0;
+  const int S = p.wide ? wide_slots() : chip_slots();
+  const bool few = (int64_t)p.MB * p.CT < S;
+  p.run = plan_runs(p.MB, few && (int64_t)p.CT * g.RS * (p.Ksp / cs::BK16) < (int64_t)1 << 30, S);
+  p.off_tail = o;
+  o += few ? (size_t)S * 2 * (p.wide ? cs::TAIL2_SLOT_FLOATS : cs::TAIL_SLOT_FLOATS) * 4 : 0;
   p.total = o;
   return p;
 }
 
 struct BwdWeight16Plan {
+  bool wide;
   int Np64, MB, CT, nch, splits, chPerSplit;
   cs::TailPlan tail;
   size_t off_xt, off_dyt, off_part, off_tail, total;
 };
+// Tile shape and split count of the bf16 weight gradient on a slice of ks kernels.
+struct Split16 {
+  bool wide;
+  int MB, CT, splits;
+};
+Split16 split16_for(const Geo& g, int ks, int64_t nch) {
+  Split16 s;
+  s.wide = wide_rows(ks);
+  s.MB = s.wide ? (ks + cs::BM2 - 1) / cs::BM2 : (ks + cs::BM - 1) / cs::BM;
+  s.CT = s.wide ? (g.CRS + cs::BN2 - 1) / cs::BN2 : (g.CRS + cs::BN - 1) / cs::BN;
+  // about 1024 narrow workgroups (two rounds of two per compute unit) or 512 wide ones (two rounds of one)
+  s.splits = choose_splits((int64_t)s.MB * s.CT, nch, false, s.wide ? 1 : 2);
+  return s;
+}
+// Floats of split partials such a call may need, and never fewer than a call on fewer kernels of the same layer
+// needs (the split count grows as the slice shrinks).
+int64_t split_partial_elems16(const Geo& g, int64_t nch) {
+  int64_t need = 0;
+  for (int ks = 1; ks <= g.Ks; ++ks) {
+    const int sp = split16_for(g, ks, nch).splits;
+    if (sp > 1) need = std::max(need, (int64_t)sp * ks * g.CRS);
+  }
+  return need;
+}
 BwdWeight16Plan plan_bwd_weight16(const Geo& g) {
   BwdWeight16Plan p;
   p.Np64 = (int)round_up(g.N, 64);
-  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
-  p.CT = (g.CRS + cs::BN - 1) / cs::BN;
   p.nch = g.PQ * (p.Np64 / cs::BK16);
+  const Split16 sp = split16_for(g, g.Ks, p.nch);
+  p.wide = sp.wide; p.MB = sp.MB; p.CT = sp.CT; p.splits = sp.splits;
   const int64_t tiles = (int64_t)p.MB * p.CT;
-  p.splits = choose_splits(tiles, p.nch, false);
   p.chPerSplit = (p.nch + p.splits - 1) / p.splits;
   p.splits = (p.nch + p.chPerSplit - 1) / p.chPerSplit;   // whole blocks of chPerSplit chunks: no empty split
   if (p.splits > 1) {
     p.tail.nFull = (int)tiles; p.tail.nTail = 0; p.tail.units = 1; p.tail.nTailWg = 0;
   } else {
-    p.tail = plan_tail((int)tiles, p.nch);
+    p.tail = p.wide ? plan_tail((int)tiles, p.nch, wide_slots()) : plan_tail((int)tiles, p.nch);
   }
   size_t o = kZeroBytes;
   p.off_xt = o;   o += seg16((int64_t)g.C * g.HW * p.Np64);
   p.off_dyt = o;  o += seg16((int64_t)g.Ks * g.PQ * p.Np64);
   p.off_part = p.off_tail = o;   // split partials or tail slots: a call uses one of them
-  o += std::max(seg(split_partial_elems(g, p.CT, p.nch, false)), tail_bytes(p.nch));
+  o += std::max(seg(split_partial_elems16(g, p.nch)), p.wide ? wide_tail_bytes(p.nch) : tail_bytes(p.nch));
   p.total = o;
   return p;
 }
@@ -826,13 +890,24 @@ int fwd_impl(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
                        (const uint16_t*)w + (size_t)g.k0 * g.CRS, g.C, g.RS, p.Cp, (uint16_t*)wp);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Cp + 64);
-    if ((rc = allow_big_lds(cs::fwd16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
-    probe.begin(st);
-    hipLaunchKernelGGL(cs::fwd16_gemm_kernel, dim3(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg)), dim3(cs::NT),
-                       cs::SMEM_BYTES, st, g, wp, p.Cp, xp, zero, yt, p.MB, p.CT, p.nch, p.tail, partial);
-    if (p.tail.nTail > 0)
-      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<2>, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, 0, p.MB,
-                         p.CT, p.nch, p.tail);
+    const dim3 grid(cs::grid_contiguous(p.tail.nFull) + cs::grid_contiguous(p.tail.nTailWg));
+    if (p.wide) {
+      if ((rc = allow_big_lds(cs::fwd16_wide_gemm_kernel, cs::SMEM2_BYTES)) != CONV_OK) return rc;
+      probe.begin(st);
+      hipLaunchKernelGGL(cs::fwd16_wide_gemm_kernel, grid, dim3(cs::NT2), cs::SMEM2_BYTES, st, g, wp, p.Cp, xp, zero, yt,
+                         p.MB, p.CT, p.nch, p.tail, partial);
+      if (p.tail.nTail > 0)
+        hipLaunchKernelGGL(cs::fwd16_wide_fixup_kernel, dim3(p.tail.nTail, 8), dim3(cs::NT2), 0, st, g, partial, yt, p.MB,
+                           p.CT, p.nch, p.tail);
+    } else {
+      if ((rc = allow_big_lds(cs::fwd16_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
+      probe.begin(st);
+      hipLaunchKernelGGL(cs::fwd16_gemm_kernel, grid, dim3(cs::NT), cs::SMEM_BYTES, st, g, wp, p.Cp, xp, zero, yt, p.MB,
+                         p.CT, p.nch, p.tail, partial);
+      if (p.tail.nTail > 0)
+        hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<2>, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, yt, 0,
+                           p.MB, p.CT, p.nch, p.tail);
+    }
     probe.end(st);
     launch_transpose_out(CONV_BF16, false, yt, g.Np, g.N, g.Ks * g.PQ, (char*)y + (size_t)g.k0 * g.PQ * 2,
                          (int64_t)g.K * g.PQ, st);
@@ -977,23 +1052,33 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
     // w[k][(c,rs)] -> w_rsck[rs][c][Ksp]: the slice's filter matrix transposed, rows re-ordered tap-major, zero past Ks
     launch_transpose_in(CONV_BF16, (const char*)w + (size_t)g.k0 * g.CRS * 2, 0, g.CRS, g.Ks, g.CRS, wp, 0, p.Ksp,
                         p.Ksp, 1, nullptr, st, true, -1, g.RS, g.C);
-    const int MB = (g.C + cs::BM - 1) / cs::BM;
-    const int CT = (g.HW * g.NB + 3) / 4;
+    const int MB = p.MB, CT = p.CT, bpt = p.wide ? 8 : 4;
     int* pre = (int*)(base + p.off_pre);
     float* partial = (float*)(base + p.off_tail);
     hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(cs::po::THREADS), 0, st, g, perm,
-                       (int*)(base + p.off_scratch), CT, p.Ksp / cs::BK16, p.run.enabled ? pre : (int*)nullptr);
+                       (int*)(base + p.off_scratch), CT, p.Ksp / cs::BK16, bpt, p.run.enabled ? pre : (int*)nullptr);
     cs::bf16_t* zero = (cs::bf16_t*)(base + p.off_zero);
     hipLaunchKernelGGL(cs::fill_zero_kernel<uint16_t>, dim3(16), dim3(256), 0, st, zero, (int64_t)32 * p.Ksp + 64);
-    const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
-    if ((rc = allow_big_lds(cs::bwd_data16_gemm_kernel, lds)) != CONV_OK) return rc;
-    probe.begin(st);
-    hipLaunchKernelGGL(cs::bwd_data16_gemm_kernel,
-                       dim3(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT)), dim3(cs::NT), lds, st, g,
-                       wp, p.Ksp, dyp, zero, perm, pre, dxt, MB, CT, p.run, partial);
-    if (p.run.enabled)
-      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<2>, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
-                         0, MB, CT, p.Ksp / cs::BK16, p.run.nRuns);
+    const dim3 grid(p.run.enabled ? (p.run.nWg + 7) / 8 * 8 : cs::grid_dealt(MB, CT));
+    if (p.wide) {
+      const int lds = cs::SMEM2_BYTES + (g.RS + 3) * 36;   // stages + tap list + eight tap offsets per tap
+      if ((rc = allow_big_lds(cs::bwd_data16_wide_gemm_kernel, lds)) != CONV_OK) return rc;
+      probe.begin(st);
+      hipLaunchKernelGGL(cs::bwd_data16_wide_gemm_kernel, grid, dim3(cs::NT2), lds, st, g, wp, p.Ksp, dyp, zero, perm, pre,
+                         dxt, MB, CT, p.run, partial);
+      if (p.run.enabled)
+        hipLaunchKernelGGL(cs::bwd_data16_wide_fixup_kernel, dim3(CT * MB, 8), dim3(cs::NT2), 0, st, g, perm, pre, partial,
+                           dxt, MB, CT, p.Ksp / cs::BK16, p.run.nRuns);
+    } else {
+      const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
+      if ((rc = allow_big_lds(cs::bwd_data16_gemm_kernel, lds)) != CONV_OK) return rc;
+      probe.begin(st);
+      hipLaunchKernelGGL(cs::bwd_data16_gemm_kernel, grid, dim3(cs::NT), lds, st, g, wp, p.Ksp, dyp, zero, perm, pre, dxt,
+                         MB, CT, p.run, partial);
+      if (p.run.enabled)
+        hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<2>, dim3(CT * MB, 4), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt,
+                           0, MB, CT, p.Ksp / cs::BK16, p.run.nRuns);
+    }
     probe.end(st);
     launch_transpose_out(CONV_BF16, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
     return check_launch();
@@ -1058,7 +1143,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   const int CT = (g.HW * g.NB + 3) / 4;
   const bool runs = (int64_t)CT * g.RS * p.nch < (int64_t)1 << 30;   // else the line would be too long for an int
   hipLaunchKernelGGL(cs::bwd_data_pixel_order_kernel, dim3(1), dim3(cs::po::THREADS), 0, st, g, perm, scratch, CT, p.nch,
-                     runs ? pre : (int*)nullptr);
+                     4, runs ? pre : (int*)nullptr);
   // tiles + tap list + per-block tap offsets
   const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
   // Channels in full row tiles first, then the half tile for a rest of at most 64 channels; both launches walk the
@@ -1117,21 +1202,29 @@ int bwd_weight_impl(const conv_desc_t* desc, const void* x, const void* dy, void
     launch_transpose_in(CONV_BF16, (const char*)dy + (size_t)g.k0 * g.PQ * 2, 0, (int64_t)g.K * g.PQ, g.N,
                         g.Ks * g.PQ, dyt, 0, p.Np64, p.Np64, 1, nullptr, st, true);
     const bool pad16 = needs_pad_checks(g);
-    if ((rc = allow_big_lds(pad16 ? cs::bwd_weight16_gemm_kernel<true> : cs::bwd_weight16_gemm_kernel<false>,
-                            cs::SMEM_BYTES)) != CONV_OK)
-      return rc;
     const int64_t sliceElems = (int64_t)g.Ks * g.CRS;
     float* out = p.splits > 1 ? (float*)(base + p.off_part) : dwslice;
     float* partial = (float*)(base + p.off_tail);
-    probe.begin(st);
-    hipLaunchKernelGGL(pad16 ? cs::bwd_weight16_gemm_kernel<true> : cs::bwd_weight16_gemm_kernel<false>,
-                       dim3(split_grid(p.MB * p.CT, p.splits, p.tail)),
-                       dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt, p.Np64, out, sliceElems, p.MB, p.CT, p.nch,
-                       p.chPerSplit, p.splits, p.tail, partial);
-    if (p.tail.nTail > 0)
-      hipLaunchKernelGGL(cs::bwd_weight_tail_fixup_kernel<2>, dim3(p.tail.nTail, 4), dim3(cs::NT), 0, st, g, partial, out,
-                         0, 0, p.MB, p.CT, p.nch, p.tail);
-    probe.end(st);
+    const dim3 grid(split_grid(p.MB * p.CT, p.splits, p.tail));
+    auto launch = [&](auto kern, auto fixup, int threads, int lds, auto... fixArgs) -> int {
+      const int r = allow_big_lds(kern, lds);
+      if (r != CONV_OK) return r;
+      probe.begin(st);
+      hipLaunchKernelGGL(kern, grid, dim3(threads), lds, st, g, dyt, xt, p.Np64, out, sliceElems, p.MB, p.CT, p.nch,
+                         p.chPerSplit, p.splits, p.tail, partial);
+      if (p.tail.nTail > 0)
+        hipLaunchKernelGGL(fixup, dim3(p.tail.nTail, threads / 64), dim3(threads), 0, st, g, partial, out, fixArgs..., p.MB,
+                           p.CT, p.nch, p.tail);
+      probe.end(st);
+      return CONV_OK;
+    };
+    if (p.wide)
+      rc = pad16 ? launch(cs::bwd_weight16_wide_gemm_kernel<true>, cs::bwd_weight16_wide_fixup_kernel, cs::NT2, cs::SMEM2_BYTES)
+                 : launch(cs::bwd_weight16_wide_gemm_kernel<false>, cs::bwd_weight16_wide_fixup_kernel, cs::NT2, cs::SMEM2_BYTES);
+    else
+      rc = pad16 ? launch(cs::bwd_weight16_gemm_kernel<true>, cs::bwd_weight_tail_fixup_kernel<2>, cs::NT, cs::SMEM_BYTES, 0, 0)
+                 : launch(cs::bwd_weight16_gemm_kernel<false>, cs::bwd_weight_tail_fixup_kernel<2>, cs::NT, cs::SMEM_BYTES, 0, 0);
+    if (rc != CONV_OK) return rc;
     if (p.splits > 1) {
       const int blocks = (int)((sliceElems + 255) / 256 < 8192 ? (sliceElems + 255) / 256 : 8192);
       hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, out, sliceElems, p.splits,
@@ -1227,21 +1320,28 @@ const char* conv_pass_path(const conv_desc_t* desc, int pass) {
     case CONV_PASS_FWD:
       if (pm.ok) return bf ? "fwd_pm_gemm_kernel: fp32 MFMA on operands converted from bf16, pixel-major, y stored in place"
                            : "fwd_pm_gemm_kernel: fp32 MFMA, pixel-major, y stored in place";
-      if (bf16_mfma_fwd_ok(g, dt)) return "fwd16_gemm_kernel: bf16 MFMA, batch-innermost work copies";
+      if (bf16_mfma_fwd_ok(g, dt))
+        return plan_fwd16(g).wide ? "fwd16_wide_gemm_kernel: bf16 MFMA, 256 x 256 tiles, batch-innermost work copies"
+                                  : "fwd16_gemm_kernel: bf16 MFMA, batch-innermost work copies";
       return bf ? "fwd_gemm_kernel: fp32 MFMA on operands converted from bf16, batch-innermost work copies"
                 : "fwd_gemm_kernel: fp32 MFMA, batch-innermost work copies";
     case CONV_PASS_BWD_DATA:
       if (pm.ok_data)
         return bf ? "bwd_data_pm_gemm_kernel: fp32 MFMA on operands converted from bf16, pixel-major T = w^T dy, then col2im_pm_kernel"
                   : "bwd_data_pm_gemm_kernel: fp32 MFMA, pixel-major T = w^T dy read from dy in place, then col2im_pm_kernel";
-      if (bf16_mfma_bwd_data_ok(g, dt)) return "bwd_data16_gemm_kernel: bf16 MFMA, per-pixel taps, batch-innermost work copies";
+      if (bf16_mfma_bwd_data_ok(g, dt))
+        return plan_bwd_data16(g).wide
+                   ? "bwd_data16_wide_gemm_kernel: bf16 MFMA, 256 x 256 tiles, per-pixel taps, batch-innermost work copies"
+                   : "bwd_data16_gemm_kernel: bf16 MFMA, per-pixel taps, batch-innermost work copies";
       if (plan_bwd_data(g).scatter)
         return bf ? "fwd_gemm_kernel: fp32 MFMA on operands converted from bf16, T = w^T dy, then col2im_out_kernel"
                   : "fwd_gemm_kernel: fp32 MFMA, T = w^T dy on batch-innermost work copies, then col2im_out_kernel";
       return bf ? "bwd_data_gemm_kernel: fp32 MFMA on operands converted from bf16, per-pixel taps, batch-innermost work copies"
                 : "bwd_data_gemm_kernel: fp32 MFMA, per-pixel taps, batch-innermost work copies";
     case CONV_PASS_BWD_WEIGHT:
-      if (bf16_mfma_bwd_weight_ok(g, dt)) return "bwd_weight16_gemm_kernel: bf16 MFMA, batch-innermost work copies";
+      if (bf16_mfma_bwd_weight_ok(g, dt))
+        return plan_bwd_weight16(g).wide ? "bwd_weight16_wide_gemm_kernel: bf16 MFMA, 256 x 256 tiles, batch-innermost work copies"
+                                         : "bwd_weight16_gemm_kernel: bf16 MFMA, batch-innermost work copies";
       if (pm.ok) return "bwd_weight_pm_gemm_kernel: fp32 MFMA, pixel-major, dy read in place";
       return bf ? "bwd_weight_gemm_kernel: fp32 MFMA on operands converted from bf16, batch-innermost work copies"
                 : "bwd_weight_gemm_kernel: fp32 MFMA, batch-innermost work copies";

@@ -123,6 +123,148 @@ __device__ __forceinline__ void gemm16_mainloop(LA& la, LB& lb, int ch_begin, in
   mfma16_group(a1, b1, acc);
 }
 
+// ------------------------------------------------------------- wide tiles ----
+// 256 x 256 tiles for eight wavefronts (2 x 4, each 128 rows x 64 columns = 4 x 2 accumulator
+// blocks): per MFMA a wavefront reads 0.75 operands from LDS instead of 1 and a workgroup stages
+// half as many bytes, which is what limits the 128 x 128 loop at this instruction's rate.
+// LDS holds two stages of two 32 KB col images (128 KB: one workgroup per compute unit).  The
+// loaders are the same: wavefront wv stages rows (or column block) 32*wv .. 32*wv+31.
+constexpr int NT2 = 512;
+constexpr int BM2 = 256, BN2 = 256;
+constexpr int TILE2_F = BM2 * BK16 / 2;         // floats of one operand stage (32 KB)
+constexpr int SMEM2_BYTES = 4 * TILE2_F * 4;
+constexpr int TAIL2_SLOT_FLOATS = 128 * NT2;    // one accumulator image of a wide tile (256 KB)
+
+template <int NBLK>
+struct Frag16N {
+  f32x4 v[NBLK];
+};
+template <int NBLK>
+__device__ __forceinline__ void read_frag16n(Frag16N<NBLK>& f, const float* tile, int wbase, int lane, int j) {
+  const int u = col_key(lane & 31), h = lane >> 5;
+  const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
+#pragma unroll
+  for (int b = 0; b < NBLK; ++b) f.v[b] = *(const f32x4*)(tile + slot * 4 + b * (32 * 8 * 4));
+}
+
+__device__ __forceinline__ void mfma16_group_wide(const Frag16N<4>& a, const Frag16N<2>& b, f32x16 (&acc)[4][2]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bf16x8 ai = __builtin_bit_cast(bf16x8, a.v[i]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ai, __builtin_bit_cast(bf16x8, b.v[j]), acc[i][j], 0, 0, 0);
+  }
+}
+
+// Same rotation across the one barrier per chunk as gemm16_mainloop.
+template <class LA, class LB>
+__device__ __forceinline__ void gemm16_mainloop_wide(LA& la, LB& lb, int ch_begin, int ch_end, float* smem,
+                                                     f32x16 (&acc)[4][2]) {
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wa = (wv >> 2) * 128, wb = (wv & 3) * 64;
+  if (ch_begin >= ch_end) return;
+  auto issue = [&](int ch, float* ta, float* tb, bool live) {
+    la.begin(ch, live);
+    lb.begin(ch, live);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      la.issue(i, ta + (wv * 4 + i) * 256);
+      lb.issue(i, tb + (wv * 4 + i) * 256);
+    }
+    la.end();
+    lb.end();
+  };
+  Frag16N<4> a0, a1;
+  Frag16N<2> b0, b1;
+  float* const A = smem;
+  float* const B = smem + 2 * TILE2_F;
+  issue(ch_begin, A, B, true);
+  __syncthreads();
+  read_frag16n(a0, A, wa, lane, 0);
+  read_frag16n(b0, B, wb, lane, 0);
+  read_frag16n(a1, A, wa, lane, 1);
+  read_frag16n(b1, B, wb, lane, 1);
+  issue(ch_begin + 1, A + TILE2_F, B + TILE2_F, ch_begin + 1 < ch_end);
+  CS_FENCE();
+  mfma16_group_wide(a0, b0, acc);
+  CS_FENCE();
+  read_frag16n(a0, A, wa, lane, 2);
+  read_frag16n(b0, B, wb, lane, 2);
+  CS_FENCE();
+  mfma16_group_wide(a1, b1, acc);
+  CS_FENCE();
+  read_frag16n(a1, A, wa, lane, 3);
+  read_frag16n(b1, B, wb, lane, 3);
+  __syncthreads();
+  int cur = TILE2_F;
+  for (int ch = ch_begin + 1; ch < ch_end; ++ch) {
+    const float* As = A + cur;
+    const float* Bs = B + cur;
+    issue(ch + 1, A + (cur ^ TILE2_F), B + (cur ^ TILE2_F), ch + 1 < ch_end);
+    CS_FENCE();
+    mfma16_group_wide(a0, b0, acc);  // step 2 of chunk ch-1
+    CS_FENCE();
+    read_frag16n(a0, As, wa, lane, 0);
+    read_frag16n(b0, Bs, wb, lane, 0);
+    CS_FENCE();
+    mfma16_group_wide(a1, b1, acc);  // step 3 of chunk ch-1
+    CS_FENCE();
+    read_frag16n(a1, As, wa, lane, 1);
+    read_frag16n(b1, Bs, wb, lane, 1);
+    CS_FENCE();
+    mfma16_group_wide(a0, b0, acc);  // step 0 of chunk ch
+    CS_FENCE();
+    read_frag16n(a0, As, wa, lane, 2);
+    read_frag16n(b0, Bs, wb, lane, 2);
+    CS_FENCE();
+    mfma16_group_wide(a1, b1, acc);  // step 1 of chunk ch
+    CS_FENCE();
+    read_frag16n(a1, As, wa, lane, 3);
+    read_frag16n(b1, Bs, wb, lane, 3);
+    __syncthreads();
+    cur ^= TILE2_F;
+  }
+  mfma16_group_wide(a0, b0, acc);  // steps 2, 3 of the last chunk
+  mfma16_group_wide(a1, b1, acc);
+}
+
+__device__ __forceinline__ void zero_acc_wide(f32x16 (&acc)[4][2]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+}
+
+// Accumulator image of a wide tile: element e = (i*2+j)*16+v of thread t at [e*NT2 + t].
+__device__ __forceinline__ void store_partial_wide(float* slot, const f32x16 (&acc)[4][2]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) slot[((i * 2 + j) * 16 + v) * NT2 + threadIdx.x] = acc[i][j][v];
+}
+
+// Sum of the scratch slots of tail tile tl, in run order, for accumulator block (bi,bj).
+__device__ __forceinline__ void gather_partials_wide(const float* partial, const TailPlan& tp, int nch, int tl,
+                                                     int bi, int bj, f32x16& acc) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  const int wfirst = (tl * nch) / tp.units;
+  const int wlast = min(tp.nTailWg - 1, (tl * nch + nch - 1) / tp.units);
+  for (int w = wfirst; w <= wlast; ++w) {
+    const int slot = (w * tp.units) / nch == tl ? 0 : 1;
+    const float* p = partial + (int64_t)(w * 2 + slot) * TAIL2_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT2 + threadIdx.x;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += p[v * NT2];
+  }
+}
+
 // ------------------------------------------------------------------ forward ----
 // A[m][kk] = w_krsc[m0+m][kk]: dense rows of R*S*Cp elements.  As in the fp32 kernels every
 // load is "wave-uniform base + fixed per-lane byte offset", so the loop spends no vector
@@ -147,6 +289,7 @@ struct Fwd16LoadA {
 // B^T[(block,n)][kk] = x_hwnc[h0+r][w0+s][n][c]: chunk = (r, s, 64 channels); the pixel of
 // a column block is uniform per wavefront (wavefront wv stages block wv of the tile), so a
 // tap that falls into the padding switches the uniform base to a block of zeros.
+template <int BPT = 4>   // column blocks per tile = wavefronts per workgroup
 struct Fwd16LoadB {
   const char* x;        // uniform: x_hwnc at the block's images
   const char* zero;     // uniform: 32 rows of Cp zeros
@@ -159,7 +302,7 @@ struct Fwd16LoadB {
       : zero((const char*)zero_) {
     const int l = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int gcb = ct * 4 + wv < g.PQ * g.NB ? ct * 4 + wv : 0;   // blocks past the end: computed, never stored
+    const int gcb = ct * BPT + wv < g.PQ * g.NB ? ct * BPT + wv : 0;   // blocks past the end: computed, never stored
     const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
     const int p = pix / g.Q, q = pix - p * g.Q;
     h0 = p * g.sh - g.ph;
@@ -209,11 +352,64 @@ __global__ __launch_bounds__(NT) void fwd16_gemm_kernel(Geo g, const bf16_t* __r
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     Fwd16LoadA la(w, (int64_t)g.RS * Cp, mb * BM, g.Ks);
-    Fwd16LoadB lb(g, x, zero, Cp, ct, cb);
+    Fwd16LoadB<4> lb(g, x, zero, Cp, ct, cb);
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) fwd_store_tile<2>(g, yt, mb * BM, ct, acc);
     else store_partial<2>(partial + (int64_t)slot * TAIL_SLOT_FLOATS, acc);
   });
+}
+
+// Accumulator block (i,j) of a wide tile: 32 kernels x 32 images of one pixel.
+__device__ __forceinline__ void fwd16_wide_store_block(const Geo& g, float* __restrict__ yt, int m0, int ct, int i, int j,
+                                                       const f32x16& acc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int gcb = ct * 8 + (wave & 3) * 2 + j;
+  if (gcb >= g.PQ * g.NB) return;
+  const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
+  const int n = nb * 32 + (lane & 31);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = m0 + (wave >> 2) * 128 + i * 32 + acc_row(v, lane);
+    if (m < g.Ks) yt[((int64_t)m * g.PQ + pix) * g.Np + n] = acc[v];
+  }
+}
+
+// Forward pass on wide tiles: MB row tiles of 256 kernels, CT column tiles of eight blocks.
+__global__ __launch_bounds__(NT2) void fwd16_wide_gemm_kernel(Geo g, const bf16_t* __restrict__ w, int Cp,
+                                                              const bf16_t* __restrict__ x,
+                                                              const bf16_t* __restrict__ zero, float* __restrict__ yt,
+                                                              int MB, int CT, int nch, TailPlan tp,
+                                                              float* __restrict__ partial) {
+  extern __shared__ __align__(16) float smem[];
+  for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
+    int mb, ct;
+    tile_from_line(L, MB, CT, mb, ct);
+    f32x16 acc[4][2];
+    zero_acc_wide(acc);
+    Fwd16LoadA la(w, (int64_t)g.RS * Cp, mb * BM2, g.Ks);
+    Fwd16LoadB<8> lb(g, x, zero, Cp, ct, cb);
+    gemm16_mainloop_wide(la, lb, cb, ce, smem, acc);
+    if (direct) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fwd16_wide_store_block(g, yt, mb * BM2, ct, i, j, acc[i][j]);
+    } else {
+      store_partial_wide(partial + (int64_t)slot * TAIL2_SLOT_FLOATS, acc);
+    }
+  });
+}
+
+// grid = (nTail, 8): one workgroup per tail tile and accumulator block.
+__global__ __launch_bounds__(NT2) void fwd16_wide_fixup_kernel(Geo g, const float* __restrict__ partial,
+                                                               float* __restrict__ yt, int MB, int CT, int nch,
+                                                               TailPlan tp) {
+  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  f32x16 acc;
+  gather_partials_wide(partial, tp, nch, blockIdx.x, bi, bj, acc);
+  int mb, ct;
+  tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
+  fwd16_wide_store_block(g, yt, mb * BM2, ct, bi, bj, acc);
 }
 
 // ----------------------------------------------------------- input gradient ----
@@ -253,6 +449,7 @@ struct BwdData16LoadA {
 // B^T[(block,n)][kk] = dy_pqnk[p][q][n][k] with (p,q) the output pixel the current tap maps
 // the block's input pixel to (from the per-tile LDS table; uniform per wavefront), or a block
 // of zeros if there is none.
+template <int BPT = 4>   // column blocks per tile = wavefronts per workgroup
 struct BwdData16LoadB {
   const char* dy;     // uniform
   const char* zero;   // uniform: 32 rows of Ksp zeros
@@ -267,7 +464,7 @@ struct BwdData16LoadB {
     wvb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
     for (int i = 0; i < 4; ++i) off[i] = (unsigned)((8 * i + (l >> 3)) * Ksp + slot8(l, i)) * 2u;
-    toff = tapoff[walk.ti * 4 + wvb];
+    toff = tapoff[walk.ti * BPT + wvb];
   }
   __device__ __forceinline__ void begin(int, bool live) {
     const int t = __builtin_amdgcn_readfirstlane(toff);
@@ -276,7 +473,7 @@ struct BwdData16LoadB {
   __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
   __device__ __forceinline__ void end() {
     walk.next();
-    toff = tapoff[walk.ti * 4 + wvb];
+    toff = tapoff[walk.ti * BPT + wvb];
   }
 };
 
@@ -348,7 +545,7 @@ __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     BwdData16LoadA la(g, wt, Ksp, mb * BM, s_taps, nkc, cb);
-    BwdData16LoadB lb(dy, zero, Ksp, s_tapoff, nkc, cb);
+    BwdData16LoadB<4> lb(dy, zero, Ksp, s_tapoff, nkc, cb);
     gemm16_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) {
 #pragma unroll
@@ -389,6 +586,158 @@ __global__ __launch_bounds__(NT) void bwd_data16_gemm_kernel(Geo g, const bf16_t
     c = 0;
     first = false;
   }
+}
+
+// Accumulator block (i,j) of a wide input-gradient tile: 32 channels x 32 images of one pixel.
+__device__ __forceinline__ void bwd_data16_wide_store_block(const Geo& g, float* __restrict__ dxt,
+                                                            const int* __restrict__ perm, int m0, int ct, int i, int j,
+                                                            const f32x16& acc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // m0 does not change from one segment of a run to the next; the opaque copy keeps the row addresses from being
+  // computed once in front of the run and held in registers across the main loop.
+  asm volatile("" : "+s"(m0));
+  const int gcb = ct * 8 + (wave & 3) * 2 + j;
+  if (gcb >= g.HW * g.NB) return;
+  const int sp = gcb / g.NB, nb = gcb - sp * g.NB;
+  const int px = perm[sp];
+  const int n = nb * 32 + (lane & 31);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int c = m0 + (wave >> 2) * 128 + i * 32 + acc_row(v, lane);
+    if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[v];
+  }
+}
+
+// Input gradient on wide tiles: MB row tiles of 256 channels, CT column tiles of eight blocks (pre, when the runs
+// are enabled, must have been measured for tiles of eight blocks).  LDS behind the stages: tap list [RS + 3] and
+// per-block offsets [RS + 3][8].
+__global__ __launch_bounds__(NT2) void bwd_data16_wide_gemm_kernel(Geo g, const bf16_t* __restrict__ wt, int Ksp,
+                                                                   const bf16_t* __restrict__ dy,
+                                                                   const bf16_t* __restrict__ zero,
+                                                                   const int* __restrict__ perm,
+                                                                   const int* __restrict__ pre,
+                                                                   float* __restrict__ dxt, int MB, int CT,
+                                                                   RunPlan rp, float* __restrict__ partial) {
+  extern __shared__ __align__(16) float smem[];
+  int* s_taps = (int*)(smem + 4 * TILE2_F);    // [RS + 3]
+  int* s_tapoff = s_taps + g.RS + 3;           // [RS + 3][8]
+  __shared__ int s_ntaps;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nkc = Ksp / BK16;
+
+  auto segment = [&](int mb, int ct, int c0, int c1, bool direct, int slot) {
+    if (wave == 0) {   // tap list of the tile: the taps that reach any of its (at most eight) pixels
+      int hp[8], vp[8], nbo[8];
+      bool ok[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int gcb = ct * 8 + j;
+        ok[j] = gcb < g.HW * g.NB;
+        const int sp = ok[j] ? gcb / g.NB : 0;
+        const int px = perm[sp];
+        nbo[j] = ok[j] ? (gcb - sp * g.NB) * 32 * Ksp : 0;
+        hp[j] = px / g.W + g.ph;
+        vp[j] = px % g.W + g.pw;
+      }
+      int cnt = 0;
+      for (int b = 0; b < g.RS; b += 64) {
+        const int tp = b + lane;
+        const int rr = tp / g.S, ss = tp - rr * g.S;
+        bool any = false;
+        int offs[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int hr = hp[j] - rr, vs = vp[j] - ss;
+          const int p = hr / g.sh, q = vs / g.sw;
+          const bool hit = tp < g.RS && ok[j] && hr >= 0 && vs >= 0 && p * g.sh == hr && q * g.sw == vs &&
+                           p < g.P && q < g.Q;
+          offs[j] = hit ? (p * g.Q + q) * g.Np * Ksp + nbo[j] : -1;
+          any |= hit;
+        }
+        const unsigned long long mask = __ballot(any);
+        if (any) {
+          const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+          s_taps[pos] = (rr << 16) | ss;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) s_tapoff[pos * 8 + j] = offs[j];
+        }
+        cnt += __popcll(mask);
+      }
+      if (lane < 24) s_tapoff[cnt * 8 + lane] = -1;   // the loaders run up to three entries past the list
+      if (lane < 3) s_taps[cnt + lane] = 0;
+      if (lane == 0) s_ntaps = cnt;
+    }
+    __syncthreads();
+    const int nchunks = s_ntaps * nkc;
+    const int cb = min(c0, nchunks), ce = min(c1, nchunks);
+    f32x16 acc[4][2];
+    zero_acc_wide(acc);
+    BwdData16LoadA la(g, wt, Ksp, mb * BM2, s_taps, nkc, cb);
+    BwdData16LoadB<8> lb(dy, zero, Ksp, s_tapoff, nkc, cb);
+    gemm16_mainloop_wide(la, lb, cb, ce, smem, acc);
+    if (direct) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bwd_data16_wide_store_block(g, dxt, perm, mb * BM2, ct, i, j, acc[i][j]);
+    } else {
+      store_partial_wide(partial + (int64_t)slot * TAIL2_SLOT_FLOATS, acc);
+    }
+    __syncthreads();   // the next segment rewrites the tap list
+  };
+
+  if (!rp.enabled) {
+    int mb, ct;
+    if (!tile_dealt(blockIdx.x, MB, CT, mb, ct)) return;
+    segment(mb, ct, 0, 0x7fffffff, true, 0);
+    return;
+  }
+  const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  if (wg >= rp.nWg) return;
+  const int run = wg / MB, mb = wg - run * MB;
+  const int total = pre[CT], units = run_units(total, nkc, rp.nRuns);
+  if ((int64_t)run * units >= total) return;
+  int pos = run * units;
+  const int end = min(pos + units, total);
+  int ct = 0;   // the tile that holds pos: pre[ct] <= pos < pre[ct+1]
+  for (int hi = CT; hi - ct > 1;) {
+    const int mid = (ct + hi) >> 1;
+    if (pre[mid] <= pos) ct = mid; else hi = mid;
+  }
+  int c = pos - pre[ct];
+  bool first = true;
+  for (; pos < end && ct < CT; ++ct) {
+    const int len = pre[ct + 1] - pre[ct];
+    const int ce = min(len, c + (end - pos));
+    segment(mb, ct, c, ce, c == 0 && ce == len, wg * 2 + (first ? 0 : 1));
+    pos += ce - c;
+    c = 0;
+    first = false;
+  }
+}
+
+// Adds up the scratch slots of every wide tile that was cut by a run boundary.  grid = (CT*MB, 8).
+__global__ __launch_bounds__(NT2) void bwd_data16_wide_fixup_kernel(Geo g, const int* __restrict__ perm,
+                                                                    const int* __restrict__ pre,
+                                                                    const float* __restrict__ partial,
+                                                                    float* __restrict__ dxt, int MB, int CT, int nkc,
+                                                                    int nRuns) {
+  const int ct = blockIdx.x / MB, mb = blockIdx.x - ct * MB;
+  const int units = run_units(pre[CT], nkc, nRuns);
+  const int a = pre[ct], b = pre[ct + 1];   // the tile's stretch of the line
+  const int r0 = a / units, r1 = (b - 1) / units;
+  if (r0 == r1) return;   // inside one run: stored directly
+  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int r = r0; r <= r1; ++r) {
+    const int slot = r * units >= a ? 0 : 1;   // a run that starts inside the tile used its first slot
+    const float* p = partial + (int64_t)((r * MB + mb) * 2 + slot) * TAIL2_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT2 + threadIdx.x;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += p[v * NT2];
+  }
+  bwd_data16_wide_store_block(g, dxt, perm, mb * BM2, ct, bi, bj, acc);
 }
 
 // ---------------------------------------------------------- weight gradient ----
@@ -507,6 +856,75 @@ __global__ __launch_bounds__(NT) void bwd_weight16_gemm_kernel(Geo g, const bf16
     return;
   }
   for_each_segment(tp, nch, compute);
+}
+
+// Accumulator block (i,j) of a wide weight-gradient tile: 32 kernels x 32 filter elements.
+__device__ __forceinline__ void bwd_weight16_wide_store_block(const Geo& g, float* __restrict__ o, int m0, int ct, int i,
+                                                              int j, const f32x16& acc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = ct * BN2 + (wave & 3) * 64 + j * 32 + (lane & 31);
+  if (col >= g.CRS) return;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = m0 + (wave >> 2) * 128 + i * 32 + acc_row(v, lane);
+    if (m < g.Ks) o[(int64_t)m * g.CRS + col] = acc[v];
+  }
+}
+
+// Weight gradient on wide tiles; splits, tail plan and outputs as in bwd_weight16_gemm_kernel.
+template <bool PAD>
+__global__ __launch_bounds__(NT2) void bwd_weight16_wide_gemm_kernel(Geo g, const bf16_t* __restrict__ dyt,
+                                                                     const bf16_t* __restrict__ xt, int Np64,
+                                                                     float* __restrict__ out, int64_t splitStride,
+                                                                     int MB, int CT, int nch, int chPerSplit,
+                                                                     int splits, TailPlan tp,
+                                                                     float* __restrict__ partial) {
+  extern __shared__ __align__(16) float smem[];
+  int z = 0, Lsplit = 0;
+  if (splits > 1) {
+    const int tiles = MB * CT;
+    int item;
+    if (!line_contiguous(blockIdx.x, tiles * splits, item)) return;
+    z = item / tiles;
+    Lsplit = item - z * tiles;
+  }
+  const int ch0 = z * chPerSplit;
+  const int ch1 = min(nch, ch0 + chPerSplit);
+  float* o = out + (int64_t)z * splitStride;
+  auto compute = [&](int L, int cb, int ce, bool direct, int slot) __attribute__((always_inline)) {
+    int mb, ct;
+    tile_from_line(L, MB, CT, mb, ct);
+    f32x16 acc[4][2];
+    zero_acc_wide(acc);
+    BwdWeight16LoadA la(dyt, (int64_t)g.PQ * Np64, mb * BM2, g.Ks);
+    BwdWeight16LoadB<PAD> lb(g, xt, Np64, ct * BN2, cb);
+    gemm16_mainloop_wide(la, lb, cb, ce, smem, acc);
+    if (direct) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bwd_weight16_wide_store_block(g, o, mb * BM2, ct, i, j, acc[i][j]);
+    } else {
+      store_partial_wide(partial + (int64_t)slot * TAIL2_SLOT_FLOATS, acc);
+    }
+  };
+  if (splits > 1) {
+    compute(Lsplit, ch0, ch1, true, 0);
+    return;
+  }
+  for_each_segment(tp, nch, compute);
+}
+
+// grid = (nTail, 8)
+__global__ __launch_bounds__(NT2) void bwd_weight16_wide_fixup_kernel(Geo g, const float* __restrict__ partial,
+                                                                      float* __restrict__ out, int MB, int CT, int nch,
+                                                                      TailPlan tp) {
+  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  f32x16 acc;
+  gather_partials_wide(partial, tp, nch, blockIdx.x, bi, bj, acc);
+  int mb, ct;
+  tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
+  bwd_weight16_wide_store_block(g, out, mb * BM2, ct, bi, bj, acc);
 }
 
 }  // namespace cs

@@ -274,11 +274,12 @@ __global__ void fwd_tap_table_kernel(Geo g, int entries, int* __restrict__ tab) 
 }
 
 // One workgroup runs the phases of pixel_order.h: perm[position] = pixel, pixels by decreasing
-// tap count, and (with `pre`) the line of column tiles.  scratch holds po::axes_ints(H, W)
-// ints, used when the per-axis tables do not fit in LDS.  Launch with po::THREADS threads.
+// tap count, and (with `pre`) the line of the CT column tiles of bpt blocks each.  scratch holds
+// po::axes_ints(H, W) ints, used when the per-axis tables do not fit in LDS.  Launch with
+// po::THREADS threads.
 __global__ __launch_bounds__(po::THREADS) void bwd_data_pixel_order_kernel(Geo g, int* __restrict__ perm,
                                                                            int* __restrict__ scratch, int CT, int nkc,
-                                                                           int* __restrict__ pre) {
+                                                                           int bpt, int* __restrict__ pre) {
   __shared__ int bins[po::BINS], rowCnt[po::AXIS_CNT], colCnt[po::AXIS_CNT], part[po::THREADS];
   __shared__ int s_axes[po::AXES_LDS];
   po::Tables<int*> t;
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(po::THREADS) void bwd_data_pixel_order_kernel(Geo g
   if (pre == nullptr) return;
   __threadfence_block();
   __syncthreads();
-  po::phase_lengths(g, t, CT, nkc, tid, T);
+  po::phase_lengths(g, t, CT, nkc, bpt, tid, T);
   __syncthreads();
   for (int d = 1; d < T; d <<= 1) {   // part[] becomes its inclusive running sum
     const int v = tid >= d ? part[tid - d] : 0;

@@ -203,23 +203,25 @@ CS_PO_FN void tile_stretch(int CT, int tid, int T, int& t0, int& t1) {
   t1 = t0 + per < CT ? t0 + per : CT;
 }
 
-// Phase 6: length of every tile into pre[ct+1], the thread's sum into part[tid].
+// Phase 6: length of every tile into pre[ct+1], the thread's sum into part[tid].  A column tile
+// is bpt (4 or 8) consecutive column blocks.
+constexpr int MAX_BPT = 8;
 template <class P>
-CS_PO_FN void phase_lengths(const Geo& g, const Tables<P>& t, int CT, int nkc, int tid, int T) {
+CS_PO_FN void phase_lengths(const Geo& g, const Tables<P>& t, int CT, int nkc, int bpt, int tid, int T) {
   const Axes<P> ax(t.axes, g.H, g.W);
   int t0, t1;
   tile_stretch(CT, tid, T, t0, t1);
   int sum = 0;
-  const bool one_pixel = g.NB % 4 == 0;   // every tile lies inside one pixel: its taps are a*b
+  const bool one_pixel = g.NB % bpt == 0;   // every tile lies inside one pixel: its taps are a*b
   for (int ct = t0; ct < t1; ++ct) {
     int taps = 0;
     if (one_pixel) {
-      const int px = t.perm[ct / (g.NB >> 2)];
+      const int px = t.perm[ct / (g.NB / bpt)];
       taps = ax.nrow[px / g.W] * ax.ncol[px % g.W];
     } else {
-      int hp[4], vp[4], np = 0;   // the tile's distinct pixels
-      for (int j = 0; j < 4; ++j) {
-        const int gcb = ct * 4 + j;
+      int hp[MAX_BPT], vp[MAX_BPT], np = 0;   // the tile's distinct pixels
+      for (int j = 0; j < bpt; ++j) {
+        const int gcb = ct * bpt + j;
         if (gcb >= g.HW * g.NB) break;
         const int sp = gcb / g.NB;
         if (j > 0 && sp == (gcb - 1) / g.NB) continue;

@@ -4,7 +4,7 @@
 // in the built-in sweep: no access outside a table; perm is a permutation of the pixels;
 // tap counts do not increase along it; pixels with the same set of taps are neighbours; pre
 // starts at 0, and pre[ct+1]-pre[ct] is nkc * max(1, taps reaching any pixel of tile ct),
-// counted here by brute force.
+// counted here by brute force, for column tiles of four and of eight blocks.
 //
 // Build: g++ -std=c++17 -O1 -g -fsanitize=address,undefined -fno-sanitize-recover=all
 #include <cstdio>
@@ -56,7 +56,10 @@ static long g_cases = 0;
     return false;                                                                                        \
   } while (0)
 
-static bool run_case(const Case& c) {
+static bool run_case(const Case& c, int bpt);
+static bool run_case(const Case& c) { return run_case(c, 4) && run_case(c, 8); }
+
+static bool run_case(const Case& c, int bpt) {
   cs::Geo g{};
   g.H = c.H; g.W = c.W; g.R = c.R; g.S = c.S; g.sh = c.sh; g.sw = c.sw; g.ph = c.ph; g.pw = c.pw;
   g.P = out_extent(c.H, c.ph, c.R, c.sh);
@@ -65,7 +68,7 @@ static bool run_case(const Case& c) {
   g.NB = c.NB; g.Np = 32 * c.NB; g.N = g.Np;
   g.HW = c.H * c.W; g.PQ = g.P * g.Q; g.RS = c.R * c.S;
   ++g_cases;
-  const int CT = (g.HW * g.NB + 3) / 4;
+  const int CT = (g.HW * g.NB + bpt - 1) / bpt;
   // extents exactly as the kernel declares them (static LDS arrays) or the host plan allocates them
   std::vector<int> bins(po::BINS, -1), rowCnt(po::AXIS_CNT, -1), colCnt(po::AXIS_CNT, -1), part(c.T, -1);
   const bool in_lds = po::axes_ints(g.H, g.W) <= po::AXES_LDS;
@@ -85,7 +88,7 @@ static bool run_case(const Case& c) {
   for (int tid = 0; tid < T; ++tid) po::phase_bins(g, t, tid, T);
   for (int tid = 0; tid < T; ++tid) po::phase_scan_bins(g, t, tid, T);
   for (int tid = 0; tid < T; ++tid) po::phase_place(g, t, tid, T);
-  for (int tid = 0; tid < T; ++tid) po::phase_lengths(g, t, CT, c.nkc, tid, T);
+  for (int tid = 0; tid < T; ++tid) po::phase_lengths(g, t, CT, c.nkc, bpt, tid, T);
   for (int tid = 1; tid < T; ++tid) part[tid] += part[tid - 1];   // the kernel's workgroup scan
   for (int tid = 0; tid < T; ++tid) po::phase_prefix(t, CT, tid, T);
 
@@ -119,13 +122,14 @@ static bool run_case(const Case& c) {
   if (pre[0] != 0) FAIL("pre[0] = %d", pre[0]);
   for (int ct = 0; ct < CT; ++ct) {
     std::set<int> u;
-    for (int j = 0; j < 4; ++j) {
-      const int gcb = ct * 4 + j;
+    for (int j = 0; j < bpt; ++j) {
+      const int gcb = ct * bpt + j;
       if (gcb >= g.HW * g.NB) break;
       for (int tp : tapset[perm[gcb / g.NB]]) u.insert(tp);
     }
     const int want = c.nkc * (u.empty() ? 1 : (int)u.size());
-    if (pre[ct + 1] - pre[ct] != want) FAIL("tile %d: length %d, expected %d", ct, pre[ct + 1] - pre[ct], want);
+    if (pre[ct + 1] - pre[ct] != want)
+      FAIL("tile %d of %d blocks: length %d, expected %d", ct, bpt, pre[ct + 1] - pre[ct], want);
   }
   if (pre[CT + 1] != -1) FAIL("pre written past CT");
   return true;

@@ -6,7 +6,7 @@ import oracle
 import paper_1712_02546_amd as cs
 from paper_1712_02546_amd import synth
 
-from helpers import BF16_TOL, FP32_TOL, Device, oracle_shape, rel_err, sample_indices
+from helpers import BF16_TOL, FP32_TOL, Device, desc_of, oracle_shape, rel_err, sample_indices
 
 pytestmark = pytest.mark.gpu
 
@@ -44,6 +44,9 @@ ADHOC = [
     synth.random_layer(23, N=6, C=4, H=16, W=16, K=140, R=3, S=3, k0=5, k1=137),
     # C*R*S = 480, the most the pixel-major path takes; 8.75 reduction chunks per image in the weight gradient
     synth.random_layer(24, N=2, C=16, H=12, W=40, K=33, R=5, S=6),
+    # bf16: more 256 x 256 tiles than compute units (whole tiles plus a shared tail), a ragged second row tile of
+    # 31 kernels, 162 channels (ragged second row tile of the input gradient), padding
+    synth.random_layer(25, N=40, C=162, H=24, W=24, K=300, R=3, S=3, pad=1, k0=3, k1=290),
 ]
 
 
@@ -74,8 +77,8 @@ def test_full_tensors_match_oracle_fp32(cfg):
     assert np.all(dw[:k0] == 7.0) and np.all(dw[k1:] == 7.0), "filters outside the slice were written"
 
 
-@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], ADHOC[16], ADHOC[19], ADHOC[20], ADHOC[21],
-                          synth.CONFIGS["cfg1"]],
+@pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], ADHOC[13], ADHOC[16], ADHOC[19],
+                          ADHOC[20], ADHOC[21], ADHOC[22], synth.CONFIGS["cfg1"]],
                          ids=lambda c: c.name)
 def test_full_tensors_match_oracle_bf16(cfg):
     xo, wo, dyo = synth.make_inputs(cfg)
@@ -93,6 +96,21 @@ def test_full_tensors_match_oracle_bf16(cfg):
     check(y[:, k0:k1], oracle.conv_fwd(sh, xo, wo)[:, k0:k1], BF16_TOL, "y vs unrounded inputs")
     check(dx, oracle.conv_bwd_data(sh, dyo, wo), BF16_TOL, "dx vs unrounded inputs")
     check(dw[k0:k1], oracle.conv_bwd_weight(sh, xo, dyo)[k0:k1], BF16_TOL, "dw vs unrounded inputs")
+
+
+def test_wide_input_gradient_tiles_one_workgroup_each_bf16():
+    """More 256 x 256 input-gradient tiles than compute units (no runs: one workgroup per tile, heaviest first),
+    with pixels that no tap reaches (1x1, stride 2).  Compared on the rounded inputs only: with one tap and 260
+    kernels per sum, the rounding of the inputs alone moves single elements of dx by 2.3 % of the tensor's rms,
+    whatever kernel adds them up; the gate on unrounded inputs is held by the cases above."""
+    cfg = ADHOC[14]
+    x, w, dy = (synth.round_to_bf16(a) for a in synth.make_inputs(cfg))
+    sh = oracle_shape(cfg)
+    dev = Device(cfg, x, w, dy, dtype=cs.CONV_BF16)
+    assert "wide" in cs.conv_pass_path(desc_of(cfg, cs.CONV_BF16), cs.PASS_BWD_DATA)
+    check(dev.fwd(), oracle.conv_fwd(sh, x, w), BF16_TOL, "y")
+    check(dev.bwd_data(), oracle.conv_bwd_data(sh, dy, w), BF16_TOL, "dx")
+    check(dev.bwd_weight(), oracle.conv_bwd_weight(sh, x, dy), FP32_TOL, "dw")
 
 
 @pytest.mark.parametrize("C", [24, 48])
