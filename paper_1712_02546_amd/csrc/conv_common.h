@@ -177,6 +177,23 @@ __device__ __forceinline__ void dma16_uv(const char* base_uniform, unsigned& lan
 // wavefront's 16-byte LDS reads run at 256 bytes per clock, with m & 7 at half of that.
 __device__ __forceinline__ int col_key(int row) { return (row >> 1) & 7; }
 
+// Tile shapes of the fp32 kernels, by the template parameter MI (32-row blocks per wavefront):
+//   MI = 2: 128 rows, MI = 1: 64 rows -- four wavefronts as 2 x 2, each MI x 2 accumulator blocks;
+//   MI = 3:  96 rows -- four wavefronts side by side (1 x 4), each 3 x 1 blocks: every wavefront does the
+//            same work, which a 2 x 2 arrangement of three row blocks could not give.
+// All shapes are 128 columns wide.
+template <int MI>
+struct Shape {
+  static_assert(MI >= 1 && MI <= 3, "tile shapes: 64, 128 or 96 rows");
+  static constexpr int NJ = MI == 3 ? 1 : 2;           // column blocks per wavefront
+  static constexpr int ROWS = MI == 3 ? 96 : 64 * MI;  // tile rows
+  static constexpr int NLOAD = ROWS / 32;              // A-operand DMA loads per wavefront and chunk
+  static constexpr int WROWS = ROWS / 4;               // A rows a wavefront stages
+  __device__ static __forceinline__ int row0(int wave) { return MI == 3 ? 0 : (wave >> 1) * (32 * MI); }
+  __device__ static __forceinline__ int col0(int wave) { return MI == 3 ? wave * 32 : (wave & 1) * 64; }
+  __device__ static __forceinline__ int colblk0(int wave) { return MI == 3 ? wave : (wave & 1) * 2; }
+};
+
 template <int NBLK>
 struct FragN {         // operands of four MFMA steps (one j) for NBLK of the wavefront's 32-wide blocks
   f32x4 v[NBLK];       // v[blk][t]
@@ -188,20 +205,22 @@ __device__ __forceinline__ void read_frag(FragN<NBLK>& f, const float* tile, int
   if constexpr (COL) {
     const int u = col_key(lane & 31), h = lane >> 5;
     const int slot = (wbase + (lane & 31)) * 8 + ((2 * j + h) ^ u);
-    f.v[0] = *(const f32x4*)(tile + slot * 4);
-    if constexpr (NBLK == 2) f.v[1] = *(const f32x4*)(tile + slot * 4 + 32 * 8 * 4);
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) f.v[b] = *(const f32x4*)(tile + slot * 4 + b * (32 * 8 * 4));
   } else {
-    static_assert(NBLK == 2, "row images always feed two blocks");
+    static_assert(NBLK <= 2, "row images feed one or two blocks");
     // The second block lies blk1 = 32 floats to the right.  blk1 is an opaque register (see
     // opaque_block_offset), so the two blocks keep separate base registers and the reads of
     // rows t, t+1 of one block (512 bytes apart) pair up into LDS reads with 256-byte offset
     // units, which reach every j and t from that one base.
     const float* p = tile + (8 * j + 4 * (lane >> 5)) * BM + wbase + (lane & 31);
-    const float* q = p + blk1;
 #pragma unroll
     for (int t = 0; t < 4; ++t) f.v[0][t] = p[t * BM];
+    if constexpr (NBLK == 2) {
+      const float* q = p + blk1;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) f.v[1][t] = q[t * BM];
+      for (int t = 0; t < 4; ++t) f.v[1][t] = q[t * BM];
+    }
   }
 }
 
@@ -211,15 +230,17 @@ __device__ __forceinline__ int opaque_block_offset() {
   return o;
 }
 
-// Four reduction steps on the wavefront's MI x 2 accumulator blocks (sixteen MFMAs for MI = 2).
+// Four reduction steps on the wavefront's MI x NJ accumulator blocks (sixteen MFMAs for MI = 2, twelve for MI = 3).
 template <int MI>
-__device__ __forceinline__ void mfma_group(const FragN<MI>& a, const Frag& b, f32x16 (&acc)[MI][2]) {
+__device__ __forceinline__ void mfma_group(const FragN<MI>& a, const FragN<Shape<MI>::NJ>& b,
+                                           f32x16 (&acc)[MI][Shape<MI>::NJ]) {
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[0][t], acc[i][0], 0, 0, 0);
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[1][t], acc[i][1], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < Shape<MI>::NJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[j][t], acc[i][j], 0, 0, 0);
     }
   }
 }
@@ -235,16 +256,16 @@ __device__ __forceinline__ void mfma_group(const FragN<MI>& a, const Frag& b, f3
 // (chunks are requested in increasing order, once each; live = false marks chunks past the
 // last one, whose loads must stay harmless so that the loop body needs no branch).  LDS
 // holds [A stage0][A stage1][B stage0][B stage1].
-// The A operand has 64*MI rows (LA::MI = 2: the 128-row tile, 1: the half tile for a short
-// last row tile), i.e. 2*MI loads per wavefront and chunk.
+// The A operand has Shape<LA::MI>::ROWS rows (128, 64 for a short last row tile, or 96), i.e. ROWS / 32 loads per
+// wavefront and chunk.
 template <class LA, class LB>
 __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, float* tb, int wv, bool live) {
-  constexpr int MI = LA::MI;
+  constexpr int NLOAD = Shape<LA::MI>::NLOAD;
   la.begin(ch, live);
   lb.begin(ch, live);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (i < 2 * MI) la.issue(i, ta + (wv * 2 * MI + i) * 256);
+    if (i < NLOAD) la.issue(i, ta + (wv * NLOAD + i) * 256);
     lb.issue(i, tb + (wv * 4 + i) * 256);
   }
   la.end();
@@ -258,18 +279,18 @@ __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, flo
 // chunk ch while G2,G3 are being read.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end, float* smem,
-                                              f32x16 (&acc)[LA::MI][2]) {
+                                              f32x16 (&acc)[LA::MI][Shape<LA::MI>::NJ]) {
   constexpr bool AC = LA::COL, BC = LB::COL;
   constexpr int MI = LA::MI;
-  static_assert(MI == 2 || AC, "the half tile needs a col-image A operand");
+  static_assert(MI == 2 || AC, "the 64- and 96-row tiles need a col-image A operand");
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wa = (wv >> 1) * (32 * MI), wb = (wv & 1) * 64;
+  const int wa = Shape<MI>::row0(wv), wb = Shape<MI>::col0(wv);
   if (ch_begin >= ch_end) return;
   const int blk1 = opaque_block_offset();
   FragN<MI> a0, a1;
-  Frag b0, b1;
+  FragN<Shape<MI>::NJ> b0, b1;
   // prologue: chunk ch_begin into stage 0
   issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
   __syncthreads();  // includes the wait for this wavefront's own DMA loads
@@ -324,22 +345,23 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
 // Four reduction steps that start a tile: the first step writes the accumulators (C operand zero) instead of
 // adding to them, so a new tile needs no clearing pass over the accumulator registers.
 template <int MI>
-__device__ __forceinline__ void mfma_group_first(const FragN<MI>& a, const Frag& b, f32x16 (&acc)[MI][2]) {
+__device__ __forceinline__ void mfma_group_first(const FragN<MI>& a, const FragN<Shape<MI>::NJ>& b,
+                                                 f32x16 (&acc)[MI][Shape<MI>::NJ]) {
+  constexpr int NJ = Shape<MI>::NJ;
   f32x16 zero;
 #pragma unroll
   for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][0], b.v[0][0], zero, 0, 0, 0);
-    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][0], b.v[1][0], zero, 0, 0, 0);
-  }
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][0], b.v[j][0], zero, 0, 0, 0);
 #pragma unroll
   for (int t = 1; t < 4; ++t) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[0][t], acc[i][0], 0, 0, 0);
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[1][t], acc[i][1], 0, 0, 0);
-    }
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[j][t], acc[i][j], 0, 0, 0);
   }
 }
 
@@ -356,16 +378,16 @@ template <class LA, class LB, class Tiles>
 __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem) {
   constexpr bool AC = LA::COL, BC = LB::COL;
   constexpr int MI = LA::MI;
-  static_assert(MI == 2 || AC, "the half tile needs a col-image A operand");
+  static_assert(MI == 2 || AC, "the 64- and 96-row tiles need a col-image A operand");
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wa = (wv >> 1) * (32 * MI), wb = (wv & 1) * 64;
+  const int wa = Shape<MI>::row0(wv), wb = Shape<MI>::col0(wv);
   if (!tiles.advance()) return;
   LA la = tiles.make_a();
   LB lb = tiles.make_b();
   const int blk1 = opaque_block_offset();
-  f32x16 acc[MI][2];
+  f32x16 acc[MI][Shape<MI>::NJ];
   // Issues the loads of the chunk that follows chunk ch of the tile being loaded; false at the end of the stream.
   auto issue_next = [&](int ch, float* ta, float* tb) -> bool {
     if (ch + 1 < nch) {
@@ -380,7 +402,7 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem) 
     return true;
   };
   FragN<MI> a0, a1;
-  Frag b0, b1;
+  FragN<Shape<MI>::NJ> b0, b1;
   issue_all(la, lb, 0, smem, smem + 2 * TILE_F, wv, true);
   __syncthreads();
   read_frag<AC>(a0, smem, wa, lane, 0, blk1);

@@ -103,16 +103,22 @@ inline size_t tail_bytes(int nch) {
 }
 
 // Row tiles of a matrix-core pass with M rows: `full` tiles of 128 rows and, when the rest is at most 64 rows, one
-// half tile (64 rows) for it, computed by a second launch; a rest above 64 rows takes a full tile.
+// half tile (64 rows) for it, computed by a second launch; a rest above 64 rows takes a full tile -- or, where the
+// pass has the 96-row kernels (three_quarter), a rest of 65..96 rows takes a 96-row tile.
 struct RowSplit {
   int full, half;   // half = 1 if a half tile follows the full ones
+  int last;         // shape (cs::Shape) of the short last tile: 0 none, 1: 64 rows, 3: 96 rows
 };
-RowSplit split_rows(int M) {
+RowSplit split_rows(int M, bool three_quarter = false) {
   RowSplit r;
   r.full = M / cs::BM;
   const int rest = M - r.full * cs::BM;
   r.half = rest > 0 && rest <= cs::BM / 2;
-  if (rest > cs::BM / 2) ++r.full;
+  r.last = r.half ? 1 : 0;
+  if (rest > cs::BM / 2) {
+    if (three_quarter && rest <= 96) r.last = 3;
+    else ++r.full;
+  }
   return r;
 }
 
@@ -174,8 +180,12 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   // workspace sized for a slice is large enough for any part of it.
   {
     const double F = 2.0 * g.Np * g.K * (double)g.CRS * g.PQ;
-    const double rows_pixel = (double)g.C / (double)(round_up(g.C, cs::BM));
-    const double rows_scatter = (double)g.CRS / (double)(round_up(g.CRS, cs::BM));
+    auto tile_rows = [](int M) {   // rows the row tiles of an M-row pass compute
+      const RowSplit r = split_rows(M, true);
+      return r.full * cs::BM + (r.last == 1 ? 64 : r.last == 3 ? 96 : 0);
+    };
+    const double rows_pixel = (double)g.C / (double)tile_rows(g.C);
+    const double rows_scatter = (double)g.CRS / (double)tile_rows(g.CRS);
     const double t_pixel = F / (130e12 * rows_pixel);
     const double t_scatter = F / (130e12 * rows_scatter) + 2.0 * 4.0 * g.CRS * (double)g.PQ * g.Np / 3e12;
     p.scatter = t_scatter < 0.9 * t_pixel && (int64_t)g.CRS * g.PQ * g.Np < kMaxElems;
@@ -244,9 +254,9 @@ int64_t split_partial_elems(const Geo& g, int CT, int64_t nch, bool pipe_bound, 
     const int sp = choose_splits((int64_t)t * CT, nch, pipe_bound, min_rounds);
     if (sp > 1) need = std::max(need, (int64_t)sp * rows * g.CRS);
   }
-  if (pipe_bound && g.Ks > 0) {   // the half tile (fp32 kernels only)
+  if (pipe_bound && g.Ks > 0) {   // the 64- or 96-row tile for the rest (fp32 kernels only)
     const int sp = choose_splits(CT, nch, pipe_bound, min_rounds);
-    if (sp > 1) need = std::max(need, (int64_t)sp * std::min(g.Ks, cs::BM / 2) * g.CRS);
+    if (sp > 1) need = std::max(need, (int64_t)sp * std::min(g.Ks, 96) * g.CRS);
   }
   return need;
 }
@@ -827,35 +837,37 @@ size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
   }
 }
 
-// The forward kernel over all rows of g (g.Ks of them): full row tiles first, then the half tile, each with its
-// own tail plan; the two launches share the scratch slots (stream order keeps them apart).
+// The forward kernel over all rows of g (g.Ks of them): full row tiles first, then the 64- or 96-row tile for the
+// rest, each with its own tail plan; the two launches share the scratch slots (stream order keeps them apart).
 int launch_fwd_gemm(const Geo& g, bool pad, const float* wmat, int ldw, const float* xt, const int* tab, int entries,
                     float* out, int CT, int nch, float* partial, hipStream_t st) {
   int rc;
-  const RowSplit rs = split_rows(g.Ks);
-  if (rs.full > 0) {
-    auto kern = pad ? cs::fwd_gemm_kernel<true, 2> : cs::fwd_gemm_kernel<false, 2>;
-    if ((rc = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc;
-    const cs::TailPlan tp = plan_tail(rs.full * CT, nch);
-    hipLaunchKernelGGL(kern,
-                       dim3(cs::grid_contiguous(tp.nFull) + cs::grid_contiguous(tp.nTailWg)), dim3(cs::NT),
-                       cs::SMEM_BYTES, st, g, wmat, ldw, xt, tab, entries, out, 0, rs.full, CT, nch, tp, partial);
+  const RowSplit rs = split_rows(g.Ks, true);
+  // one launch over `tiles` row tiles of shape mi from row m0
+  auto launch = [&](auto kern, auto fixup, int mi, int m0, int tiles) -> int {
+    const int r = allow_big_lds(kern, cs::SMEM_BYTES);
+    if (r != CONV_OK) return r;
+    const cs::TailPlan tp = plan_tail(tiles * CT, nch);
+    hipLaunchKernelGGL(kern, dim3(cs::grid_contiguous(tp.nFull) + cs::grid_contiguous(tp.nTailWg)), dim3(cs::NT),
+                       cs::SMEM_BYTES, st, g, wmat, ldw, xt, tab, entries, out, m0, tiles, CT, nch, tp, partial);
     if (tp.nTail > 0)
-      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<2>, dim3(tp.nTail, 4), dim3(cs::NT), 0, st, g, partial, out, 0,
-                         rs.full, CT, nch, tp);
-  }
-  if (rs.half) {
-    auto kern = pad ? cs::fwd_gemm_kernel<true, 1> : cs::fwd_gemm_kernel<false, 1>;
-    if ((rc = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc;
-    const cs::TailPlan tp = plan_tail(CT, nch);
-    const int m0 = rs.full * cs::BM;
-    hipLaunchKernelGGL(kern,
-                       dim3(cs::grid_contiguous(tp.nFull) + cs::grid_contiguous(tp.nTailWg)), dim3(cs::NT),
-                       cs::SMEM_BYTES, st, g, wmat, ldw, xt, tab, entries, out, m0, 1, CT, nch, tp, partial);
-    if (tp.nTail > 0)
-      hipLaunchKernelGGL(cs::fwd_tail_fixup_kernel<1>, dim3(tp.nTail, 2), dim3(cs::NT), 0, st, g, partial, out, m0, 1,
-                         CT, nch, tp);
-  }
+      hipLaunchKernelGGL(fixup, dim3(tp.nTail, mi == 2 ? 4 : mi == 1 ? 2 : 3), dim3(cs::NT), 0, st, g, partial, out, m0,
+                         tiles, CT, nch, tp);
+    return CONV_OK;
+  };
+  const int m1 = rs.full * cs::BM;
+  if (rs.full > 0 &&
+      (rc = pad ? launch(cs::fwd_gemm_kernel<true, 2>, cs::fwd_tail_fixup_kernel<2>, 2, 0, rs.full)
+                : launch(cs::fwd_gemm_kernel<false, 2>, cs::fwd_tail_fixup_kernel<2>, 2, 0, rs.full)) != CONV_OK)
+    return rc;
+  if (rs.last == 1 &&
+      (rc = pad ? launch(cs::fwd_gemm_kernel<true, 1>, cs::fwd_tail_fixup_kernel<1>, 1, m1, 1)
+                : launch(cs::fwd_gemm_kernel<false, 1>, cs::fwd_tail_fixup_kernel<1>, 1, m1, 1)) != CONV_OK)
+    return rc;
+  if (rs.last == 3 &&
+      (rc = pad ? launch(cs::fwd_gemm_kernel<true, 3>, cs::fwd_tail_fixup_kernel<3>, 3, m1, 1)
+                : launch(cs::fwd_gemm_kernel<false, 3>, cs::fwd_tail_fixup_kernel<3>, 3, m1, 1)) != CONV_OK)
+    return rc;
   return CONV_OK;
 }
 
@@ -1150,27 +1162,26 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   const int lds = cs::SMEM_BYTES + (g.RS + 3) * 20;
   // Channels in full row tiles first, then the half tile for a rest of at most 64 channels; both launches walk the
   // same line of column tiles and share the scratch slots (stream order keeps them apart).
-  const RowSplit rs = split_rows(g.C);
+  const RowSplit rs = split_rows(g.C, true);
+  // one launch over `tiles` row tiles of shape mi from channel c0
+  auto launch = [&](auto kern, auto fixup, int mi, int c0, int tiles) -> int {
+    const int r = allow_big_lds(kern, lds);
+    if (r != CONV_OK) return r;
+    const cs::RunPlan rp = plan_runs(tiles, runs);
+    hipLaunchKernelGGL(kern, dim3(rp.enabled ? (rp.nWg + 7) / 8 * 8 : cs::grid_dealt(tiles, CT)), dim3(cs::NT), lds, st, g,
+                       wt, p.Ksp, dyt, perm, pre, dxt, c0, tiles, CT, rp, partial);
+    if (rp.enabled)
+      hipLaunchKernelGGL(fixup, dim3(CT * tiles, mi == 2 ? 4 : mi == 1 ? 2 : 3), dim3(cs::NT), 0, st, g, perm, pre, partial,
+                         dxt, c0, tiles, CT, p.nch, rp.nRuns);
+    return CONV_OK;
+  };
   probe.begin(st);
-  if (rs.full > 0) {
-    if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel<2>, lds)) != CONV_OK) return rc;
-    const cs::RunPlan rp = plan_runs(rs.full, runs);
-    hipLaunchKernelGGL(cs::bwd_data_gemm_kernel<2>, dim3(rp.enabled ? (rp.nWg + 7) / 8 * 8 : cs::grid_dealt(rs.full, CT)),
-                       dim3(cs::NT), lds, st, g, wt, p.Ksp, dyt, perm, pre, dxt, 0, rs.full, CT, rp, partial);
-    if (rp.enabled)
-      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<2>, dim3(CT * rs.full, 4), dim3(cs::NT), 0, st, g, perm, pre, partial,
-                         dxt, 0, rs.full, CT, p.nch, rp.nRuns);
-  }
-  if (rs.half) {
-    if ((rc = allow_big_lds(cs::bwd_data_gemm_kernel<1>, lds)) != CONV_OK) return rc;
-    const cs::RunPlan rp = plan_runs(1, runs);
-    const int c0 = rs.full * cs::BM;
-    hipLaunchKernelGGL(cs::bwd_data_gemm_kernel<1>, dim3(rp.enabled ? (rp.nWg + 7) / 8 * 8 : cs::grid_dealt(1, CT)),
-                       dim3(cs::NT), lds, st, g, wt, p.Ksp, dyt, perm, pre, dxt, c0, 1, CT, rp, partial);
-    if (rp.enabled)
-      hipLaunchKernelGGL(cs::bwd_data_fixup_kernel<1>, dim3(CT, 2), dim3(cs::NT), 0, st, g, perm, pre, partial, dxt, c0,
-                         1, CT, p.nch, rp.nRuns);
-  }
+  if (rs.full > 0) rc = launch(cs::bwd_data_gemm_kernel<2>, cs::bwd_data_fixup_kernel<2>, 2, 0, rs.full);
+  if (rc == CONV_OK && rs.last == 1)
+    rc = launch(cs::bwd_data_gemm_kernel<1>, cs::bwd_data_fixup_kernel<1>, 1, rs.full * cs::BM, 1);
+  if (rc == CONV_OK && rs.last == 3)
+    rc = launch(cs::bwd_data_gemm_kernel<3>, cs::bwd_data_fixup_kernel<3>, 3, rs.full * cs::BM, 1);
+  if (rc != CONV_OK) return rc;
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
   launch_transpose_out(desc->dtype, desc->accumulate != 0, dxt, g.Np, g.N, g.C * g.HW, dx, (int64_t)g.C * g.HW, st);
@@ -1254,12 +1265,12 @@ int bwd_weight_impl(const conv_desc_t* desc, const void* x, const void* dy, void
                       g.Ks * g.PQ, dyt, 0, g.Np, g.Np, 1, nullptr, st);
   const bool pad = needs_pad_checks(g);
   float* scratch = (float*)(base + p.off_part);   // split partials or tail slots
-  // One launch over `tiles` row tiles of 64*mi rows from row m0: the reduction split (partials, then a sum in
-  // split order) or whole tiles with a shared tail.
+  // One launch over `tiles` row tiles of shape mi (128, 64 or 96 rows) from row m0: the reduction split (partials,
+  // then a sum in split order) or whole tiles with a shared tail.
   auto launch = [&](auto kern, auto fixup, int mi, int m0, int tiles) -> int {
     int rc2;
     if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
-    const int rows = std::min(g.Ks - m0, tiles * 64 * mi);
+    const int rows = std::min(g.Ks - m0, tiles * (mi == 3 ? 96 : 64 * mi));
     const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true);
     cs::TailPlan tp;
     if (splits > 1) { tp.nFull = tiles * p.CT; tp.nTail = 0; tp.units = 1; tp.nTailWg = 0; }
@@ -1270,8 +1281,8 @@ int bwd_weight_impl(const conv_desc_t* desc, const void* x, const void* dy, void
     hipLaunchKernelGGL(kern, dim3(split_grid(tiles * p.CT, splits, tp)), dim3(cs::NT), cs::SMEM_BYTES, st, g, dyt, xt,
                        out, stride, m0, rowBase, tiles, p.CT, p.nch, splits, tp, scratch);
     if (tp.nTail > 0)
-      hipLaunchKernelGGL(fixup, dim3(tp.nTail, 2 * mi), dim3(cs::NT), 0, st, g, scratch, out, m0, rowBase, tiles, p.CT,
-                         p.nch, tp);
+      hipLaunchKernelGGL(fixup, dim3(tp.nTail, mi == 2 ? 4 : mi == 1 ? 2 : 3), dim3(cs::NT), 0, st, g, scratch, out, m0,
+                         rowBase, tiles, p.CT, p.nch, tp);
     if (splits > 1) {
       const int blocks = (int)((stride + 255) / 256 < 8192 ? (stride + 255) / 256 : 8192);
       hipLaunchKernelGGL(cs::splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, scratch, stride, splits,
@@ -1279,14 +1290,17 @@ int bwd_weight_impl(const conv_desc_t* desc, const void* x, const void* dy, void
     }
     return CONV_OK;
   };
-  const RowSplit rs = split_rows(g.Ks);
+  const RowSplit rs = split_rows(g.Ks, true);
   probe.begin(st);
   if (rs.full > 0)
     rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 2>, cs::bwd_weight_tail_fixup_kernel<2>, 2, 0, rs.full)
              : launch(cs::bwd_weight_gemm_kernel<false, 2>, cs::bwd_weight_tail_fixup_kernel<2>, 2, 0, rs.full);
-  if (rc == CONV_OK && rs.half)
+  if (rc == CONV_OK && rs.last == 1)
     rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 1>, cs::bwd_weight_tail_fixup_kernel<1>, 1, rs.full * cs::BM, 1)
              : launch(cs::bwd_weight_gemm_kernel<false, 1>, cs::bwd_weight_tail_fixup_kernel<1>, 1, rs.full * cs::BM, 1);
+  if (rc == CONV_OK && rs.last == 3)
+    rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 3>, cs::bwd_weight_tail_fixup_kernel<3>, 3, rs.full * cs::BM, 1)
+             : launch(cs::bwd_weight_gemm_kernel<false, 3>, cs::bwd_weight_tail_fixup_kernel<3>, 3, rs.full * cs::BM, 1);
   probe.end(st);
   if (rc != CONV_OK) return rc;
   return check_launch();

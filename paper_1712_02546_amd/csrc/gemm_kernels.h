@@ -18,16 +18,16 @@ namespace cs {
 template <int MI_>
 struct FwdLoadA {
   static constexpr bool COL = true;
-  static constexpr int MI = MI_;   // tile rows / 64
+  static constexpr int MI = MI_;   // tile shape (Shape<MI>)
   const char* tile;   // uniform: row m0 of the filter matrix
   const char* ub;     // uniform: tile + the chunk being issued
-  unsigned off[2 * MI];
+  unsigned off[Shape<MI>::NLOAD];
   __device__ FwdLoadA(const float* w, int ldw, int m0, int Ks) : tile((const char*)(w + (int64_t)m0 * ldw)) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 2 * MI; ++i) {
-      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-      const int m = min(16 * MI * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
+    for (int i = 0; i < Shape<MI>::NLOAD; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(Shape<MI>::WROWS * wv + 8 * i + (l >> 3)));
+      const int m = min(Shape<MI>::WROWS * wv + 8 * i + (l >> 3), Ks - 1 - m0);  // rows past the slice repeat the last one
       off[i] = ((unsigned)m * (unsigned)ldw + kq4) * 4u;
     }
   }
@@ -114,27 +114,27 @@ struct FwdLoadB {
   __device__ __forceinline__ void end() {}
 };
 
-// Accumulator images in wavefront layout: element e = (i*2+j)*16+v of thread t at [e*NT + t].
+// Accumulator images in wavefront layout: element e = (i*NJ+j)*16+v of thread t at [e*NT + t].
 template <int MI>
-__device__ __forceinline__ void store_partial(float* slot, const f32x16 (&acc)[MI][2]) {
+__device__ __forceinline__ void store_partial(float* slot, const f32x16 (&acc)[MI][Shape<MI>::NJ]) {
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) slot[((i * 2 + j) * 16 + v) * NT + threadIdx.x] = acc[i][j][v];
+      for (int v = 0; v < 16; ++v) slot[((i * Shape<MI>::NJ + j) * 16 + v) * NT + threadIdx.x] = acc[i][j][v];
 }
 
-// Sum of the scratch slots of tail tile tl, in run order, for accumulator block (bi,bj).
+// Sum of the scratch slots of tail tile tl, in run order, for the accumulator block stored as number blk.
 __device__ __forceinline__ void gather_partials(const float* partial, const TailPlan& tp, int nch, int tl,
-                                                int bi, int bj, f32x16& acc) {
+                                                int blk, f32x16& acc) {
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   const int wfirst = (tl * nch) / tp.units;
   const int wlast = min(tp.nTailWg - 1, (tl * nch + nch - 1) / tp.units);
   for (int w = wfirst; w <= wlast; ++w) {
     const int slot = (w * tp.units) / nch == tl ? 0 : 1;   // a run's first tile uses slot 0, its second slot 1
-    const float* p = partial + (int64_t)(w * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
+    const float* p = partial + (int64_t)(w * 2 + slot) * TAIL_SLOT_FLOATS + blk * 16 * NT + threadIdx.x;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];
   }
@@ -173,23 +173,22 @@ template <int MI>
 __device__ __forceinline__ void fwd_store_block(const Geo& g, float* __restrict__ yt, int m0, int ct, int i, int j,
                                                 const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int gcb = ct * 4 + wn * 2 + j;
+  const int gcb = ct * 4 + Shape<MI>::colblk0(wave) + j;
   if (gcb >= g.PQ * g.NB) return;
   const int pix = gcb / g.NB, nb = gcb - pix * g.NB;
   const int n = nb * 32 + (lane & 31);
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int m = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
+    const int m = m0 + Shape<MI>::row0(wave) + i * 32 + acc_row(v, lane);
     if (m < g.Ks) yt[((int64_t)m * g.PQ + pix) * g.Np + n] = acc[v];
   }
 }
 
 template <int MI>
 __device__ __forceinline__ void fwd_store_tile(const Geo& g, float* __restrict__ yt, int m0, int ct,
-                                               const f32x16 (&acc)[MI][2]) {
+                                               const f32x16 (&acc)[MI][Shape<MI>::NJ]) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
     for (int i = 0; i < MI; ++i) fwd_store_block<MI>(g, yt, m0, ct, i, j, acc[i][j]);
 }
@@ -206,12 +205,12 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
   for_each_segment(tp, nch, [&](int L, int cb, int ce, bool direct, int slot) {
     int mb, ct;
     tile_from_line(L, MB, CT, mb, ct);
-    const int m0 = mOrigin + mb * (64 * MI);
-    f32x16 acc[MI][2];
+    const int m0 = mOrigin + mb * Shape<MI>::ROWS;
+    f32x16 acc[MI][Shape<MI>::NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     FwdLoadA<MI> la(w, ldw, m0, g.Ks);
@@ -222,18 +221,18 @@ __global__ __launch_bounds__(NT) void fwd_gemm_kernel(Geo g, const float* __rest
   });
 }
 
-// Adds up the scratch slots of each tail tile and stores the tile.  grid = (nTail, 2*MI): one
+// Adds up the scratch slots of each tail tile and stores the tile.  grid = (nTail, MI*NJ): one
 // workgroup per tile and accumulator block.
 template <int MI>
 __global__ __launch_bounds__(NT) void fwd_tail_fixup_kernel(Geo g, const float* __restrict__ partial,
                                                             float* __restrict__ yt, int mOrigin, int MB, int CT,
                                                             int nch, TailPlan tp) {
-  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  const int bi = blockIdx.y / Shape<MI>::NJ, bj = blockIdx.y % Shape<MI>::NJ;
   f32x16 acc;
-  gather_partials(partial, tp, nch, blockIdx.x, bi, bj, acc);
+  gather_partials(partial, tp, nch, blockIdx.x, blockIdx.y, acc);
   int mb, ct;
   tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
-  fwd_store_block<MI>(g, yt, mOrigin + mb * (64 * MI), ct, bi, bj, acc);
+  fwd_store_block<MI>(g, yt, mOrigin + mb * Shape<MI>::ROWS, ct, bi, bj, acc);
 }
 
 // --------------------------------------------------------- input gradient ----
@@ -258,11 +257,11 @@ struct TapWalk {
 template <int MI_>
 struct BwdDataLoadA {
   static constexpr bool COL = true;
-  static constexpr int MI = MI_;   // tile rows / 64
+  static constexpr int MI = MI_;   // tile shape (Shape<MI>)
   const char* wt;     // uniform: w_t at channel m0 of tap 0
   const char* ub;     // uniform base of the chunk being issued
   const int* taps;
-  unsigned off[2 * MI];
+  unsigned off[Shape<MI>::NLOAD];
   unsigned tapBytes;  // one tap: C rows (a whole work copy is below 4 GiB)
   int tap;            // flat tap r*S+s of walk.ti, fetched one call ahead (uniform, held in a vector register)
   TapWalk walk;
@@ -270,9 +269,9 @@ struct BwdDataLoadA {
       : wt((const char*)(wt_ + (int64_t)m0 * Ksp)), taps(taps_), tapBytes((unsigned)g.C * (unsigned)Ksp * 4u), walk(nkc_, ch0) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 2 * MI; ++i) {
-      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-      const int c = min(16 * MI * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // channels past the end repeat the last one (never stored)
+    for (int i = 0; i < Shape<MI>::NLOAD; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(Shape<MI>::WROWS * wv + 8 * i + (l >> 3)));
+      const int c = min(Shape<MI>::WROWS * wv + 8 * i + (l >> 3), g.C - 1 - m0);   // channels past the end repeat the last one (never stored)
       off[i] = ((unsigned)c * (unsigned)Ksp + kq4) * 4u;
     }
     tap = taps[walk.ti];
@@ -352,15 +351,14 @@ __device__ __forceinline__ void bwd_data_store_block(const Geo& g, float* __rest
                                                      const int* __restrict__ perm, int m0, int ct, int i, int j,
                                                      const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int gcb = ct * 4 + wn * 2 + j;
+  const int gcb = ct * 4 + Shape<MI>::colblk0(wave) + j;
   if (gcb >= g.HW * g.NB) return;
   const int sp = gcb / g.NB, nb = gcb - sp * g.NB;
   const int px = perm[sp];
   const int n = nb * 32 + (lane & 31);
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int c = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
+    const int c = m0 + Shape<MI>::row0(wave) + i * 32 + acc_row(v, lane);
     if (c < g.C) dxt[((int64_t)c * g.HW + px) * g.Np + n] = acc[v];
   }
 }
@@ -429,12 +427,12 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
     __syncthreads();
     const int nchunks = s_ntaps * nkc;
     const int cb = min(c0, nchunks), ce = min(c1, nchunks);
-    const int m0 = mOrigin + mb * (64 * MI);
-    f32x16 acc[MI][2];
+    const int m0 = mOrigin + mb * Shape<MI>::ROWS;
+    f32x16 acc[MI][Shape<MI>::NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     BwdDataLoadA<MI> la(g, wt, Ksp, m0, s_taps, nkc, cb);
@@ -442,7 +440,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
     gemm_mainloop(la, lb, cb, ce, smem, acc);
     if (direct) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
         for (int i = 0; i < MI; ++i) bwd_data_store_block<MI>(g, dxt, perm, m0, ct, i, j, acc[i][j]);
     } else {
@@ -484,7 +482,7 @@ __global__ __launch_bounds__(NT) void bwd_data_gemm_kernel(Geo g, const float* _
   }
 }
 
-// Adds up the scratch slots of every tile that was cut by a run boundary.  grid = (CT*MB, 2*MI);
+// Adds up the scratch slots of every tile that was cut by a run boundary.  grid = (CT*MB, MI*NJ);
 // nkc and nRuns as in the kernel that wrote the slots.
 template <int MI>
 __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __restrict__ perm,
@@ -497,17 +495,17 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
   const int a = pre[ct], b = pre[ct + 1];   // the tile's stretch of the line
   const int r0 = a / units, r1 = (b - 1) / units;
   if (r0 == r1) return;   // inside one run: stored directly
-  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  const int bi = blockIdx.y / Shape<MI>::NJ, bj = blockIdx.y % Shape<MI>::NJ;
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   for (int r = r0; r <= r1; ++r) {
     const int slot = r * units >= a ? 0 : 1;   // a run that starts inside the tile used its first slot
-    const float* p = partial + (int64_t)((r * MB + mb) * 2 + slot) * TAIL_SLOT_FLOATS + (bi * 2 + bj) * 16 * NT + threadIdx.x;
+    const float* p = partial + (int64_t)((r * MB + mb) * 2 + slot) * TAIL_SLOT_FLOATS + blockIdx.y * 16 * NT + threadIdx.x;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] += p[v * NT];
   }
-  bwd_data_store_block<MI>(g, dxt, perm, mOrigin + mb * (64 * MI), ct, bi, bj, acc);
+  bwd_data_store_block<MI>(g, dxt, perm, mOrigin + mb * Shape<MI>::ROWS, ct, bi, bj, acc);
 }
 
 // ---------------------------------------------------------- weight gradient ----
@@ -518,18 +516,18 @@ __global__ __launch_bounds__(NT) void bwd_data_fixup_kernel(Geo g, const int* __
 template <int MI_>
 struct BwdWeightLoadA {
   static constexpr bool COL = true;
-  static constexpr int MI = MI_;   // tile rows / 64
+  static constexpr int MI = MI_;   // tile shape (Shape<MI>)
   const char* tile;   // uniform: row m0 of dy_t
   const char* ub;     // uniform: tile + the chunk being issued
-  unsigned off[2 * MI];
+  unsigned off[Shape<MI>::NLOAD];
   int first, stride;  // step i of the walk is chunk first + i*stride
   __device__ BwdWeightLoadA(const Geo& g, const float* dyt, int m0, int first_, int stride_)
       : tile((const char*)(dyt + (int64_t)m0 * g.PQ * g.Np)), first(first_), stride(stride_) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 2 * MI; ++i) {
-      const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-      const int m = min(16 * MI * wv + 8 * i + (l >> 3), g.Ks - 1 - m0);  // rows past the slice repeat the last one
+    for (int i = 0; i < Shape<MI>::NLOAD; ++i) {
+      const int kq4 = 4 * ((l & 7) ^ col_key(Shape<MI>::WROWS * wv + 8 * i + (l >> 3)));
+      const int m = min(Shape<MI>::WROWS * wv + 8 * i + (l >> 3), g.Ks - 1 - m0);  // rows past the slice repeat the last one
       off[i] = ((unsigned)m * (unsigned)(g.PQ * g.Np) + kq4) * 4u;
     }
   }
@@ -610,21 +608,20 @@ template <int MI>
 __device__ __forceinline__ void bwd_weight_store_block(const Geo& g, float* __restrict__ o, int m0, int rowBase,
                                                        int ct, int i, int j, const f32x16& acc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
+  const int col = ct * BN + Shape<MI>::col0(wave) + j * 32 + (lane & 31);
   if (col >= g.CRS) return;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int m = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
+    const int m = m0 + Shape<MI>::row0(wave) + i * 32 + acc_row(v, lane);
     if (m < g.Ks) o[(int64_t)(m - rowBase) * g.CRS + col] = acc[v];
   }
 }
 
 template <int MI>
 __device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __restrict__ o, int m0, int rowBase, int ct,
-                                                      const f32x16 (&acc)[MI][2]) {
+                                                      const f32x16 (&acc)[MI][Shape<MI>::NJ]) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
     for (int i = 0; i < MI; ++i) bwd_weight_store_block<MI>(g, o, m0, rowBase, ct, i, j, acc[i][j]);
 }
@@ -655,16 +652,16 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
   auto body = [&](int L, int cb, int ce, bool direct, int slot) {
     int mb, ct;
     tile_from_line(L, MB, CT, mb, ct);
-    const int m0 = mOrigin + mb * (64 * MI);
+    const int m0 = mOrigin + mb * Shape<MI>::ROWS;
     if (direct) {   // a whole tile: every chunk of this split
       cb = 0;
       ce = (nch - z + splits - 1) / splits;
     }
-    f32x16 acc[MI][2];
+    f32x16 acc[MI][Shape<MI>::NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     BwdWeightLoadA<MI> la(g, dyt, m0, z, splits);
@@ -680,17 +677,17 @@ __global__ __launch_bounds__(NT) void bwd_weight_gemm_kernel(Geo g, const float*
   for_each_segment(tp, nch, body);
 }
 
-// grid = (nTail, 2*MI)
+// grid = (nTail, MI*NJ)
 template <int MI>
 __global__ __launch_bounds__(NT) void bwd_weight_tail_fixup_kernel(Geo g, const float* __restrict__ partial,
                                                                    float* __restrict__ out, int mOrigin, int rowBase,
                                                                    int MB, int CT, int nch, TailPlan tp) {
-  const int bi = blockIdx.y >> 1, bj = blockIdx.y & 1;
+  const int bi = blockIdx.y / Shape<MI>::NJ, bj = blockIdx.y % Shape<MI>::NJ;
   f32x16 acc;
-  gather_partials(partial, tp, nch, blockIdx.x, bi, bj, acc);
+  gather_partials(partial, tp, nch, blockIdx.x, blockIdx.y, acc);
   int mb, ct;
   tile_from_line(tp.nFull + blockIdx.x, MB, CT, mb, ct);
-  bwd_weight_store_block<MI>(g, out, mOrigin + mb * (64 * MI), rowBase, ct, bi, bj, acc);
+  bwd_weight_store_block<MI>(g, out, mOrigin + mb * Shape<MI>::ROWS, rowBase, ct, bi, bj, acc);
 }
 
 }  // namespace cs

@@ -47,6 +47,10 @@ ADHOC = [
     # bf16: more 256 x 256 tiles than compute units (whole tiles plus a shared tail), a ragged second row tile of
     # 31 kernels, 162 channels (ragged second row tile of the input gradient), padding
     synth.random_layer(25, N=40, C=162, H=24, W=24, K=300, R=3, S=3, pad=1, k0=3, k1=290),
+    # a full row tile plus a 96-row tile with ragged rows in every pass: 210 = 128 + 82 channels, 215 = 128 + 87 kernels
+    synth.random_layer(26, N=33, C=210, H=9, W=9, K=215, R=3, S=3, pad=1),
+    # only a 96-row tile, stride 2, batch of one block: 90 channels, 70 kernels
+    synth.random_layer(27, N=20, C=90, H=11, W=10, K=70, R=3, S=2, stride=2),
 ]
 
 
