@@ -677,7 +677,7 @@ int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void*
   const int entries = (p.nch + 4) * cs::BK;
   hipLaunchKernelGGL(cs::pm_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, pm.pg.Hp, pm.pg.Wp, entries,
                      tab);
-  const RowSplit rs = split_rows(g.Ks);
+  const RowSplit rs = split_rows(g.Ks, true);
   probe.begin(st);
   auto launch = [&](auto kern, auto* yout, int m0, int tiles) -> int {
     int rc2;
@@ -689,10 +689,12 @@ int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void*
   rc = CONV_OK;
   if (dtype == CONV_F32) {
     if (rs.full > 0) rc = launch(cs::fwd_pm_gemm_kernel<2, float>, (float*)y, 0, rs.full);
-    if (rc == CONV_OK && rs.half) rc = launch(cs::fwd_pm_gemm_kernel<1, float>, (float*)y, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::fwd_pm_gemm_kernel<1, float>, (float*)y, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::fwd_pm_gemm_kernel<3, float>, (float*)y, rs.full * cs::BM, 1);
   } else {
     if (rs.full > 0) rc = launch(cs::fwd_pm_gemm_kernel<2, uint16_t>, (uint16_t*)y, 0, rs.full);
-    if (rc == CONV_OK && rs.half) rc = launch(cs::fwd_pm_gemm_kernel<1, uint16_t>, (uint16_t*)y, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::fwd_pm_gemm_kernel<1, uint16_t>, (uint16_t*)y, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::fwd_pm_gemm_kernel<3, uint16_t>, (uint16_t*)y, rs.full * cs::BM, 1);
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;
@@ -725,7 +727,7 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
                       nullptr, st);
   float* T = (float*)(base + p.off_T);
   const bool vec4 = g.PQ % 4 == 0;
-  const RowSplit rs = split_rows(g.CRS);
+  const RowSplit rs = split_rows(g.CRS, true);
   probe.begin(st);
   auto launch = [&](auto kern, int m0, int tiles) -> int {
     int rc2;
@@ -737,10 +739,12 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
   rc = CONV_OK;
   if (vec4) {
     if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, true>, 0, rs.full);
-    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_data_pm_gemm_kernel<1, true>, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, true>, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, true>, rs.full * cs::BM, 1);
   } else {
     if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, false>, 0, rs.full);
-    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_data_pm_gemm_kernel<1, false>, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, false>, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, false>, rs.full * cs::BM, 1);
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;
@@ -775,7 +779,7 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
   auto launch = [&](auto kern, int mi, int m0, int tiles) -> int {
     int rc2;
     if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
-    const int rows = std::min(g.Ks - m0, tiles * 64 * mi);
+    const int rows = std::min(g.Ks - m0, tiles * (mi == 3 ? 96 : 64 * mi));
     const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true, kPmSplitRounds);
     const int64_t stride = (int64_t)rows * g.CRS;
     float* out = splits > 1 ? scratch : dwslice;
@@ -788,15 +792,17 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
     return CONV_OK;
   };
   const bool vec4 = g.PQ % 4 == 0;
-  const RowSplit rs = split_rows(g.Ks);
+  const RowSplit rs = split_rows(g.Ks, true);
   rc = CONV_OK;
   probe.begin(st);
   if (vec4) {
     if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, true>, 2, 0, rs.full);
-    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, true>, 1, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, true>, 1, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, true>, 3, rs.full * cs::BM, 1);
   } else {
     if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, false>, 2, 0, rs.full);
-    if (rc == CONV_OK && rs.half) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, false>, 1, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, false>, 1, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, false>, 3, rs.full * cs::BM, 1);
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;

@@ -94,12 +94,11 @@ __global__ void pm_pixel_table_kernel(Geo g, int Wp, int NC, int* __restrict__ t
 // (image, pixel) index; element (m, n, pix) goes to out[n*imgPitch + m*PQ + pix].
 template <int MI, typename TOUT>
 __device__ __forceinline__ void pm_store_tile(TOUT* __restrict__ out, int rows, int64_t imgPitch, int PQ, int NPQ,
-                                              int m0, int ct, const f32x16 (&acc)[MI][2]) {
+                                              int m0, int ct, const f32x16 (&acc)[MI][Shape<MI>::NJ]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
+  for (int j = 0; j < Shape<MI>::NJ; ++j) {
+    const int col = ct * BN + Shape<MI>::col0(wave) + j * 32 + (lane & 31);
     if (col >= NPQ) continue;
     const int n = col / PQ, pix = col - n * PQ;
     TOUT* base = out + (int64_t)n * imgPitch + pix;
@@ -107,7 +106,7 @@ __device__ __forceinline__ void pm_store_tile(TOUT* __restrict__ out, int rows, 
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * (32 * MI) + i * 32 + acc_row(v, lane);
+        const int m = m0 + Shape<MI>::row0(wave) + i * 32 + acc_row(v, lane);
         if (m < rows) store_from_f32<TOUT>(base + (int64_t)m * PQ, acc[i][j][v]);
       }
   }
@@ -209,13 +208,13 @@ struct PmTiles {
     return true;
   }
   __device__ __forceinline__ bool same_b() const { return sameb; }
-  __device__ __forceinline__ FwdLoadA<MI> make_a() const { return FwdLoadA<MI>(a, lda, mOrigin + ld_mb * (64 * MI), rows); }
+  __device__ __forceinline__ FwdLoadA<MI> make_a() const { return FwdLoadA<MI>(a, lda, mOrigin + ld_mb * Shape<MI>::ROWS, rows); }
   __device__ __forceinline__ LB make_b() const { return makeB(ld_ct); }
-  __device__ __forceinline__ void store(const f32x16 (&acc)[MI][2]) {
+  __device__ __forceinline__ void store(const f32x16 (&acc)[MI][Shape<MI>::NJ]) {
+    constexpr int NJ = Shape<MI>::NJ;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = mOrigin + st_mb * (64 * MI);
+    const int m0 = mOrigin + st_mb * Shape<MI>::ROWS;
     const int ct = st_ct;
     if (++st_mb == MB) {
       st_mb = 0;
@@ -224,8 +223,8 @@ struct PmTiles {
     if (cache_ct != ct) {   // the lane's two pixels: their offset in `out`, half-wave row included
       cache_ct = ct;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = ct * BN + wn * 64 + j * 32 + (lane & 31);
+      for (int j = 0; j < NJ; ++j) {
+        const int col = ct * BN + Shape<MI>::col0(wave) + j * 32 + (lane & 31);
         sok[j] = col < pg.NPQ;
         const int c = min(col, pg.NPQ - 1);
         const int n = c / g.PQ, pix = c - n * g.PQ;
@@ -233,10 +232,10 @@ struct PmTiles {
       }
     }
     const int64_t rowBytes = (int64_t)g.PQ * sizeof(TOUT);
-    const char* sb = (const char*)out + (int64_t)(m0 + wm * (32 * MI)) * rowBytes;
-    if (m0 + 64 * MI <= rows && (ct + 1) * BN <= pg.NPQ) {   // whole tile inside: no per-element tests
+    const char* sb = (const char*)out + (int64_t)(m0 + Shape<MI>::row0(wave)) * rowBytes;
+    if (m0 + Shape<MI>::ROWS <= rows && (ct + 1) * BN <= pg.NPQ) {   // whole tile inside: no per-element tests
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -244,9 +243,9 @@ struct PmTiles {
             store_uv<TOUT>(sb + (i * 32 + 8 * (v >> 2) + (v & 3)) * rowBytes, soff[j], acc[i][j][v]);
       return;
     }
-    const int mlane = m0 + wm * (32 * MI) + 4 * (lane >> 5);
+    const int mlane = m0 + Shape<MI>::row0(wave) + 4 * (lane >> 5);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       if (!sok[j]) continue;
 #pragma unroll
       for (int i = 0; i < MI; ++i)
@@ -418,26 +417,26 @@ struct PmDyLoadA {
   const char* ub;
   int64_t imgBytes;
   int PQ, N;
-  unsigned off[VEC4 ? 2 * MI : 8 * MI];
+  unsigned off[VEC4 ? Shape<MI>::NLOAD : 4 * Shape<MI>::NLOAD];
   PmChunkWalk walk;
   __device__ PmDyLoadA(const Geo& g, const PmGeo& pg, const float* dy_k0, int64_t imgPitch, int m0, int first, int stride)
       : dy((const char*)dy_k0), imgBytes(imgPitch * 4), PQ(g.PQ), N(g.N), walk(first, stride, pg.NC) {
     const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if (VEC4) {
 #pragma unroll
-      for (int i = 0; i < 2 * MI; ++i) {
-        const int kq4 = 4 * ((l & 7) ^ col_key(8 * i + (l >> 3)));
-        const int m = min(m0 + 16 * MI * wv + 8 * i + (l >> 3), g.Ks - 1);
+      for (int i = 0; i < Shape<MI>::NLOAD; ++i) {
+        const int kq4 = 4 * ((l & 7) ^ col_key(Shape<MI>::WROWS * wv + 8 * i + (l >> 3)));
+        const int m = min(m0 + Shape<MI>::WROWS * wv + 8 * i + (l >> 3), g.Ks - 1);
         off[i] = ((unsigned)m * (unsigned)g.PQ + kq4) * 4u;
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 2 * MI; ++i)
+      for (int i = 0; i < Shape<MI>::NLOAD; ++i)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          const int row = 8 * i + 2 * jj + (l >> 5);                       // within the wavefront's rows
+          const int row = Shape<MI>::WROWS * wv + 8 * i + 2 * jj + (l >> 5);   // row of the tile
           const int kk = ((((l & 31) >> 2) ^ col_key(row)) << 2) + (l & 3);   // element stored at this lane's LDS position
-          const int m = min(m0 + 16 * MI * wv + row, g.Ks - 1);
+          const int m = min(m0 + row, g.Ks - 1);
           off[i * 4 + jj] = ((unsigned)m * (unsigned)g.PQ + kk) * 4u;
         }
     }
@@ -533,13 +532,13 @@ __global__ __launch_bounds__(NT) void bwd_weight_pm_gemm_kernel(Geo g, PmGeo pg,
   const int z = item / tiles, L = item - z * tiles;
   int mb, ct;
   tile_from_line(L, MB, CT, mb, ct);
-  const int m0 = mOrigin + mb * (64 * MI);
+  const int m0 = mOrigin + mb * Shape<MI>::ROWS;
   const int count = (nch - z + splits - 1) / splits;
-  f32x16 acc[MI][2];
+  f32x16 acc[MI][Shape<MI>::NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   PmDyLoadA<MI, VEC4> la(g, pg, dy_k0, imgPitch, m0, z, splits);
