@@ -105,9 +105,12 @@ inline size_t tail_bytes(int nch) {
 // Row tiles of a matrix-core pass with M rows: `full` tiles of 128 rows and, when the rest is at most 64 rows, one
 // half tile (64 rows) for it, computed by a second launch; a rest above 64 rows takes a full tile -- or, where the
 // pass has the 96-row kernels (three_quarter), a rest of 65..96 rows takes a 96-row tile.
+// When 96-row tiles alone cover M in no more rows than that mix, they are used for the whole pass: one launch
+// instead of two (a 188-kernel share: two 96-row tiles instead of 128 + 64).
 struct RowSplit {
   int full, half;   // half = 1 if a half tile follows the full ones
-  int last;         // shape (cs::Shape) of the short last tile: 0 none, 1: 64 rows, 3: 96 rows
+  int last;         // shape (cs::Shape) of the launch after the full tiles: 0 none, 1: 64 rows, 3: 96 rows
+  int nlast;        // its row tiles
 };
 RowSplit split_rows(int M, bool three_quarter = false) {
   RowSplit r;
@@ -115,9 +118,15 @@ RowSplit split_rows(int M, bool three_quarter = false) {
   const int rest = M - r.full * cs::BM;
   r.half = rest > 0 && rest <= cs::BM / 2;
   r.last = r.half ? 1 : 0;
+  r.nlast = r.half ? 1 : 0;
   if (rest > cs::BM / 2) {
-    if (three_quarter && rest <= 96) r.last = 3;
+    if (three_quarter && rest <= 96) { r.last = 3; r.nlast = 1; }
     else ++r.full;
+  }
+  if (three_quarter && r.full > 0 && r.last != 0) {
+    const int rows = r.full * cs::BM + (r.last == 1 ? 64 : 96), n96 = (M + 95) / 96;
+    // (no more row tiles than 128-row tiles would be: the split partials of the weight gradient are sized by those)
+    if (n96 * 96 <= rows && n96 <= (M + cs::BM - 1) / cs::BM) { r.full = 0; r.half = 0; r.last = 3; r.nlast = n96; }
   }
   return r;
 }
@@ -690,11 +699,11 @@ int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void*
   if (dtype == CONV_F32) {
     if (rs.full > 0) rc = launch(cs::fwd_pm_gemm_kernel<2, float>, (float*)y, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::fwd_pm_gemm_kernel<1, float>, (float*)y, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::fwd_pm_gemm_kernel<3, float>, (float*)y, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::fwd_pm_gemm_kernel<3, float>, (float*)y, rs.full * cs::BM, rs.nlast);
   } else {
     if (rs.full > 0) rc = launch(cs::fwd_pm_gemm_kernel<2, uint16_t>, (uint16_t*)y, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::fwd_pm_gemm_kernel<1, uint16_t>, (uint16_t*)y, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::fwd_pm_gemm_kernel<3, uint16_t>, (uint16_t*)y, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::fwd_pm_gemm_kernel<3, uint16_t>, (uint16_t*)y, rs.full * cs::BM, rs.nlast);
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;
@@ -740,11 +749,11 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
   if (vec4) {
     if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, true>, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, true>, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, true>, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, true>, rs.full * cs::BM, rs.nlast);
   } else {
     if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, false>, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, false>, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, false>, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, false>, rs.full * cs::BM, rs.nlast);
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;
@@ -798,11 +807,11 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
   if (vec4) {
     if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, true>, 2, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, true>, 1, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, true>, 3, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, true>, 3, rs.full * cs::BM, rs.nlast);
   } else {
     if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, false>, 2, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, false>, 1, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, false>, 3, rs.full * cs::BM, 1);
+    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, false>, 3, rs.full * cs::BM, rs.nlast);
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;
@@ -871,8 +880,8 @@ int launch_fwd_gemm(const Geo& g, bool pad, const float* wmat, int ldw, const fl
                 : launch(cs::fwd_gemm_kernel<false, 1>, cs::fwd_tail_fixup_kernel<1>, 1, m1, 1)) != CONV_OK)
     return rc;
   if (rs.last == 3 &&
-      (rc = pad ? launch(cs::fwd_gemm_kernel<true, 3>, cs::fwd_tail_fixup_kernel<3>, 3, m1, 1)
-                : launch(cs::fwd_gemm_kernel<false, 3>, cs::fwd_tail_fixup_kernel<3>, 3, m1, 1)) != CONV_OK)
+      (rc = pad ? launch(cs::fwd_gemm_kernel<true, 3>, cs::fwd_tail_fixup_kernel<3>, 3, m1, rs.nlast)
+                : launch(cs::fwd_gemm_kernel<false, 3>, cs::fwd_tail_fixup_kernel<3>, 3, m1, rs.nlast)) != CONV_OK)
     return rc;
   return CONV_OK;
 }
@@ -1186,7 +1195,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   if (rc == CONV_OK && rs.last == 1)
     rc = launch(cs::bwd_data_gemm_kernel<1>, cs::bwd_data_fixup_kernel<1>, 1, rs.full * cs::BM, 1);
   if (rc == CONV_OK && rs.last == 3)
-    rc = launch(cs::bwd_data_gemm_kernel<3>, cs::bwd_data_fixup_kernel<3>, 3, rs.full * cs::BM, 1);
+    rc = launch(cs::bwd_data_gemm_kernel<3>, cs::bwd_data_fixup_kernel<3>, 3, rs.full * cs::BM, rs.nlast);
   if (rc != CONV_OK) return rc;
   probe.end(st);
   // dx_t[C*H*W][Np] -> dx[N][C*H*W]
@@ -1305,8 +1314,8 @@ int bwd_weight_impl(const conv_desc_t* desc, const void* x, const void* dy, void
     rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 1>, cs::bwd_weight_tail_fixup_kernel<1>, 1, rs.full * cs::BM, 1)
              : launch(cs::bwd_weight_gemm_kernel<false, 1>, cs::bwd_weight_tail_fixup_kernel<1>, 1, rs.full * cs::BM, 1);
   if (rc == CONV_OK && rs.last == 3)
-    rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 3>, cs::bwd_weight_tail_fixup_kernel<3>, 3, rs.full * cs::BM, 1)
-             : launch(cs::bwd_weight_gemm_kernel<false, 3>, cs::bwd_weight_tail_fixup_kernel<3>, 3, rs.full * cs::BM, 1);
+    rc = pad ? launch(cs::bwd_weight_gemm_kernel<true, 3>, cs::bwd_weight_tail_fixup_kernel<3>, 3, rs.full * cs::BM, rs.nlast)
+             : launch(cs::bwd_weight_gemm_kernel<false, 3>, cs::bwd_weight_tail_fixup_kernel<3>, 3, rs.full * cs::BM, rs.nlast);
   probe.end(st);
   if (rc != CONV_OK) return rc;
   return check_launch();

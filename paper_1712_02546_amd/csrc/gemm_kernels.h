@@ -1,10 +1,11 @@
-// The three matrix-core passes.  Each is an implicit GEMM on 128x128 tiles (MI = 2; a
-// last row tile of at most 64 rows is computed on 64x128 tiles, MI = 1, by a launch of
-// its own) whose 32-lane column blocks are "32 images at one pixel" (fwd, bwd_data) or
-// 32 filter taps (bwd_weight); the operand loaders below are the only pass-specific code.
+// The three matrix-core passes.  Each is an implicit GEMM on 128x128 tiles (MI = 2; a last
+// row tile of at most 64 rows is computed on 64x128 tiles, MI = 1, one of 65 to 96 rows on
+// 96x128 tiles, MI = 3, by a launch of its own; see Shape<MI> in conv_common.h) whose 32-lane
+// column blocks are "32 images at one pixel" (fwd, bwd_data) or 32 filter taps (bwd_weight);
+// the operand loaders below are the only pass-specific code.
 // A loader computes, per lane, the global address of the 16 bytes that lane moves
 // into LDS for each of its wavefront's DMA loads per chunk (four for a 128-row or
-// 128-column operand, two for the 64 rows of a half tile; see the staging notes in
+// 128-column operand, three for 96 rows, two for 64; see the staging notes in
 // conv_common.h for the row and col tile images).
 #pragma once
 #include "conv_common.h"
