@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "conv_common.h"
@@ -757,13 +758,37 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
   }
   probe.end(st);
   if (rc != CONV_OK) return rc;
-  const int blocks = grid_for((int64_t)g.N * g.C * g.HW, 1 << 20);
+  // one thread per group of `stride` columns for strides up to 4, else per column
+  auto col2im = [&](auto* out, auto acc_tag) {
+    using TO = std::remove_pointer_t<decltype(out)>;
+    constexpr bool A = decltype(acc_tag)::value;
+    const int nv = g.sw <= 4 ? g.sw : 1;
+    const int blocks = (grid_for((int64_t)g.N * g.C * g.H * ((g.W + nv - 1) / nv), 1 << 20) + 7) / 8 * 8;
+    // strides 2..4 with at most three taps per axis on any element: the variant with all loads in flight
+    const bool few = g.sw >= 2 && g.sw <= 4 && (g.R + g.sh - 1) / g.sh <= 3 && (g.S + g.sw - 1) / g.sw <= 3;
+    switch (g.sw <= 4 ? g.sw : 0) {
+      case 1: hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 1, false>), dim3(blocks), dim3(256), 0, st, g, T, out); break;
+      case 2:
+        if (few) hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 2, true>), dim3(blocks), dim3(256), 0, st, g, T, out);
+        else hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 2, false>), dim3(blocks), dim3(256), 0, st, g, T, out);
+        break;
+      case 3:
+        if (few) hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 3, true>), dim3(blocks), dim3(256), 0, st, g, T, out);
+        else hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 3, false>), dim3(blocks), dim3(256), 0, st, g, T, out);
+        break;
+      case 4:
+        if (few) hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 4, true>), dim3(blocks), dim3(256), 0, st, g, T, out);
+        else hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 4, false>), dim3(blocks), dim3(256), 0, st, g, T, out);
+        break;
+      default: hipLaunchKernelGGL((cs::col2im_pm_kernel<TO, A, 0, false>), dim3(blocks), dim3(256), 0, st, g, T, out); break;
+    }
+  };
   if (dtype == CONV_F32) {
-    if (acc) hipLaunchKernelGGL((cs::col2im_pm_kernel<float, true>), dim3(blocks), dim3(256), 0, st, g, T, (float*)dx);
-    else hipLaunchKernelGGL((cs::col2im_pm_kernel<float, false>), dim3(blocks), dim3(256), 0, st, g, T, (float*)dx);
+    if (acc) col2im((float*)dx, std::true_type{});
+    else col2im((float*)dx, std::false_type{});
   } else {
-    if (acc) hipLaunchKernelGGL((cs::col2im_pm_kernel<uint16_t, true>), dim3(blocks), dim3(256), 0, st, g, T, (uint16_t*)dx);
-    else hipLaunchKernelGGL((cs::col2im_pm_kernel<uint16_t, false>), dim3(blocks), dim3(256), 0, st, g, T, (uint16_t*)dx);
+    if (acc) col2im((uint16_t*)dx, std::true_type{});
+    else col2im((uint16_t*)dx, std::false_type{});
   }
   return check_launch();
 }

@@ -357,36 +357,90 @@ __global__ __launch_bounds__(NT, 2) void bwd_data_pm_gemm_kernel(Geo g, PmGeo pg
 }
 
 // dx[n][c][h][v] (+)= sum over the taps (r,s) whose window position (p,q) lands on (h,v) of
-// T[n][(c,r,s)][p*Q+q], in increasing (r,s) order.  One thread per input element, v fastest, so
-// a wavefront reads runs of q along each T row it touches.  Misses read a clamped element and
-// add a selected zero (branch-free: several taps' loads in flight).
-template <typename TOUT, bool ACC>
+// T[n][(c,r,s)][p*Q+q], in increasing (r,s) order.  One thread per group of SW = stride consecutive
+// input columns (SW = 0: any stride, one column per thread): column j of every group takes the
+// same taps s at consecutive q, so for each (r, s) a wavefront reads 64 consecutive elements of
+// one T row (with one column per thread and stride 4 it read 16-element pieces of four rows and
+// fetched 2.15 times the bytes of T; now 1.5 times).  Misses read a clamped element and add a
+// selected zero (branch-free: several taps' loads in flight).
+template <typename TOUT, bool ACC, int SW, bool UNROLLED>
 __global__ __launch_bounds__(256) void col2im_pm_kernel(Geo g, const float* __restrict__ T, TOUT* __restrict__ dx) {
-  const int64_t total = (int64_t)g.N * g.C * g.HW;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-    const int v = (int)(i % g.W);
-    const int64_t t = i / g.W;
+  constexpr int NV = SW > 0 ? SW : 1;
+  const int sw = SW > 0 ? SW : g.sw;
+  const int groups = (g.W + NV - 1) / NV;   // column groups per input row
+  const int64_t total = (int64_t)g.N * g.C * g.H * groups;
+  // the grid is a multiple of 8: workgroups that follow each other on one XCD take neighbouring stretches, so the
+  // cache lines that two stretches share (T rows are not line-aligned) are fetched into one L2 only
+  const int64_t lb = (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  for (int64_t i = lb * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int vg = (int)(i % groups);
+    const int64_t t = i / groups;
     const int h = (int)(t % g.H);
     const int64_t nc = t / g.H;               // n*C + c
     const float* Tc = T + nc * g.RS * g.PQ;   // T[n][(c,0,0)][0]
-    float acc = 0.f;
-    for (int r = (h + g.ph) % g.sh; r < g.R; r += g.sh) {
-      const int hr = h + g.ph - r;
-      const int p = hr / g.sh;
-      const bool rok = hr >= 0 && p < g.P;
-      const int pc = rok ? p : 0;
-#pragma unroll 5
-      for (int s = (v + g.pw) % g.sw; s < g.S; s += g.sw) {
-        const int vs = v + g.pw - s;
-        const int q = vs / g.sw;
-        const bool ok = rok && vs >= 0 && q < g.Q;
-        const float tv = Tc[(int64_t)(r * g.S + s) * g.PQ + pc * g.Q + (ok ? q : 0)];
-        acc += ok ? tv : 0.f;
+    float acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = 0.f;
+    if constexpr (UNROLLED) {
+      // At most three taps per axis reach an element (ceil(R/sh), ceil(S/sw) <= 3): all 9*NV loads are issued
+      // before the first is used, taps that do not exist or miss read a clamped element and add a selected zero.
+      float val[3][NV][3];
+#pragma unroll
+      for (int rr = 0; rr < 3; ++rr) {
+        const int r = (h + g.ph) % g.sh + rr * g.sh;
+        const int hr = h + g.ph - r;
+        const int p = hr / g.sh;
+        const bool rok = r < g.R && hr >= 0 && p < g.P;
+        const float* Tr = Tc + (int64_t)min(r, g.R - 1) * g.S * g.PQ + (rok ? p : 0) * g.Q;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          const int v = vg * NV + j;
+#pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            const int sx = (v + g.pw) % sw + k * sw;
+            const int vs = v + g.pw - sx;
+            const int q = vs / sw;
+            const bool ok = rok && sx < g.S && vs >= 0 && q < g.Q;
+            const float tv = Tr[(int64_t)min(sx, g.S - 1) * g.PQ + (ok ? q : 0)];
+            val[rr][j][k] = ok ? tv : 0.f;
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+#pragma unroll
+        for (int rr = 0; rr < 3; ++rr)
+#pragma unroll
+          for (int k = 0; k < 3; ++k) acc[j] += val[rr][j][k];
+    } else {
+      for (int r = (h + g.ph) % g.sh; r < g.R; r += g.sh) {
+        const int hr = h + g.ph - r;
+        const int p = hr / g.sh;
+        const bool rok = hr >= 0 && p < g.P;
+        const float* Tr = Tc + (int64_t)r * g.S * g.PQ + (rok ? p : 0) * g.Q;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+          const int v = vg * NV + j;   // columns past W: computed on clamped elements, never stored
+#pragma unroll 3
+          for (int s = (v + g.pw) % sw; s < g.S; s += sw) {
+            const int vs = v + g.pw - s;
+            const int q = vs / sw;
+            const bool ok = rok && vs >= 0 && q < g.Q;
+            const float tv = Tr[(int64_t)s * g.PQ + (ok ? q : 0)];
+            acc[j] += ok ? tv : 0.f;
+          }
+        }
       }
     }
-    TOUT* o = dx + i;
-    if (ACC) acc += load_as_f32<TOUT>(o);
-    store_from_f32<TOUT>(o, acc);
+    TOUT* o = dx + ((nc * g.H + h) * (int64_t)g.W + vg * NV);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      if (vg * NV + j < g.W) {
+        float a = acc[j];
+        if (ACC) a += load_as_f32<TOUT>(o + j);
+        store_from_f32<TOUT>(o + j, a);
+      }
+    }
   }
 }
 
