@@ -73,8 +73,15 @@ def test_workspace_never_grows_when_the_slice_shrinks(layer, dtype):
             assert shifted == need, (p, k1)
 
 
-def test_workspace_is_monotone_over_every_slice_size():
-    layer = dict(N=64, C=128, H=56, W=56, K=300, R=3, S=3, pad_h=1, pad_w=1)
+@pytest.mark.parametrize("layer", [
+    dict(N=64, C=128, H=56, W=56, K=300, R=3, S=3, pad_h=1, pad_w=1),
+    # tile shapes and tile-sharing schemes change with the slice: 96-row and 256-row tiles, wide input-gradient tiles
+    # only where their runs are long
+    dict(N=128, C=500, H=14, W=14, K=1500, R=5, S=5),
+    dict(N=32, C=200, H=20, W=20, K=700, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=64, C=3, H=64, W=64, K=200, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
+], ids=lambda d: f"C{d['C']}K{d['K']}")
+def test_workspace_is_monotone_over_every_slice_size(layer):
     for dtype in (cs.CONV_F32, cs.CONV_BF16):
         for p in (cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT):
             sizes = [cs.conv_workspace_bytes(cs.ConvDesc(**layer, dtype=dtype, k0=0, k1=k1), p)
