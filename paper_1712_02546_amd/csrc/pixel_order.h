@@ -219,26 +219,49 @@ CS_PO_FN void phase_lengths(const Geo& g, const Tables<P>& t, int CT, int nkc, i
       const int px = t.perm[ct / (g.NB / bpt)];
       taps = ax.nrow[px / g.W] * ax.ncol[px % g.W];
     } else {
-      int hp[MAX_BPT], vp[MAX_BPT], np = 0;   // the tile's distinct pixels
+      // The tile's distinct pixels, each with its row and column taps as arithmetic progressions (first tap,
+      // count; the step is the stride).  The taps are walked once, every progression with a running "next tap":
+      // no division per tap and pixel.
+      int fr[MAX_BPT], na[MAX_BPT], fs[MAX_BPT], nb[MAX_BPT], np = 0;
       for (int j = 0; j < bpt; ++j) {
         const int gcb = ct * bpt + j;
         if (gcb >= g.HW * g.NB) break;
         const int sp = gcb / g.NB;
         if (j > 0 && sp == (gcb - 1) / g.NB) continue;
         const int px = t.perm[sp];
-        hp[np] = px / g.W + g.ph;
-        vp[np] = px % g.W + g.pw;
+        const int h = px / g.W, v = px - h * g.W;
+        const int a = ax.nrow[h], b = ax.ncol[v];
+        const int first_r = ax.rowKey[h] - a * g.R, first_s = ax.colKey[v] - b * g.S;
+        for (int k = 0; k < MAX_BPT; ++k)
+          if (k == np) { na[k] = a; fr[k] = first_r; nb[k] = b; fs[k] = first_s; }
         ++np;
       }
-      for (int r = 0; r < g.R; ++r)
-        for (int s = 0; s < g.S; ++s) {
-          bool any = false;
-          for (int j = 0; j < np; ++j) {
-            const int hr = hp[j] - r, vs = vp[j] - s;
-            any |= hr >= 0 && vs >= 0 && hr % g.sh == 0 && vs % g.sw == 0 && hr / g.sh < g.P && vs / g.sw < g.Q;
+      // (loops over all MAX_BPT entries with a test, so that a GPU build keeps the small arrays in registers)
+      for (int j = np; j < MAX_BPT; ++j) { na[j] = 0; nb[j] = 0; fr[j] = 0; fs[j] = 0; }
+      int nr[MAX_BPT], ir[MAX_BPT];
+      for (int j = 0; j < MAX_BPT; ++j) { nr[j] = fr[j]; ir[j] = 0; }
+      for (int r = 0; r < g.R; ++r) {
+        unsigned rowhit = 0;   // pixels that row tap r reaches
+        for (int j = 0; j < MAX_BPT; ++j)
+          if (ir[j] < na[j] && r == nr[j]) {
+            rowhit |= 1u << j;
+            nr[j] += g.sh;
+            ++ir[j];
           }
+        if (rowhit == 0) continue;
+        int ns[MAX_BPT], is[MAX_BPT];
+        for (int j = 0; j < MAX_BPT; ++j) { ns[j] = fs[j]; is[j] = 0; }
+        for (int sx = 0; sx < g.S; ++sx) {
+          bool any = false;
+          for (int j = 0; j < MAX_BPT; ++j)
+            if (is[j] < nb[j] && sx == ns[j]) {
+              any |= (rowhit >> j) & 1u;
+              ns[j] += g.sw;
+              ++is[j];
+            }
           taps += any;
         }
+      }
     }
     const int len = (taps > 1 ? taps : 1) * nkc;
     t.pre[ct + 1] = len;
