@@ -131,7 +131,7 @@ CS_PO_FN void phase_ranks(const Geo& g, const Tables<P>& t, int tid, int T) {
     ax.rowSame[h] = same;
     add_to(t.rowCnt[a], 1);
   }
-  for (int v = tid; v < g.W; v += T) {
+  for (int v = T - 1 - tid; v < g.W; v += T) {   // from the last thread down: other wavefronts than the rows'
     const int key = ax.colKey[v], b = ax.ncol[v];
     int rank = 0, less = 0, same = 0;
     for (int vv = 0; vv < g.W; ++vv) {
@@ -203,6 +203,15 @@ CS_PO_FN void tile_stretch(int CT, int tid, int T, int& t0, int& t1) {
   t1 = t0 + per < CT ? t0 + per : CT;
 }
 
+// Common elements of two arithmetic progressions with the same step: {f1 + i*step, i < n1} and {f2 + i*step, i < n2}.
+CS_PO_FN int common_taps(int f1, int n1, int f2, int n2, int step) {
+  if (n1 <= 0 || n2 <= 0 || (f1 - f2) % step != 0) return 0;
+  const int lo = f1 > f2 ? f1 : f2;
+  const int l1 = f1 + (n1 - 1) * step, l2 = f2 + (n2 - 1) * step;
+  const int hi = l1 < l2 ? l1 : l2;
+  return hi >= lo ? (hi - lo) / step + 1 : 0;
+}
+
 // Phase 6: length of every tile into pre[ct+1], the thread's sum into part[tid].  A column tile
 // is bpt (4 or 8) consecutive column blocks.
 constexpr int MAX_BPT = 8;
@@ -220,8 +229,8 @@ CS_PO_FN void phase_lengths(const Geo& g, const Tables<P>& t, int CT, int nkc, i
       taps = ax.nrow[px / g.W] * ax.ncol[px % g.W];
     } else {
       // The tile's distinct pixels, each with its row and column taps as arithmetic progressions (first tap,
-      // count; the step is the stride).  The taps are walked once, every progression with a running "next tap":
-      // no division per tap and pixel.
+      // count; the step is the stride).  One or two pixels (the usual case) have a closed form; for more the taps
+      // are walked once, every progression with a running "next tap": no division per tap and pixel.
       int fr[MAX_BPT], na[MAX_BPT], fs[MAX_BPT], nb[MAX_BPT], np = 0;
       for (int j = 0; j < bpt; ++j) {
         const int gcb = ct * bpt + j;
@@ -236,30 +245,37 @@ CS_PO_FN void phase_lengths(const Geo& g, const Tables<P>& t, int CT, int nkc, i
           if (k == np) { na[k] = a; fr[k] = first_r; nb[k] = b; fs[k] = first_s; }
         ++np;
       }
-      // (loops over all MAX_BPT entries with a test, so that a GPU build keeps the small arrays in registers)
-      for (int j = np; j < MAX_BPT; ++j) { na[j] = 0; nb[j] = 0; fr[j] = 0; fs[j] = 0; }
-      int nr[MAX_BPT], ir[MAX_BPT];
-      for (int j = 0; j < MAX_BPT; ++j) { nr[j] = fr[j]; ir[j] = 0; }
-      for (int r = 0; r < g.R; ++r) {
-        unsigned rowhit = 0;   // pixels that row tap r reaches
-        for (int j = 0; j < MAX_BPT; ++j)
-          if (ir[j] < na[j] && r == nr[j]) {
-            rowhit |= 1u << j;
-            nr[j] += g.sh;
-            ++ir[j];
-          }
-        if (rowhit == 0) continue;
-        int ns[MAX_BPT], is[MAX_BPT];
-        for (int j = 0; j < MAX_BPT; ++j) { ns[j] = fs[j]; is[j] = 0; }
-        for (int sx = 0; sx < g.S; ++sx) {
-          bool any = false;
+      if (np == 1) {
+        taps = na[0] * nb[0];
+      } else if (np == 2) {   // |R1 x S1| + |R2 x S2| - |R1 & R2| * |S1 & S2|
+        taps = na[0] * nb[0] + na[1] * nb[1] -
+               common_taps(fr[0], na[0], fr[1], na[1], g.sh) * common_taps(fs[0], nb[0], fs[1], nb[1], g.sw);
+      } else {
+        // (loops over all MAX_BPT entries with a test, so that a GPU build keeps the small arrays in registers)
+        for (int j = np; j < MAX_BPT; ++j) { na[j] = 0; nb[j] = 0; fr[j] = 0; fs[j] = 0; }
+        int nr[MAX_BPT], ir[MAX_BPT];
+        for (int j = 0; j < MAX_BPT; ++j) { nr[j] = fr[j]; ir[j] = 0; }
+        for (int r = 0; r < g.R; ++r) {
+          unsigned rowhit = 0;   // pixels that row tap r reaches
           for (int j = 0; j < MAX_BPT; ++j)
-            if (is[j] < nb[j] && sx == ns[j]) {
-              any |= (rowhit >> j) & 1u;
-              ns[j] += g.sw;
-              ++is[j];
+            if (ir[j] < na[j] && r == nr[j]) {
+              rowhit |= 1u << j;
+              nr[j] += g.sh;
+              ++ir[j];
             }
-          taps += any;
+          if (rowhit == 0) continue;
+          int ns[MAX_BPT], is[MAX_BPT];
+          for (int j = 0; j < MAX_BPT; ++j) { ns[j] = fs[j]; is[j] = 0; }
+          for (int sx = 0; sx < g.S; ++sx) {
+            bool any = false;
+            for (int j = 0; j < MAX_BPT; ++j)
+              if (is[j] < nb[j] && sx == ns[j]) {
+                any |= (rowhit >> j) & 1u;
+                ns[j] += g.sw;
+                ++is[j];
+              }
+            taps += any;
+          }
         }
       }
     }
