@@ -433,10 +433,11 @@ Split16 split16_for(const Geo& g, int ks, int64_t nch) {
   s.wide = wide_rows(ks);
   s.MB = s.wide ? (ks + cs::BM2 - 1) / cs::BM2 : (ks + cs::BM - 1) / cs::BM;
   s.CT = s.wide ? (g.CRS + cs::BN2 - 1) / cs::BN2 : (g.CRS + cs::BN - 1) / cs::BN;
-  // about 1024 narrow workgroups (two rounds of two per compute unit) or 512 wide ones (two rounds of one); wide
-  // tiles that fill the compute units by themselves are not split (their remainder is shared out as a tail)
+  // about 1024 narrow workgroups (two rounds of two per compute unit) or 512 wide ones (two rounds of one); from a
+  // quarter as many wide tiles as compute units on, the reduction is not split but the tiles are shared out in
+  // equal runs (measured on 98 tiles: 0.24 ms in six splits, 0.20 ms in two, less in runs)
   const int64_t tiles = (int64_t)s.MB * s.CT;
-  s.splits = s.wide ? (tiles >= wide_slots() ? 1 : choose_splits(tiles, nch, false, 1)) : choose_splits(tiles, nch, false, 2);
+  s.splits = s.wide ? (tiles >= wide_slots() / 4 ? 1 : choose_splits(tiles, nch, false, 1)) : choose_splits(tiles, nch, false, 2);
   return s;
 }
 // Floats of split partials such a call may need, and never fewer than a call on fewer kernels of the same layer
