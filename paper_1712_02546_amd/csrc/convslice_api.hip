@@ -163,13 +163,17 @@ FwdPlan plan_fwd(const Geo& g, int dtype) {
 // kernel) and cut by the kernels themselves; the host only fixes the number of runs.  Each run of the line is
 // computed by MB workgroups, one per row tile, which therefore walk through the same pixels, taps and k-chunks at
 // the same time and share the dy operand.
-cs::RunPlan plan_runs(int MB, bool possible, int S = 0) {
+// rounds: workgroups per slot.  One gives every workgroup the longest run; with three, a slot that is freed early
+// (the two workgroups of a compute unit do not advance at the same pace) is refilled, which pays when the runs
+// stay long.
+inline int run_rounds(int64_t line, int MB) { return line / std::max(1, chip_slots() / MB) >= 250 ? 3 : 1; }
+cs::RunPlan plan_runs(int MB, bool possible, int S = 0, int rounds = 1) {
   cs::RunPlan rp;
   rp.enabled = 0; rp.nRuns = 1; rp.nWg = 0;
   if (S <= 0) S = chip_slots();
   if (!possible || S / MB < 1) return rp;
   rp.enabled = 1;
-  rp.nRuns = S / MB;
+  rp.nRuns = rounds * S / MB;
   rp.nWg = rp.nRuns * MB;
   return rp;
 }
@@ -177,6 +181,8 @@ cs::RunPlan plan_runs(int MB, bool possible, int S = 0) {
 struct BwdDataPlan {
   bool scatter;   // few input channels: T = w^T * dy on the matrix cores, then a col2im gather
   int Cp, Ksp, nch, CT1;   // Ksp: pitch of w' in the scatter form, a multiple of BK; CT1: its column tiles
+  int rounds;              // per-pixel form: workgroups per slot when the line is cut into runs (the most any launch uses)
+  int64_t line;            // chunks on the line of column tiles, about
   size_t off_dyt, off_wt, off_dxt, off_perm, off_pre, off_scratch, off_tab, off_T, off_tail, total;
 };
 
@@ -225,7 +231,20 @@ BwdDataPlan plan_bwd_data(const Geo& g) {
   const int CT = (g.HW * g.NB + 3) / 4;
   p.off_pre = o;  o += seg((int64_t)CT + 2);
   p.off_scratch = o; o += seg(cs::po::axes_ints(g.H, g.W));
-  p.off_tail = o; o += (size_t)chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4;   // two slots per workgroup, whatever the slice
+  // Rounds of runs (plan_runs): three where a third of the line per slot is still a long run.  Chunks on the line,
+  // about: taps that reach a pixel, summed over the pixels = (valid (p,r) pairs) x (valid (q,s) pairs), times the
+  // column tiles per pixel and the k-chunks per tap.  (Measured: runs of 918 chunks 3.65 ms, three rounds of 306
+  // 3.57 ms; 313 -> 104: 1.345 -> 1.307 ms; 131 -> 44: 0.597 -> 0.605 ms.)
+  {
+    int64_t rows = 0, cols = 0;
+    for (int pp = 0; pp < g.P; ++pp)
+      for (int r = 0; r < g.R; ++r) rows += (unsigned)(pp * g.sh - g.ph + r) < (unsigned)g.H;
+    for (int q = 0; q < g.Q; ++q)
+      for (int ss = 0; ss < g.S; ++ss) cols += (unsigned)(q * g.sw - g.pw + ss) < (unsigned)g.W;
+    p.line = rows * cols * g.NB / 4 * p.nch;
+    p.rounds = run_rounds(p.line, (g.C + cs::BM - 1) / cs::BM);
+  }
+  p.off_tail = o; o += (size_t)p.rounds * chip_slots() * 2 * cs::TAIL_SLOT_FLOATS * 4;   // two slots per workgroup
   p.total = o;
   return p;
 }
@@ -1214,7 +1233,7 @@ int conv_bwd_data(const conv_desc_t* desc, const void* dy, const void* w, void* 
   auto launch = [&](auto kern, auto fixup, int mi, int c0, int tiles) -> int {
     const int r = allow_big_lds(kern, lds);
     if (r != CONV_OK) return r;
-    const cs::RunPlan rp = plan_runs(tiles, runs);
+    const cs::RunPlan rp = plan_runs(tiles, runs, 0, std::min(p.rounds, run_rounds(p.line, tiles)));
     hipLaunchKernelGGL(kern, dim3(rp.enabled ? (rp.nWg + 7) / 8 * 8 : cs::grid_dealt(tiles, CT)), dim3(cs::NT), lds, st, g,
                        wt, p.Ksp, dyt, perm, pre, dxt, c0, tiles, CT, rp, partial);
     if (rp.enabled)
