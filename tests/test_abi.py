@@ -173,6 +173,23 @@ def test_pass_path_names_the_kernel_family():
     assert cs.conv_pass_path(cs.ConvDesc(N=0, C=3, H=32, W=32, K=5, R=5, S=5), 0) == "invalid descriptor"
 
 
+def test_pass_path_names_the_bf16_tile_shape():
+    """256 x 256 tiles for slices of more than 128 rows; the input gradient takes them only where its runs are long
+    or its tiles outnumber the compute units."""
+    big = dict(N=128, C=500, H=14, W=14, K=1500, R=5, S=5, dtype=cs.CONV_BF16)
+    for p in (cs.PASS_FWD, cs.PASS_BWD_DATA, cs.PASS_BWD_WEIGHT):
+        assert "_wide_gemm_kernel" in cs.conv_pass_path(cs.ConvDesc(**big), p), p
+    share = cs.ConvDesc(**big, k0=500, k1=1000)          # a third of the kernels: short runs
+    assert "_wide_gemm_kernel" in cs.conv_pass_path(share, cs.PASS_FWD)
+    assert cs.conv_pass_path(share, cs.PASS_BWD_DATA).startswith("bwd_data16_gemm_kernel")
+    small = cs.ConvDesc(**big, k0=0, k1=128)             # 128 kernels: one narrow row tile
+    assert cs.conv_pass_path(small, cs.PASS_FWD).startswith("fwd16_gemm_kernel")
+    assert cs.conv_pass_path(small, cs.PASS_BWD_WEIGHT).startswith("bwd_weight16_gemm_kernel")
+    c96 = cs.ConvDesc(N=64, C=96, H=27, W=27, K=256, R=5, S=5, pad_h=2, pad_w=2, dtype=cs.CONV_BF16)
+    assert "_wide_gemm_kernel" in cs.conv_pass_path(c96, cs.PASS_FWD)
+    assert cs.conv_pass_path(c96, cs.PASS_BWD_DATA).startswith("bwd_data16_gemm_kernel")   # 96 channels: narrow rows
+
+
 def test_null_descriptor():
     lib = cs.load()
     assert lib.conv_fwd(None, 1, 1, 1, 1, 0, None) == -1
