@@ -251,14 +251,20 @@ def test_benchmark_configs_every_element(name, dtype):
 
 @pytest.mark.parametrize("k0,k1", [(188, 376), (1313, 1500), (0, 64)])
 def test_eighth_of_the_large_layer_every_element_fp32(k0, k1):
-    """One of eight equal shares of the 1500-kernel layer (Eq. (1) with equal devices): a full
-    row tile plus a half row tile in the forward and weight-gradient passes; and a share that
-    is a half tile only."""
+    """One of eight equal shares of the 1500-kernel layer (Eq. (1) with equal devices): two
+    96-row tiles in the forward and weight-gradient passes; and a share that is a 64-row tile
+    only."""
     _full(synth.CONFIGS["cfg3"].with_slice(k0, k1), cs.CONV_F32)
 
 
 def test_large_layer_every_element_bf16():
     _full(synth.CONFIGS["cfg3"], cs.CONV_BF16)
+
+
+def test_device_share_of_the_large_layer_every_element_bf16():
+    """Kernels 500..999: 256 x 256 tiles in the forward and weight-gradient passes (the latter in equal runs),
+    128 x 128 tiles in the input gradient, whose runs would be short."""
+    _full(synth.CONFIGS["cfg4"], cs.CONV_BF16)
 
 
 def test_full_size_oracle_cache_is_released():
