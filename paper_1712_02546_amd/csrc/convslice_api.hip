@@ -566,6 +566,36 @@ PmFwdPlan plan_pm_fwd(const Geo& g, const PmPlan& pm, int dtype) {
   return p;
 }
 
+// bf16 forward pass of a few-channel layer on the bf16 matrix cores (fwd16_pm_gemm_kernel).
+struct Pm16Plan {
+  bool ok;
+  cs::Pm16Geo pg;
+  int nch, MB, CT, NPQ;
+  int64_t ldw;
+  size_t off_xc, off_wk, total;
+};
+Pm16Plan plan_pm16_fwd(const Geo& g, const PmPlan& pm, int dtype) {
+  Pm16Plan p;
+  p.pg.Cp = g.C <= 8 ? 8 : 16;
+  p.pg.WPC = cs::BK16 / p.pg.Cp;
+  p.pg.CPR = (g.S + p.pg.WPC - 1) / p.pg.WPC;
+  p.pg.Hb = (g.P - 1) * g.sh + g.R;
+  p.pg.Wb = (g.Q - 1) * g.sw + p.pg.CPR * p.pg.WPC;
+  p.nch = g.R * p.pg.CPR;
+  p.ldw = (int64_t)p.nch * cs::BK16;
+  p.NPQ = pm.pg.NPQ;
+  p.MB = (g.Ks + cs::BM - 1) / cs::BM;
+  p.CT = (p.NPQ + cs::BN - 1) / cs::BN;
+  const int64_t xc_elems = (int64_t)g.N * p.pg.Hb * p.pg.Wb * p.pg.Cp;
+  p.ok = dtype == CONV_BF16 && pm.ok && g.C <= 16 && xc_elems < kMaxElems && (int64_t)g.Ks * p.ldw < kMaxElems &&
+         (int64_t)p.MB * p.CT < ((int64_t)1 << 30);
+  size_t o = 0;
+  p.off_xc = o; o += seg16(xc_elems);
+  p.off_wk = o; o += seg16((int64_t)g.Ks * p.ldw);
+  p.total = o;
+  return p;
+}
+
 struct PmBwdDataPlan {
   int Ksp, nch;
   size_t off_dy, off_wt, off_T, total;
@@ -684,6 +714,30 @@ const float* pm_input(const Geo& g, const PmPlan& pm, int dtype, const void* x, 
     hipLaunchKernelGGL(cs::pm_border_copy_kernel<uint16_t>, dim3(grid_for(count)), dim3(256), 0, st, g, pm.pg.Hp,
                        pm.pg.Wp, (const uint16_t*)x, xb);
   return xb;
+}
+
+int pm16_fwd(const Geo& g, const Pm16Plan& p, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+             hipStream_t st, const Probe& probe, bool input_ready) {
+  int rc;
+  if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
+  char* base = (char*)ws;
+  uint16_t* xc = (uint16_t*)(base + p.off_xc);
+  uint16_t* wk = (uint16_t*)(base + p.off_wk);
+  if (!input_ready) {
+    const int blocks = grid_for((int64_t)g.N * p.pg.Hb * p.pg.Wb, 1 << 20);
+    if (p.pg.Cp == 8)
+      hipLaunchKernelGGL(cs::pm16_channels_last_kernel<8>, dim3(blocks), dim3(256), 0, st, g, p.pg, (const uint16_t*)x, xc);
+    else
+      hipLaunchKernelGGL(cs::pm16_channels_last_kernel<16>, dim3(blocks), dim3(256), 0, st, g, p.pg, (const uint16_t*)x, xc);
+  }
+  hipLaunchKernelGGL(cs::pm16_filters_kernel, dim3(grid_for((int64_t)g.Ks * p.ldw)), dim3(256), 0, st, g, p.pg,
+                     (const uint16_t*)w + (size_t)g.k0 * g.CRS, wk);
+  if ((rc = allow_big_lds(cs::fwd16_pm_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
+  probe.begin(st);
+  hipLaunchKernelGGL(cs::fwd16_pm_gemm_kernel, dim3(cs::grid_contiguous(p.MB * p.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g,
+                     p.pg, wk, p.ldw, xc, (uint16_t*)y, p.NPQ, p.MB, p.CT, p.nch);
+  probe.end(st);
+  return check_launch();
 }
 
 int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
@@ -890,7 +944,10 @@ size_t conv_workspace_bytes(const conv_desc_t* desc, int pass) {
   const PmPlan pm = plan_pm(g, desc->dtype);
   switch (pass) {
     case CONV_PASS_FWD:
-      if (pm.ok) return plan_pm_fwd(g, pm, desc->dtype).total;
+      if (pm.ok) {
+        const Pm16Plan p16 = plan_pm16_fwd(g, pm, desc->dtype);
+        return p16.ok ? p16.total : plan_pm_fwd(g, pm, desc->dtype).total;
+      }
       return bf16_mfma_fwd_ok(g, desc->dtype) ? plan_fwd16(g).total : plan_fwd(g, desc->dtype).total;
     case CONV_PASS_BWD_DATA:
       if (pm.ok_data) return plan_pm_bwd_data(g, desc->dtype).total;
@@ -951,7 +1008,11 @@ int fwd_impl(const conv_desc_t* desc, const void* x, const void* w, void* y, voi
   if (misaligned(x, 16) || misaligned(w, 16) || misaligned(y, 16)) return CONV_ERR_ALIGN;
   if (g.Ks == 0) return CONV_OK;
   const PmPlan pm = plan_pm(g, desc->dtype);
-  if (pm.ok) return pm_fwd(g, pm, desc->dtype, x, w, y, ws, ws_bytes, (hipStream_t)hip_stream, probe, input_ready);
+  if (pm.ok) {
+    const Pm16Plan p16 = plan_pm16_fwd(g, pm, desc->dtype);
+    if (p16.ok) return pm16_fwd(g, p16, x, w, y, ws, ws_bytes, (hipStream_t)hip_stream, probe, input_ready);
+    return pm_fwd(g, pm, desc->dtype, x, w, y, ws, ws_bytes, (hipStream_t)hip_stream, probe, input_ready);
+  }
   if (bf16_mfma_fwd_ok(g, desc->dtype)) {
     const Fwd16Plan p = plan_fwd16(g);
     if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
@@ -1400,6 +1461,8 @@ const char* conv_pass_path(const conv_desc_t* desc, int pass) {
   const PmPlan pm = plan_pm(g, dt);
   switch (pass) {
     case CONV_PASS_FWD:
+      if (pm.ok && plan_pm16_fwd(g, pm, dt).ok)
+        return "fwd16_pm_gemm_kernel: bf16 MFMA, pixel-major on a channels-last copy of x, y stored in place";
       if (pm.ok) return bf ? "fwd_pm_gemm_kernel: fp32 MFMA on operands converted from bf16, pixel-major, y stored in place"
                            : "fwd_pm_gemm_kernel: fp32 MFMA, pixel-major, y stored in place";
       if (bf16_mfma_fwd_ok(g, dt))

@@ -19,6 +19,7 @@
 #pragma once
 #include "conv_common.h"
 #include "gemm_kernels.h"
+#include "gemm_bf16_kernels.h"
 
 namespace cs {
 
@@ -599,6 +600,123 @@ __global__ __launch_bounds__(NT) void bwd_weight_pm_gemm_kernel(Geo g, PmGeo pg,
   PmTapLoadB lb(g, pg, xb, zero, pixtab, ct * BN, z, splits);
   gemm_mainloop(la, lb, 0, count, smem, acc);
   bwd_weight_store_tile<MI>(g, out + (int64_t)z * splitStride, m0, rowBase, ct, acc);
+}
+
+// ------------------------------------------- forward, bf16 matrix cores ----
+// Few input channels in bfloat16.  v_mfma_f32_32x32x16_bf16 wants eight consecutive reduction
+// elements per lane, which a gather of single taps cannot give; one filter ROW can: in a copy of x
+// with the channels innermost, xc[n][hb][wb][Cp] (Cp = 8 or 16 channels, zero filled; zero border
+// of ph rows / pw columns, and enough columns on the right that every read below stays inside),
+// the taps (r, s..s+WPC-1, all channels) of a window are 64 consecutive elements.  So the
+// reduction is laid out as (r, j, 64 elements): R * CPR chunks with CPR = ceil(S / WPC),
+// WPC = 64 / Cp window columns per chunk, and the filters are re-laid to match,
+// wk[k][r][CPR * WPC][Cp], zero where s >= S or c >= C: the columns a chunk reads past the window
+// meet zero weights.  A column of the GEMM is an output pixel of one image; its byte offset in xc
+// never changes, the chunk's (r, j) offset moves in the uniform base: the addressing of the other
+// bf16 kernels.  Tiles are 128 kernels x 128 pixels, y is written in place (bf16, NCHW).
+struct Pm16Geo {
+  int Cp, WPC, CPR, Hb, Wb;   // padded channels, window columns per chunk, chunks per filter row, extents of xc
+};
+
+// xc[n][hb][wb][c] = x[n][c][hb-ph][wb-pw] inside the image and for c < C, else 0.  One thread per (n, hb, wb).
+template <int CP>
+__global__ __launch_bounds__(256) void pm16_channels_last_kernel(Geo g, Pm16Geo pg, const uint16_t* __restrict__ x,
+                                                                 uint16_t* __restrict__ xc) {
+  const int64_t total = (int64_t)g.N * pg.Hb * pg.Wb;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int wb = (int)(i % pg.Wb);
+    const int64_t t = i / pg.Wb;
+    const int hb = (int)(t % pg.Hb);
+    const int64_t n = t / pg.Hb;
+    const int h = hb - g.ph, v = wb - g.pw;
+    const bool in = h >= 0 && h < g.H && v >= 0 && v < g.W;
+    const uint16_t* src = x + (n * g.C * g.H + (in ? h : 0)) * (int64_t)g.W + (in ? v : 0);
+    uint16_t vals[CP];
+#pragma unroll
+    for (int c = 0; c < CP; ++c) vals[c] = (in && c < g.C) ? src[(int64_t)min(c, g.C - 1) * g.HW] : (uint16_t)0;
+    uint4* dst = (uint4*)(xc + i * CP);
+#pragma unroll
+    for (int q = 0; q < CP / 8; ++q) {
+      uint4 u;
+      u.x = vals[8 * q + 0] | ((unsigned)vals[8 * q + 1] << 16);
+      u.y = vals[8 * q + 2] | ((unsigned)vals[8 * q + 3] << 16);
+      u.z = vals[8 * q + 4] | ((unsigned)vals[8 * q + 5] << 16);
+      u.w = vals[8 * q + 6] | ((unsigned)vals[8 * q + 7] << 16);
+      dst[q] = u;
+    }
+  }
+}
+
+// wk[k][r][s'][c'] = w[k0+k][c'][r][s'] for s' < S, c' < C, else 0; one thread per element of wk.
+__global__ __launch_bounds__(256) void pm16_filters_kernel(Geo g, Pm16Geo pg, const uint16_t* __restrict__ w_k0,
+                                                           uint16_t* __restrict__ wk) {
+  const int SP = pg.CPR * pg.WPC;
+  const int64_t total = (int64_t)g.Ks * g.R * SP * pg.Cp;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % pg.Cp);
+    int64_t t = i / pg.Cp;
+    const int s = (int)(t % SP);
+    t /= SP;
+    const int r = (int)(t % g.R);
+    const int64_t k = t / g.R;
+    wk[i] = (c < g.C && s < g.S) ? w_k0[((k * g.C + c) * g.R + r) * g.S + s] : (uint16_t)0;
+  }
+}
+
+// B^T[col][kk] = xc[n][p*sh + r][q*sw + j*WPC ..][..]: 64 consecutive elements per column and chunk.
+struct Pm16LoadB {
+  const char* xc;     // uniform
+  const char* ub;
+  unsigned off[4];
+  unsigned rowBytes;  // one row of xc
+  int CPR;
+  int r, j;           // uniform walk over the next chunk to issue
+  __device__ Pm16LoadB(const Geo& g, const Pm16Geo& pg, const uint16_t* xc_, int NPQ, int ct, int ch0)
+      : xc((const char*)xc_), rowBytes((unsigned)pg.Wb * (unsigned)pg.Cp * 2u), CPR(pg.CPR) {
+    const int l = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int col = min(ct * BN + wv * 32 + 8 * i + (l >> 3), NPQ - 1);   // columns past the end: computed, never stored
+      const int n = col / g.PQ, pix = col - n * g.PQ;
+      const int pp = pix / g.Q, q = pix - pp * g.Q;
+      off[i] = (unsigned)((((int64_t)n * pg.Hb + pp * g.sh) * pg.Wb + q * g.sw) * pg.Cp + slot8(l, i)) * 2u;
+    }
+    r = ch0 / CPR;
+    j = ch0 - r * CPR;
+  }
+  __device__ __forceinline__ void begin(int, bool live) {
+    ub = xc + (live ? (unsigned)r * rowBytes + (unsigned)j * (BK16 * 2u) : 0u);
+  }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
+  __device__ __forceinline__ void end() {   // branch-free carry over (j, r)
+    ++j;
+    const int c = j == CPR;
+    j = c ? 0 : j;
+    r += c;
+  }
+};
+
+// grid = grid_contiguous(MB * CT): one workgroup per tile, tiles dealt to the XCDs in contiguous blocks.
+__global__ __launch_bounds__(NT) void fwd16_pm_gemm_kernel(Geo g, Pm16Geo pg, const bf16_t* __restrict__ wk, int64_t ldw,
+                                                           const bf16_t* __restrict__ xc, uint16_t* __restrict__ y,
+                                                           int NPQ, int MB, int CT, int nch) {
+  extern __shared__ __align__(16) float smem[];
+  int L;
+  if (!line_contiguous(blockIdx.x, MB * CT, L)) return;
+  int mb, ct;
+  tile_from_line(L, MB, CT, mb, ct);
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
+  Fwd16LoadA la(wk, ldw, mb * BM, g.Ks);
+  Pm16LoadB lb(g, pg, xc, NPQ, ct, 0);
+  gemm16_mainloop(la, lb, 0, nch, smem, acc);
+  pm_store_tile<2, uint16_t>(y + (int64_t)g.k0 * g.PQ, g.Ks, (int64_t)g.K * g.PQ, g.PQ, NPQ, mb * BM, ct, acc);
 }
 
 }  // namespace cs
