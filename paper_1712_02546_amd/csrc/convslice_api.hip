@@ -597,14 +597,26 @@ Pm16Plan plan_pm16_fwd(const Geo& g, const PmPlan& pm, int dtype) {
 }
 
 struct PmBwdDataPlan {
+  bool mfma16;   // bf16: T on the bf16 matrix cores from a channels-last copy of the slice's maps
   int Ksp, nch;
   size_t off_dy, off_wt, off_T, total;
 };
 PmBwdDataPlan plan_pm_bwd_data(const Geo& g, int dtype) {
   PmBwdDataPlan p;
+  const int64_t Kp16 = round_up(g.Ks, cs::BK16);
+  p.mfma16 = dtype == CONV_BF16 && (int64_t)g.N * g.PQ * Kp16 < kMaxElems && (int64_t)g.CRS * Kp16 < kMaxElems;
+  size_t o = 0;
+  if (p.mfma16) {
+    p.Ksp = (int)Kp16;
+    p.nch = p.Ksp / cs::BK16;
+    p.off_dy = o; o += seg16((int64_t)g.N * g.PQ * p.Ksp);
+    p.off_wt = o; o += seg16((int64_t)g.CRS * p.Ksp);
+    p.off_T = o;  o += seg((int64_t)g.N * g.CRS * g.PQ);
+    p.total = o;
+    return p;
+  }
   p.Ksp = (int)round_up(g.Ks, cs::BK);
   p.nch = p.Ksp / cs::BK;
-  size_t o = 0;
   p.off_dy = o; o += dtype != CONV_F32 ? seg((int64_t)g.N * g.Ks * g.PQ) : 0;   // fp32 copy of the slice's maps
   p.off_wt = o; o += seg((int64_t)g.CRS * p.Ksp);
   p.off_T = o;  o += seg((int64_t)g.N * g.CRS * g.PQ);
@@ -798,46 +810,62 @@ int pm_bwd_data(const Geo& g, const PmPlan& pm, int dtype, bool acc, const void*
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
   char* base = (char*)ws;
   const size_t es = elem_size(dtype);
-  // the slice's maps in fp32: dy in place, or a compact copy of the slice's channels for bf16
-  const float* dy_k0;
-  int64_t imgPitch;
-  if (dtype == CONV_F32) {
-    dy_k0 = (const float*)dy + (size_t)g.k0 * g.PQ;
-    imgPitch = (int64_t)g.K * g.PQ;
-  } else {
-    float* d = (float*)(base + p.off_dy);
-    imgPitch = (int64_t)g.Ks * g.PQ;
-    hipLaunchKernelGGL(cs::pm_slice_to_f32_kernel, dim3(grid_for((int64_t)g.N * imgPitch)), dim3(256), 0, st,
-                       (const uint16_t*)dy + (size_t)g.k0 * g.PQ, (int64_t)g.K * g.PQ, imgPitch, g.N, d);
-    dy_k0 = d;
-  }
-  // w[k][(c,r,s)] -> wt[(c,r,s)][Ksp], zero past Ks
-  float* wt = (float*)(base + p.off_wt);
-  launch_transpose_in(dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0, p.Ksp, p.Ksp, 1,
-                      nullptr, st);
   float* T = (float*)(base + p.off_T);
-  const bool vec4 = g.PQ % 4 == 0;
-  const RowSplit rs = split_rows(g.CRS, true);
-  probe.begin(st);
-  auto launch = [&](auto kern, int m0, int tiles) -> int {
-    int rc2;
-    if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
-    hipLaunchKernelGGL(kern, dim3(stream_grid((int64_t)tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wt,
-                       p.Ksp, dy_k0, imgPitch, T, m0, tiles, p.nch);
-    return CONV_OK;
-  };
-  rc = CONV_OK;
-  if (vec4) {
-    if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, true>, 0, rs.full);
-    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, true>, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, true>, rs.full * cs::BM, rs.nlast);
+  if (p.mfma16) {
+    // dy[n][k0+k][pix] -> dyc[n][pix][Ksp] and w[k0+k][(c,r,s)] -> wt[(c,r,s)][Ksp], both bf16, zero past Ks
+    uint16_t* dyc = (uint16_t*)(base + p.off_dy);
+    uint16_t* wt16 = (uint16_t*)(base + p.off_wt);
+    launch_transpose_in(dtype, (const uint16_t*)dy + (size_t)g.k0 * g.PQ, (int64_t)g.K * g.PQ, g.PQ, g.Ks, g.PQ, dyc,
+                        (int64_t)g.PQ * p.Ksp, p.Ksp, p.Ksp, g.N, nullptr, st, true);
+    launch_transpose_in(dtype, (const uint16_t*)w + (size_t)g.k0 * g.CRS, 0, g.CRS, g.Ks, g.CRS, wt16, 0, p.Ksp, p.Ksp, 1,
+                        nullptr, st, true);
+    if ((rc = allow_big_lds(cs::bwd_data16_pm_gemm_kernel, cs::SMEM_BYTES)) != CONV_OK) return rc;
+    const int MB = (g.CRS + cs::BM - 1) / cs::BM;
+    probe.begin(st);
+    hipLaunchKernelGGL(cs::bwd_data16_pm_gemm_kernel, dim3(cs::grid_contiguous(MB * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES,
+                       st, wt16, p.Ksp, g.CRS, dyc, T, g.PQ, pm.pg.NPQ, MB, pm.pg.CT);
+    probe.end(st);
   } else {
-    if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, false>, 0, rs.full);
-    if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, false>, rs.full * cs::BM, 1);
-    if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, false>, rs.full * cs::BM, rs.nlast);
+    // the slice's maps in fp32: dy in place, or a compact copy of the slice's channels for bf16
+    const float* dy_k0;
+    int64_t imgPitch;
+    if (dtype == CONV_F32) {
+      dy_k0 = (const float*)dy + (size_t)g.k0 * g.PQ;
+      imgPitch = (int64_t)g.K * g.PQ;
+    } else {
+      float* d = (float*)(base + p.off_dy);
+      imgPitch = (int64_t)g.Ks * g.PQ;
+      hipLaunchKernelGGL(cs::pm_slice_to_f32_kernel, dim3(grid_for((int64_t)g.N * imgPitch)), dim3(256), 0, st,
+                         (const uint16_t*)dy + (size_t)g.k0 * g.PQ, (int64_t)g.K * g.PQ, imgPitch, g.N, d);
+      dy_k0 = d;
+    }
+    // w[k][(c,r,s)] -> wt[(c,r,s)][Ksp], zero past Ks
+    float* wt = (float*)(base + p.off_wt);
+    launch_transpose_in(dtype, (const char*)w + (size_t)g.k0 * g.CRS * es, 0, g.CRS, g.Ks, g.CRS, wt, 0, p.Ksp, p.Ksp, 1,
+                        nullptr, st);
+    const bool vec4 = g.PQ % 4 == 0;
+    const RowSplit rs = split_rows(g.CRS, true);
+    probe.begin(st);
+    auto launch = [&](auto kern, int m0, int tiles) -> int {
+      int rc2;
+      if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
+      hipLaunchKernelGGL(kern, dim3(stream_grid((int64_t)tiles * pm.pg.CT)), dim3(cs::NT), cs::SMEM_BYTES, st, g, pm.pg, wt,
+                         p.Ksp, dy_k0, imgPitch, T, m0, tiles, p.nch);
+      return CONV_OK;
+    };
+    rc = CONV_OK;
+    if (vec4) {
+      if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, true>, 0, rs.full);
+      if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, true>, rs.full * cs::BM, 1);
+      if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, true>, rs.full * cs::BM, rs.nlast);
+    } else {
+      if (rs.full > 0) rc = launch(cs::bwd_data_pm_gemm_kernel<2, false>, 0, rs.full);
+      if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_data_pm_gemm_kernel<1, false>, rs.full * cs::BM, 1);
+      if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_data_pm_gemm_kernel<3, false>, rs.full * cs::BM, rs.nlast);
+    }
+    probe.end(st);
+    if (rc != CONV_OK) return rc;
   }
-  probe.end(st);
-  if (rc != CONV_OK) return rc;
   // one thread per group of `stride` columns for strides up to 4, else per column
   auto col2im = [&](auto* out, auto acc_tag) {
     using TO = std::remove_pointer_t<decltype(out)>;
@@ -1471,6 +1499,8 @@ const char* conv_pass_path(const conv_desc_t* desc, int pass) {
       return bf ? "fwd_gemm_kernel: fp32 MFMA on operands converted from bf16, batch-innermost work copies"
                 : "fwd_gemm_kernel: fp32 MFMA, batch-innermost work copies";
     case CONV_PASS_BWD_DATA:
+      if (pm.ok_data && plan_pm_bwd_data(g, dt).mfma16)
+        return "bwd_data16_pm_gemm_kernel: bf16 MFMA, pixel-major T = w^T dy on a channels-last copy of dy, then col2im_pm_kernel";
       if (pm.ok_data)
         return bf ? "bwd_data_pm_gemm_kernel: fp32 MFMA on operands converted from bf16, pixel-major T = w^T dy, then col2im_pm_kernel"
                   : "bwd_data_pm_gemm_kernel: fp32 MFMA, pixel-major T = w^T dy read from dy in place, then col2im_pm_kernel";

@@ -719,4 +719,51 @@ __global__ __launch_bounds__(NT) void fwd16_pm_gemm_kernel(Geo g, Pm16Geo pg, co
   pm_store_tile<2, uint16_t>(y + (int64_t)g.k0 * g.PQ, g.Ks, (int64_t)g.K * g.PQ, g.PQ, NPQ, mb * BM, ct, acc);
 }
 
+// ------------------------------------ input gradient, bf16 matrix cores ----
+// T = w^T dy is a 1 x 1 convolution of dy with C*R*S "kernels" over the slice's Ks "channels": with the
+// maps of the slice copied channels-last, dyc[(n, pix)][Kp] (Kp = Ks rounded up to the chunk, zero
+// filled), the 64 reduction elements of a column and chunk are consecutive, and the filters transposed,
+// wt[(c,r,s)][Kp].  B^T[col][kk] = dyc[col][ch*64 + kk].
+struct Pm16DyLoadB {
+  const char* dyc;   // uniform
+  const char* ub;
+  unsigned off[4];
+  __device__ Pm16DyLoadB(const uint16_t* dyc_, int Kp, int NPQ, int ct) : dyc((const char*)dyc_) {
+    const int l = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int col = min(ct * BN + wv * 32 + 8 * i + (l >> 3), NPQ - 1);   // columns past the end: computed, never stored
+      off[i] = ((unsigned)col * (unsigned)Kp + slot8(l, i)) * 2u;
+    }
+  }
+  __device__ __forceinline__ void begin(int ch, bool live) { ub = dyc + (live ? (unsigned)ch * (BK16 * 2u) : 0u); }
+  __device__ __forceinline__ void issue(int i, float* dst) { dma16_uv(ub, off[i], dst); }
+  __device__ __forceinline__ void end() {}
+};
+
+// T[n][j][pix] = sum_k wt[j][k] * dyc[(n, pix)][k], fp32 (a bf16 T would halve this pass's traffic, but sums of
+// taps that cancel then miss the bf16 tolerance); one workgroup per 128 x 128 tile, tiles dealt to the
+// XCDs in contiguous blocks (grid = grid_contiguous(MB * CT)).
+__global__ __launch_bounds__(NT) void bwd_data16_pm_gemm_kernel(const bf16_t* __restrict__ wt, int Kp, int CRS,
+                                                                const bf16_t* __restrict__ dyc, float* __restrict__ T,
+                                                                int PQ, int NPQ, int MB, int CT) {
+  extern __shared__ __align__(16) float smem[];
+  int L;
+  if (!line_contiguous(blockIdx.x, MB * CT, L)) return;
+  int mb, ct;
+  tile_from_line(L, MB, CT, mb, ct);
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
+  Fwd16LoadA la(wt, Kp, mb * BM, CRS);
+  Pm16DyLoadB lb(dyc, Kp, NPQ, ct);
+  gemm16_mainloop(la, lb, 0, Kp / BK16, smem, acc);
+  pm_store_tile<2, float>(T, CRS, (int64_t)CRS * PQ, PQ, NPQ, mb * BM, ct, acc);
+}
+
 }  // namespace cs
