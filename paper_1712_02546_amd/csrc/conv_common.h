@@ -374,8 +374,10 @@ __device__ __forceinline__ void mfma_group_first(const FragN<MI>& a, const FragN
 // the A loader of that tile; its B loader is built by make_b(), or, when same_b() says that the tile has the
 // column tile of the one before, the current B loader is only restarted (restart()); store(acc) stores the
 // oldest tile not yet stored (tiles are stored in the order they were loaded).
+// lastg = groups of eight reduction elements that hold data in a tile's last chunk (1..4): the third and fourth
+// group of that chunk are skipped when they are all padding (their A operand is zero).
 template <class LA, class LB, class Tiles>
-__device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem) {
+__device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, int lastg = 4) {
   constexpr bool AC = LA::COL, BC = LB::COL;
   constexpr int MI = LA::MI;
   static_assert(MI == 2 || AC, "the 64- and 96-row tiles need a col-image A operand");
@@ -431,12 +433,12 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem) 
     const float* Bs = smem + 2 * TILE_F + cur;
     more = issue_next(ch, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F));
     CS_FENCE();
-    mfma_group(a0, b0, acc);  // G2 of the chunk before
+    if (!(newtile && lastg <= 2)) mfma_group(a0, b0, acc);  // G2 of the chunk before
     CS_FENCE();
     read_frag<AC>(a0, As, wa, lane, 0, blk1);
     read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
     CS_FENCE();
-    mfma_group(a1, b1, acc);  // G3 of the chunk before
+    if (!(newtile && lastg <= 3)) mfma_group(a1, b1, acc);  // G3 of the chunk before
     CS_FENCE();
     read_frag<AC>(a1, As, wa, lane, 1, blk1);
     read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
@@ -458,8 +460,8 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem) 
     __syncthreads();
     cur ^= TILE_F;
   }
-  mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
-  mfma_group(a1, b1, acc);
+  if (lastg > 2) mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
+  if (lastg > 3) mfma_group(a1, b1, acc);
   tiles.store(acc);
 }
 

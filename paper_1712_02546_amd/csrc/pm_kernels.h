@@ -279,7 +279,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_pm_gemm_kernel(Geo g, PmGeo pg, con
   int begin, end;
   stream_run(MB * pg.CT, begin, end);
   tiles.start(begin, end);
-  gemm_stream<FwdLoadA<MI>, PmFwdLoadB>(tiles, nch, smem);
+  gemm_stream<FwdLoadA<MI>, PmFwdLoadB>(tiles, nch, smem, (g.CRS - (nch - 1) * BK + 7) >> 3);
 }
 
 // --------------------------------------------------------- input gradient ----
@@ -354,7 +354,7 @@ __global__ __launch_bounds__(NT, 2) void bwd_data_pm_gemm_kernel(Geo g, PmGeo pg
   int begin, end;
   stream_run(MB * pg.CT, begin, end);
   tiles.start(begin, end);
-  gemm_stream<FwdLoadA<MI>, PmDyLoadB<VEC4>>(tiles, nch, smem);
+  gemm_stream<FwdLoadA<MI>, PmDyLoadB<VEC4>>(tiles, nch, smem, (g.Ks - (nch - 1) * BK + 7) >> 3);
 }
 
 // dx[n][c][h][v] (+)= sum over the taps (r,s) whose window position (p,q) lands on (h,v) of
