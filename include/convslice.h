@@ -156,7 +156,11 @@ int conv_bwd_weight(const conv_desc_t *desc, const void *x, const void *dy, void
  * thread.  That call records start_event (a hipEvent_t passed as void*) on its
  * stream right before its matrix-core kernel and stop_event right after it, so
  * the kernel's duration can be read with hipEventElapsedTime once the stream
- * has drained; the layout kernels around it are outside the bracket.  The probe
+ * has drained; the layout kernels around it are outside the bracket (a pass
+ * that runs its matrix-core kernel once per group of images -- the input
+ * gradient of a few-channel layer whose intermediate exceeds 160 MiB -- is
+ * bracketed from the first group's kernel to the last one's, with the sums
+ * over taps of the groups in between).  The probe
  * is consumed by that call (also when it fails or has nothing to launch).
  * Passing NULL for either event disarms it.  Always returns CONV_OK.
  */

@@ -136,6 +136,26 @@ def test_few_channel_input_gradient_keeps_fp32_sums_bf16():
     check(dev.bwd_weight()[k0:k1], oracle.conv_bwd_weight(sh, x, dy)[k0:k1], FP32_TOL, "dw")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_few_channel_input_gradient_in_image_groups(dtype):
+    """T = w^T dy of this layer is 169 MiB (13 images x 363 taps x 97 x 97 pixels), above the size up to which it is
+    computed in one pass: the images go through in groups of 7 and 6, on top of an initial dx (accumulate)."""
+    cfg = synth.random_layer(29, N=13, C=3, H=200, W=200, K=16, R=11, S=11, stride=2, pad=2, k0=1, k1=15)
+    bf = dtype == "bf16"
+    x, w, dy = synth.make_inputs(cfg)
+    if bf:
+        x, w, dy = (synth.round_to_bf16(a) for a in (x, w, dy))
+    init = np.random.default_rng(5).standard_normal((cfg.N, cfg.C, cfg.H, cfg.W)).astype(np.float32)
+    if bf:
+        init = synth.round_to_bf16(init)
+    dev = Device(cfg, x, w, dy, dtype=cs.CONV_BF16 if bf else cs.CONV_F32)
+    assert "pm_gemm_kernel" in cs.conv_pass_path(desc_of(cfg, dev.dtype), cs.PASS_BWD_DATA)
+    ref = oracle.conv_bwd_data(oracle_shape(cfg), dy, w)
+    tol = BF16_TOL if bf else FP32_TOL
+    check(dev.bwd_data(), ref, tol, "dx")
+    check(dev.bwd_data(accumulate=1, init=init), ref + init, tol, "dx on top of an initial value")
+
+
 @pytest.mark.parametrize("C", [24, 48])
 def test_disjoint_slices_assemble_the_full_layer(C):
     """Same inputs, different kernels per device, outputs side by side (Section 4.1.2):
