@@ -46,12 +46,12 @@
  * Precision.  CONV_F32: fp32 tensors, fp32 matrix-core (MFMA) products and
  * accumulation.  CONV_BF16: x, w, y, dy, dx are bfloat16 (upper 16 bits of an
  * fp32, round-to-nearest-even on output), accumulation is fp32, dw is fp32.
- * bf16 products run on the bf16 matrix-core instructions, with two
- * exceptions that convert their operands to fp32 copies and run the fp32
- * kernels: the input gradient of layers with at most 32 input channels, and
- * the forward pass of layers with 17 to 31 input channels (or with at most
- * 16 that the few-channel path does not take: C*R*S > 480 or P*Q < 32).  The
- * forward pass of first layers (C = 3) and every weight gradient are bf16
+ * bf16 products run on the bf16 matrix-core instructions, with one
+ * exception that converts its operands to fp32 copies and runs the fp32
+ * kernels: layers with 17 to 31 input channels (32 too for the input
+ * gradient), or with at most 16 that the few-channel path does not take
+ * (C*R*S > 480 or P*Q < 32), in their forward pass and input gradient.  All
+ * three passes of first layers (C = 3) and every weight gradient are bf16
  * MFMA.  conv_pass_path() names the kernel and arithmetic of a pass.
  *
  * Limits.  Each tensor (and each internal transposed copy, whose batch extent
