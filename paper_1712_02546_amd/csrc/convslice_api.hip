@@ -576,7 +576,7 @@ struct Pm16Plan {
 };
 Pm16Plan plan_pm16_fwd(const Geo& g, const PmPlan& pm, int dtype) {
   Pm16Plan p;
-  p.pg.Cp = g.C <= 8 ? 8 : 16;
+  p.pg.Cp = (g.C <= 4 && g.sw % 2 == 0) ? 4 : g.C <= 8 ? 8 : 16;   // 4: windows must start on 16-byte boundaries
   p.pg.WPC = cs::BK16 / p.pg.Cp;
   p.pg.CPR = (g.S + p.pg.WPC - 1) / p.pg.WPC;
   p.pg.Hb = (g.P - 1) * g.sh + g.R;
@@ -737,7 +737,9 @@ int pm16_fwd(const Geo& g, const Pm16Plan& p, const void* x, const void* w, void
   uint16_t* wk = (uint16_t*)(base + p.off_wk);
   if (!input_ready) {
     const int blocks = grid_for((int64_t)g.N * p.pg.Hb * p.pg.Wb, 1 << 20);
-    if (p.pg.Cp == 8)
+    if (p.pg.Cp == 4)
+      hipLaunchKernelGGL(cs::pm16_channels_last_kernel<4>, dim3(blocks), dim3(256), 0, st, g, p.pg, (const uint16_t*)x, xc);
+    else if (p.pg.Cp == 8)
       hipLaunchKernelGGL(cs::pm16_channels_last_kernel<8>, dim3(blocks), dim3(256), 0, st, g, p.pg, (const uint16_t*)x, xc);
     else
       hipLaunchKernelGGL(cs::pm16_channels_last_kernel<16>, dim3(blocks), dim3(256), 0, st, g, p.pg, (const uint16_t*)x, xc);

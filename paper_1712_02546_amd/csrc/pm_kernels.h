@@ -605,7 +605,8 @@ __global__ __launch_bounds__(NT) void bwd_weight_pm_gemm_kernel(Geo g, PmGeo pg,
 // ------------------------------------------- forward, bf16 matrix cores ----
 // Few input channels in bfloat16.  v_mfma_f32_32x32x16_bf16 wants eight consecutive reduction
 // elements per lane, which a gather of single taps cannot give; one filter ROW can: in a copy of x
-// with the channels innermost, xc[n][hb][wb][Cp] (Cp = 8 or 16 channels, zero filled; zero border
+// with the channels innermost, xc[n][hb][wb][Cp] (Cp = 4, 8 or 16 channels, zero filled; Cp = 4 only with an even
+// horizontal stride, so that every window starts on a 16-byte boundary; zero border
 // of ph rows / pw columns, and enough columns on the right that every read below stays inside),
 // the taps (r, s..s+WPC-1, all channels) of a window are 64 consecutive elements.  So the
 // reduction is laid out as (r, j, 64 elements): R * CPR chunks with CPR = ceil(S / WPC),
@@ -634,6 +635,12 @@ __global__ __launch_bounds__(256) void pm16_channels_last_kernel(Geo g, Pm16Geo 
     uint16_t vals[CP];
 #pragma unroll
     for (int c = 0; c < CP; ++c) vals[c] = (in && c < g.C) ? src[(int64_t)min(c, g.C - 1) * g.HW] : (uint16_t)0;
+    if constexpr (CP == 4) {
+      uint2 u;
+      u.x = vals[0] | ((unsigned)vals[1] << 16);
+      u.y = vals[2] | ((unsigned)vals[3] << 16);
+      *(uint2*)(xc + i * CP) = u;
+    }
     uint4* dst = (uint4*)(xc + i * CP);
 #pragma unroll
     for (int q = 0; q < CP / 8; ++q) {
