@@ -51,6 +51,9 @@ ADHOC = [
     synth.random_layer(26, N=33, C=210, H=9, W=9, K=215, R=3, S=3, pad=1),
     # only a 96-row tile, stride 2, batch of one block: 90 channels, 70 kernels
     synth.random_layer(27, N=20, C=90, H=11, W=10, K=70, R=3, S=2, stride=2),
+    # 1 200 forward tiles of 18 chunks for 512 workgroup slots: two rounds of whole tiles, 176 tiles shared in runs of
+    # 7 chunks; 36 weight-gradient tiles of 2 400 chunks, the reduction split
+    synth.random_layer(30, N=32, C=64, H=48, W=50, K=260, R=3, S=3, pad=1, k0=2, k1=258),
     # few channels, one filter row with stride 4: three of four rows of dx are reached by no tap, the rest by one or two
     synth.random_layer(28, N=100, C=12, H=15, W=19, K=288, R=1, S=5, stride=4, pad=3, k0=29, k1=122),
 ]
@@ -124,8 +127,7 @@ def test_few_channel_input_gradient_keeps_fp32_sums_bf16():
     three quarters of dx are zero by construction, so the error metric's rms floor is low and taps that cancel
     show: the sums over kernels must reach the sum over taps unrounded (T in fp32), or single elements miss the
     tolerance.  Rounded inputs only, for the reason given in the test above."""
-    cfg = ADHOC[-1]
-    assert cfg.name == "adhoc28"
+    cfg = next(c for c in ADHOC if c.name == "adhoc28")
     x, w, dy = (synth.round_to_bf16(a) for a in synth.make_inputs(cfg))
     sh = oracle_shape(cfg)
     k0, k1 = cfg.slice
