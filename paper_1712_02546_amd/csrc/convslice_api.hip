@@ -596,6 +596,19 @@ Pm16Plan plan_pm16_fwd(const Geo& g, const PmPlan& pm, int dtype) {
   return p;
 }
 
+// Images per pass over T: T = w^T dy is four bytes per (tap, channel, pixel), many times the size of dy and dx,
+// and is written once and read once.  Computed for a group of images at a time, with the sum over taps following
+// each group, a T of more than the chip's 256 MB memory-side cache stays in that cache between the two kernels
+// instead of going out to memory and back (64 images of 3 x 224 x 224 under 11 x 11 stride 4, T = 281 MB: the bf16
+// input gradient takes 0.222 ms in one pass, 0.181 ms in two groups; groups of a quarter of the cache are slower
+// than one pass, the launches get too short).
+constexpr int64_t kPmTGroupBytes = (int64_t)160 << 20;
+int pm_T_group(const Geo& g) {
+  const int64_t bytes = (int64_t)g.N * g.CRS * g.PQ * 4;
+  const int64_t groups = (bytes + kPmTGroupBytes - 1) / kPmTGroupBytes;
+  return (int)((g.N + groups - 1) / groups);
+}
+
 struct PmBwdDataPlan {
   bool mfma16;   // bf16: T on the bf16 matrix cores from a channels-last copy of the slice's maps
   int Ksp, nch;
@@ -611,7 +624,7 @@ PmBwdDataPlan plan_pm_bwd_data(const Geo& g, int dtype) {
     p.nch = p.Ksp / cs::BK16;
     p.off_dy = o; o += seg16((int64_t)g.N * g.PQ * p.Ksp);
     p.off_wt = o; o += seg16((int64_t)g.CRS * p.Ksp);
-    p.off_T = o;  o += seg((int64_t)g.N * g.CRS * g.PQ);
+    p.off_T = o;  o += seg((int64_t)pm_T_group(g) * g.CRS * g.PQ);   // one group of images at a time
     p.total = o;
     return p;
   }
@@ -619,7 +632,7 @@ PmBwdDataPlan plan_pm_bwd_data(const Geo& g, int dtype) {
   p.nch = p.Ksp / cs::BK;
   p.off_dy = o; o += dtype != CONV_F32 ? seg((int64_t)g.N * g.Ks * g.PQ) : 0;   // fp32 copy of the slice's maps
   p.off_wt = o; o += seg((int64_t)g.CRS * p.Ksp);
-  p.off_T = o;  o += seg((int64_t)g.N * g.CRS * g.PQ);
+  p.off_T = o;  o += seg((int64_t)pm_T_group(g) * g.CRS * g.PQ);   // one group of images at a time
   p.total = o;
   return p;
 }
@@ -803,19 +816,6 @@ int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void*
   probe.end(st);
   if (rc != CONV_OK) return rc;
   return check_launch();
-}
-
-// Images per pass over T: T = w^T dy is four bytes per (tap, channel, pixel), many times the size of dy and dx,
-// and is written once and read once.  Computed for a group of images at a time, with the sum over taps following
-// each group, a T of more than the chip's 256 MB memory-side cache stays in that cache between the two kernels
-// instead of going out to memory and back (64 images of 3 x 224 x 224 under 11 x 11 stride 4, T = 281 MB: the bf16
-// input gradient takes 0.222 ms in one pass, 0.181 ms in two groups; groups of a quarter of the cache are slower
-// than one pass, the launches get too short).
-constexpr int64_t kPmTGroupBytes = (int64_t)160 << 20;
-int pm_T_group(const Geo& g) {
-  const int64_t bytes = (int64_t)g.N * g.CRS * g.PQ * 4;
-  const int64_t groups = (bytes + kPmTGroupBytes - 1) / kPmTGroupBytes;
-  return (int)((g.N + groups - 1) / groups);
 }
 
 int pm_bwd_data(const Geo& gAll, const PmPlan& pmAll, int dtype, bool acc, const void* dy, const void* w, void* dx, void* ws,
