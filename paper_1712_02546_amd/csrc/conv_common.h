@@ -431,23 +431,51 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, 
     ch = newtile ? 0 : ch;
     const float* As = smem + cur;
     const float* Bs = smem + 2 * TILE_F + cur;
-    more = issue_next(ch, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F));
-    CS_FENCE();
-    if (!(newtile && lastg <= 2)) mfma_group(a0, b0, acc);  // G2 of the chunk before
-    CS_FENCE();
-    read_frag<AC>(a0, As, wa, lane, 0, blk1);
-    read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
-    CS_FENCE();
-    if (!(newtile && lastg <= 3)) mfma_group(a1, b1, acc);  // G3 of the chunk before
-    CS_FENCE();
-    read_frag<AC>(a1, As, wa, lane, 1, blk1);
-    read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
-    CS_FENCE();
-    if (newtile) {
+    float* ta = smem + (cur ^ TILE_F);
+    float* tb = smem + 2 * TILE_F + (cur ^ TILE_F);
+    // The chunk to load now: the next one of this tile, or the first one of the next tile (loaders rebuilt;
+    // register work only, so that the loads themselves sit in the straight-line code below, among the MFMAs).
+    // At the end of the stream the loads are issued once more as harmless dummies (live = false).
+    int chn = ch + 1;
+    bool live = true;
+    if (chn == nch) {
+      chn = 0;
+      live = tiles.advance();
+      if (live) {
+        la = tiles.make_a();
+        if (tiles.same_b()) lb.restart();
+        else lb = tiles.make_b();
+      }
+    }
+    if (!newtile) {
+      issue_all(la, lb, chn, ta, tb, wv, live);
+      CS_FENCE();
+      mfma_group(a0, b0, acc);  // G2 of the chunk before
+      CS_FENCE();
+      read_frag<AC>(a0, As, wa, lane, 0, blk1);
+      read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
+      CS_FENCE();
+      mfma_group(a1, b1, acc);  // G3 of the chunk before
+      CS_FENCE();
+      read_frag<AC>(a1, As, wa, lane, 1, blk1);
+      read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
+      CS_FENCE();
+      mfma_group(a0, b0, acc);  // G0 of this chunk
+    } else {
+      issue_all(la, lb, chn, ta, tb, wv, live);
+      CS_FENCE();
+      if (lastg > 2) mfma_group(a0, b0, acc);  // G2 of the chunk before, the last of its tile
+      CS_FENCE();
+      read_frag<AC>(a0, As, wa, lane, 0, blk1);
+      read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
+      CS_FENCE();
+      if (lastg > 3) mfma_group(a1, b1, acc);  // G3 of the chunk before
+      CS_FENCE();
+      read_frag<AC>(a1, As, wa, lane, 1, blk1);
+      read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
+      CS_FENCE();
       tiles.store(acc);
       mfma_group_first(a0, b0, acc);  // G0 of this chunk, starting a tile
-    } else {
-      mfma_group(a0, b0, acc);        // G0 of this chunk
     }
     CS_FENCE();
     read_frag<AC>(a0, As, wa, lane, 2, blk1);
@@ -459,6 +487,7 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, 
     read_frag<BC>(b1, Bs, wb, lane, 3, blk1);
     __syncthreads();
     cur ^= TILE_F;
+    more = live;
   }
   if (lastg > 2) mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
   if (lastg > 3) mfma_group(a1, b1, acc);
