@@ -48,11 +48,9 @@
  * fp32, round-to-nearest-even on output), accumulation is fp32, dw is fp32.
  * bf16 products run on the bf16 matrix-core instructions, with one
  * exception that converts its operands to fp32 copies and runs the fp32
- * kernels: layers with 17 to 31 input channels (32 too for the input
- * gradient), or with at most 16 that the few-channel path does not take
- * (C*R*S > 480 or P*Q < 32), in their forward pass and input gradient.  All
- * three passes of first layers (C = 3) and every weight gradient are bf16
- * MFMA.  conv_pass_path() names the kernel and arithmetic of a pass.
+ * kernels: forward pass and input gradient of layers with fewer than 8
+ * input channels that the few-channel path does not take (C*R*S > 480 or
+ * P*Q < 32).  conv_pass_path() names the kernel and arithmetic of a pass.
  *
  * Limits.  Each tensor (and each internal transposed copy, whose batch extent
  * is rounded up to a multiple of 32) must have fewer than 2^30 - 4096 elements

@@ -334,15 +334,20 @@ struct Probe {
 // ---- bfloat16 matrix-core paths (packed bf16 work copies, see gemm_bf16_kernels.h) ----
 inline size_t seg16(int64_t halves) { return (size_t)round_up(halves * 2, 256); }
 
-// Forward and input gradient need >= 32 input channels to fill the channel-innermost copies.
+// Forward pass and input gradient pad the channels to 64 in their channel-innermost copies (forward) or fill C of a
+// tile's 128 rows (input gradient).  The instruction is sixteen times as dense as the fp32 one, so that still pays
+// down to 8 channels (measured against the fp32 kernels on converted operands: 16 channels 7x7 0.42 -> 0.27 ms per
+// step, 8 channels 9x9 0.43 -> 0.32 ms, 17 channels 3x3 0.182 -> 0.173 ms; 4 channels 11x11: forward 0.096 -> 0.127 ms).
+// Layers with at most 16 channels come here only when the few-channel path does not take them.
+constexpr int kBf16MinChannels = 8;
 bool bf16_mfma_fwd_ok(const Geo& g, int dtype) {
   const int64_t Cp = round_up(g.C, 64);
-  return dtype == CONV_BF16 && g.C >= 32 && (int64_t)g.HW * g.Np * Cp < kMaxElems &&
+  return dtype == CONV_BF16 && g.C >= kBf16MinChannels && (int64_t)g.HW * g.Np * Cp < kMaxElems &&
          (int64_t)g.Ks * g.RS * Cp < kMaxElems;
 }
 bool bf16_mfma_bwd_data_ok(const Geo& g, int dtype) {
   const int64_t Ksp = round_up(g.Ks, 64);
-  return dtype == CONV_BF16 && g.C > 32 && (int64_t)g.PQ * g.Np * Ksp < kMaxElems &&
+  return dtype == CONV_BF16 && g.C >= kBf16MinChannels && (int64_t)g.PQ * g.Np * Ksp < kMaxElems &&
          (int64_t)g.RS * g.C * Ksp < kMaxElems;
 }
 bool bf16_mfma_bwd_weight_ok(const Geo& g, int dtype) {

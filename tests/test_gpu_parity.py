@@ -54,6 +54,10 @@ ADHOC = [
     # 1 200 forward tiles of 18 chunks for 512 workgroup slots: two rounds of whole tiles, 176 tiles shared in runs of
     # 7 chunks; 36 weight-gradient tiles of 2 400 chunks, the reduction split
     synth.random_layer(30, N=32, C=64, H=48, W=50, K=260, R=3, S=3, pad=1, k0=2, k1=258),
+    # bf16: 17 channels (a quarter of a 64-channel chunk, 17 of an input-gradient tile's 128 rows), and 8 channels with
+    # C*R*S = 512, just past what the few-channel path takes
+    synth.random_layer(31, N=20, C=17, H=12, W=11, K=70, R=3, S=3, pad=1, k0=3, k1=70),
+    synth.random_layer(32, N=9, C=8, H=14, W=13, K=40, R=8, S=8, pad=2),
     # few channels, one filter row with stride 4: three of four rows of dx are reached by no tap, the rest by one or two
     synth.random_layer(28, N=100, C=12, H=15, W=19, K=288, R=1, S=5, stride=4, pad=3, k0=29, k1=122),
 ]
@@ -87,7 +91,8 @@ def test_full_tensors_match_oracle_fp32(cfg):
 
 
 @pytest.mark.parametrize("cfg", [ADHOC[1], ADHOC[3], ADHOC[4], ADHOC[7], ADHOC[11], ADHOC[12], ADHOC[13], ADHOC[16], ADHOC[19],
-                          ADHOC[20], ADHOC[21], ADHOC[22], synth.CONFIGS["cfg1"]],
+                          ADHOC[20], ADHOC[21], ADHOC[22], synth.CONFIGS["cfg1"]]
+                         + [c for c in ADHOC if c.name in ("adhoc31", "adhoc32")],
                          ids=lambda c: c.name)
 def test_full_tensors_match_oracle_bf16(cfg):
     xo, wo, dyo = synth.make_inputs(cfg)
