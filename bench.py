@@ -115,7 +115,7 @@ def cpu_baseline(cfg, x, w, dy, images):
 PASS_OF = {"conv_fwd": 0, "conv_bwd_data": 1, "conv_bwd_weight": 2}
 
 
-def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
+def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False, graph=False):
     """Times `steps` steps of one configuration; returns the result dictionary."""
     import numpy as np
     import torch
@@ -191,6 +191,21 @@ def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
                 fn(desc, a, b, out, ws, stream)
             torch.cuda.synchronize()
             k["entry_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+    graph_ms = None
+    if graph:  # the same step recorded once into a HIP graph and replayed (what a launch-bound caller would do)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _, fn, (a, b, out) in passes:
+                fn(desc, a, b, out, ws, torch.cuda.current_stream().cuda_stream)
+        for _ in range(warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
+        del g
     dom = max(kern, key=lambda k: k["avg_ms"])
     peak = PEAK_TFLOPS[dtype_name]
     # A converted-operand path multiplies on the fp32 matrix cores whatever the tensor dtype is.
@@ -224,6 +239,8 @@ def measure(cfg_name, dtype_name, steps, warmup, cpu_images=0, per_pass=False):
         "roofline": roofline,
         "kernels": kern,
     }
+    if graph_ms is not None:
+        out["ms_per_step_graph_replay"] = graph_ms
     if cpu_images > 0:
         out["cpu_baseline"] = cpu_baseline(cfg, x, w, dy, cpu_images)
     del xd, wd, dyd, y, dx, dw, ws
@@ -375,6 +392,8 @@ def main():
     ap.add_argument("--cpu-images", type=int, default=1 << 30,
                     help="images in the CPU-oracle sample (default: the whole batch; 0 = skip)")
     ap.add_argument("--table", action="store_true", help="measure all configurations (not the contract line)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the step into a HIP graph and time its replay (extra key ms_per_step_graph_replay)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="first run one plain device copy of this many MiB (a kernel of known HBM traffic "
                          "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings with)")
@@ -429,24 +448,25 @@ def main():
         return
 
     if not args.table:
-        print(json.dumps(measure(args.config, args.dtype, args.steps, args.warmup, args.cpu_images)))
+        print(json.dumps(measure(args.config, args.dtype, args.steps, args.warmup, args.cpu_images, graph=args.graph)))
         return
 
     runs = [("cfg1", "f32"), ("cfg2", "f32"), ("cfg3", "f32"), ("cfg4", "f32"), ("cfg5a", "f32"), ("cfg5b", "f32"),
             ("cfg5a", "bf16"), ("cfg5b", "bf16"), ("cfg3", "bf16")]
     rows = []
     for name, dt in runs:
-        r = measure(name, dt, args.steps, args.warmup, 0, per_pass=True)
+        r = measure(name, dt, args.steps, args.warmup, 0, per_pass=True, graph=True)
         print(json.dumps(r), flush=True)
         rows.append((name, dt, r))
-    print("| cfg | dtype | fwd ms | bwd_data ms | bwd_weight ms | step ms | TFLOP/s | % MFMA peak | GB/s on minimal bytes |",
-          file=sys.stderr)
-    print("|---|---|---|---|---|---|---|---|---|", file=sys.stderr)
+    print("| cfg | dtype | fwd ms | bwd_data ms | bwd_weight ms | step ms | TFLOP/s | % MFMA peak | GB/s on minimal bytes | "
+          "step ms replayed from a HIP graph |", file=sys.stderr)
+    print("|---|---|---|---|---|---|---|---|---|---|", file=sys.stderr)
     for name, dt, r in rows:
         k = {x["entry"]: x for x in r["kernels"]}
         print(f"| {name} | {dt} | {k['conv_fwd']['entry_ms']:.3f} | {k['conv_bwd_data']['entry_ms']:.3f} | "
               f"{k['conv_bwd_weight']['entry_ms']:.3f} | {r['ms_per_step']:.3f} | {r['value']:.2f} | "
-              f"{100 * r['frac_of_mfma_peak']:.1f} | {r['hbm_gbs_on_min_bytes']:.0f} |", file=sys.stderr)
+              f"{100 * r['frac_of_mfma_peak']:.1f} | {r['hbm_gbs_on_min_bytes']:.0f} | "
+              f"{r['ms_per_step_graph_replay']:.3f} |", file=sys.stderr)
 
 
 if __name__ == "__main__":
