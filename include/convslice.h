@@ -37,6 +37,10 @@
  * NULL = default stream) and the call returns without synchronising.  The
  * library allocates no device memory and keeps no state between calls apart
  * from one-time kernel attribute set-up and the one-shot timing probe below.
+ * A call enqueues kernel launches only (no copies, no memsets, no events unless
+ * the probe is armed), so after one ordinary call of the same layer and pass
+ * on the device (which does the attribute set-up) the calls can be recorded
+ * into a HIP graph by stream capture and replayed.
  *
  * Errors.  Every entry point returns CONV_OK (0) or a negative conv_status_t.
  * All argument checks happen before the first launch; on an argument error
