@@ -177,21 +177,25 @@ __device__ __forceinline__ void dma16_uv(const char* base_uniform, unsigned& lan
 // wavefront's 16-byte LDS reads run at 256 bytes per clock, with m & 7 at half of that.
 __device__ __forceinline__ int col_key(int row) { return (row >> 1) & 7; }
 
-// Tile shapes of the fp32 kernels, by the template parameter MI (32-row blocks per wavefront):
+// Tile shapes of the fp32 kernels, by the template parameter MI:
 //   MI = 2: 128 rows, MI = 1: 64 rows -- four wavefronts as 2 x 2, each MI x 2 accumulator blocks;
 //   MI = 3:  96 rows -- four wavefronts side by side (1 x 4), each 3 x 1 blocks: every wavefront does the
 //            same work, which a 2 x 2 arrangement of three row blocks could not give.
-// All shapes are 128 columns wide.
+//   MI = 4: 128 rows x 96 columns -- four wavefronts on top of each other (4 x 1), each 1 x 3 blocks: for passes
+//            whose column extent is at most 96 (the weight gradient of a layer with C*R*S <= 96), where the fourth
+//            column block of the other shapes would multiply padding.
+// The other shapes are 128 columns wide.  RB = 32-row blocks per wavefront, NJ = 32-column blocks per wavefront.
 template <int MI>
 struct Shape {
-  static_assert(MI >= 1 && MI <= 3, "tile shapes: 64, 128 or 96 rows");
-  static constexpr int NJ = MI == 3 ? 1 : 2;           // column blocks per wavefront
-  static constexpr int ROWS = MI == 3 ? 96 : 64 * MI;  // tile rows
+  static_assert(MI >= 1 && MI <= 4, "tile shapes: 64, 128 or 96 rows, or 128 rows x 96 columns");
+  static constexpr int RB = MI == 4 ? 1 : MI;                      // row blocks per wavefront
+  static constexpr int NJ = MI == 3 ? 1 : MI == 4 ? 3 : 2;         // column blocks per wavefront
+  static constexpr int ROWS = MI == 3 ? 96 : MI == 4 ? 128 : 64 * MI;  // tile rows
   static constexpr int NLOAD = ROWS / 32;              // A-operand DMA loads per wavefront and chunk
   static constexpr int WROWS = ROWS / 4;               // A rows a wavefront stages
-  __device__ static __forceinline__ int row0(int wave) { return MI == 3 ? 0 : (wave >> 1) * (32 * MI); }
-  __device__ static __forceinline__ int col0(int wave) { return MI == 3 ? wave * 32 : (wave & 1) * 64; }
-  __device__ static __forceinline__ int colblk0(int wave) { return MI == 3 ? wave : (wave & 1) * 2; }
+  __device__ static __forceinline__ int row0(int wave) { return MI == 3 ? 0 : MI == 4 ? wave * 32 : (wave >> 1) * (32 * MI); }
+  __device__ static __forceinline__ int col0(int wave) { return MI == 3 ? wave * 32 : MI == 4 ? 0 : (wave & 1) * 64; }
+  __device__ static __forceinline__ int colblk0(int wave) { return MI == 3 ? wave : MI == 4 ? 0 : (wave & 1) * 2; }
 };
 
 template <int NBLK>
@@ -208,7 +212,7 @@ __device__ __forceinline__ void read_frag(FragN<NBLK>& f, const float* tile, int
 #pragma unroll
     for (int b = 0; b < NBLK; ++b) f.v[b] = *(const f32x4*)(tile + slot * 4 + b * (32 * 8 * 4));
   } else {
-    static_assert(NBLK <= 2, "row images feed one or two blocks");
+    static_assert(NBLK <= 3, "row images feed up to three blocks");
     // The second block lies blk1 = 32 floats to the right.  blk1 is an opaque register (see
     // opaque_block_offset), so the two blocks keep separate base registers and the reads of
     // rows t, t+1 of one block (512 bytes apart) pair up into LDS reads with 256-byte offset
@@ -216,10 +220,15 @@ __device__ __forceinline__ void read_frag(FragN<NBLK>& f, const float* tile, int
     const float* p = tile + (8 * j + 4 * (lane >> 5)) * BM + wbase + (lane & 31);
 #pragma unroll
     for (int t = 0; t < 4; ++t) f.v[0][t] = p[t * BM];
-    if constexpr (NBLK == 2) {
+    if constexpr (NBLK >= 2) {
       const float* q = p + blk1;
 #pragma unroll
       for (int t = 0; t < 4; ++t) f.v[1][t] = q[t * BM];
+    }
+    if constexpr (NBLK == 3) {
+      const float* q2 = p + 2 * blk1;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) f.v[2][t] = q2[t * BM];
     }
   }
 }
@@ -232,12 +241,12 @@ __device__ __forceinline__ int opaque_block_offset() {
 
 // Four reduction steps on the wavefront's MI x NJ accumulator blocks (sixteen MFMAs for MI = 2, twelve for MI = 3).
 template <int MI>
-__device__ __forceinline__ void mfma_group(const FragN<MI>& a, const FragN<Shape<MI>::NJ>& b,
-                                           f32x16 (&acc)[MI][Shape<MI>::NJ]) {
+__device__ __forceinline__ void mfma_group(const FragN<Shape<MI>::RB>& a, const FragN<Shape<MI>::NJ>& b,
+                                           f32x16 (&acc)[Shape<MI>::RB][Shape<MI>::NJ]) {
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    for (int i = 0; i < Shape<MI>::RB; ++i) {
 #pragma unroll
       for (int j = 0; j < Shape<MI>::NJ; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][t], b.v[j][t], acc[i][j], 0, 0, 0);
@@ -279,7 +288,7 @@ __device__ __forceinline__ void issue_all(LA& la, LB& lb, int ch, float* ta, flo
 // chunk ch while G2,G3 are being read.
 template <class LA, class LB>
 __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int ch_end, float* smem,
-                                              f32x16 (&acc)[LA::MI][Shape<LA::MI>::NJ]) {
+                                              f32x16 (&acc)[Shape<LA::MI>::RB][Shape<LA::MI>::NJ]) {
   constexpr bool AC = LA::COL, BC = LB::COL;
   constexpr int MI = LA::MI;
   static_assert(MI == 2 || AC, "the 64- and 96-row tiles need a col-image A operand");
@@ -289,7 +298,7 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   const int wa = Shape<MI>::row0(wv), wb = Shape<MI>::col0(wv);
   if (ch_begin >= ch_end) return;
   const int blk1 = opaque_block_offset();
-  FragN<MI> a0, a1;
+  FragN<Shape<MI>::RB> a0, a1;
   FragN<Shape<MI>::NJ> b0, b1;
   // prologue: chunk ch_begin into stage 0
   issue_all(la, lb, ch_begin, smem, smem + 2 * TILE_F, wv, true);
@@ -300,12 +309,12 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
   read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 1, blk1);
   issue_all(la, lb, ch_begin + 1, smem + TILE_F, smem + 3 * TILE_F, wv, ch_begin + 1 < ch_end);
   CS_FENCE();
-  mfma_group(a0, b0, acc);
+  mfma_group<MI>(a0, b0, acc);
   CS_FENCE();
   read_frag<AC>(a0, smem, wa, lane, 2, blk1);
   read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 2, blk1);
   CS_FENCE();
-  mfma_group(a1, b1, acc);
+  mfma_group<MI>(a1, b1, acc);
   CS_FENCE();
   read_frag<AC>(a1, smem, wa, lane, 3, blk1);
   read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 3, blk1);
@@ -316,30 +325,30 @@ __device__ __forceinline__ void gemm_mainloop(LA& la, LB& lb, int ch_begin, int 
     const float* Bs = smem + 2 * TILE_F + cur;
     issue_all(la, lb, ch + 1, smem + (cur ^ TILE_F), smem + 2 * TILE_F + (cur ^ TILE_F), wv, ch + 1 < ch_end);
     CS_FENCE();
-    mfma_group(a0, b0, acc);  // G2 of chunk ch-1
+    mfma_group<MI>(a0, b0, acc);  // G2 of chunk ch-1
     CS_FENCE();
     read_frag<AC>(a0, As, wa, lane, 0, blk1);
     read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
     CS_FENCE();
-    mfma_group(a1, b1, acc);  // G3 of chunk ch-1
+    mfma_group<MI>(a1, b1, acc);  // G3 of chunk ch-1
     CS_FENCE();
     read_frag<AC>(a1, As, wa, lane, 1, blk1);
     read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
     CS_FENCE();
-    mfma_group(a0, b0, acc);  // G0 of chunk ch
+    mfma_group<MI>(a0, b0, acc);  // G0 of chunk ch
     CS_FENCE();
     read_frag<AC>(a0, As, wa, lane, 2, blk1);
     read_frag<BC>(b0, Bs, wb, lane, 2, blk1);
     CS_FENCE();
-    mfma_group(a1, b1, acc);  // G1 of chunk ch
+    mfma_group<MI>(a1, b1, acc);  // G1 of chunk ch
     CS_FENCE();
     read_frag<AC>(a1, As, wa, lane, 3, blk1);
     read_frag<BC>(b1, Bs, wb, lane, 3, blk1);
     __syncthreads();
     cur ^= TILE_F;
   }
-  mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
-  mfma_group(a1, b1, acc);
+  mfma_group<MI>(a0, b0, acc);  // G2, G3 of the last chunk
+  mfma_group<MI>(a1, b1, acc);
 }
 
 // Four reduction steps that start a tile: the first step writes the accumulators (C operand zero) instead of
@@ -419,7 +428,7 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, 
   read_frag<AC>(a0, smem, wa, lane, 2, blk1);
   read_frag<BC>(b0, smem + 2 * TILE_F, wb, lane, 2, blk1);
   CS_FENCE();
-  mfma_group(a1, b1, acc);
+  mfma_group<MI>(a1, b1, acc);
   CS_FENCE();
   read_frag<AC>(a1, smem, wa, lane, 3, blk1);
   read_frag<BC>(b1, smem + 2 * TILE_F, wb, lane, 3, blk1);
@@ -450,26 +459,26 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, 
     if (!newtile) {
       issue_all(la, lb, chn, ta, tb, wv, live);
       CS_FENCE();
-      mfma_group(a0, b0, acc);  // G2 of the chunk before
+      mfma_group<MI>(a0, b0, acc);  // G2 of the chunk before
       CS_FENCE();
       read_frag<AC>(a0, As, wa, lane, 0, blk1);
       read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
       CS_FENCE();
-      mfma_group(a1, b1, acc);  // G3 of the chunk before
+      mfma_group<MI>(a1, b1, acc);  // G3 of the chunk before
       CS_FENCE();
       read_frag<AC>(a1, As, wa, lane, 1, blk1);
       read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
       CS_FENCE();
-      mfma_group(a0, b0, acc);  // G0 of this chunk
+      mfma_group<MI>(a0, b0, acc);  // G0 of this chunk
     } else {
       issue_all(la, lb, chn, ta, tb, wv, live);
       CS_FENCE();
-      if (lastg > 2) mfma_group(a0, b0, acc);  // G2 of the chunk before, the last of its tile
+      if (lastg > 2) mfma_group<MI>(a0, b0, acc);  // G2 of the chunk before, the last of its tile
       CS_FENCE();
       read_frag<AC>(a0, As, wa, lane, 0, blk1);
       read_frag<BC>(b0, Bs, wb, lane, 0, blk1);
       CS_FENCE();
-      if (lastg > 3) mfma_group(a1, b1, acc);  // G3 of the chunk before
+      if (lastg > 3) mfma_group<MI>(a1, b1, acc);  // G3 of the chunk before
       CS_FENCE();
       read_frag<AC>(a1, As, wa, lane, 1, blk1);
       read_frag<BC>(b1, Bs, wb, lane, 1, blk1);
@@ -481,7 +490,7 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, 
     read_frag<AC>(a0, As, wa, lane, 2, blk1);
     read_frag<BC>(b0, Bs, wb, lane, 2, blk1);
     CS_FENCE();
-    mfma_group(a1, b1, acc);  // G1 of this chunk
+    mfma_group<MI>(a1, b1, acc);  // G1 of this chunk
     CS_FENCE();
     read_frag<AC>(a1, As, wa, lane, 3, blk1);
     read_frag<BC>(b1, Bs, wb, lane, 3, blk1);
@@ -489,8 +498,8 @@ __device__ __forceinline__ void gemm_stream(Tiles& tiles, int nch, float* smem, 
     cur ^= TILE_F;
     more = live;
   }
-  if (lastg > 2) mfma_group(a0, b0, acc);  // G2, G3 of the last chunk
-  if (lastg > 3) mfma_group(a1, b1, acc);
+  if (lastg > 2) mfma_group<MI>(a0, b0, acc);  // G2, G3 of the last chunk
+  if (lastg > 3) mfma_group<MI>(a1, b1, acc);
   tiles.store(acc);
 }
 

@@ -956,7 +956,7 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
   auto launch = [&](auto kern, int mi, int m0, int tiles) -> int {
     int rc2;
     if ((rc2 = allow_big_lds(kern, cs::SMEM_BYTES)) != CONV_OK) return rc2;
-    const int rows = std::min(g.Ks - m0, tiles * (mi == 3 ? 96 : 64 * mi));
+    const int rows = std::min(g.Ks - m0, tiles * (mi == 3 ? 96 : mi == 4 ? 128 : 64 * mi));
     const int splits = choose_splits((int64_t)tiles * p.CT, p.nch, true, kPmSplitRounds);
     const int64_t stride = (int64_t)rows * g.CRS;
     float* out = splits > 1 ? scratch : dwslice;
@@ -971,13 +971,16 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
   const bool vec4 = g.PQ % 4 == 0;
   const RowSplit rs = split_rows(g.Ks, true);
   rc = CONV_OK;
+  const bool narrow = g.CRS <= 96;   // 128 x 96 tiles: a fourth column block would multiply padding
   probe.begin(st);
   if (vec4) {
-    if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, true>, 2, 0, rs.full);
+    if (rs.full > 0) rc = narrow ? launch(cs::bwd_weight_pm_gemm_kernel<4, true>, 4, 0, rs.full)
+                                 : launch(cs::bwd_weight_pm_gemm_kernel<2, true>, 2, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, true>, 1, rs.full * cs::BM, 1);
     if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, true>, 3, rs.full * cs::BM, rs.nlast);
   } else {
-    if (rs.full > 0) rc = launch(cs::bwd_weight_pm_gemm_kernel<2, false>, 2, 0, rs.full);
+    if (rs.full > 0) rc = narrow ? launch(cs::bwd_weight_pm_gemm_kernel<4, false>, 4, 0, rs.full)
+                                 : launch(cs::bwd_weight_pm_gemm_kernel<2, false>, 2, 0, rs.full);
     if (rc == CONV_OK && rs.last == 1) rc = launch(cs::bwd_weight_pm_gemm_kernel<1, false>, 1, rs.full * cs::BM, 1);
     if (rc == CONV_OK && rs.last == 3) rc = launch(cs::bwd_weight_pm_gemm_kernel<3, false>, 3, rs.full * cs::BM, rs.nlast);
   }

@@ -620,11 +620,11 @@ __device__ __forceinline__ void bwd_weight_store_block(const Geo& g, float* __re
 
 template <int MI>
 __device__ __forceinline__ void bwd_weight_store_tile(const Geo& g, float* __restrict__ o, int m0, int rowBase, int ct,
-                                                      const f32x16 (&acc)[MI][Shape<MI>::NJ]) {
+                                                      const f32x16 (&acc)[Shape<MI>::RB][Shape<MI>::NJ]) {
 #pragma unroll
   for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
-    for (int i = 0; i < MI; ++i) bwd_weight_store_block<MI>(g, o, m0, rowBase, ct, i, j, acc[i][j]);
+    for (int i = 0; i < Shape<MI>::RB; ++i) bwd_weight_store_block<MI>(g, o, m0, rowBase, ct, i, j, acc[i][j]);
 }
 
 // out[z][m][j]: partial (or final when one split) weight gradients of the slice.  Either

@@ -589,9 +589,9 @@ __global__ __launch_bounds__(NT) void bwd_weight_pm_gemm_kernel(Geo g, PmGeo pg,
   tile_from_line(L, MB, CT, mb, ct);
   const int m0 = mOrigin + mb * Shape<MI>::ROWS;
   const int count = (nch - z + splits - 1) / splits;
-  f32x16 acc[MI][Shape<MI>::NJ];
+  f32x16 acc[Shape<MI>::RB][Shape<MI>::NJ];
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+  for (int i = 0; i < Shape<MI>::RB; ++i)
 #pragma unroll
     for (int j = 0; j < Shape<MI>::NJ; ++j)
 #pragma unroll
