@@ -781,24 +781,24 @@ int pm_fwd(const Geo& g, const PmPlan& pm, int dtype, const void* x, const void*
   const size_t es = elem_size(dtype);
   const float* xb = pm_input(g, pm, dtype, x, (float*)(base + p.off_xb), st, input_ready);
   const float* wmat;
-  if (p.repitch) {
+  int* tab = (int*)(base + p.off_tab);
+  const int entries = (p.nch + 4) * cs::BK;
+  const int tblocks = (entries + 255) / 256;
+  if (p.repitch) {   // filter rows to fp32 rows of pitch ldw and the tap table, one launch
     float* wp = (float*)(base + p.off_w);
     const char* wsrc = (const char*)w + (size_t)g.k0 * g.CRS * es;
-    const int blocks = grid_for((int64_t)g.Ks * p.ldw, 4096);
+    const int rblocks = grid_for((int64_t)g.Ks * p.ldw, 4096);
     if (dtype == CONV_F32)
-      hipLaunchKernelGGL(cs::repitch_rows_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)wsrc,
-                         (int64_t)g.CRS, g.Ks, g.CRS, wp, p.ldw);
+      hipLaunchKernelGGL(cs::pm_fwd_setup_kernel<float>, dim3(rblocks + tblocks), dim3(256), 0, st, g, (const float*)wsrc,
+                         wp, p.ldw, rblocks, pm.pg.Hp, pm.pg.Wp, entries, tab);
     else
-      hipLaunchKernelGGL(cs::repitch_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)wsrc,
-                         (int64_t)g.CRS, g.Ks, g.CRS, wp, p.ldw);
+      hipLaunchKernelGGL(cs::pm_fwd_setup_kernel<uint16_t>, dim3(rblocks + tblocks), dim3(256), 0, st, g,
+                         (const uint16_t*)wsrc, wp, p.ldw, rblocks, pm.pg.Hp, pm.pg.Wp, entries, tab);
     wmat = wp;
   } else {
     wmat = (const float*)w + (size_t)g.k0 * g.CRS;
+    hipLaunchKernelGGL(cs::pm_tap_table_kernel, dim3(tblocks), dim3(256), 0, st, g, pm.pg.Hp, pm.pg.Wp, entries, tab);
   }
-  int* tab = (int*)(base + p.off_tab);
-  const int entries = (p.nch + 4) * cs::BK;
-  hipLaunchKernelGGL(cs::pm_tap_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, st, g, pm.pg.Hp, pm.pg.Wp, entries,
-                     tab);
   const RowSplit rs = split_rows(g.Ks, true);
   probe.begin(st);
   auto launch = [&](auto kern, auto* yout, int m0, int tiles) -> int {
@@ -944,11 +944,10 @@ int pm_bwd_weight(const Geo& g, const PmPlan& pm, const void* x, const void* dy,
   if ((rc = check_ws(ws, ws_bytes, p.total)) != CONV_OK) return rc;
   char* base = (char*)ws;
   float* zero = (float*)base;
-  hipLaunchKernelGGL(cs::fill_zero_kernel<float>, dim3(1), dim3(256), 0, st, zero, (int64_t)cs::ZERO_PAGE_FLOATS);
   const float* xb = pm_input(g, pm, CONV_F32, x, (float*)(base + p.off_xb), st, input_ready);
   int* pixtab = (int*)(base + p.off_pix);
   hipLaunchKernelGGL(cs::pm_pixel_table_kernel, dim3((pm.pg.NC * 32 + 255) / 256), dim3(256), 0, st, g, pm.pg.Wp, pm.pg.NC,
-                     pixtab);
+                     pixtab, zero);   // clears the zero page too
   const float* dy_k0 = (const float*)dy + (size_t)g.k0 * g.PQ;
   const int64_t imgPitch = (int64_t)g.K * g.PQ;
   float* dwslice = (float*)dw + (size_t)g.k0 * g.CRS;

@@ -76,12 +76,38 @@ __global__ void pm_tap_table_kernel(Geo g, int Hp, int Wp, int entries, int* __r
   tab[i] = ((c * Hp + r) * Wp + s) * 4;
 }
 
+// The forward pass's two set-up jobs in one launch (they are a few microseconds each, most of it the launch):
+// blocks below rblocks copy the filter rows to fp32 rows of pitch ldw, zero past C*R*S (repitch_rows_kernel's job),
+// the others write the tap table (pm_tap_table_kernel's).
+template <typename Tin>
+__global__ __launch_bounds__(256) void pm_fwd_setup_kernel(Geo g, const Tin* __restrict__ wsrc, float* __restrict__ wdst,
+                                                           int ldw, int rblocks, int Hp, int Wp, int entries,
+                                                           int* __restrict__ tab) {
+  if ((int)blockIdx.x >= rblocks) {
+    const int i = ((int)blockIdx.x - rblocks) * blockDim.x + threadIdx.x;
+    if (i >= entries) return;
+    const int j = i < g.CRS ? i : 0;
+    const int c = j / g.RS, rs = j - c * g.RS;
+    const int r = rs / g.S, s = rs - r * g.S;
+    tab[i] = ((c * Hp + r) * Wp + s) * 4;
+    return;
+  }
+  const int64_t total = (int64_t)g.Ks * ldw;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)rblocks * blockDim.x) {
+    const int r = (int)(i / ldw), c = (int)(i - (int64_t)r * ldw);
+    wdst[i] = c < g.CRS ? load_as_f32<Tin>(wsrc + (int64_t)r * g.CRS + c) : 0.f;
+  }
+}
+
 // Weight gradient: reduction chunk pc of an image covers 32 output pixels.  tab[pc*32 + kk] =
 // byte offset of the window origin of that chunk's pixel kk inside one image of xb, or -1 if the
 // pixel does not count.  The last chunk of an image is moved back so that it ends with the
 // image's last pixel (the dy rows are read in place and must not be over-read); the pixels it
 // shares with the chunk before are the ones that do not count.  Needs P*Q >= 32.
-__global__ void pm_pixel_table_kernel(Geo g, int Wp, int NC, int* __restrict__ tab) {
+// The first workgroup also clears the zero page (zero_page may be null).
+__global__ void pm_pixel_table_kernel(Geo g, int Wp, int NC, int* __restrict__ tab, float* __restrict__ zero_page) {
+  if (zero_page && blockIdx.x == 0)
+    for (int z = threadIdx.x; z < ZERO_PAGE_FLOATS; z += blockDim.x) zero_page[z] = 0.f;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= NC * 32) return;
   const int pc = i >> 5, kk = i & 31;
